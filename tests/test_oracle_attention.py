@@ -1,0 +1,110 @@
+"""Pins for the oracle's forest attention against library attention routines and invariances.
+
+* a single chain tree is ordinary causal attention over [prefix ; chain];
+* a general forest equals masked attention with a mask built by brute force (matrix closure);
+* GQA with Hkv = Hq equals MHA on repeated KV heads; sibling order only permutes outputs.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from dsbd_synth import bf16_bits_to_f32, make_workload
+from oracle import attention, forest
+from test_oracle_forest import closure_by_matrix_powers
+
+
+def f64(bits):
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def logical_prefix(w, t):
+    p = int(w.tree_prompt[t])
+    ks, vs = [], []
+    if w.k_shared[p] is not None:
+        ks.append(f64(w.k_shared[p])); vs.append(f64(w.v_shared[p]))
+    ks.append(f64(w.k_own[t])); vs.append(f64(w.v_own[t]))
+    return np.concatenate(ks, 0), np.concatenate(vs, 0)
+
+
+def run_oracle(w):
+    pk, pv = zip(*[logical_prefix(w, t) for t in range(w.n_trees)])
+    return attention.forest_attention(w.parent, w.tree_off, f64(w.q), f64(w.k_tree), f64(w.v_tree), list(pk), list(pv))
+
+
+def test_single_chain_is_causal_attention():
+    w = make_workload("c1", W=1, tree_nodes=5, L=11, Hq=4, Hkv=4, D=64)
+    out, lse = run_oracle(w)
+    pk, pv = logical_prefix(w, 0)
+    K = np.concatenate([pk, f64(w.k_tree)], 0)     # [L+5, H, D]
+    Vv = np.concatenate([pv, f64(w.v_tree)], 0)
+    L = pk.shape[0]
+    # queries for every position: the prefix queries are dummies, only the last 5 rows are compared
+    Q = np.concatenate([np.zeros((L, 4, 64)), f64(w.q)], 0)
+    tq = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(K).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(Vv).permute(1, 0, 2)[None]
+    ref = F.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()[L:]
+    assert np.max(np.abs(ref - out)) < 1e-12
+    # lse against a direct log-sum-exp of the causal scores
+    s = np.einsum("nhd,mhd->hnm", f64(w.q), K) / 8.0
+    for i in range(5):
+        ref_lse = torch.logsumexp(torch.from_numpy(s[:, i, :L + i + 1]), dim=-1).numpy()
+        assert np.max(np.abs(ref_lse - lse[i])) < 1e-12
+
+
+@pytest.mark.parametrize("cfg,kw", [("c2", dict(L=9)), ("c3", dict(L=12, shared_len=5)),
+                                    ("c4", dict(L=(3, 9), n_prompts=3)), ("c5", dict(L=7))])
+def test_forest_equals_masked_library_attention(cfg, kw):
+    w = make_workload(cfg, V=8, Hq=4, Hkv=2, D=64, **kw)
+    out, lse = run_oracle(w)
+    reach = closure_by_matrix_powers(w.parent)
+    tree = forest.tree_of_node(w.tree_off, w.n_nodes)
+    group = 2
+    for t in range(w.n_trees):
+        a, b = int(w.tree_off[t]), int(w.tree_off[t + 1])
+        pk, pv = logical_prefix(w, t)
+        L = pk.shape[0]
+        K = np.concatenate([pk, f64(w.k_tree)[a:b]], 0)
+        Vv = np.concatenate([pv, f64(w.v_tree)[a:b]], 0)
+        mask = np.concatenate([np.ones((b - a, L), dtype=bool), reach[a:b, a:b]], 1)
+        tq = torch.from_numpy(f64(w.q)[a:b]).permute(1, 0, 2)[None]                      # [1,Hq,n,D]
+        tk = torch.from_numpy(np.repeat(K, group, axis=1)).permute(1, 0, 2)[None]         # KV head h//group
+        tv = torch.from_numpy(np.repeat(Vv, group, axis=1)).permute(1, 0, 2)[None]
+        ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=torch.from_numpy(mask))[0].permute(1, 0, 2).numpy()
+        assert np.max(np.abs(ref - out[a:b])) < 1e-12
+        assert (tree[a:b] == t).all()
+
+
+def test_gqa_with_all_heads_equals_mha_and_sibling_permutation():
+    w = make_workload("c2", L=6, V=8, Hq=4, Hkv=4, D=64)
+    out, _ = run_oracle(w)
+    # the same data presented as GQA with one KV head per query head group of size 1 is identical by
+    # construction; present it instead as Hkv=2 with duplicated KV heads and Hq=4
+    pk, pv = zip(*[logical_prefix(w, t) for t in range(w.n_trees)])
+    dup = lambda x: np.repeat(x[:, ::2, :], 2, axis=1)        # heads (0,0,2,2): MHA view of a 2-KV-head GQA
+    out_mha, _ = attention.forest_attention(w.parent, w.tree_off, f64(w.q), dup(f64(w.k_tree)), dup(f64(w.v_tree)),
+                                            [dup(x) for x in pk], [dup(x) for x in pv])
+    half = lambda x: x[:, ::2, :]
+    out_gqa, _ = attention.forest_attention(w.parent, w.tree_off, f64(w.q), half(f64(w.k_tree)), half(f64(w.v_tree)),
+                                            [half(x) for x in pk], [half(x) for x in pv])
+    assert np.array_equal(out_mha, out_gqa)
+    # swapping the two children of the first root (nodes 1,2 and their chains 3,4 / 5,6) permutes outputs only
+    perm = np.arange(w.n_nodes)
+    perm[[1, 2, 3, 4, 5, 6]] = [2, 1, 4, 3, 6, 5]
+    inv = np.argsort(perm)
+    parent2 = np.array([-1 if w.parent[perm[i]] < 0 else inv[w.parent[perm[i]]] for i in range(w.n_nodes)])
+    forest.check_forest(parent2, w.tree_off)
+    out2, _ = attention.forest_attention(parent2, w.tree_off, f64(w.q)[perm], f64(w.k_tree)[perm], f64(w.v_tree)[perm],
+                                         list(pk), list(pv))
+    assert np.max(np.abs(out2 - out[perm])) < 1e-12
+
+
+def test_single_query_helper_matches_full():
+    w = make_workload("c3", L=10, shared_len=4, V=8, Hq=4, Hkv=2, D=64)
+    out, lse = run_oracle(w)
+    for n, h in [(0, 0), (17, 3), (119, 2)]:
+        t = int(forest.tree_of_node(w.tree_off, w.n_nodes)[n])
+        pk, pv = logical_prefix(w, t)
+        o, l = attention.forest_attention_at(w.parent, w.tree_off, f64(w.q), f64(w.k_tree), f64(w.v_tree), pk, pv, n, h)
+        assert np.allclose(o, out[n, h], atol=1e-14) and abs(l - lse[n, h]) < 1e-12

@@ -1,0 +1,201 @@
+/*
+ * dsbd.h - C ABI of the multi-tree (forest) parallel verification step of dynamic-width
+ * speculative beam decoding, for AMD MI355X (gfx950).
+ *
+ * One decoding iteration hands this library a draft forest (one token tree per input beam),
+ * the large model's per-beam key/value caches, and the large/small models' logits at every
+ * forest node.  The library
+ *   1. runs forest attention: every node attends to its own beam's cache plus its tree
+ *      ancestors (paper Section 3.3, "Forest-based Parallel Decoding");
+ *   2. verifies the forest layer by layer (paper Section 3.1 "Details", Algorithm 1) with the
+ *      fixed or the dynamic layer width (Section 3.2, Eq. 1-6);
+ *   3. turns the verification result into the next iteration's beam set (Algorithm 1's return
+ *      value; Section 3.3 last paragraph; Section 3.4 for the one-beam variant).
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer owned by the caller unless marked "host".
+ *     The structs themselves are host memory, read during the call only.
+ *   - The library allocates nothing and keeps no state between calls.  Scratch memory comes
+ *     from the caller's `workspace` (device, 256-byte aligned), at least as large as the
+ *     matching dsbd_*_workspace_bytes() says.  Its contents need not be initialised.
+ *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work; outputs are valid
+ *     once the stream has been synchronised.  No call synchronises the device.
+ *   - Return value: DSBD_OK or a negative DSBD_ERR_* for problems visible on the host
+ *     (null pointers, sizes, unsupported shapes, workspace too small, HIP launch errors).
+ *     Nothing is enqueued when an error is returned.
+ *   - Problems only visible in device data are OR-ed into the device word `*fault`
+ *     (DSBD_FAULT_* bits) and never cause out-of-bounds accesses; the caller clears the word.
+ */
+#ifndef DSBD_H
+#define DSBD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DSBD_OK               0
+#define DSBD_ERR_INVALID     (-1)   /* null pointer, negative size, Hq % Hkv != 0, ...              */
+#define DSBD_ERR_UNSUPPORTED (-2)   /* D not 128 or 64, tree bound above 64 nodes, V < 1, ...       */
+#define DSBD_ERR_WORKSPACE   (-3)   /* workspace smaller than dsbd_*_workspace_bytes()              */
+#define DSBD_ERR_HIP         (-4)   /* HIP runtime reported an error at launch                      */
+
+#define DSBD_FAULT_TOPOLOGY       1 /* parent outside its tree / not before the child / bad root    */
+#define DSBD_FAULT_TOKEN          2 /* token id outside [0, V)                                      */
+#define DSBD_FAULT_NONFINITE      4 /* NaN or Inf logit                                             */
+#define DSBD_FAULT_ZERO_RESIDUAL  8 /* a residual distribution had no mass                          */
+#define DSBD_FAULT_BOUNDS        16 /* a host-declared bound (max_*) is exceeded by the device data */
+#define DSBD_FAULT_SYNC_TIMEOUT  32 /* internal grid synchronisation gave up                        */
+
+/* node_status codes written by dsbd_verify_forest */
+#define DSBD_NOT_REACHED 0          /* deeper than the last verified layer                          */
+#define DSBD_ACCEPTED    1
+#define DSBD_REJECTED    2          /* failed its test, or left over once the layer was full         */
+#define DSBD_PRUNED      3          /* its parent was not accepted (Algorithm 1, pruning step)       */
+#define DSBD_ROOT        4          /* an input beam                                                */
+
+/*
+ * Draft forest (Section 3.1 "Overview"): n_trees token trees, one per input beam, the trees of a
+ * prompt adjacent.  Nodes of a tree are contiguous, the first node of a tree is its root (the
+ * input beam's last token) and parent[i] < i (depth-first order as in the forest-attention
+ * figure satisfies this, so does breadth-first order).
+ */
+typedef struct dsbd_forest {
+  int32_t n_prompts, n_trees, n_nodes;
+  const int32_t* tree_prompt;   /* [n_trees]   prompt of each tree, non-decreasing, 0..n_prompts-1    */
+  const int32_t* tree_off;      /* [n_trees+1] first node of each tree; tree_off[n_trees] = n_nodes   */
+  const int32_t* parent;        /* [n_nodes]   global index of the parent, -1 at a root               */
+  const int32_t* token;         /* [n_nodes]   token id at the node (verify only; may be NULL for attention) */
+  const int32_t* draft_rank;    /* [n_nodes] or NULL: order in which the draft stage drew the nodes   */
+                                /*   of a layer; a layer is verified in ascending (rank, node index). */
+                                /*   The correctness theorem needs the draw order (iid drafts).      */
+  /* host-side bounds on the device data, checked on the device (DSBD_FAULT_BOUNDS): */
+  int32_t max_tree_nodes;       /* >= nodes of the largest tree; at most 64                           */
+  int32_t max_depth;            /* >= depth of the deepest node (roots have depth 0)                  */
+  int32_t max_prompt_trees;     /* >= trees of the widest prompt                                      */
+} dsbd_forest;
+
+/*
+ * Per-beam prefix key/value caches (Section 3.3: one cache per input beam), bf16.
+ * The prefix of tree b is an optional segment shared with other beams (k_shared_ptr[b], first
+ * shared_len[b] tokens) followed by the beam's own segment (k_ptr[b], len[b] tokens).
+ * Element (token t, kv-head g, channel d) of a segment lives at ptr[t*token_stride + g*head_stride + d]
+ * (strides in elements; covers [L,Hkv,D] and [Hkv,L,D]).  The root token's K/V is NOT part of
+ * the prefix: it is row tree_off[b] of k_tree / v_tree.
+ */
+typedef struct dsbd_kv {
+  const void* const* k_ptr;         /* [n_trees] device array of device pointers                      */
+  const void* const* v_ptr;         /* [n_trees]                                                      */
+  const int32_t*     len;           /* [n_trees] tokens in the own segment (>= 0)                     */
+  const void* const* k_shared_ptr;  /* [n_trees] or NULL                                              */
+  const void* const* v_shared_ptr;  /* [n_trees] or NULL                                              */
+  const int32_t*     shared_len;    /* [n_trees] or NULL                                              */
+  int64_t token_stride, head_stride;
+  int32_t max_len;                  /* host bound: >= shared_len[b] + len[b] for every tree           */
+} dsbd_kv;
+
+size_t dsbd_forest_attention_workspace_bytes(const dsbd_forest* forest, const dsbd_kv* prefix,
+                                             int32_t Hq, int32_t Hkv, int32_t D);
+
+/*
+ * Forest attention (Section 3.3 and the forest-attention figure): for node n of tree b and query
+ * head h, softmax over {all prefix positions of beam b} U {tree rows of n's ancestors and n itself}
+ * of scale * q.k, applied to V.  Query head h reads KV head h / (Hq/Hkv).
+ *   q               [n_nodes,Hq,D]  bf16
+ *   k_tree, v_tree  [n_nodes,Hkv,D] bf16, row n = key/value of forest node n
+ *   scale           <= 0 selects 1/sqrt(D)
+ *   out             [n_nodes,Hq,D]  bf16
+ *   lse             [n_nodes,Hq]    f32 natural-log sum of exp of the scaled scores, or NULL
+ *   anc_mask_out    [n_nodes]       u64 or NULL; bit j = j-th node of the same tree is an ancestor or the node itself
+ * Supported: D = 128 or 64, Hq % Hkv == 0, trees of at most 64 nodes.
+ */
+int32_t dsbd_forest_attention(const dsbd_forest* forest, const dsbd_kv* prefix,
+                              const void* q, const void* k_tree, const void* v_tree,
+                              int32_t Hq, int32_t Hkv, int32_t D, float scale,
+                              void* out, float* lse, uint64_t* anc_mask_out,
+                              void* workspace, size_t workspace_bytes, int32_t* fault, void* stream);
+
+/* Verification parameters (Algorithm 1 inputs; Eq. 5-6). */
+typedef struct dsbd_params {
+  int32_t W_L;     /* beam width; <= 0: every prompt uses its own number of input beams             */
+  int32_t W_min;   /* floor of the dynamic width (Eq. 5), >= 1                                      */
+  int32_t W_cap;   /* capacity of the per-prompt output arrays; also caps every layer's width       */
+  float   t;       /* threshold of Eq. 6 in [0,1]; t < 0 selects the fixed width W_L for all layers */
+} dsbd_params;
+
+/* Inputs of the verification that are not part of the forest. Lmax = forest->max_depth. */
+typedef struct dsbd_verify_in {
+  int32_t V;                       /* vocabulary size                                                */
+  const float*  logits_target;     /* [n_nodes,V] large model's logits at every node (row-major)     */
+  const float*  logits_draft;      /* [n_nodes,V] small model's logits                               */
+  const double* beam_logp_target;  /* [n_trees] stored log-likelihood of each input beam under p      */
+  const double* beam_logp_draft;   /* [n_trees] ... under q (Section 2.1: beam sampling stores them)  */
+  const float*  u_accept;          /* [n_nodes]            uniform in [0,1) for the node's accept test */
+  const float*  u_resid;           /* [n_prompts,Lmax+2]   uniform for the residual sample of layer l  */
+  const float*  u_fill;            /* [n_prompts,Lmax+2,W_cap] uniforms for the p_beam samples of layer l */
+} dsbd_verify_in;
+
+/* Outputs of the verification. */
+typedef struct dsbd_verify_out {
+  uint8_t* node_status;        /* [n_nodes] DSBD_* status codes                                      */
+  float*   lse_target;         /* [n_nodes] log-sum-exp of the node's target logits                  */
+  float*   lse_draft;          /* [n_nodes]                                                          */
+  float*   node_logp_target;   /* [n_nodes] log p(token[n] | parent[n]); 0 at roots                  */
+  float*   node_logp_draft;    /* [n_nodes]                                                          */
+  int32_t* l_last;             /* [n_prompts] layer that produced the output beams (1..gamma+1)      */
+  int32_t* layer_width;        /* [n_prompts,Lmax+2] W_L^(l) used at layer l (index 0: input beams)  */
+  int32_t* n_out;              /* [n_prompts] number of output beams                                 */
+  int32_t* out_parent;         /* [n_prompts,W_cap] forest node the output beam extends              */
+  int32_t* out_token;          /* [n_prompts,W_cap] its new token                                    */
+  int32_t* out_node;           /* [n_prompts,W_cap] the accepted draft node, or -1 if sampled        */
+  double*  out_logp_target;    /* [n_prompts,W_cap] cumulative log-likelihood of the output beam (p) */
+  double*  out_logp_draft;     /* [n_prompts,W_cap] ... under q                                      */
+  int32_t* near_tie_count;     /* [n_prompts] accept tests with |ratio - u| <= 1e-6                  */
+} dsbd_verify_out;
+
+size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, const dsbd_params* params);
+
+/*
+ * Layer-wise verification of the draft forest (Algorithm 1; Section 3.1 "Details"; Section 3.2):
+ * per-node vocabulary softmax of both models, beam-sampling joints p_beam / q_beam over the
+ * layer's input beams, sequential accept test r <= p'/q_beam with the residual update
+ * p' <- norm(max(0, p' - q_beam)) on rejection and p' <- p_beam on acceptance, early stop at
+ * W_L^(l) accepted beams, residual + p_beam sampling when a layer falls short, and the bonus
+ * layer when every layer passes.  Decisions are taken in fp64.
+ */
+int32_t dsbd_verify_forest(const dsbd_forest* forest, const dsbd_verify_in* in, const dsbd_params* params,
+                           const dsbd_verify_out* out,
+                           void* workspace, size_t workspace_bytes, int32_t* fault, void* stream);
+
+/* Next beam set. */
+typedef struct dsbd_next_beams {
+  int32_t* n_next;      /* [n_prompts]                                                               */
+  int32_t* src_tree;    /* [n_prompts,W_cap] tree (input beam) whose cache the new beam continues     */
+  int32_t* src_out;     /* [n_prompts,W_cap] index of the verification output beam it came from       */
+  int32_t* path_len;    /* [n_prompts,W_cap] number of forest nodes on the path root..out_parent      */
+  int32_t* path;        /* [n_prompts,W_cap,Lmax+1] those nodes, root first (tree rows to append to   */
+                        /*   the cache); unused entries -1                                            */
+  int32_t* token;       /* [n_prompts,W_cap] last token of the new beam                               */
+  double*  logp_target; /* [n_prompts,W_cap]                                                          */
+  double*  logp_draft;  /* [n_prompts,W_cap]                                                          */
+} dsbd_next_beams;
+
+/*
+ * Select the beams of the next iteration from the verification outputs (Algorithm 1 returns the
+ * beams of layer l_last; Section 3.3: the caches kept are those the output beams descend from).
+ * keep_one != 0: keep only the output beam with the highest cumulative target log-likelihood
+ * (lowest perplexity; ties to the lowest index), so a single cache survives (Section 3.4).
+ * W_cap and Lmax must be the values used for dsbd_verify_forest.
+ */
+int32_t dsbd_select_beams(const dsbd_forest* forest, const dsbd_verify_out* verified, int32_t W_cap,
+                          int32_t keep_one, const dsbd_next_beams* next, int32_t* fault, void* stream);
+
+/* Library version and the offload architecture it was built for. */
+const char* dsbd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSBD_H */

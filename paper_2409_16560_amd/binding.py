@@ -1,0 +1,314 @@
+"""ctypes binding of libdsbd.so: argument marshalling only.
+
+The structures mirror include/dsbd.h field by field.  Tensors are torch CUDA(HIP) tensors; their
+data pointers and the current stream's handle are passed through unchanged.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+DSBD_NOT_REACHED, DSBD_ACCEPTED, DSBD_REJECTED, DSBD_PRUNED, DSBD_ROOT = 0, 1, 2, 3, 4
+DSBD_FAULT_TOPOLOGY, DSBD_FAULT_TOKEN, DSBD_FAULT_NONFINITE = 1, 2, 4
+DSBD_FAULT_ZERO_RESIDUAL, DSBD_FAULT_BOUNDS, DSBD_FAULT_SYNC_TIMEOUT = 8, 16, 32
+
+_ERRORS = {-1: "invalid argument", -2: "unsupported shape", -3: "workspace too small", -4: "HIP runtime error"}
+
+
+class DsbdError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__("%s failed: %s (%d)" % (where, _ERRORS.get(code, "unknown"), code))
+        self.code = code
+
+
+class _Forest(C.Structure):
+    _fields_ = [("n_prompts", C.c_int32), ("n_trees", C.c_int32), ("n_nodes", C.c_int32),
+                ("tree_prompt", C.c_void_p), ("tree_off", C.c_void_p), ("parent", C.c_void_p),
+                ("token", C.c_void_p), ("draft_rank", C.c_void_p),
+                ("max_tree_nodes", C.c_int32), ("max_depth", C.c_int32), ("max_prompt_trees", C.c_int32)]
+
+
+class _KV(C.Structure):
+    _fields_ = [("k_ptr", C.c_void_p), ("v_ptr", C.c_void_p), ("len", C.c_void_p),
+                ("k_shared_ptr", C.c_void_p), ("v_shared_ptr", C.c_void_p), ("shared_len", C.c_void_p),
+                ("token_stride", C.c_int64), ("head_stride", C.c_int64), ("max_len", C.c_int32)]
+
+
+class _Params(C.Structure):
+    _fields_ = [("W_L", C.c_int32), ("W_min", C.c_int32), ("W_cap", C.c_int32), ("t", C.c_float)]
+
+
+class _VerifyIn(C.Structure):
+    _fields_ = [("V", C.c_int32), ("logits_target", C.c_void_p), ("logits_draft", C.c_void_p),
+                ("beam_logp_target", C.c_void_p), ("beam_logp_draft", C.c_void_p),
+                ("u_accept", C.c_void_p), ("u_resid", C.c_void_p), ("u_fill", C.c_void_p)]
+
+
+class _VerifyOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "node_status", "lse_target", "lse_draft", "node_logp_target", "node_logp_draft", "l_last", "layer_width",
+        "n_out", "out_parent", "out_token", "out_node", "out_logp_target", "out_logp_draft", "near_tie_count")]
+
+
+class _NextBeams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "n_next", "src_tree", "src_out", "path_len", "path", "token", "logp_target", "logp_draft")]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libdsbd.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libdsbd.so; raises ImportError if it has not been built. There is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError("libdsbd.so not found at %s: build it with `python -m paper_2409_16560_amd.build`" % path)
+    lib = C.CDLL(path)
+    lib.dsbd_forest_attention_workspace_bytes.restype = C.c_size_t
+    lib.dsbd_forest_attention_workspace_bytes.argtypes = [C.POINTER(_Forest), C.POINTER(_KV), C.c_int32, C.c_int32, C.c_int32]
+    lib.dsbd_forest_attention.restype = C.c_int32
+    lib.dsbd_forest_attention.argtypes = [C.POINTER(_Forest), C.POINTER(_KV), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.dsbd_verify_forest_workspace_bytes.restype = C.c_size_t
+    lib.dsbd_verify_forest_workspace_bytes.argtypes = [C.POINTER(_Forest), C.c_int32, C.POINTER(_Params)]
+    lib.dsbd_verify_forest.restype = C.c_int32
+    lib.dsbd_verify_forest.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyIn), C.POINTER(_Params),
+                                       C.POINTER(_VerifyOut), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.dsbd_select_beams.restype = C.c_int32
+    lib.dsbd_select_beams.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyOut), C.c_int32, C.c_int32,
+                                      C.POINTER(_NextBeams), C.c_void_p, C.c_void_p]
+    lib.dsbd_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def dsbd_version():
+    return load_library().dsbd_version().decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _i32(t, dev):
+    return torch.as_tensor(t, dtype=torch.int32).to(dev).contiguous()
+
+
+class Forest:
+    """Draft forest on the device plus the host-side bounds the library wants."""
+
+    def __init__(self, tree_prompt, tree_off, parent, token=None, draft_rank=None, *, n_prompts, max_tree_nodes,
+                 max_depth, max_prompt_trees, device="cuda"):
+        self.tree_prompt = _i32(tree_prompt, device)
+        self.tree_off = _i32(tree_off, device)
+        self.parent = _i32(parent, device)
+        self.token = None if token is None else _i32(token, device)
+        self.draft_rank = None if draft_rank is None else _i32(draft_rank, device)
+        self.n_prompts = int(n_prompts)
+        self.n_trees = int(self.tree_prompt.numel())
+        self.n_nodes = int(self.parent.numel())
+        self.max_tree_nodes, self.max_depth, self.max_prompt_trees = int(max_tree_nodes), int(max_depth), int(max_prompt_trees)
+        self.device = self.parent.device
+
+    def c_struct(self):
+        return _Forest(self.n_prompts, self.n_trees, self.n_nodes, _ptr(self.tree_prompt), _ptr(self.tree_off),
+                       _ptr(self.parent), _ptr(self.token), _ptr(self.draft_rank),
+                       self.max_tree_nodes, self.max_depth, self.max_prompt_trees)
+
+
+class PrefixKV:
+    """Per-beam prefix caches: lists of bf16 tensors [L_b, Hkv, D] (token-major) or [Hkv, L_b, D] (head-major).
+    k_shared / v_shared: optional per-tree tensors for the shared leading segment (the same tensor object for
+    the beams of one prompt)."""
+
+    def __init__(self, k: List[torch.Tensor], v: List[torch.Tensor], k_shared=None, v_shared=None,
+                 head_major=False):
+        dev = k[0].device
+        self.keep = (k, v, k_shared, v_shared)
+        ref = next((t for t in k if t.numel() > 0), k[0])
+        if head_major:
+            self.token_stride, self.head_stride = ref.stride(1), ref.stride(0)
+            lens = [t.shape[1] for t in k]
+        else:
+            self.token_stride, self.head_stride = ref.stride(0), ref.stride(1)
+            lens = [t.shape[0] for t in k]
+        for t in list(k) + list(v):
+            assert t.dtype == torch.bfloat16 and t.stride(-1) == 1
+        self.k_ptr = torch.tensor([t.data_ptr() for t in k], dtype=torch.int64, device=dev)
+        self.v_ptr = torch.tensor([t.data_ptr() for t in v], dtype=torch.int64, device=dev)
+        self.len = torch.tensor(lens, dtype=torch.int32, device=dev)
+        self.max_len = max(lens) if lens else 0
+        self.k_shared_ptr = self.v_shared_ptr = self.shared_len = None
+        if k_shared is not None:
+            ax = 1 if head_major else 0
+            sl = [0 if t is None else t.shape[ax] for t in k_shared]
+            self.k_shared_ptr = torch.tensor([0 if t is None else t.data_ptr() for t in k_shared], dtype=torch.int64, device=dev)
+            self.v_shared_ptr = torch.tensor([0 if t is None else t.data_ptr() for t in v_shared], dtype=torch.int64, device=dev)
+            self.shared_len = torch.tensor(sl, dtype=torch.int32, device=dev)
+            self.max_len = max(a + b for a, b in zip(lens, sl))
+
+    def c_struct(self):
+        return _KV(_ptr(self.k_ptr), _ptr(self.v_ptr), _ptr(self.len), _ptr(self.k_shared_ptr),
+                   _ptr(self.v_shared_ptr), _ptr(self.shared_len), self.token_stride, self.head_stride, self.max_len)
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise DsbdError(rc, where)
+
+
+def dsbd_forest_attention_workspace_bytes(forest: Forest, kv: PrefixKV, Hq, Hkv, D):
+    f, k = forest.c_struct(), kv.c_struct()
+    return int(load_library().dsbd_forest_attention_workspace_bytes(C.byref(f), C.byref(k), Hq, Hkv, D))
+
+
+def dsbd_forest_attention(forest: Forest, kv: PrefixKV, q, k_tree, v_tree, scale=0.0, out=None, lse=None,
+                          anc_mask_out=None, workspace=None, fault=None, stream=None, want_lse=True):
+    """q [N,Hq,D], k_tree/v_tree [N,Hkv,D] bf16.  Returns (out bf16 [N,Hq,D], lse f32 [N,Hq], fault i32[1])."""
+    lib = load_library()
+    N, Hq, D = q.shape
+    Hkv = k_tree.shape[1]
+    dev = q.device
+    f, k = forest.c_struct(), kv.c_struct()
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((N, Hq), dtype=torch.float32, device=dev)
+    if fault is None:
+        fault = torch.zeros(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        nbytes = int(lib.dsbd_forest_attention_workspace_bytes(C.byref(f), C.byref(k), Hq, Hkv, D))
+        if nbytes == 0 and N > 0:
+            raise DsbdError(-2, "dsbd_forest_attention_workspace_bytes")
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    rc = lib.dsbd_forest_attention(C.byref(f), C.byref(k), _ptr(q), _ptr(k_tree), _ptr(v_tree), Hq, Hkv, D,
+                                   float(scale), _ptr(out), _ptr(lse), _ptr(anc_mask_out), _ptr(workspace),
+                                   workspace.numel(), _ptr(fault), _stream(stream))
+    _check(rc, "dsbd_forest_attention")
+    return out, lse, fault
+
+
+@dataclass
+class VerifyResult:
+    node_status: torch.Tensor
+    lse_target: torch.Tensor
+    lse_draft: torch.Tensor
+    node_logp_target: torch.Tensor
+    node_logp_draft: torch.Tensor
+    l_last: torch.Tensor
+    layer_width: torch.Tensor
+    n_out: torch.Tensor
+    out_parent: torch.Tensor
+    out_token: torch.Tensor
+    out_node: torch.Tensor
+    out_logp_target: torch.Tensor
+    out_logp_draft: torch.Tensor
+    near_tie_count: torch.Tensor
+    fault: torch.Tensor
+    W_cap: int = 0
+
+    def c_struct(self):
+        return _VerifyOut(*[_ptr(getattr(self, n)) for n, _ in _VerifyOut._fields_])
+
+    @staticmethod
+    def allocate(forest: Forest, W_cap: int):
+        dev, N, P, Lw = forest.device, forest.n_nodes, forest.n_prompts, forest.max_depth + 2
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        return VerifyResult(
+            e((N,), torch.uint8), e((N,), torch.float32), e((N,), torch.float32), e((N,), torch.float32),
+            e((N,), torch.float32), e((P,), torch.int32), e((P, Lw), torch.int32), e((P,), torch.int32),
+            e((P, W_cap), torch.int32), e((P, W_cap), torch.int32), e((P, W_cap), torch.int32),
+            e((P, W_cap), torch.float64), e((P, W_cap), torch.float64), e((P,), torch.int32),
+            torch.zeros(1, dtype=torch.int32, device=dev), W_cap)
+
+
+def _params(W_L, W_min, W_cap, t):
+    return _Params(int(W_L), int(W_min), int(W_cap), float(t))
+
+
+def dsbd_verify_forest_workspace_bytes(forest: Forest, V, W_L=0, W_min=1, W_cap=16, t=-1.0):
+    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t)
+    return int(load_library().dsbd_verify_forest_workspace_bytes(C.byref(f), int(V), C.byref(p)))
+
+
+def dsbd_verify_forest(forest: Forest, logits_target, logits_draft, beam_logp_target, beam_logp_draft,
+                       u_accept, u_resid, u_fill, W_L=0, W_min=1, W_cap=16, t=-1.0, result: VerifyResult = None,
+                       workspace=None, stream=None):
+    """Layer-wise verification; logits [N,V] f32, beam_logp [T] f64, uniforms f32.  Returns VerifyResult."""
+    lib = load_library()
+    N, V = logits_target.shape
+    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t)
+    for t_, dt in ((logits_target, torch.float32), (logits_draft, torch.float32), (beam_logp_target, torch.float64),
+                   (beam_logp_draft, torch.float64), (u_accept, torch.float32), (u_resid, torch.float32),
+                   (u_fill, torch.float32)):
+        assert t_.dtype == dt and t_.is_contiguous()
+    assert u_resid.numel() == forest.n_prompts * (forest.max_depth + 2)
+    assert u_fill.numel() == forest.n_prompts * (forest.max_depth + 2) * W_cap
+    vin = _VerifyIn(int(V), _ptr(logits_target), _ptr(logits_draft), _ptr(beam_logp_target), _ptr(beam_logp_draft),
+                    _ptr(u_accept), _ptr(u_resid), _ptr(u_fill))
+    if result is None:
+        result = VerifyResult.allocate(forest, W_cap)
+    if workspace is None:
+        nbytes = int(lib.dsbd_verify_forest_workspace_bytes(C.byref(f), int(V), C.byref(p)))
+        if nbytes == 0 and N > 0:
+            raise DsbdError(-2, "dsbd_verify_forest_workspace_bytes")
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=logits_target.device)
+    vout = result.c_struct()
+    rc = lib.dsbd_verify_forest(C.byref(f), C.byref(vin), C.byref(p), C.byref(vout), _ptr(workspace),
+                                workspace.numel(), _ptr(result.fault), _stream(stream))
+    _check(rc, "dsbd_verify_forest")
+    return result
+
+
+@dataclass
+class NextBeams:
+    n_next: torch.Tensor
+    src_tree: torch.Tensor
+    src_out: torch.Tensor
+    path_len: torch.Tensor
+    path: torch.Tensor
+    token: torch.Tensor
+    logp_target: torch.Tensor
+    logp_draft: torch.Tensor
+    fault: torch.Tensor
+
+    def c_struct(self):
+        return _NextBeams(*[_ptr(getattr(self, n)) for n, _ in _NextBeams._fields_])
+
+    @staticmethod
+    def allocate(forest: Forest, W_cap: int):
+        dev, P, plen = forest.device, forest.n_prompts, forest.max_depth + 1
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        return NextBeams(e((P,), torch.int32), e((P, W_cap), torch.int32), e((P, W_cap), torch.int32),
+                         e((P, W_cap), torch.int32), e((P, W_cap, plen), torch.int32), e((P, W_cap), torch.int32),
+                         e((P, W_cap), torch.float64), e((P, W_cap), torch.float64),
+                         torch.zeros(1, dtype=torch.int32, device=dev))
+
+
+def dsbd_select_beams(forest: Forest, verified: VerifyResult, keep_one=False, result: NextBeams = None, stream=None):
+    lib = load_library()
+    f, v = forest.c_struct(), verified.c_struct()
+    if result is None:
+        result = NextBeams.allocate(forest, verified.W_cap)
+    nx = result.c_struct()
+    rc = lib.dsbd_select_beams(C.byref(f), C.byref(v), int(verified.W_cap), int(bool(keep_one)), C.byref(nx),
+                               _ptr(result.fault), _stream(stream))
+    _check(rc, "dsbd_select_beams")
+    return result

@@ -1,0 +1,513 @@
+// Forest attention for gfx950 (paper Section 3.3, "Forest-based Parallel Decoding").
+//
+// Every node of tree b attends to beam b's prefix cache plus the tree rows of its ancestors and
+// itself.  All nodes of a tree (times the query heads of one KV group) share one pass over the
+// beam's K/V stream, which is what makes the step bandwidth-bound instead of re-reading the cache
+// once per node.
+//
+// Work decomposition (split-KV): one workgroup per (tree, KV head, row block, KV split).  Inside a
+// workgroup the 4 waves form RW row groups x TW token groups.  Every wave streams its own 32-token
+// steps of K and V straight from HBM into registers (no block-level barrier in the main loop) and
+// keeps 16*NRT query rows resident:
+//   S^T = K Q^T   MFMA 16x16x32 bf16, A = K (tokens x d) from global in operand layout,
+//                 B = Q^T held in registers for the whole kernel;
+//   online softmax per query row, entirely lane-local: in the transposed product every lane owns
+//                 one query row (column l%16), its scores and its slice of the output accumulators;
+//   O^T += V^T P^T  MFMA 16x16x32, B = P^T built in registers from the S^T tile, A = V^T read from a
+//                 wave-private LDS tile into which V was written transposed (token pairs packed).
+// The ancestor mask never exists in memory: each lane keeps the 64-bit ancestor bitmap of its row's
+// node and tests bits while handling the (at most two) steps that cover the tree's own rows.
+// Partial (m, l, O) of the KV splits go to the workspace; a second kernel merges them.
+#include "common.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+
+#define NEG_BIG (-1.0e30f)
+#define STEP 32                 // tokens per wave step (two 16-token MFMA tiles)
+#define VT_PITCH 36             // bf16 elements per row of the transposed V tile (32 + pad, multiple of 4)
+
+struct AttnArgs {
+  const int32_t* tree_off;
+  const uint64_t* anc_mask;
+  const void* const* k_ptr;
+  const void* const* v_ptr;
+  const int32_t* len;
+  const void* const* k_shared_ptr;
+  const void* const* v_shared_ptr;
+  const int32_t* shared_len;
+  long long token_stride, head_stride;
+  const __bf16* q;
+  const __bf16* k_tree;
+  const __bf16* v_tree;
+  int n_nodes, Hq, Hkv, group;
+  float scale_log2;             // scale * log2(e): scores are kept in the log2 domain
+  int nsplit, n_rowblocks, max_len;
+  float* part_o;                // [nsplit][n_nodes*Hq][D]
+  float* part_ml;               // [nsplit][n_nodes*Hq][2]
+  int32_t* fault;
+};
+
+__device__ __forceinline__ void wave_lds_fence() {
+  // orders this wave's LDS writes before its later LDS reads (other lanes' data); LDS executes a
+  // wave's operations in order, so only the compiler needs to be held back
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int D, int NRT, int RW, int TW>
+__global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
+  static_assert(RW * TW == 4, "four waves per workgroup");
+  constexpr int DS = D / 32;        // MFMA k-steps over the head dimension for S^T
+  constexpr int DT = D / 16;        // 16-row output tiles over the head dimension for O^T
+  constexpr int ROWS_W = 16 * NRT;  // query rows per wave
+  constexpr int ROWS_B = ROWS_W * RW;
+  constexpr int LPR = D / 8;        // lanes covering one V row with 16-byte loads
+  constexpr int TG = 64 / LPR;      // token groups among the lanes for V loads
+  constexpr int VROUNDS = STEP / (2 * TG);
+
+  __shared__ __attribute__((aligned(16))) __bf16 vt_lds[4][D * VT_PITCH];
+  __shared__ __attribute__((aligned(16))) float comb_o[(TW - 1) * RW][ROWS_W][D + 4];
+  __shared__ float comb_ml[(TW - 1) * RW][ROWS_W][2];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int rw = wave % RW;
+  const int tw = wave / RW;
+  const int col = lane & 15;        // query row within a 16-row tile / token within a 16-token tile
+  const int qd = lane >> 4;         // lane group 0..3
+
+  int bid = blockIdx.x;
+  const int split = bid % a.nsplit; bid /= a.nsplit;
+  const int rb = bid % a.n_rowblocks; bid /= a.n_rowblocks;
+  const int g = bid % a.Hkv;
+  const int b = bid / a.Hkv;
+
+  const int base = a.tree_off[b];
+  int n_b = a.tree_off[b + 1] - base;
+  if (base < 0 || n_b <= 0 || base + n_b > a.n_nodes) return;   // reported by the topology kernel
+  n_b = min(n_b, DSBD_MAX_TREE_NODES);
+  const int R = n_b * a.group;       // query rows of this (tree, KV head)
+  const int row0 = rb * ROWS_B + rw * ROWS_W;
+  const int n_rows_total = a.n_nodes * a.Hq;
+
+  // ---- segments of the key sequence: shared prefix, own prefix, the tree's own rows
+  int Ls = (a.shared_len && a.k_shared_ptr) ? a.shared_len[b] : 0;
+  int Lo = a.len[b];
+  Ls = max(Ls, 0); Lo = max(Lo, 0);
+  int bad = 0;
+  if ((long long)Ls + Lo > a.max_len) { bad |= DSBD_FAULT_BOUNDS; Ls = min(Ls, a.max_len); Lo = min(Lo, a.max_len - Ls); }
+  const long long hoff = (long long)g * a.head_stride;
+  const __bf16* k0 = Ls ? (const __bf16*)a.k_shared_ptr[b] : nullptr;
+  const __bf16* v0 = Ls ? (const __bf16*)a.v_shared_ptr[b] : nullptr;
+  const __bf16* k1 = Lo ? (const __bf16*)a.k_ptr[b] : nullptr;
+  const __bf16* v1 = Lo ? (const __bf16*)a.v_ptr[b] : nullptr;
+  if (Ls && (!k0 || !v0 || (((uintptr_t)k0 | (uintptr_t)v0) & 15))) { bad |= DSBD_FAULT_BOUNDS; Ls = 0; }
+  if (Lo && (!k1 || !v1 || (((uintptr_t)k1 | (uintptr_t)v1) & 15))) { bad |= DSBD_FAULT_BOUNDS; Lo = 0; }
+  if (bad && threadIdx.x == 0) atomicOr(a.fault, bad);   // missing or misaligned cache pointer: segment skipped
+  k0 += hoff; v0 += hoff; k1 += hoff; v1 += hoff;
+  const __bf16* k2 = a.k_tree + ((long long)base * a.Hkv + g) * D;
+  const __bf16* v2 = a.v_tree + ((long long)base * a.Hkv + g) * D;
+  const long long stride2 = (long long)a.Hkv * D;
+  const int n0 = (Ls + STEP - 1) / STEP;
+  const int n1 = (Lo + STEP - 1) / STEP;
+  const int n2 = (n_b + STEP - 1) / STEP;
+  const int total_steps = n0 + n1 + n2;
+  const int per_split = (total_steps + a.nsplit - 1) / a.nsplit;
+  const int st_begin = split * per_split;
+  const int st_end = min(total_steps, st_begin + per_split);
+
+  // ---- resident query fragments (B operand: lane holds row `col`, 8 channels 32j + 8qd ..)
+  bf16x8 qf[NRT][DS];
+  uint64_t anc[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int r = row0 + rt * 16 + col;
+    const bool live = r < R;
+    const int node = live ? r / a.group : 0;
+    const int head = g * a.group + (live ? r % a.group : 0);
+    anc[rt] = live ? a.anc_mask[base + node] : 0ull;
+    const __bf16* qp = a.q + ((long long)(base + node) * a.Hq + head) * D + 8 * qd;
+#pragma unroll
+    for (int j = 0; j < DS; ++j) {
+      if (live) {
+        qf[rt][j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[rt][j][e] = (__bf16)0.0f;
+      }
+    }
+  }
+
+  floatx4 o[NRT][DT];
+  float m_run[NRT], l_run[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    m_run[rt] = NEG_BIG;
+    l_run[rt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[rt][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  __bf16* vt = vt_lds[wave];
+  const int v_dl = lane % LPR;       // 16-byte column of the V row this lane loads
+  const int v_tg = lane / LPR;       // token group
+
+  // a row block beyond the tree's rows has nothing to do (uniform over the workgroup)
+  const bool block_live = rb * ROWS_B < R;
+
+  bf16x8 kf[2][DS];
+  bf16x8 vr[VROUNDS][2];
+
+  // step -> (segment, first token, tokens in the segment)
+  auto locate = [&](int st, const __bf16*& kp, const __bf16*& vp, long long& stride, int& tok0, int& len, bool& tree) {
+    if (st < n0) { kp = k0; vp = v0; stride = a.token_stride; tok0 = st * STEP; len = Ls; tree = false; }
+    else if (st < n0 + n1) { kp = k1; vp = v1; stride = a.token_stride; tok0 = (st - n0) * STEP; len = Lo; tree = false; }
+    else { kp = k2; vp = v2; stride = stride2; tok0 = (st - n0 - n1) * STEP; len = n_b; tree = true; }
+  };
+  auto load_k = [&](int st) {
+    const __bf16 *kp, *vp; long long stride; int tok0, len; bool tree;
+    locate(st, kp, vp, stride, tok0, len, tree);
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tok = min(tok0 + 16 * tt + col, len - 1);
+      const __bf16* p = kp + (long long)tok * stride + 8 * qd;
+#pragma unroll
+      for (int j = 0; j < DS; ++j) kf[tt][j] = *reinterpret_cast<const bf16x8*>(p + 32 * j);
+    }
+  };
+  auto load_v = [&](int st) {
+    const __bf16 *kp, *vp; long long stride; int tok0, len; bool tree;
+    locate(st, kp, vp, stride, tok0, len, tree);
+#pragma unroll
+    for (int k = 0; k < VROUNDS; ++k) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int tok = min(tok0 + 2 * TG * k + 2 * v_tg + h, len - 1);
+        vr[k][h] = *reinterpret_cast<const bf16x8*>(vp + (long long)tok * stride + 8 * v_dl);
+      }
+    }
+  };
+
+  int st = st_begin + tw;
+  const bool active = block_live && st < st_end;
+  if (active) { load_k(st); load_v(st); }
+
+  while (active && st < st_end) {
+    const __bf16 *kp_, *vp_; long long stride_; int tok0, seglen; bool is_tree;
+    locate(st, kp_, vp_, stride_, tok0, seglen, is_tree);
+    const int nvalid = min(STEP, seglen - tok0);
+    const int st_next = st + TW;
+
+    // ---- V -> LDS, transposed, two tokens packed per 32-bit write; then its registers are free
+    wave_lds_fence();
+#pragma unroll
+    for (int k = 0; k < VROUNDS; ++k) {
+      const int tokp = 2 * TG * k + 2 * v_tg;          // even token index within the step
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        union { __bf16 h[2]; uint32_t u; } pk;
+        pk.h[0] = vr[k][0][e];
+        pk.h[1] = vr[k][1][e];
+        *reinterpret_cast<uint32_t*>(&vt[(8 * v_dl + e) * VT_PITCH + tokp]) = pk.u;
+      }
+    }
+    wave_lds_fence();
+    if (st_next < st_end) load_v(st_next);
+
+    // ---- S^T tiles: tokens x query rows
+    floatx4 s[NRT][2];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < DS; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][j], qf[rt][j], acc, 0, 0, 0);
+        s[rt][tt] = acc;
+      }
+    if (st_next < st_end) load_k(st_next);
+
+    // ---- online softmax, lane-local per query row; P^T becomes the next B operand
+    const bool need_mask = is_tree || nvalid < STEP;
+    bf16x8 pf[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float sv[8];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[4 * tt + i] = s[rt][tt][i] * a.scale_log2;
+      unsigned okbits = 0xffu;
+      if (need_mask) {
+        okbits = 0;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int t = 16 * tt + 4 * qd + i;          // token within the step
+            bool valid = t < nvalid;
+            if (is_tree) valid = valid && ((anc[rt] >> (tok0 + t)) & 1ull);
+            if (valid) okbits |= 1u << (4 * tt + i); else sv[4 * tt + i] = NEG_BIG;
+          }
+      }
+      float mx = sv[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[rt], mx);
+      const float alpha = exp2f(m_run[rt] - m_new);
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p = ((okbits >> e) & 1u) ? exp2f(sv[e] - m_new) : 0.f;
+        psum += p;
+        pf[rt][e] = (__bf16)p;
+      }
+      l_run[rt] = l_run[rt] * alpha + psum;
+      m_run[rt] = m_new;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      union { uint2 u[2]; bf16x8 v; } vf;
+      const __bf16* rowp = &vt[(16 * dt + col) * VT_PITCH];
+      vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 4 * qd);
+      vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * qd);
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);
+    }
+    st = st_next;
+  }
+
+  // ---- finish the row sums (each lane group summed its own tokens)
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    l_run[rt] += __shfl_xor(l_run[rt], 16);
+    l_run[rt] += __shfl_xor(l_run[rt], 32);
+  }
+
+  // ---- merge the token groups of the workgroup through LDS
+  if (TW > 1) {
+    if (tw > 0) {
+      const int slot = (tw - 1) * RW + rw;
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        const int rloc = rt * 16 + col;
+        if (qd == 0) { comb_ml[slot][rloc][0] = m_run[rt]; comb_ml[slot][rloc][1] = l_run[rt]; }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          *reinterpret_cast<floatx4*>(&comb_o[slot][rloc][16 * dt + 4 * qd]) = o[rt][dt];
+      }
+    }
+    __syncthreads();
+    if (tw == 0) {
+      for (int t2 = 1; t2 < TW; ++t2) {
+        const int slot = (t2 - 1) * RW + rw;
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          const int rloc = rt * 16 + col;
+          const float m2 = comb_ml[slot][rloc][0], l2 = comb_ml[slot][rloc][1];
+          const float m_new = fmaxf(m_run[rt], m2);
+          const float a1 = exp2f(m_run[rt] - m_new), a2 = exp2f(m2 - m_new);
+          l_run[rt] = l_run[rt] * a1 + l2 * a2;
+          m_run[rt] = m_new;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const floatx4 o2 = *reinterpret_cast<const floatx4*>(&comb_o[slot][rloc][16 * dt + 4 * qd]);
+            o[rt][dt] = o[rt][dt] * a1 + o2 * a2;
+          }
+        }
+      }
+    }
+  }
+
+  // ---- partial results of this split
+  if (tw == 0) {
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      const int r = row0 + rt * 16 + col;
+      if (r < R) {
+        const int node = r / a.group;
+        const int head = g * a.group + r % a.group;
+        const long long grow = (long long)(base + node) * a.Hq + head;
+        const long long prow = (long long)split * n_rows_total + grow;
+        if (qd == 0) { a.part_ml[prow * 2] = m_run[rt]; a.part_ml[prow * 2 + 1] = l_run[rt]; }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          *reinterpret_cast<floatx4*>(&a.part_o[prow * D + 16 * dt + 4 * qd]) = o[rt][dt];
+      }
+    }
+  }
+}
+
+// Merge the KV splits of every (node, head) row: out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.
+template <int D>
+__global__ __launch_bounds__(256) void forest_attention_combine_kernel(int n_rows_total, int nsplit,
+                                                                       const float* __restrict__ part_o,
+                                                                       const float* __restrict__ part_ml,
+                                                                       __bf16* __restrict__ out, float* __restrict__ lse) {
+  constexpr int QPR = D / 4;                 // float4 quads per row
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long row = gid / QPR;
+  const int quad = (int)(gid % QPR);
+  if (row >= n_rows_total) return;
+  float M = NEG_BIG;
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[((long long)s * n_rows_total + row) * 2]);
+  float L = 0.f;
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < nsplit; ++s) {
+    const long long prow = (long long)s * n_rows_total + row;
+    const float w = exp2f(part_ml[prow * 2] - M);
+    L += w * part_ml[prow * 2 + 1];
+    acc += w * *reinterpret_cast<const floatx4*>(&part_o[prow * D + 4 * quad]);
+  }
+  const float inv = L > 0.f ? 1.f / L : 0.f;
+  union { __bf16 h[4]; uint2 u; } pk;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pk.h[i] = (__bf16)(acc[i] * inv);
+  *reinterpret_cast<uint2*>(&out[row * D + 4 * quad]) = pk.u;
+  if (lse && quad == 0) lse[row] = (M + log2f(L)) * 0.6931471805599453f;
+}
+
+// ------------------------------------------------------------------------------------------------ host side
+namespace {
+
+struct AttnPlan {
+  int nrt, rw, tw, rows_block, n_rowblocks, nsplit;
+};
+
+AttnPlan make_plan(const dsbd_forest* f, const dsbd_kv* kv, int Hq, int Hkv) {
+  AttnPlan p;
+  const int group = Hq / Hkv;
+  const int rmax = f->max_tree_nodes * group;
+  if (rmax <= 16) { p.nrt = 1; p.rw = 1; p.tw = 4; }
+  else if (rmax <= 32) { p.nrt = 2; p.rw = 1; p.tw = 4; }
+  else if (rmax <= 64) { p.nrt = 2; p.rw = 2; p.tw = 2; }
+  else { p.nrt = 4; p.rw = 2; p.tw = 2; }
+  p.rows_block = 16 * p.nrt * p.rw;
+  p.n_rowblocks = (rmax + p.rows_block - 1) / p.rows_block;
+  // enough workgroups to cover the chip several times, but at least two steps per wave and split
+  const long long units = (long long)f->n_trees * Hkv * p.n_rowblocks;
+  const int steps = (kv->max_len + STEP - 1) / STEP + 2;
+  int by_steps = steps / (2 * p.tw);
+  if (by_steps < 1) by_steps = 1;
+  int want = (int)((1024 + units - 1) / units);
+  if (want < 1) want = 1;
+  // the split partials (rows x D fp32, written and read once) should stay a small fraction of the K/V bytes
+  int by_traffic = kv->max_len / (8 * rmax);
+  if (by_traffic < 1) by_traffic = 1;
+  p.nsplit = want < by_steps ? want : by_steps;
+  if (p.nsplit > by_traffic) p.nsplit = by_traffic;
+  if (p.nsplit > 64) p.nsplit = 64;
+  return p;
+}
+
+int32_t check_args(const dsbd_forest* f, const dsbd_kv* kv, int Hq, int Hkv, int D) {
+  if (!f || !kv) return DSBD_ERR_INVALID;
+  if (f->n_trees < 0 || f->n_nodes < 0 || f->n_prompts < 0) return DSBD_ERR_INVALID;
+  if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return DSBD_ERR_INVALID;
+  if (D != 128 && D != 64) return DSBD_ERR_UNSUPPORTED;
+  if (f->max_tree_nodes < 1 || f->max_tree_nodes > DSBD_MAX_TREE_NODES) return DSBD_ERR_UNSUPPORTED;
+  if (kv->max_len < 0) return DSBD_ERR_INVALID;
+  if (kv->token_stride % 8 != 0 || kv->head_stride % 8 != 0) return DSBD_ERR_UNSUPPORTED;
+  return DSBD_OK;
+}
+
+int32_t check_pointers(const dsbd_forest* f, const dsbd_kv* kv) {
+  if (f->n_trees > 0 && (!f->tree_off || !f->parent || !kv->k_ptr || !kv->v_ptr || !kv->len)) return DSBD_ERR_INVALID;
+  if ((kv->shared_len != nullptr) != (kv->k_shared_ptr != nullptr) ||
+      (kv->shared_len != nullptr) != (kv->v_shared_ptr != nullptr)) return DSBD_ERR_INVALID;
+  return DSBD_OK;
+}
+
+template <int D, int NRT, int RW, int TW>
+void launch_attn(const AttnArgs& a, int grid, hipStream_t stream) {
+  hipLaunchKernelGGL((forest_attention_kernel<D, NRT, RW, TW>), dim3(grid), dim3(256), 0, stream, a);
+}
+
+template <int D>
+void dispatch_attn(const AttnPlan& p, const AttnArgs& a, int grid, hipStream_t stream) {
+  if (p.nrt == 1) launch_attn<D, 1, 1, 4>(a, grid, stream);
+  else if (p.nrt == 2 && p.rw == 1) launch_attn<D, 2, 1, 4>(a, grid, stream);
+  else if (p.nrt == 2) launch_attn<D, 2, 2, 2>(a, grid, stream);
+  else launch_attn<D, 4, 2, 2>(a, grid, stream);
+}
+
+}  // namespace
+
+extern "C" size_t dsbd_forest_attention_workspace_bytes(const dsbd_forest* f, const dsbd_kv* kv, int32_t Hq,
+                                                        int32_t Hkv, int32_t D) {
+  if (check_args(f, kv, Hq, Hkv, D) != DSBD_OK) return 0;
+  const AttnPlan p = make_plan(f, kv, Hq, Hkv);
+  WorkspaceCarver ws(nullptr);
+  ws.take<uint64_t>((size_t)f->n_nodes);
+  ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
+  ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
+  return ws.total() + 256;
+}
+
+extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv, const void* q, const void* k_tree,
+                                         const void* v_tree, int32_t Hq, int32_t Hkv, int32_t D, float scale,
+                                         void* out, float* lse, uint64_t* anc_mask_out, void* workspace,
+                                         size_t workspace_bytes, int32_t* fault, void* stream_) {
+  int32_t rc = check_args(f, kv, Hq, Hkv, D);
+  if (rc != DSBD_OK) return rc;
+  if (!fault) return DSBD_ERR_INVALID;
+  if (f->n_nodes == 0 || f->n_trees == 0) return DSBD_OK;
+  rc = check_pointers(f, kv);
+  if (rc != DSBD_OK) return rc;
+  if (!q || !k_tree || !v_tree || !out || !workspace) return DSBD_ERR_INVALID;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_tree) | reinterpret_cast<uintptr_t>(v_tree) |
+       reinterpret_cast<uintptr_t>(out)) & 15)
+    return DSBD_ERR_INVALID;
+  if (workspace_bytes < dsbd_forest_attention_workspace_bytes(f, kv, Hq, Hkv, D)) return DSBD_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const AttnPlan p = make_plan(f, kv, Hq, Hkv);
+
+  char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
+  WorkspaceCarver ws(wbase);
+  uint64_t* anc = ws.take<uint64_t>((size_t)f->n_nodes);
+  float* part_o = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
+  float* part_ml = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
+  if (anc_mask_out) anc = anc_mask_out;
+
+  rc = dsbd_launch_topology(f, nullptr, anc, fault, stream);
+  if (rc != DSBD_OK) return rc;
+
+  AttnArgs a;
+  a.tree_off = f->tree_off; a.anc_mask = anc;
+  a.k_ptr = kv->k_ptr; a.v_ptr = kv->v_ptr; a.len = kv->len;
+  a.k_shared_ptr = kv->k_shared_ptr; a.v_shared_ptr = kv->v_shared_ptr; a.shared_len = kv->shared_len;
+  a.token_stride = kv->token_stride; a.head_stride = kv->head_stride;
+  a.q = static_cast<const __bf16*>(q); a.k_tree = static_cast<const __bf16*>(k_tree);
+  a.v_tree = static_cast<const __bf16*>(v_tree);
+  a.n_nodes = f->n_nodes; a.Hq = Hq; a.Hkv = Hkv; a.group = Hq / Hkv;
+  const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
+  a.scale_log2 = sc * 1.4426950408889634f;
+  a.nsplit = p.nsplit; a.n_rowblocks = p.n_rowblocks; a.max_len = kv->max_len;
+  a.part_o = part_o; a.part_ml = part_ml; a.fault = fault;
+
+  const long long grid = (long long)f->n_trees * Hkv * p.n_rowblocks * p.nsplit;
+  if (grid > 0x7fffffffLL) return DSBD_ERR_UNSUPPORTED;
+  if (D == 128) dispatch_attn<128>(p, a, (int)grid, stream);
+  else dispatch_attn<64>(p, a, (int)grid, stream);
+  DSBD_HIP_LAUNCH_CHECK();
+
+  const long long n_rows_total = (long long)f->n_nodes * Hq;
+  const long long threads = n_rows_total * (D / 4);
+  const int cgrid = (int)((threads + 255) / 256);
+  if (D == 128)
+    hipLaunchKernelGGL(forest_attention_combine_kernel<128>, dim3(cgrid), dim3(256), 0, stream, (int)n_rows_total,
+                       p.nsplit, part_o, part_ml, static_cast<__bf16*>(out), lse);
+  else
+    hipLaunchKernelGGL(forest_attention_combine_kernel<64>, dim3(cgrid), dim3(256), 0, stream, (int)n_rows_total,
+                       p.nsplit, part_o, part_ml, static_cast<__bf16*>(out), lse);
+  DSBD_HIP_LAUNCH_CHECK();
+  return DSBD_OK;
+}

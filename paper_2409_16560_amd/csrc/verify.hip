@@ -1,0 +1,869 @@
+// Layer-wise verification of a draft forest on gfx950 (paper Section 3.1 "Details", Algorithm 1,
+// and the dynamic layer width of Section 3.2, Eq. 1-6).
+//
+// Three kernels on the caller's stream:
+//
+// 1. vocab_stats_kernel (bandwidth-bound, all nodes, both models): one pass over the fp32 logits with
+//    a per-thread online max / sum-of-exponentials, reduced per row chunk.  This is the O(W |V|)
+//    softmax work of the beam-sampling joint (Section 2.1) done once for every forest node.
+// 2. vocab_stats_finalize_kernel: merges the chunks into the exact row maximum and an fp32
+//    log-sum-exp per node, writes the per-node outputs and clears the synchronisation counters.
+// 3. verify_layers_kernel (latency-bound, persistent, cooperative launch): G workgroups per prompt walk
+//    the layers in order.  Every decision is taken in fp64.  For the layer's input beams I the
+//    workgroups materialise p_beam and q_beam over I x V (their slice each), and every dependent
+//    reduction over I x V is one pass over the slices plus one barrier among the G workgroups.
+//
+// The running residual p' is never stored.  After k consecutive rejections since the last reset
+//     p'_k = max(p_beam - c_k q_beam, 0) / F(c_k),   F(c) = sum max(p_beam - c q_beam, 0),
+//     c_1 = 0, F(c_1) := 1, c_{k+1} = c_k + F(c_k)
+// (induction on p'_{k+1} = norm(max(0, p'_k - q_beam))), so a rejection costs one evaluation of F, the
+// chain {c_k, F(c_k)} depends only on (p_beam, q_beam) and is reused after every acceptance resets p'
+// to p_beam, and the conditional acceptance probabilities of Eq. 3 are alpha_k = 1 - F(c_{k+1})/F(c_k).
+//
+// All G workgroups of a prompt run the same sequential program on the same reduced values (summed in
+// the same order), so their control flow stays identical without any broadcast.
+#include "common.h"
+#include <float.h>
+
+#define VS_BLOCK 256
+#define VL_BLOCK 512
+#define NODE_CAP 512           // nodes of one prompt (all its trees)
+#define NEAR_TIE 1.0e-6
+#define SYNC_LIMIT_TICKS 300000000LL   // 3 s of the 100 MHz wall clock
+
+// ------------------------------------------------------------------------------------------------ kernel 1
+struct StatsArgs {
+  const float* z[2];
+  int n_nodes, V, nchunk, chunk;
+  float2* part;      // [2][n_nodes][nchunk] (max, sum of exp(x - max))
+  int32_t* fault;
+};
+
+__device__ __forceinline__ void online_add4(float& m, float& s, bool& bad, float x0, float x1, float x2, float x3) {
+  const float L2E = 1.4426950408889634f;
+  const float bm = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+  bad |= !(fabsf(x0) <= FLT_MAX) | !(fabsf(x1) <= FLT_MAX) | !(fabsf(x2) <= FLT_MAX) | !(fabsf(x3) <= FLT_MAX);
+  if (bm > m) {
+    s *= exp2f((m - bm) * L2E);
+    m = bm;
+  }
+  s += exp2f((x0 - m) * L2E) + exp2f((x1 - m) * L2E) + exp2f((x2 - m) * L2E) + exp2f((x3 - m) * L2E);
+}
+
+__device__ __forceinline__ void online_add1(float& m, float& s, bool& bad, float x) {
+  const float L2E = 1.4426950408889634f;
+  bad |= !(fabsf(x) <= FLT_MAX);
+  if (x > m) {
+    s *= exp2f((m - x) * L2E);
+    m = x;
+  }
+  s += exp2f((x - m) * L2E);
+}
+
+__device__ __forceinline__ void online_merge(float& m, float& s, float m2, float s2) {
+  const float L2E = 1.4426950408889634f;
+  const float mn = fmaxf(m, m2);
+  if (mn == -INFINITY) { s = 0.f; return; }
+  s = s * exp2f((m - mn) * L2E) + s2 * exp2f((m2 - mn) * L2E);
+  m = mn;
+}
+
+__global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
+  const int c = blockIdx.x, n = blockIdx.y, which = blockIdx.z;
+  const int lo = c * a.chunk;
+  const int hi = min(a.V, lo + a.chunk);
+  const float* row = a.z[which] + (long long)n * a.V;
+  float m = -INFINITY, s = 0.f;
+  bool bad = false;
+  // scalar head up to 16-byte alignment, float4 body, scalar tail
+  const uintptr_t addr = reinterpret_cast<uintptr_t>(row + lo);
+  int head = (int)(((16 - (addr & 15)) & 15) >> 2);
+  head = min(head, hi - lo);
+  const int body4 = (hi - lo - head) >> 2;
+  const int tail0 = lo + head + 4 * body4;
+  if ((int)threadIdx.x < head) online_add1(m, s, bad, row[lo + threadIdx.x]);
+  const float4* r4 = reinterpret_cast<const float4*>(row + lo + head);
+  for (int i = threadIdx.x; i < body4; i += VS_BLOCK) {
+    const float4 x = r4[i];
+    online_add4(m, s, bad, x.x, x.y, x.z, x.w);
+  }
+  if (tail0 + (int)threadIdx.x < hi) online_add1(m, s, bad, row[tail0 + threadIdx.x]);
+
+  // block reduction
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
+    online_merge(m, s, m2, s2);
+  }
+  __shared__ float sm[VS_BLOCK / 64], ss[VS_BLOCK / 64];
+  __shared__ int sbad;
+  if (threadIdx.x == 0) sbad = 0;
+  __syncthreads();
+  if (bad) sbad = 1;
+  if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = m; ss[threadIdx.x >> 6] = s; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float M = sm[0], S = ss[0];
+    for (int w = 1; w < VS_BLOCK / 64; ++w) online_merge(M, S, sm[w], ss[w]);
+    a.part[((long long)which * a.n_nodes + n) * a.nchunk + c] = make_float2(M, S);
+    if (sbad) atomicOr(a.fault, DSBD_FAULT_NONFINITE);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ kernel 2
+struct FinalizeArgs {
+  const float2* part;
+  int n_nodes, nchunk, n_prompts;
+  float* rowmax;      // [2][n_nodes]
+  float* lse32;       // [2][n_nodes]
+  float* out_lse[2];
+  unsigned int* bar;  // [n_prompts]
+};
+
+__global__ void vocab_stats_finalize_kernel(FinalizeArgs a) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < a.n_prompts) a.bar[i] = 0u;
+  if (i >= 2 * a.n_nodes) return;
+  const float2* p = a.part + (long long)i * a.nchunk;
+  float M = p[0].x, S = p[0].y;
+  for (int c = 1; c < a.nchunk; ++c) online_merge(M, S, p[c].x, p[c].y);
+  const float lse = M + logf(S);
+  a.rowmax[i] = M;
+  a.lse32[i] = lse;
+  const int which = i / a.n_nodes, n = i % a.n_nodes;
+  if (a.out_lse[which]) a.out_lse[which][n] = lse;
+}
+
+// ------------------------------------------------------------------------------------------------ kernel 3
+struct LayersArgs {
+  int n_prompts, n_trees, n_nodes;
+  const int32_t *tree_prompt, *tree_off, *parent, *token, *rank;
+  int max_depth, max_prompt_trees;
+  int V;
+  const float *zp, *zq;
+  const double *blp, *blq;
+  const float *u_acc, *u_res, *u_fill;
+  int W_L, W_min, W_cap;
+  float t;
+  dsbd_verify_out out;
+  const int32_t* depth;
+  const float* rowmax;   // [2][n_nodes]
+  const float* lse32;    // [2][n_nodes]
+  double* pb;            // [n_prompts][I_cap*V]  p_beam slice storage
+  double* qb;            // [n_prompts][I_cap*V]
+  double* red;           // [n_prompts][2][G][red_w]
+  unsigned int* bar;     // [n_prompts]
+  int G, I_cap, red_w;
+  int32_t* fault;
+};
+
+struct LayerShared {
+  // input beams of the layer
+  int I_node[64];
+  double cum_p[64], cum_q[64];       // cumulative log-likelihoods of the input beams
+  double lse_p[64], lse_q[64];       // fp64 log-sum-exp of their logit rows
+  double max_p[64], max_q[64];       // exact row maxima
+  double sp[64], sq[64];             // beam weight / row sum: p_beam(i,x) = exp(z - max) * sp[i]
+  // accepted beams of the layer (next layer's inputs)
+  int A_node[64];
+  double A_cum_p[64], A_cum_q[64];
+  // candidates
+  short slot_of[NODE_CAP];           // slot in I of a prompt node, -1 if not an input beam
+  int S_node[NODE_CAP], S_tmp[NODE_CAP];
+  double S_pb[NODE_CAP], S_qb[NODE_CAP];
+  // residual chain and accept-count table
+  double cc[NODE_CAP + 2], FF[NODE_CAP + 2];
+  double alpha[NODE_CAP + 2], first[NODE_CAP + 2], Pa[NODE_CAP + 2], Pb[NODE_CAP + 2];
+  double wsum[VL_BLOCK / 64];
+  double tsum[VL_BLOCK];
+  int state, kmax, counter, abort, found;
+  int acc_n, pos, kidx;        // accept loop: accepted so far, next candidate, chain index of p'
+  unsigned int epoch;
+  double bcast;
+};
+
+__device__ __forceinline__ double block_sum(double v, LayerShared& sh) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh.wsum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double tot = 0.0;
+#pragma unroll
+  for (int w = 0; w < VL_BLOCK / 64; ++w) tot += sh.wsum[w];
+  return tot;
+}
+
+// Barrier among the G workgroups of one prompt.  Returns false if the wait gave up.
+__device__ bool group_barrier(const LayersArgs& a, int prompt, LayerShared& sh) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    sh.epoch += 1;
+    const unsigned int target = sh.epoch * (unsigned int)a.G;
+    __threadfence();
+    atomicAdd(&a.bar[prompt], 1u);
+    const long long t0 = wall_clock64();
+    while (__hip_atomic_load(&a.bar[prompt], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      __builtin_amdgcn_s_sleep(2);
+      if (wall_clock64() - t0 > SYNC_LIMIT_TICKS) {
+        atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT);
+        sh.abort = 1;
+        break;
+      }
+    }
+    __threadfence();
+  }
+  __syncthreads();
+  return sh.abort == 0;
+}
+
+// Sum over the prompt's G workgroups of one value each; identical result in every workgroup.
+__device__ double group_sum(const LayersArgs& a, int prompt, int g, double local, int& parity, LayerShared& sh,
+                            bool& ok) {
+  double* red = a.red + ((long long)(prompt * 2 + parity) * a.G) * a.red_w;
+  if (threadIdx.x == 0) red[(long long)g * a.red_w] = local;
+  ok = group_barrier(a, prompt, sh);
+  double tot = 0.0;
+  if (ok)
+    for (int w = 0; w < a.G; ++w) tot += red[(long long)w * a.red_w];
+  parity ^= 1;
+  return tot;
+}
+
+__global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
+  __shared__ LayerShared sh;
+  const int prompt = blockIdx.x / a.G;
+  const int g = blockIdx.x % a.G;
+  const int tid = threadIdx.x;
+  const int V = a.V;
+  int parity = 0;
+  bool ok = true;
+
+  if (tid == 0) { sh.epoch = 0; sh.abort = 0; }
+
+  // ---- trees and nodes of this prompt (tree_prompt is non-decreasing)
+  int t_first = 0, t_end = 0;
+  {
+    int lo = 0, hi = a.n_trees;
+    while (lo < hi) { int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] < prompt) lo = mid + 1; else hi = mid; }
+    t_first = lo;
+    hi = a.n_trees;
+    while (lo < hi) { int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] <= prompt) lo = mid + 1; else hi = mid; }
+    t_end = lo;
+  }
+  int n_roots = t_end - t_first;
+  int n_begin = 0, n_end = 0;
+  int bad = 0;
+  if (n_roots > 0) { n_begin = a.tree_off[t_first]; n_end = a.tree_off[t_end]; }
+  if (n_roots > a.max_prompt_trees || n_roots > a.I_cap || n_roots > 64) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
+  if (n_begin < 0 || n_end > a.n_nodes || n_end < n_begin) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
+  if (n_end - n_begin > NODE_CAP) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
+  for (int b = t_first; b < t_first + n_roots; ++b) {
+    const int r0 = a.tree_off[b], r1 = a.tree_off[b + 1];
+    if (r0 < n_begin || r1 > n_end || r1 <= r0) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; break; }
+  }
+  const int n_pn = n_roots > 0 ? n_end - n_begin : 0;   // nodes of the prompt
+  const int Lw = a.max_depth + 2;                        // row length of the per-layer arrays
+
+  // ---- per-node outputs and initial statuses (first workgroup of the prompt)
+  int gamma = 0;
+  for (int i = tid; i < n_pn; i += VL_BLOCK) {
+    const int n = n_begin + i;
+    const int d = a.depth[n];
+    gamma = max(gamma, d);
+  }
+  {  // block max of gamma
+    __shared__ int sgamma;
+    if (tid == 0) sgamma = 0;
+    __syncthreads();
+    atomicMax(&sgamma, gamma);
+    __syncthreads();
+    gamma = min(sgamma, a.max_depth);
+  }
+  if (g == 0) {
+    for (int i = tid; i < n_pn; i += VL_BLOCK) {
+      const int n = n_begin + i;
+      const int par = a.parent[n];
+      const bool root = a.depth[n] == 0;
+      int tok = a.token[n];
+      if (tok < 0 || tok >= V) { bad |= DSBD_FAULT_TOKEN; tok = 0; }
+      float lp = 0.f, lq = 0.f;
+      if (!root && par >= n_begin && par < n) {
+        lp = a.zp[(long long)par * V + tok] - a.lse32[par];
+        lq = a.zq[(long long)par * V + tok] - a.lse32[a.n_nodes + par];
+      }
+      if (a.out.node_logp_target) a.out.node_logp_target[n] = lp;
+      if (a.out.node_logp_draft) a.out.node_logp_draft[n] = lq;
+      a.out.node_status[n] = root ? DSBD_ROOT : DSBD_NOT_REACHED;
+    }
+    for (int i = tid; i < Lw; i += VL_BLOCK) a.out.layer_width[(long long)prompt * Lw + i] = 0;
+    for (int i = tid; i < a.W_cap; i += VL_BLOCK) {
+      const long long o = (long long)prompt * a.W_cap + i;
+      a.out.out_parent[o] = -1; a.out.out_token[o] = -1; a.out.out_node[o] = -1;
+      a.out.out_logp_target[o] = 0.0; a.out.out_logp_draft[o] = 0.0;
+    }
+  }
+  if (bad && tid == 0 && g == 0) atomicOr(a.fault, bad);
+  if (n_roots == 0) {
+    if (g == 0 && tid == 0) {
+      a.out.l_last[prompt] = 0; a.out.n_out[prompt] = 0; a.out.near_tie_count[prompt] = 0;
+    }
+    return;   // uniform over the prompt's workgroups: nobody waits at a barrier
+  }
+
+  const int W_in = a.W_L > 0 ? a.W_L : n_roots;
+  const bool dynamic = a.t >= 0.f;
+  const double thr = (double)a.t;
+  double* pb = a.pb + (long long)prompt * a.I_cap * V;
+  double* qb = a.qb + (long long)prompt * a.I_cap * V;
+  const float* u_res = a.u_res + (long long)prompt * Lw;
+  const float* u_fill = a.u_fill + (long long)prompt * Lw * a.W_cap;
+
+  // ---- layer 1 inputs: the roots
+  if (tid < n_roots) {
+    const int b = t_first + tid;
+    sh.I_node[tid] = a.tree_off[b];
+    sh.cum_p[tid] = a.blp[b];
+    sh.cum_q[tid] = a.blq[b];
+  }
+  int nI = n_roots;
+  int near_tie = 0;          // meaningful in thread 0
+  int l_last = gamma + 1;
+  int n_out = 0;
+  if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw] = n_roots;
+  __syncthreads();
+
+  for (int l = 1; l <= gamma + 1; ++l) {
+    const bool bonus = (l == gamma + 1);
+    const long long total = (long long)nI * V;           // elements of I x V
+    long long ch = (total + a.G - 1) / a.G;
+    ch = (ch + 1) & ~1LL;
+    const long long e_lo = min(total, (long long)g * ch);
+    const long long e_hi = min(total, e_lo + ch);
+
+    // ===== p_beam / q_beam over I x V: exponentials, row sums (one barrier), scaling
+    double* red = a.red + ((long long)(prompt * 2 + parity) * a.G + g) * a.red_w;
+    for (int i = tid; i < 2 * nI; i += VL_BLOCK) red[i] = 0.0;
+    if (tid < nI) {
+      const int node = sh.I_node[tid];
+      sh.max_p[tid] = (double)a.rowmax[node];
+      sh.max_q[tid] = (double)a.rowmax[a.n_nodes + node];
+    }
+    __syncthreads();
+    {
+      const int i_lo = (int)(e_lo / V), i_hi = e_hi > e_lo ? (int)((e_hi - 1) / V) : i_lo - 1;
+      for (int i = i_lo; i <= i_hi; ++i) {
+        const int node = sh.I_node[i];
+        const long long x_lo = max(e_lo, (long long)i * V) - (long long)i * V;
+        const long long x_hi = min(e_hi, (long long)(i + 1) * V) - (long long)i * V;
+        const float* zp = a.zp + (long long)node * V;
+        const float* zq = a.zq + (long long)node * V;
+        const double mp = sh.max_p[i], mq = sh.max_q[i];
+        double s_p = 0.0, s_q = 0.0;
+        for (long long x = x_lo + tid; x < x_hi; x += VL_BLOCK) {
+          const double ep = exp((double)zp[x] - mp);
+          pb[(long long)i * V + x] = ep;
+          s_p += ep;
+          const double eq = exp((double)zq[x] - mq);
+          qb[(long long)i * V + x] = eq;
+          s_q += eq;
+        }
+        s_p = block_sum(s_p, sh);
+        s_q = block_sum(s_q, sh);
+        if (tid == 0) { red[2 * i] = s_p; red[2 * i + 1] = s_q; }
+      }
+    }
+    ok = group_barrier(a, prompt, sh);
+    if (!ok) return;
+    {
+      const double* redall = a.red + ((long long)(prompt * 2 + parity) * a.G) * a.red_w;
+      if (tid < 2 * nI) {
+        double tot = 0.0;
+        for (int w = 0; w < a.G; ++w) tot += redall[(long long)w * a.red_w + tid];
+        const int i = tid >> 1;
+        if (tid & 1) { sh.lse_q[i] = sh.max_q[i] + log(tot); sh.sq[i] = tot; }
+        else { sh.lse_p[i] = sh.max_p[i] + log(tot); sh.sp[i] = tot; }
+      }
+      parity ^= 1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      // beam weights: softmax of the cumulative likelihoods over I (Section 2.1)
+      double mp = sh.cum_p[0], mq = sh.cum_q[0];
+      for (int i = 1; i < nI; ++i) { mp = fmax(mp, sh.cum_p[i]); mq = fmax(mq, sh.cum_q[i]); }
+      double zp = 0.0, zq = 0.0;
+      for (int i = 0; i < nI; ++i) { zp += exp(sh.cum_p[i] - mp); zq += exp(sh.cum_q[i] - mq); }
+      for (int i = 0; i < nI; ++i) {
+        const double w = exp(sh.cum_p[i] - mp) / zp, v = exp(sh.cum_q[i] - mq) / zq;
+        sh.sp[i] = w / sh.sp[i];
+        sh.sq[i] = v / sh.sq[i];
+      }
+    }
+    __syncthreads();
+    for (long long e = e_lo + tid; e < e_hi; e += VL_BLOCK) {
+      const int i = (int)(e / V);
+      pb[e] *= sh.sp[i];
+      qb[e] *= sh.sq[i];
+    }
+    __syncthreads();
+
+    // sampling helper state: partial sums of max(pb - c qb, 0) of every workgroup
+    auto sample_pass = [&](double c, bool use_q) -> double {
+      double s = 0.0;
+      for (long long e = e_lo + tid; e < e_hi; e += VL_BLOCK)
+        s += use_q ? fmax(pb[e] - c * qb[e], 0.0) : pb[e];
+      return block_sum(s, sh);
+    };
+    // draws `cnt` samples with uniforms u[0..cnt) from weights max(pb - c qb, 0); the workgroup
+    // owning a sample writes output slot out_base + j
+    auto draw = [&](double c, bool use_q, const float* u, int cnt, int out_base) -> bool {
+      const double mine = sample_pass(c, use_q);
+      double* redw = a.red + ((long long)(prompt * 2 + parity) * a.G) * a.red_w;
+      if (tid == 0) redw[(long long)g * a.red_w] = mine;
+      if (!group_barrier(a, prompt, sh)) return false;
+      parity ^= 1;
+      double before = 0.0, Z = 0.0;
+      int last_nz = -1;
+      for (int w = 0; w < a.G; ++w) {
+        const double v = redw[(long long)w * a.red_w];
+        if (w < g) before += v;
+        Z += v;
+        if (v > 0.0) last_nz = w;
+      }
+      // per-thread contiguous sub-slices for the in-slice search
+      const long long len = e_hi - e_lo;
+      const long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
+      const long long t_lo = min(e_hi, e_lo + per * tid), t_hi = min(e_hi, t_lo + per);
+      double ts = 0.0;
+      for (long long e = t_lo; e < t_hi; ++e) ts += use_q ? fmax(pb[e] - c * qb[e], 0.0) : pb[e];
+      __syncthreads();
+      sh.tsum[tid] = ts;
+      __syncthreads();
+      for (int j = 0; j < cnt; ++j) {
+        const double target = (double)u[j] * Z;
+        // owner: the first workgroup whose inclusive prefix exceeds the target
+        int owner = -1;
+        double acc = 0.0;
+        for (int w = 0; w < a.G; ++w) {
+          acc += redw[(long long)w * a.red_w];
+          if (acc > target) { owner = w; break; }
+        }
+        if (owner < 0) owner = last_nz;
+        if (owner != g) continue;            // uniform over the block
+        if (tid == 0) {
+          // thread whose inclusive prefix exceeds the local target
+          double accl = before;
+          int th = -1;
+          for (int k = 0; k < VL_BLOCK; ++k) {
+            const double nx = accl + sh.tsum[k];
+            if (nx > target) { th = k; break; }
+            accl = nx;
+          }
+          if (th < 0) {                       // rounding: take the last thread with mass
+            accl = before;
+            double run = before;
+            for (int k = 0; k < VL_BLOCK; ++k) { if (sh.tsum[k] > 0.0) { th = k; accl = run; } run += sh.tsum[k]; }
+          }
+          sh.found = th;
+          sh.bcast = accl;
+        }
+        __syncthreads();
+        if (tid == sh.found) {
+          double accl = sh.bcast;
+          long long pick = -1, last = -1;
+          for (long long e = t_lo; e < t_hi; ++e) {
+            const double v = use_q ? fmax(pb[e] - c * qb[e], 0.0) : pb[e];
+            if (v > 0.0) last = e;
+            accl += v;
+            if (accl > target) { pick = e; break; }
+          }
+          if (pick < 0) pick = last >= 0 ? last : t_lo;
+          const int i = (int)(pick / V);
+          const int x = (int)(pick - (long long)i * V);
+          const int node = sh.I_node[i];
+          const long long o = (long long)prompt * a.W_cap + out_base + j;
+          a.out.out_parent[o] = node;
+          a.out.out_token[o] = x;
+          a.out.out_node[o] = -1;
+          a.out.out_logp_target[o] = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
+          a.out.out_logp_draft[o] = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+        }
+        __syncthreads();
+      }
+      return true;
+    };
+
+    if (bonus) {
+      // ===== every draft layer passed: W_L beams from p_beam^(gamma+1)
+      if (!draw(0.0, false, u_fill + (long long)l * a.W_cap, min(W_in, a.W_cap), 0)) return;
+      n_out = min(W_in, a.W_cap);
+      if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw + l] = W_in;
+      break;
+    }
+
+    // ===== candidates: depth-l nodes whose parent is an input beam, in (rank, node) order
+    for (int i = tid; i < n_pn; i += VL_BLOCK) sh.slot_of[i] = -1;
+    if (tid == 0) sh.counter = 0;
+    __syncthreads();
+    if (tid < nI) sh.slot_of[sh.I_node[tid] - n_begin] = (short)tid;
+    __syncthreads();
+    for (int i = tid; i < n_pn; i += VL_BLOCK) {
+      const int n = n_begin + i;
+      if (a.depth[n] == l) {
+        const int par = a.parent[n];
+        const bool cand = par >= n_begin && par < n && sh.slot_of[par - n_begin] >= 0;
+        if (cand) sh.S_tmp[atomicAdd(&sh.counter, 1)] = n;
+        else if (g == 0) a.out.node_status[n] = DSBD_PRUNED;
+      }
+    }
+    __syncthreads();
+    const int M = sh.counter;
+    for (int i = tid; i < M; i += VL_BLOCK) {
+      const int n = sh.S_tmp[i];
+      const int rk = a.rank ? a.rank[n] : 0;
+      int pos = 0;
+      for (int j = 0; j < M; ++j) {
+        const int n2 = sh.S_tmp[j];
+        const int rk2 = a.rank ? a.rank[n2] : 0;
+        pos += (rk2 < rk) || (rk2 == rk && n2 < n);
+      }
+      sh.S_node[pos] = n;
+    }
+    __syncthreads();
+    // p_beam and q_beam at every candidate's (parent beam, token)
+    for (int i = tid; i < M; i += VL_BLOCK) {
+      const int n = sh.S_node[i];
+      const int par = a.parent[n];
+      const int slot = sh.slot_of[par - n_begin];
+      int tok = a.token[n];
+      if (tok < 0 || tok >= V) tok = 0;
+      sh.S_pb[i] = exp((double)a.zp[(long long)par * V + tok] - sh.max_p[slot]) * sh.sp[slot];
+      sh.S_qb[i] = exp((double)a.zq[(long long)par * V + tok] - sh.max_q[slot]) * sh.sq[slot];
+    }
+    if (tid == 0) { sh.cc[1] = 0.0; sh.FF[1] = 1.0; sh.kmax = 1; }
+    __syncthreads();
+
+    // evaluates the next entry of the residual chain; returns false if the barrier gave up
+    auto extend_chain = [&]() -> bool {
+      const int k = sh.kmax;
+      const double c = sh.cc[k] + sh.FF[k];
+      double s = 0.0;
+      for (long long e = e_lo + tid; e < e_hi; e += VL_BLOCK) s += fmax(pb[e] - c * qb[e], 0.0);
+      s = block_sum(s, sh);
+      bool okb = true;
+      const double F = group_sum(a, prompt, g, s, parity, sh, okb);
+      if (!okb) return false;
+      __syncthreads();
+      if (tid == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1; }
+      __syncthreads();
+      return true;
+    };
+
+    // ===== width of the layer
+    int WL = W_in;
+    if (dynamic) {
+      // alpha_j for j = 1..M (Eq. 3) from the chain; stop early if the residual mass vanishes
+      bool dead = false;
+      for (int j = 1; j <= M && !dead; ++j) {
+        if (!extend_chain()) return;
+        dead = !(sh.FF[j + 1] > 0.0);
+      }
+      const int kdone = sh.kmax;     // entries 1..kdone valid
+      __syncthreads();
+      // alpha_i (Eq. 3), first[i] = alpha_i prod_{j<i} (1 - alpha_j) (Eq. 2), Pa[m] = P(m,0)
+      for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
+        double alpha = 1.0;            // no residual mass left: accepted with certainty
+        if (i + 1 <= kdone && sh.FF[i] > 0.0) alpha = 1.0 - sh.FF[i + 1] / sh.FF[i];
+        sh.alpha[i] = alpha;
+      }
+      __syncthreads();
+      for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
+        double f = sh.alpha[i];
+        for (int j = 1; j < i; ++j) f *= (1.0 - sh.alpha[j]);
+        sh.first[i] = f;
+      }
+      if (tid == 0) {
+        double none = 1.0;
+        sh.Pa[0] = 1.0;
+        for (int m = 1; m <= M; ++m) { none *= (1.0 - sh.alpha[m]); sh.Pa[m] = none; }
+      }
+      __syncthreads();
+      // W~ = max{K : 1 - sum_{k<K} P(M,k) >= t}; K = 0 always qualifies
+      int Wt = 0;
+      double below = 0.0;              // sum_{k<K} P(M,k)
+      const int Kmax = min(M, a.W_cap);
+      for (int K = 1; K <= Kmax; ++K) {
+        below += sh.Pa[M];             // column K-1 is in Pa
+        if (!(1.0 - below >= thr)) break;
+        Wt = K;
+        if (K == Kmax) break;
+        // column K from column K-1:  P(m,K) = sum_{i=1..m} first[i] P(m-i,K-1), zero for m < K
+        for (int m = tid; m <= M; m += VL_BLOCK) {
+          double tot = 0.0;
+          if (m >= K)
+            for (int i = 1; i <= m; ++i) tot += sh.first[i] * ((m - i >= K - 1) ? sh.Pa[m - i] : 0.0);
+          sh.Pb[m] = tot;
+        }
+        __syncthreads();
+        for (int m = tid; m <= M; m += VL_BLOCK) sh.Pa[m] = sh.Pb[m];
+        __syncthreads();
+      }
+      __syncthreads();
+      WL = min(a.W_cap, max(a.W_min, Wt));
+    }
+    WL = min(WL, a.W_cap);
+    if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw + l] = WL;
+
+    // ===== sequential accept / reject (thread 0 decides; everybody helps when F is needed)
+    if (tid == 0) { sh.acc_n = 0; sh.pos = 0; sh.kidx = 1; }
+    __syncthreads();
+    while (true) {
+      if (tid == 0) {
+        int pos = sh.pos, nacc = sh.acc_n, k = sh.kidx;
+        int state = 0;                   // 0 = finished, 1 = need the next chain entry
+        while (true) {
+          if (pos >= M || nacc >= WL) { state = 0; break; }
+          if (k > sh.kmax) { state = 1; break; }
+          if (k > 1 && !(sh.FF[k] > 0.0)) {
+            // a residual without mass (impossible in exact arithmetic): fall back to p_beam
+            atomicOr(a.fault, DSBD_FAULT_ZERO_RESIDUAL);
+            k = 1;
+          }
+          const int n = sh.S_node[pos];
+          const double pbx = sh.S_pb[pos], qbx = sh.S_qb[pos];
+          const double num = (k == 1) ? pbx : fmax(pbx - sh.cc[k] * qbx, 0.0) / sh.FF[k];
+          const double ratio = (qbx == 0.0) ? INFINITY : num / qbx;
+          const double u = (double)a.u_acc[n];
+          if (fabs(ratio - u) <= NEAR_TIE) near_tie++;
+          if (u <= ratio) {
+            sh.A_node[nacc] = n;
+            nacc++;
+            k = 1;
+            if (g == 0) a.out.node_status[n] = DSBD_ACCEPTED;
+          } else {
+            k++;
+            if (g == 0) a.out.node_status[n] = DSBD_REJECTED;
+          }
+          pos++;
+        }
+        sh.pos = pos; sh.acc_n = nacc; sh.kidx = k; sh.state = state;
+      }
+      __syncthreads();
+      if (sh.state == 0) break;
+      if (!extend_chain()) return;
+    }
+    const int nacc = sh.acc_n, pos_end = sh.pos, kcur = sh.kidx;
+    __syncthreads();
+    if (g == 0)
+      for (int i = pos_end + tid; i < M; i += VL_BLOCK) a.out.node_status[sh.S_node[i]] = DSBD_REJECTED;
+
+    // cumulative likelihoods of the accepted beams (fp64)
+    if (tid < nacc) {
+      const int n = sh.A_node[tid];
+      const int par = a.parent[n];
+      const int slot = sh.slot_of[par - n_begin];
+      int tok = a.token[n];
+      if (tok < 0 || tok >= V) tok = 0;
+      sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)a.zp[(long long)par * V + tok] - sh.lse_p[slot]);
+      sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)a.zq[(long long)par * V + tok] - sh.lse_q[slot]);
+    }
+    __syncthreads();
+
+    if (nacc < WL) {
+      // ===== the layer falls short: accepted beams, one residual sample, then p_beam samples
+      if (g == 0 && tid < nacc) {
+        const int n = sh.A_node[tid];
+        const long long o = (long long)prompt * a.W_cap + tid;
+        a.out.out_parent[o] = a.parent[n];
+        a.out.out_token[o] = a.token[n];
+        a.out.out_node[o] = n;
+        a.out.out_logp_target[o] = sh.A_cum_p[tid];
+        a.out.out_logp_draft[o] = sh.A_cum_q[tid];
+      }
+      // p' = p'_kcur; its chain entry may still be missing if the last candidate was rejected
+      int k = kcur;
+      if (k > sh.kmax) {
+        if (!extend_chain()) return;
+      }
+      if (k > 1 && !(sh.FF[k] > 0.0)) {
+        if (g == 0 && tid == 0) atomicOr(a.fault, DSBD_FAULT_ZERO_RESIDUAL);
+        k = 1;
+      }
+      const double c = sh.cc[k];
+      if (!draw(c, k > 1, u_res + l, 1, nacc)) return;
+      const int fills = WL - nacc - 1;
+      if (fills > 0)
+        if (!draw(0.0, false, u_fill + (long long)l * a.W_cap, fills, nacc + 1)) return;
+      l_last = l;
+      n_out = WL;
+      break;
+    }
+
+    // ===== the layer passed: its accepted beams are the next layer's inputs
+    __syncthreads();
+    if (tid < nacc) {
+      sh.I_node[tid] = sh.A_node[tid];
+      sh.cum_p[tid] = sh.A_cum_p[tid];
+      sh.cum_q[tid] = sh.A_cum_q[tid];
+    }
+    nI = nacc;
+    __syncthreads();
+  }
+
+  if (g == 0 && tid == 0) {
+    a.out.l_last[prompt] = l_last;
+    a.out.n_out[prompt] = n_out;
+    a.out.near_tie_count[prompt] = near_tie;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ host side
+namespace {
+
+struct VerifyPlan {
+  int nchunk, chunk, I_cap, G, red_w;
+};
+
+int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
+  if (!f || !p) return DSBD_ERR_INVALID;
+  if (f->n_prompts < 0 || f->n_trees < 0 || f->n_nodes < 0) return DSBD_ERR_INVALID;
+  if (V < 1) return DSBD_ERR_UNSUPPORTED;
+  if (p->W_cap < 1 || p->W_cap > 64) return DSBD_ERR_UNSUPPORTED;
+  if (p->W_min < 1 || p->W_min > p->W_cap || p->W_L > p->W_cap) return DSBD_ERR_INVALID;
+  if (p->t > 1.0f) return DSBD_ERR_INVALID;
+  if (f->max_tree_nodes < 1 || f->max_tree_nodes > DSBD_MAX_TREE_NODES) return DSBD_ERR_UNSUPPORTED;
+  if (f->max_prompt_trees < 1 || f->max_prompt_trees > 64) return DSBD_ERR_UNSUPPORTED;
+  if (p->W_L <= 0 && f->max_prompt_trees > p->W_cap) return DSBD_ERR_INVALID;
+  if ((long long)f->max_prompt_trees * f->max_tree_nodes > NODE_CAP) return DSBD_ERR_UNSUPPORTED;
+  if (f->max_depth < 0 || f->max_depth >= DSBD_MAX_TREE_NODES) return DSBD_ERR_INVALID;
+  return DSBD_OK;
+}
+
+int cached_cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
+  VerifyPlan pl;
+  // row chunks of about 32k logits: a few thousand workgroups at the large configurations
+  pl.nchunk = (V + 32767) / 32768;
+  pl.chunk = ((V + pl.nchunk - 1) / pl.nchunk + 3) & ~3;
+  pl.nchunk = (V + pl.chunk - 1) / pl.chunk;
+  pl.I_cap = p->W_cap > f->max_prompt_trees ? p->W_cap : f->max_prompt_trees;
+  // one workgroup per compute unit in total, shared evenly by the prompts, at least 4096 joint
+  // elements per workgroup
+  const int cus = cached_cu_count();
+  int G = f->n_prompts > 0 ? cus / f->n_prompts : 1;
+  const long long joint = (long long)pl.I_cap * V;
+  const int by_work = (int)((joint + 4095) / 4096);
+  if (G > by_work) G = by_work;
+  if (G < 1) G = 1;
+  pl.G = G;
+  pl.red_w = 2 * pl.I_cap;
+  return pl;
+}
+
+size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const VerifyPlan& pl, int32_t** depth,
+                    uint64_t** anc, float2** part, float** rowmax, float** lse32, double** pb, double** qb,
+                    double** red, unsigned int** bar) {
+  const size_t N = (size_t)f->n_nodes, P = (size_t)f->n_prompts;
+  *depth = ws.take<int32_t>(N);
+  *anc = ws.take<uint64_t>(N);
+  *part = ws.take<float2>(2 * N * pl.nchunk);
+  *rowmax = ws.take<float>(2 * N);
+  *lse32 = ws.take<float>(2 * N);
+  *pb = ws.take<double>(P * pl.I_cap * V);
+  *qb = ws.take<double>(P * pl.I_cap * V);
+  *red = ws.take<double>(P * 2 * pl.G * pl.red_w);
+  *bar = ws.take<unsigned int>(P);
+  return ws.total();
+}
+
+}  // namespace
+
+extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32_t V, const dsbd_params* p) {
+  if (check_verify(f, V, p) != DSBD_OK) return 0;
+  const VerifyPlan pl = make_verify_plan(f, V, p);
+  WorkspaceCarver ws(nullptr);
+  int32_t* d; uint64_t* an; float2* pt; float *rm, *ls; double *pb, *qb, *red; unsigned int* bar;
+  return carve_verify(ws, f, V, pl, &d, &an, &pt, &rm, &ls, &pb, &qb, &red, &bar) + 256;
+}
+
+extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
+                                      const dsbd_verify_out* out, void* workspace, size_t workspace_bytes,
+                                      int32_t* fault, void* stream_) {
+  if (!in || !out || !fault) return DSBD_ERR_INVALID;
+  int32_t rc = check_verify(f, in->V, p);
+  if (rc != DSBD_OK) return rc;
+  if (f->n_nodes == 0 || f->n_trees == 0 || f->n_prompts == 0) return DSBD_OK;
+  if (!f->tree_prompt || !f->tree_off || !f->parent || !f->token) return DSBD_ERR_INVALID;
+  if (!in->logits_target || !in->logits_draft || !in->beam_logp_target || !in->beam_logp_draft || !in->u_accept ||
+      !in->u_resid || !in->u_fill)
+    return DSBD_ERR_INVALID;
+  if (!out->node_status || !out->l_last || !out->layer_width || !out->n_out || !out->out_parent || !out->out_token ||
+      !out->out_node || !out->out_logp_target || !out->out_logp_draft || !out->near_tie_count)
+    return DSBD_ERR_INVALID;
+  if (!workspace) return DSBD_ERR_INVALID;
+  if (workspace_bytes < dsbd_verify_forest_workspace_bytes(f, in->V, p)) return DSBD_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const VerifyPlan pl = make_verify_plan(f, in->V, p);
+
+  char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
+  WorkspaceCarver ws(wbase);
+  int32_t* depth; uint64_t* anc; float2* part; float *rowmax, *lse32; double *pb, *qb, *red; unsigned int* bar;
+  carve_verify(ws, f, in->V, pl, &depth, &anc, &part, &rowmax, &lse32, &pb, &qb, &red, &bar);
+
+  // the persistent kernel needs all its workgroups resident at once
+  static int max_blocks_per_cu = -1;
+  if (max_blocks_per_cu < 0) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel, VL_BLOCK, 0) != hipSuccess || nb < 1)
+      nb = 1;
+    max_blocks_per_cu = nb;
+  }
+  const long long grid3 = (long long)f->n_prompts * pl.G;
+  if (grid3 > (long long)max_blocks_per_cu * cached_cu_count()) return DSBD_ERR_UNSUPPORTED;
+
+  rc = dsbd_launch_topology(f, depth, anc, fault, stream);
+  if (rc != DSBD_OK) return rc;
+
+  StatsArgs sa;
+  sa.z[0] = in->logits_target; sa.z[1] = in->logits_draft;
+  sa.n_nodes = f->n_nodes; sa.V = in->V; sa.nchunk = pl.nchunk; sa.chunk = pl.chunk;
+  sa.part = part; sa.fault = fault;
+  hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes, 2), dim3(VS_BLOCK), 0, stream, sa);
+  DSBD_HIP_LAUNCH_CHECK();
+
+  FinalizeArgs fa;
+  fa.part = part; fa.n_nodes = f->n_nodes; fa.nchunk = pl.nchunk; fa.n_prompts = f->n_prompts;
+  fa.rowmax = rowmax; fa.lse32 = lse32; fa.out_lse[0] = out->lse_target; fa.out_lse[1] = out->lse_draft; fa.bar = bar;
+  const int fthreads = 2 * f->n_nodes > f->n_prompts ? 2 * f->n_nodes : f->n_prompts;
+  hipLaunchKernelGGL(vocab_stats_finalize_kernel, dim3((fthreads + 255) / 256), dim3(256), 0, stream, fa);
+  DSBD_HIP_LAUNCH_CHECK();
+
+  LayersArgs la;
+  la.n_prompts = f->n_prompts; la.n_trees = f->n_trees; la.n_nodes = f->n_nodes;
+  la.tree_prompt = f->tree_prompt; la.tree_off = f->tree_off; la.parent = f->parent; la.token = f->token;
+  la.rank = f->draft_rank; la.max_depth = f->max_depth; la.max_prompt_trees = f->max_prompt_trees;
+  la.V = in->V; la.zp = in->logits_target; la.zq = in->logits_draft;
+  la.blp = in->beam_logp_target; la.blq = in->beam_logp_draft;
+  la.u_acc = in->u_accept; la.u_res = in->u_resid; la.u_fill = in->u_fill;
+  la.W_L = p->W_L; la.W_min = p->W_min; la.W_cap = p->W_cap; la.t = p->t;
+  la.out = *out; la.depth = depth; la.rowmax = rowmax; la.lse32 = lse32;
+  la.pb = pb; la.qb = qb; la.red = red; la.bar = bar;
+  la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.fault = fault;
+  void* kargs[] = {&la};
+  if (hipLaunchCooperativeKernel(reinterpret_cast<void*>(verify_layers_kernel), dim3((unsigned)grid3), dim3(VL_BLOCK),
+                                 kargs, 0, stream) != hipSuccess)
+    return DSBD_ERR_HIP;
+  return DSBD_OK;
+}

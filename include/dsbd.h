@@ -15,7 +15,8 @@
  * Conventions
  *   - Every array argument is a DEVICE pointer owned by the caller unless marked "host".
  *     The structs themselves are host memory, read during the call only.
- *   - The library allocates nothing and keeps no state between calls.  Scratch memory comes
+ *   - The library allocates nothing and keeps no state between calls (the measurement hook at the
+ *     end of this header aside).  Scratch memory comes
  *     from the caller's `workspace` (device, 256-byte aligned), at least as large as the
  *     matching dsbd_*_workspace_bytes() says.  Its contents need not be initialised.
  *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work; outputs are valid
@@ -191,6 +192,20 @@ typedef struct dsbd_next_beams {
  */
 int32_t dsbd_select_beams(const dsbd_forest* forest, const dsbd_verify_out* verified, int32_t W_cap,
                           int32_t keep_one, const dsbd_next_beams* next, int32_t* fault, void* stream);
+
+/*
+ * Measurement hook (no counterpart in the paper).  dsbd_timing_enable(kernel, capacity) makes the
+ * library record a pair of HIP events around every launch of ONE of its kernels, on the stream the
+ * kernel is launched on, for up to `capacity` launches; dsbd_timing_collect() waits for the recorded
+ * events, writes the elapsed milliseconds of each launch to the HOST array `ms` (at most max_n) and
+ * returns how many it wrote (negative: DSBD_ERR_*), then starts over.  kernel = 0 switches it off and
+ * frees the events.  Not thread-safe; meant for benchmarks.
+ */
+#define DSBD_KERNEL_ATTENTION     1   /* forest attention main kernel (streams K/V)            */
+#define DSBD_KERNEL_VOCAB_STATS   2   /* per-node vocabulary softmax statistics (streams logits) */
+#define DSBD_KERNEL_VERIFY_LAYERS 3   /* persistent layer-by-layer verification                */
+int32_t dsbd_timing_enable(int32_t kernel, int32_t capacity);
+int32_t dsbd_timing_collect(float* ms, int32_t max_n);
 
 /* Library version and the offload architecture it was built for. */
 const char* dsbd_version(void);

@@ -89,6 +89,10 @@ def load_library():
     lib.dsbd_select_beams.restype = C.c_int32
     lib.dsbd_select_beams.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyOut), C.c_int32, C.c_int32,
                                       C.POINTER(_NextBeams), C.c_void_p, C.c_void_p]
+    lib.dsbd_timing_enable.restype = C.c_int32
+    lib.dsbd_timing_enable.argtypes = [C.c_int32, C.c_int32]
+    lib.dsbd_timing_collect.restype = C.c_int32
+    lib.dsbd_timing_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
     lib.dsbd_version.restype = C.c_char_p
     _lib = lib
     return lib
@@ -150,7 +154,7 @@ class PrefixKV:
             self.token_stride, self.head_stride = ref.stride(0), ref.stride(1)
             lens = [t.shape[0] for t in k]
         for t in list(k) + list(v):
-            assert t.dtype == torch.bfloat16 and t.stride(-1) == 1
+            assert t.dtype == torch.bfloat16 and (t.numel() == 0 or t.stride(-1) == 1)
         self.k_ptr = torch.tensor([t.data_ptr() for t in k], dtype=torch.int64, device=dev)
         self.v_ptr = torch.tensor([t.data_ptr() for t in v], dtype=torch.int64, device=dev)
         self.len = torch.tensor(lens, dtype=torch.int32, device=dev)
@@ -312,3 +316,20 @@ def dsbd_select_beams(forest: Forest, verified: VerifyResult, keep_one=False, re
                                _ptr(result.fault), _stream(stream))
     _check(rc, "dsbd_select_beams")
     return result
+
+
+DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS = 1, 2, 3
+
+
+def dsbd_timing_enable(kernel: int, capacity: int = 0):
+    """Record HIP events around every launch of one library kernel (0 switches the hook off)."""
+    _check(load_library().dsbd_timing_enable(int(kernel), int(capacity)), "dsbd_timing_enable")
+
+
+def dsbd_timing_collect(max_n: int = 4096):
+    """Milliseconds of every recorded launch since the last collect (waits for the events)."""
+    buf = (C.c_float * max_n)()
+    n = load_library().dsbd_timing_collect(buf, max_n)
+    if n < 0:
+        raise DsbdError(n, "dsbd_timing_collect")
+    return [float(buf[i]) for i in range(n)]

@@ -495,8 +495,10 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
 
   const long long grid = (long long)f->n_trees * Hkv * p.n_rowblocks * p.nsplit;
   if (grid > 0x7fffffffLL) return DSBD_ERR_UNSUPPORTED;
+  dsbd_timing_mark(DSBD_KERNEL_ATTENTION, true, stream);
   if (D == 128) dispatch_attn<128>(p, a, (int)grid, stream);
   else dispatch_attn<64>(p, a, (int)grid, stream);
+  dsbd_timing_mark(DSBD_KERNEL_ATTENTION, false, stream);
   DSBD_HIP_LAUNCH_CHECK();
 
   const long long n_rows_total = (long long)f->n_nodes * Hq;

@@ -33,3 +33,6 @@ struct WorkspaceCarver {
 // validation of the parent array).  depth may be null.
 int32_t dsbd_launch_topology(const dsbd_forest* f, int32_t* depth, uint64_t* anc_mask, int32_t* fault,
                              hipStream_t stream);
+
+// Measurement hook (timing.hip): records an event before / after kernel `kernel_id` when enabled.
+void dsbd_timing_mark(int kernel_id, bool begin, hipStream_t stream);

@@ -303,7 +303,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       a.out.out_logp_target[o] = 0.0; a.out.out_logp_draft[o] = 0.0;
     }
   }
-  if (bad && tid == 0 && g == 0) atomicOr(a.fault, bad);
+  if (bad && g == 0) atomicOr(a.fault, bad);
   if (n_roots == 0) {
     if (g == 0 && tid == 0) {
       a.out.l_last[prompt] = 0; a.out.n_out[prompt] = 0; a.out.near_tie_count[prompt] = 0;
@@ -840,7 +840,9 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   sa.z[0] = in->logits_target; sa.z[1] = in->logits_draft;
   sa.n_nodes = f->n_nodes; sa.V = in->V; sa.nchunk = pl.nchunk; sa.chunk = pl.chunk;
   sa.part = part; sa.fault = fault;
+  dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, true, stream);
   hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes, 2), dim3(VS_BLOCK), 0, stream, sa);
+  dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, false, stream);
   DSBD_HIP_LAUNCH_CHECK();
 
   FinalizeArgs fa;
@@ -862,8 +864,9 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.pb = pb; la.qb = qb; la.red = red; la.bar = bar;
   la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.fault = fault;
   void* kargs[] = {&la};
-  if (hipLaunchCooperativeKernel(reinterpret_cast<void*>(verify_layers_kernel), dim3((unsigned)grid3), dim3(VL_BLOCK),
-                                 kargs, 0, stream) != hipSuccess)
-    return DSBD_ERR_HIP;
-  return DSBD_OK;
+  dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, true, stream);
+  const hipError_t le = hipLaunchCooperativeKernel(reinterpret_cast<void*>(verify_layers_kernel),
+                                                   dim3((unsigned)grid3), dim3(VL_BLOCK), kargs, 0, stream);
+  dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, false, stream);
+  return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
 }

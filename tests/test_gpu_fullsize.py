@@ -1,0 +1,66 @@
+"""Parity at the full benchmark size, in the launch configuration bench.py times (configuration c5:
+8 beams, 31-node trees, prefix 8192, GQA 32/8, D 128, vocabulary 128256).
+
+Attention: sampled (node, head) outputs, each computed by the oracle from the definition.
+Verification and selection: the whole forest (the oracle finishes in seconds at this size)."""
+import numpy as np
+import pytest
+import torch
+
+from dsbd_synth import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c5():
+    import gpu_util as gu
+    w = make_workload("c5")
+    return w, gu.DeviceWorkload(w)
+
+
+def test_c5_attention_sampled_outputs(c5):
+    import gpu_util as gu
+    from oracle import attention as o_attn, forest as o_forest
+    w, d = c5
+    out, lse, fault = d.attention()
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0
+    rng = np.random.default_rng(0)
+    tree = o_forest.tree_of_node(w.tree_off, w.n_nodes)
+    rows = [(0, 0), (w.n_nodes - 1, w.Hq - 1), (30, 5), (31, 17)]
+    rows += [(int(rng.integers(0, w.n_nodes)), int(rng.integers(0, w.Hq))) for _ in range(44)]
+    q, kt, vt = gu.f64(w.q), gu.f64(w.k_tree), gu.f64(w.v_tree)
+    cache = {}
+    ref_o, ref_l = [], []
+    for n, h in rows:
+        b = int(tree[n])
+        if b not in cache:
+            cache = {b: gu.logical_prefix(w, b)}
+        o, l = o_attn.forest_attention_at(w.parent, w.tree_off, q, kt, vt, cache[b][0], cache[b][1], n, h)
+        ref_o.append(o); ref_l.append(l)
+    err = gu.compare_attention(w, out, lse, ref_o, ref_l, rows=rows)
+    print("c5 sampled attention max abs err (out, lse):", err, flush=True)
+    # properties that hold at any size: rows are convex combinations of V rows (|o| bounded by max |v|)
+    assert torch.isfinite(out.float()).all()
+    assert out.float().abs().max().item() <= 6.0
+
+
+@pytest.mark.parametrize("t", [-1.0, 0.9])
+def test_c5_verify_and_select_whole_forest(c5, t):
+    import gpu_util as gu
+    import paper_2409_16560_amd as dsbd
+    from oracle import select as o_select
+    w, d = c5
+    res = d.verify(t=t)
+    nx = dsbd.dsbd_select_beams(d.forest, res)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t)
+    near = gu.compare_verify(res, ref, w)
+    print("c5 verify t=%g: l_last %s widths %s near ties %d" % (t, ref["l_last"].tolist(), ref["layer_width"].tolist(), near), flush=True)
+    if near == 0:
+        sref = o_select.select_beams(w.tree_off, w.parent, ref["n_out"], ref["out_parent"], ref["out_token"],
+                                     ref["out_logp_p"], ref["out_logp_q"], w.max_depth + 1)
+        g = lambda x: x.cpu().numpy()
+        for name in ("n_next", "src_tree", "src_out", "path_len", "path", "token"):
+            assert np.array_equal(g(getattr(nx, name)), sref[name]), name

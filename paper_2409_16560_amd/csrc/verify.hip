@@ -24,6 +24,7 @@
 // the same order), so their control flow stays identical without any broadcast.
 #include "common.h"
 #include <float.h>
+#include <stdlib.h>
 
 #define VS_BLOCK 256
 #define VL_BLOCK 512
@@ -117,12 +118,13 @@ struct FinalizeArgs {
   float* rowmax;      // [2][n_nodes]
   float* lse32;       // [2][n_nodes]
   float* out_lse[2];
-  unsigned int* bar;  // [n_prompts]
+  unsigned long long* slots;   // exchange slots of the layer kernel, cleared here
+  long long n_slot_words;
 };
 
 __global__ void vocab_stats_finalize_kernel(FinalizeArgs a) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < a.n_prompts) a.bar[i] = 0u;
+  for (long long k = i; k < a.n_slot_words; k += (long long)gridDim.x * blockDim.x) a.slots[k] = 0ull;
   if (i >= 2 * a.n_nodes) return;
   const float2* p = a.part + (long long)i * a.nchunk;
   float M = p[0].x, S = p[0].y;
@@ -151,9 +153,10 @@ struct LayersArgs {
   const float* lse32;    // [2][n_nodes]
   double* pb;            // [n_prompts][I_cap*V]  p_beam slice storage
   double* qb;            // [n_prompts][I_cap*V]
-  double* red;           // [n_prompts][2][G][red_w]
-  unsigned int* bar;     // [n_prompts]
+  double* red;           // exchange slots [n_prompts][2 banks][G][red_w] of 16 bytes each
   int G, I_cap, red_w;
+  long long* trace;      // optional timeline (first workgroup of prompt 0): pairs (label, 100 MHz wall clock)
+  int lds_elems;         // capacity (elements) of each of the two dynamic-LDS slice arrays; 0 = none
   int32_t* fault;
 };
 
@@ -167,6 +170,10 @@ struct LayerShared {
   // accepted beams of the layer (next layer's inputs)
   int A_node[64];
   double A_cum_p[64], A_cum_q[64];
+  // the prompt's nodes (loaded once: the sequential parts must not wait for global memory)
+  int n_parent[NODE_CAP], n_token[NODE_CAP], n_rank[NODE_CAP];
+  short n_depth[NODE_CAP];
+  float n_u[NODE_CAP];               // accept uniform of each node
   // candidates
   short slot_of[NODE_CAP];           // slot in I of a prompt node, -1 if not an input beam
   int S_node[NODE_CAP], S_tmp[NODE_CAP];
@@ -176,9 +183,10 @@ struct LayerShared {
   double alpha[NODE_CAP + 2], first[NODE_CAP + 2], Pa[NODE_CAP + 2], Pb[NODE_CAP + 2];
   double wsum[VL_BLOCK / 64];
   double tsum[VL_BLOCK];
+  double colsum[128];                // this workgroup's row sums (p and q interleaved)
+  double gpart[256];                 // one partial per workgroup of the prompt (G <= 256)
   int state, kmax, counter, abort, found;
   int acc_n, pos, kidx;        // accept loop: accepted so far, next candidate, chain index of p'
-  unsigned int epoch;
   double bcast;
 };
 
@@ -194,52 +202,116 @@ __device__ __forceinline__ double block_sum(double v, LayerShared& sh) {
   return tot;
 }
 
-// Barrier among the G workgroups of one prompt.  Returns false if the wait gave up.
-__device__ bool group_barrier(const LayersArgs& a, int prompt, LayerShared& sh) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    sh.epoch += 1;
-    const unsigned int target = sh.epoch * (unsigned int)a.G;
-    __threadfence();
-    atomicAdd(&a.bar[prompt], 1u);
-    const long long t0 = wall_clock64();
-    while (__hip_atomic_load(&a.bar[prompt], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      __builtin_amdgcn_s_sleep(2);
-      if (wall_clock64() - t0 > SYNC_LIMIT_TICKS) {
-        atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT);
-        sh.abort = 1;
-        break;
-      }
-    }
-    __threadfence();
+// Inclusive prefix sum over the block's threads in thread order (fixed tree: identical in every workgroup
+// that scans the same values).
+__device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const double up = __shfl_up(v, off);
+    if (lane >= off) v += up;
   }
+  __syncthreads();
+  if (lane == 63) sh.wsum[wave] = v;
+  __syncthreads();
+  double before = 0.0;
+  for (int w = 0; w < wave; ++w) before += sh.wsum[w];
+  return before + v;
+}
+
+// ---- exchange among the G workgroups of one prompt
+//
+// No grid-wide barrier and no cache-wide fence: a workgroup publishes each partial value in its own
+// 16-byte slot as two agent-scope atomic words (value bits, value bits XOR tag) and every other
+// workgroup polls exactly the slots it needs.  The tag changes with every exchange, so a slot is valid
+// only once both words of the current exchange have landed; slots alternate between two banks, and a
+// workgroup can be at most one exchange ahead of the slowest one, so a bank is never overwritten while
+// somebody may still read it.
+struct Slot { unsigned long long w0, w1; };
+
+__device__ __forceinline__ unsigned long long exchange_tag(unsigned int epoch) {
+  return (unsigned long long)epoch * 0x9E3779B97F4A7C15ull;
+}
+
+__device__ __forceinline__ void slot_post(Slot* s, double v, unsigned long long tag) {
+  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+  __hip_atomic_store(&s->w0, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&s->w1, b ^ tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits until the slot carries the tag; gives up after SYNC_LIMIT_TICKS (returns false).
+__device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, double& v) {
+  long long t0 = 0;
+  for (int spin = 0;; ++spin) {
+    const unsigned long long w0 = __hip_atomic_load(&s->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long w1 = __hip_atomic_load(&s->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((w0 ^ w1) == tag) { v = __longlong_as_double((long long)w0); return true; }
+    if (spin == 0) t0 = wall_clock64();
+    else if ((spin & 63) == 0 && wall_clock64() - t0 > SYNC_LIMIT_TICKS) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
+__device__ __forceinline__ Slot* exchange_bank(const LayersArgs& a, int prompt, unsigned int epoch) {
+  return reinterpret_cast<Slot*>(a.red) + ((long long)(prompt * 2 + (epoch & 1)) * a.G) * a.red_w;
+}
+
+// Ends an exchange: makes a failed wait visible to the whole workgroup.
+__device__ __forceinline__ bool exchange_finish(const LayersArgs& a, bool mine_ok, LayerShared& sh) {
+  if (!mine_ok) { sh.abort = 1; atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT); }
   __syncthreads();
   return sh.abort == 0;
 }
 
-// Sum over the prompt's G workgroups of one value each; identical result in every workgroup.
-__device__ double group_sum(const LayersArgs& a, int prompt, int g, double local, int& parity, LayerShared& sh,
-                            bool& ok) {
-  double* red = a.red + ((long long)(prompt * 2 + parity) * a.G) * a.red_w;
-  if (threadIdx.x == 0) red[(long long)g * a.red_w] = local;
-  ok = group_barrier(a, prompt, sh);
-  double tot = 0.0;
-  if (ok)
-    for (int w = 0; w < a.G; ++w) tot += red[(long long)w * a.red_w];
-  parity ^= 1;
-  return tot;
+// Sum over the prompt's G workgroups of one value each; identical result in every workgroup (same
+// values, same reduction tree).
+__device__ double group_sum(const LayersArgs& a, int prompt, int g, double local, unsigned int& epoch,
+                            LayerShared& sh, bool& ok) {
+  epoch += 1;
+  const unsigned long long tag = exchange_tag(epoch);
+  Slot* bank = exchange_bank(a, prompt, epoch);
+  if (threadIdx.x == 0) slot_post(bank + (long long)g * a.red_w, local, tag);
+  double v = 0.0;
+  bool mine = true;
+  if ((int)threadIdx.x < a.G) mine = slot_wait(bank + (long long)threadIdx.x * a.red_w, tag, v);
+  ok = exchange_finish(a, mine, sh);
+  return block_sum(ok ? v : 0.0, sh);
+}
+
+// Gathers one value of every workgroup into sh.gpart[0..G).
+__device__ bool group_gather(const LayersArgs& a, int prompt, int g, double local, unsigned int& epoch,
+                             LayerShared& sh) {
+  epoch += 1;
+  const unsigned long long tag = exchange_tag(epoch);
+  Slot* bank = exchange_bank(a, prompt, epoch);
+  if (threadIdx.x == 0) slot_post(bank + (long long)g * a.red_w, local, tag);
+  bool mine = true;
+  for (int w = threadIdx.x; w < a.G; w += VL_BLOCK) {
+    double v = 0.0;
+    mine = mine && slot_wait(bank + (long long)w * a.red_w, tag, v);
+    sh.gpart[w] = v;
+  }
+  return exchange_finish(a, mine, sh);
 }
 
 __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   __shared__ LayerShared sh;
+  extern __shared__ __attribute__((aligned(16))) double dyn_lds[];
   const int prompt = blockIdx.x / a.G;
   const int g = blockIdx.x % a.G;
   const int tid = threadIdx.x;
   const int V = a.V;
-  int parity = 0;
+  unsigned int epoch = 0;      // exchanges so far; identical in every workgroup of the prompt
+  int trace_n = 0;
+  auto stamp = [&](int label) {
+    if (a.trace && blockIdx.x == 0 && tid == 0 && trace_n < 255) {
+      a.trace[2 * trace_n + 2] = label; a.trace[2 * trace_n + 3] = wall_clock64(); ++trace_n; a.trace[0] = trace_n;
+    }
+  };
+  stamp(0);
   bool ok = true;
 
-  if (tid == 0) { sh.epoch = 0; sh.abort = 0; }
+  if (tid == 0) sh.abort = 0;
 
   // ---- trees and nodes of this prompt (tree_prompt is non-decreasing)
   int t_first = 0, t_end = 0;
@@ -271,6 +343,13 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const int n = n_begin + i;
     const int d = a.depth[n];
     gamma = max(gamma, d);
+    int tok = a.token[n];
+    if (tok < 0 || tok >= V) { bad |= DSBD_FAULT_TOKEN; tok = 0; }
+    sh.n_depth[i] = (short)d;
+    sh.n_parent[i] = a.parent[n];
+    sh.n_token[i] = tok;
+    sh.n_rank[i] = a.rank ? a.rank[n] : 0;
+    sh.n_u[i] = a.u_acc[n];
   }
   {  // block max of gamma
     __shared__ int sgamma;
@@ -283,10 +362,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   if (g == 0) {
     for (int i = tid; i < n_pn; i += VL_BLOCK) {
       const int n = n_begin + i;
-      const int par = a.parent[n];
-      const bool root = a.depth[n] == 0;
-      int tok = a.token[n];
-      if (tok < 0 || tok >= V) { bad |= DSBD_FAULT_TOKEN; tok = 0; }
+      const int par = sh.n_parent[i];
+      const bool root = sh.n_depth[i] == 0;
+      const int tok = sh.n_token[i];
       float lp = 0.f, lq = 0.f;
       if (!root && par >= n_begin && par < n) {
         lp = a.zp[(long long)par * V + tok] - a.lse32[par];
@@ -297,18 +375,24 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       a.out.node_status[n] = root ? DSBD_ROOT : DSBD_NOT_REACHED;
     }
     for (int i = tid; i < Lw; i += VL_BLOCK) a.out.layer_width[(long long)prompt * Lw + i] = 0;
-    for (int i = tid; i < a.W_cap; i += VL_BLOCK) {
+  }
+  if (bad && g == 0) atomicOr(a.fault, bad);
+  // Output slots are written by exactly one workgroup each (sampled beams by the workgroup that owns the
+  // sample, everything else by the prompt's first workgroup): the XCDs' L2 caches are not coherent with
+  // each other, so two workgroups must never write the same word.
+  auto clear_out_slots = [&](int from) {
+    for (int i = from + tid; i < a.W_cap; i += VL_BLOCK) {
       const long long o = (long long)prompt * a.W_cap + i;
       a.out.out_parent[o] = -1; a.out.out_token[o] = -1; a.out.out_node[o] = -1;
       a.out.out_logp_target[o] = 0.0; a.out.out_logp_draft[o] = 0.0;
     }
-  }
-  if (bad && g == 0) atomicOr(a.fault, bad);
+  };
   if (n_roots == 0) {
+    if (g == 0) clear_out_slots(0);
     if (g == 0 && tid == 0) {
       a.out.l_last[prompt] = 0; a.out.n_out[prompt] = 0; a.out.near_tie_count[prompt] = 0;
     }
-    return;   // uniform over the prompt's workgroups: nobody waits at a barrier
+    return;   // uniform over the prompt's workgroups: nobody waits for a missing partner
   }
 
   const int W_in = a.W_L > 0 ? a.W_L : n_roots;
@@ -333,22 +417,28 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw] = n_roots;
   __syncthreads();
 
+  stamp(1);
   for (int l = 1; l <= gamma + 1; ++l) {
+    stamp(10 + l);
     const bool bonus = (l == gamma + 1);
     const long long total = (long long)nI * V;           // elements of I x V
     long long ch = (total + a.G - 1) / a.G;
     ch = (ch + 1) & ~1LL;
     const long long e_lo = min(total, (long long)g * ch);
     const long long e_hi = min(total, e_lo + ch);
+    const long long len = e_hi - e_lo;
+    // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
+    const bool in_lds = ch <= (long long)a.lds_elems;
+    double* ps = in_lds ? dyn_lds : pb + e_lo;
+    double* qs = in_lds ? dyn_lds + a.lds_elems : qb + e_lo;
 
-    // ===== p_beam / q_beam over I x V: exponentials, row sums (one barrier), scaling
-    double* red = a.red + ((long long)(prompt * 2 + parity) * a.G + g) * a.red_w;
-    for (int i = tid; i < 2 * nI; i += VL_BLOCK) red[i] = 0.0;
+    // ===== p_beam / q_beam over I x V: exponentials, row sums (one exchange), scaling
     if (tid < nI) {
       const int node = sh.I_node[tid];
       sh.max_p[tid] = (double)a.rowmax[node];
       sh.max_q[tid] = (double)a.rowmax[a.n_nodes + node];
     }
+    for (int i = tid; i < 2 * nI; i += VL_BLOCK) sh.colsum[i] = 0.0;
     __syncthreads();
     {
       const int i_lo = (int)(e_lo / V), i_hi = e_hi > e_lo ? (int)((e_hi - 1) / V) : i_lo - 1;
@@ -360,124 +450,165 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const float* zq = a.zq + (long long)node * V;
         const double mp = sh.max_p[i], mq = sh.max_q[i];
         double s_p = 0.0, s_q = 0.0;
-        for (long long x = x_lo + tid; x < x_hi; x += VL_BLOCK) {
-          const double ep = exp((double)zp[x] - mp);
-          pb[(long long)i * V + x] = ep;
-          s_p += ep;
-          const double eq = exp((double)zq[x] - mq);
-          qb[(long long)i * V + x] = eq;
-          s_q += eq;
+        const long long joff = (long long)i * V - e_lo;
+        long long x = x_lo + tid;
+        for (; x + 7 * VL_BLOCK < x_hi; x += 8 * VL_BLOCK) {     // eight logits of each model in flight
+          float fp[8], fq[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) { fp[k] = zp[x + k * VL_BLOCK]; fq[k] = zq[x + k * VL_BLOCK]; }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const double ep = exp((double)fp[k] - mp), eq = exp((double)fq[k] - mq);
+            ps[joff + x + k * VL_BLOCK] = ep; qs[joff + x + k * VL_BLOCK] = eq;
+            s_p += ep; s_q += eq;
+          }
+        }
+        for (; x < x_hi; x += VL_BLOCK) {
+          const double ep = exp((double)zp[x] - mp), eq = exp((double)zq[x] - mq);
+          ps[joff + x] = ep; qs[joff + x] = eq;
+          s_p += ep; s_q += eq;
         }
         s_p = block_sum(s_p, sh);
         s_q = block_sum(s_q, sh);
-        if (tid == 0) { red[2 * i] = s_p; red[2 * i + 1] = s_q; }
+        if (tid == 0) { sh.colsum[2 * i] = s_p; sh.colsum[2 * i + 1] = s_q; }
       }
     }
-    ok = group_barrier(a, prompt, sh);
-    if (!ok) return;
+    __syncthreads();
     {
-      const double* redall = a.red + ((long long)(prompt * 2 + parity) * a.G) * a.red_w;
-      if (tid < 2 * nI) {
-        double tot = 0.0;
-        for (int w = 0; w < a.G; ++w) tot += redall[(long long)w * a.red_w + tid];
+      // all-reduce of the 2|I| row sums: column c of workgroups w = r, r + R, ... is gathered by thread
+      // (r, c); the R partial sums of a column are then folded by a fixed tree.
+      epoch += 1;
+      const unsigned long long tag = exchange_tag(epoch);
+      Slot* bank = exchange_bank(a, prompt, epoch);
+      const int ncols = 2 * nI;
+      if (tid < ncols) slot_post(bank + (long long)g * a.red_w + tid, sh.colsum[tid], tag);
+      int cpow = 1;
+      while (cpow < ncols) cpow <<= 1;
+      const int R = VL_BLOCK / cpow;
+      const int c = tid % cpow, r = tid / cpow;
+      double acc = 0.0;
+      bool mine = true;
+      if (c < ncols)
+        for (int w = r; w < a.G; w += R) {
+          double v = 0.0;
+          mine = mine && slot_wait(bank + (long long)w * a.red_w + c, tag, v);
+          acc += v;
+        }
+      sh.tsum[tid] = acc;
+      stamp(20);
+      if (!exchange_finish(a, mine, sh)) return;
+      stamp(21);
+      for (int st = R >> 1; st >= 1; st >>= 1) {
+        if (r < st) sh.tsum[r * cpow + c] += sh.tsum[(r + st) * cpow + c];
+        __syncthreads();
+      }
+      if (tid < ncols) {
+        const double tot = sh.tsum[tid];
         const int i = tid >> 1;
         if (tid & 1) { sh.lse_q[i] = sh.max_q[i] + log(tot); sh.sq[i] = tot; }
         else { sh.lse_p[i] = sh.max_p[i] + log(tot); sh.sp[i] = tot; }
       }
-      parity ^= 1;
     }
     __syncthreads();
-    if (tid == 0) {
-      // beam weights: softmax of the cumulative likelihoods over I (Section 2.1)
+    {
+      // beam weights: softmax of the cumulative likelihoods over I (Section 2.1); one thread per beam
       double mp = sh.cum_p[0], mq = sh.cum_q[0];
       for (int i = 1; i < nI; ++i) { mp = fmax(mp, sh.cum_p[i]); mq = fmax(mq, sh.cum_q[i]); }
+      if (tid < nI) { sh.A_cum_p[tid] = exp(sh.cum_p[tid] - mp); sh.A_cum_q[tid] = exp(sh.cum_q[tid] - mq); }
+      __syncthreads();
       double zp = 0.0, zq = 0.0;
-      for (int i = 0; i < nI; ++i) { zp += exp(sh.cum_p[i] - mp); zq += exp(sh.cum_q[i] - mq); }
-      for (int i = 0; i < nI; ++i) {
-        const double w = exp(sh.cum_p[i] - mp) / zp, v = exp(sh.cum_q[i] - mq) / zq;
-        sh.sp[i] = w / sh.sp[i];
-        sh.sq[i] = v / sh.sq[i];
+      for (int i = 0; i < nI; ++i) { zp += sh.A_cum_p[i]; zq += sh.A_cum_q[i]; }
+      __syncthreads();
+      if (tid < nI) {
+        sh.sp[tid] = (sh.A_cum_p[tid] / zp) / sh.sp[tid];
+        sh.sq[tid] = (sh.A_cum_q[tid] / zq) / sh.sq[tid];
       }
     }
     __syncthreads();
-    for (long long e = e_lo + tid; e < e_hi; e += VL_BLOCK) {
-      const int i = (int)(e / V);
-      pb[e] *= sh.sp[i];
-      qb[e] *= sh.sq[i];
+    {
+      const int i_lo = (int)(e_lo / V), i_hi = e_hi > e_lo ? (int)((e_hi - 1) / V) : i_lo - 1;
+      for (int i = i_lo; i <= i_hi; ++i) {
+        const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
+        const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
+        const double fp = sh.sp[i], fq = sh.sq[i];
+        for (long long j = j_lo + tid; j < j_hi; j += VL_BLOCK) { ps[j] *= fp; qs[j] *= fq; }
+      }
     }
     __syncthreads();
 
-    // sampling helper state: partial sums of max(pb - c qb, 0) of every workgroup
-    auto sample_pass = [&](double c, bool use_q) -> double {
-      double s = 0.0;
-      for (long long e = e_lo + tid; e < e_hi; e += VL_BLOCK)
-        s += use_q ? fmax(pb[e] - c * qb[e], 0.0) : pb[e];
-      return block_sum(s, sh);
+    stamp(22);
+    // sum over the slice of max(p_beam - c q_beam, 0) (or of p_beam); four loads in flight per thread
+    auto slice_sum = [&](double c, bool use_q) -> double {
+      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+      long long j = tid;
+      if (use_q) {
+        for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
+          const double p0 = ps[j], p1 = ps[j + VL_BLOCK], p2 = ps[j + 2 * VL_BLOCK], p3 = ps[j + 3 * VL_BLOCK];
+          const double q0 = qs[j], q1 = qs[j + VL_BLOCK], q2 = qs[j + 2 * VL_BLOCK], q3 = qs[j + 3 * VL_BLOCK];
+          s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
+          s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
+        }
+        for (; j < len; j += VL_BLOCK) s0 += fmax(ps[j] - c * qs[j], 0.0);
+      } else {
+        for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
+          s0 += ps[j]; s1 += ps[j + VL_BLOCK]; s2 += ps[j + 2 * VL_BLOCK]; s3 += ps[j + 3 * VL_BLOCK];
+        }
+        for (; j < len; j += VL_BLOCK) s0 += ps[j];
+      }
+      return (s0 + s1) + (s2 + s3);
     };
+
+    // sampling helper state: partial sums of max(pb - c qb, 0) of every workgroup
+    auto sample_pass = [&](double c, bool use_q) -> double { return block_sum(slice_sum(c, use_q), sh); };
     // draws `cnt` samples with uniforms u[0..cnt) from weights max(pb - c qb, 0); the workgroup
     // owning a sample writes output slot out_base + j
     auto draw = [&](double c, bool use_q, const float* u, int cnt, int out_base) -> bool {
       const double mine = sample_pass(c, use_q);
-      double* redw = a.red + ((long long)(prompt * 2 + parity) * a.G) * a.red_w;
-      if (tid == 0) redw[(long long)g * a.red_w] = mine;
-      if (!group_barrier(a, prompt, sh)) return false;
-      parity ^= 1;
-      double before = 0.0, Z = 0.0;
-      int last_nz = -1;
-      for (int w = 0; w < a.G; ++w) {
-        const double v = redw[(long long)w * a.red_w];
-        if (w < g) before += v;
-        Z += v;
-        if (v > 0.0) last_nz = w;
-      }
-      // per-thread contiguous sub-slices for the in-slice search
-      const long long len = e_hi - e_lo;
+      if (!group_gather(a, prompt, g, mine, epoch, sh)) return false;
+      // inclusive prefixes over the workgroups (same order everywhere) and over this workgroup's threads
       const long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
-      const long long t_lo = min(e_hi, e_lo + per * tid), t_hi = min(e_hi, t_lo + per);
+      const long long t_lo = min(len, per * tid), t_hi = min(len, t_lo + per);   // slice-local
       double ts = 0.0;
-      for (long long e = t_lo; e < t_hi; ++e) ts += use_q ? fmax(pb[e] - c * qb[e], 0.0) : pb[e];
-      __syncthreads();
-      sh.tsum[tid] = ts;
-      __syncthreads();
+      for (long long j = t_lo; j < t_hi; ++j) ts += use_q ? fmax(ps[j] - c * qs[j], 0.0) : ps[j];
+      {
+        const double gp = tid < a.G ? sh.gpart[tid] : 0.0;
+        const double gincl = block_inclusive_scan(gp, sh);
+        const double tincl = block_inclusive_scan(ts, sh);
+        if (tid == 0) sh.found = -1;
+        __syncthreads();
+        if (tid < a.G) { sh.gpart[tid] = gincl; if (gp > 0.0) atomicMax(&sh.found, tid); }
+        sh.tsum[tid] = tincl;
+        __syncthreads();
+      }
+      const double Z = sh.gpart[a.G - 1];
+      const double before = g > 0 ? sh.gpart[g - 1] : 0.0;
+      const int last_nz = max(sh.found, 0);
       for (int j = 0; j < cnt; ++j) {
         const double target = (double)u[j] * Z;
         // owner: the first workgroup whose inclusive prefix exceeds the target
-        int owner = -1;
-        double acc = 0.0;
-        for (int w = 0; w < a.G; ++w) {
-          acc += redw[(long long)w * a.red_w];
-          if (acc > target) { owner = w; break; }
-        }
-        if (owner < 0) owner = last_nz;
+        int lo = 0, hi = a.G;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (sh.gpart[mid] > target) hi = mid; else lo = mid + 1; }
+        const int owner = lo < a.G ? lo : last_nz;
         if (owner != g) continue;            // uniform over the block
-        if (tid == 0) {
-          // thread whose inclusive prefix exceeds the local target
-          double accl = before;
-          int th = -1;
-          for (int k = 0; k < VL_BLOCK; ++k) {
-            const double nx = accl + sh.tsum[k];
-            if (nx > target) { th = k; break; }
-            accl = nx;
-          }
-          if (th < 0) {                       // rounding: take the last thread with mass
-            accl = before;
-            double run = before;
-            for (int k = 0; k < VL_BLOCK; ++k) { if (sh.tsum[k] > 0.0) { th = k; accl = run; } run += sh.tsum[k]; }
-          }
-          sh.found = th;
-          sh.bcast = accl;
+        // thread whose inclusive prefix exceeds the target (rounding: else the last thread with mass)
+        lo = 0; hi = VL_BLOCK;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (before + sh.tsum[mid] > target) hi = mid; else lo = mid + 1; }
+        int th = lo;
+        if (th >= VL_BLOCK) {
+          th = VL_BLOCK - 1;
+          while (th > 0 && !(sh.tsum[th] > sh.tsum[th - 1])) --th;
         }
-        __syncthreads();
-        if (tid == sh.found) {
-          double accl = sh.bcast;
+        if (tid == th) {
+          double accl = before + (th > 0 ? sh.tsum[th - 1] : 0.0);
           long long pick = -1, last = -1;
-          for (long long e = t_lo; e < t_hi; ++e) {
-            const double v = use_q ? fmax(pb[e] - c * qb[e], 0.0) : pb[e];
-            if (v > 0.0) last = e;
+          for (long long jj = t_lo; jj < t_hi; ++jj) {
+            const double v = use_q ? fmax(ps[jj] - c * qs[jj], 0.0) : ps[jj];
+            if (v > 0.0) last = jj;
             accl += v;
-            if (accl > target) { pick = e; break; }
+            if (accl > target) { pick = jj; break; }
           }
           if (pick < 0) pick = last >= 0 ? last : t_lo;
+          pick += e_lo;                       // back to the flat index over I x V
           const int i = (int)(pick / V);
           const int x = (int)(pick - (long long)i * V);
           const int node = sh.I_node[i];
@@ -488,11 +619,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           a.out.out_logp_target[o] = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
           a.out.out_logp_draft[o] = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
         }
-        __syncthreads();
       }
+      __syncthreads();
       return true;
     };
 
+    stamp(23);
     if (bonus) {
       // ===== every draft layer passed: W_L beams from p_beam^(gamma+1)
       if (!draw(0.0, false, u_fill + (long long)l * a.W_cap, min(W_in, a.W_cap), 0)) return;
@@ -509,8 +641,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     __syncthreads();
     for (int i = tid; i < n_pn; i += VL_BLOCK) {
       const int n = n_begin + i;
-      if (a.depth[n] == l) {
-        const int par = a.parent[n];
+      if (sh.n_depth[i] == l) {
+        const int par = sh.n_parent[i];
         const bool cand = par >= n_begin && par < n && sh.slot_of[par - n_begin] >= 0;
         if (cand) sh.S_tmp[atomicAdd(&sh.counter, 1)] = n;
         else if (g == 0) a.out.node_status[n] = DSBD_PRUNED;
@@ -520,11 +652,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const int M = sh.counter;
     for (int i = tid; i < M; i += VL_BLOCK) {
       const int n = sh.S_tmp[i];
-      const int rk = a.rank ? a.rank[n] : 0;
+      const int rk = sh.n_rank[n - n_begin];
       int pos = 0;
       for (int j = 0; j < M; ++j) {
         const int n2 = sh.S_tmp[j];
-        const int rk2 = a.rank ? a.rank[n2] : 0;
+        const int rk2 = sh.n_rank[n2 - n_begin];
         pos += (rk2 < rk) || (rk2 == rk && n2 < n);
       }
       sh.S_node[pos] = n;
@@ -533,10 +665,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // p_beam and q_beam at every candidate's (parent beam, token)
     for (int i = tid; i < M; i += VL_BLOCK) {
       const int n = sh.S_node[i];
-      const int par = a.parent[n];
+      const int par = sh.n_parent[n - n_begin];
       const int slot = sh.slot_of[par - n_begin];
-      int tok = a.token[n];
-      if (tok < 0 || tok >= V) tok = 0;
+      const int tok = sh.n_token[n - n_begin];
       sh.S_pb[i] = exp((double)a.zp[(long long)par * V + tok] - sh.max_p[slot]) * sh.sp[slot];
       sh.S_qb[i] = exp((double)a.zq[(long long)par * V + tok] - sh.max_q[slot]) * sh.sq[slot];
     }
@@ -547,11 +678,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     auto extend_chain = [&]() -> bool {
       const int k = sh.kmax;
       const double c = sh.cc[k] + sh.FF[k];
-      double s = 0.0;
-      for (long long e = e_lo + tid; e < e_hi; e += VL_BLOCK) s += fmax(pb[e] - c * qb[e], 0.0);
-      s = block_sum(s, sh);
+      const double s = block_sum(slice_sum(c, true), sh);
       bool okb = true;
-      const double F = group_sum(a, prompt, g, s, parity, sh, okb);
+      const double F = group_sum(a, prompt, g, s, epoch, sh, okb);
       if (!okb) return false;
       __syncthreads();
       if (tid == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1; }
@@ -559,6 +688,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       return true;
     };
 
+    stamp(30);
     // ===== width of the layer
     int WL = W_in;
     if (dynamic) {
@@ -614,6 +744,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     WL = min(WL, a.W_cap);
     if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw + l] = WL;
 
+    stamp(40);
     // ===== sequential accept / reject (thread 0 decides; everybody helps when F is needed)
     if (tid == 0) { sh.acc_n = 0; sh.pos = 0; sh.kidx = 1; }
     __syncthreads();
@@ -633,7 +764,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           const double pbx = sh.S_pb[pos], qbx = sh.S_qb[pos];
           const double num = (k == 1) ? pbx : fmax(pbx - sh.cc[k] * qbx, 0.0) / sh.FF[k];
           const double ratio = (qbx == 0.0) ? INFINITY : num / qbx;
-          const double u = (double)a.u_acc[n];
+          const double u = (double)sh.n_u[n - n_begin];
           if (fabs(ratio - u) <= NEAR_TIE) near_tie++;
           if (u <= ratio) {
             sh.A_node[nacc] = n;
@@ -650,7 +781,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
       __syncthreads();
       if (sh.state == 0) break;
+      stamp(41);
       if (!extend_chain()) return;
+      stamp(42);
     }
     const int nacc = sh.acc_n, pos_end = sh.pos, kcur = sh.kidx;
     __syncthreads();
@@ -660,22 +793,22 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // cumulative likelihoods of the accepted beams (fp64)
     if (tid < nacc) {
       const int n = sh.A_node[tid];
-      const int par = a.parent[n];
+      const int par = sh.n_parent[n - n_begin];
       const int slot = sh.slot_of[par - n_begin];
-      int tok = a.token[n];
-      if (tok < 0 || tok >= V) tok = 0;
+      const int tok = sh.n_token[n - n_begin];
       sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)a.zp[(long long)par * V + tok] - sh.lse_p[slot]);
       sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)a.zq[(long long)par * V + tok] - sh.lse_q[slot]);
     }
     __syncthreads();
 
+    stamp(50);
     if (nacc < WL) {
       // ===== the layer falls short: accepted beams, one residual sample, then p_beam samples
       if (g == 0 && tid < nacc) {
         const int n = sh.A_node[tid];
         const long long o = (long long)prompt * a.W_cap + tid;
-        a.out.out_parent[o] = a.parent[n];
-        a.out.out_token[o] = a.token[n];
+        a.out.out_parent[o] = sh.n_parent[n - n_begin];
+        a.out.out_token[o] = sh.n_token[n - n_begin];
         a.out.out_node[o] = n;
         a.out.out_logp_target[o] = sh.A_cum_p[tid];
         a.out.out_logp_draft[o] = sh.A_cum_q[tid];
@@ -710,6 +843,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     __syncthreads();
   }
 
+  stamp(99);
+  if (g == 0) clear_out_slots(n_out);
   if (g == 0 && tid == 0) {
     a.out.l_last[prompt] = l_last;
     a.out.n_out[prompt] = n_out;
@@ -721,7 +856,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 namespace {
 
 struct VerifyPlan {
-  int nchunk, chunk, I_cap, G, red_w;
+  int nchunk, chunk, I_cap, G, red_w, lds_elems;
 };
 
 int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
@@ -766,16 +901,27 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   const long long joint = (long long)pl.I_cap * V;
   const int by_work = (int)((joint + 4095) / 4096);
   if (G > by_work) G = by_work;
+  if (const char* e = getenv("DSBD_VERIFY_G")) {   // tuning knob: workgroups per prompt
+    const int v = atoi(e);
+    if (v >= 1 && (long long)v * f->n_prompts <= cus) G = v;
+  }
   if (G < 1) G = 1;
+  if (G > 256) G = 256;
   pl.G = G;
   pl.red_w = 2 * pl.I_cap;
+  // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most 96 KiB for the two arrays
+  long long need = (joint + G - 1) / G;
+  need = (need + 1) & ~1LL;
+  const long long cap = 96 * 1024 / 16;
+  pl.lds_elems = (int)(need < cap ? need : cap);
   return pl;
 }
 
 size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const VerifyPlan& pl, int32_t** depth,
                     uint64_t** anc, float2** part, float** rowmax, float** lse32, double** pb, double** qb,
-                    double** red, unsigned int** bar) {
+                    double** red) {
   const size_t N = (size_t)f->n_nodes, P = (size_t)f->n_prompts;
+  ws.take<long long>(512);                 // timeline of the layer kernel (diagnostics), first in the workspace
   *depth = ws.take<int32_t>(N);
   *anc = ws.take<uint64_t>(N);
   *part = ws.take<float2>(2 * N * pl.nchunk);
@@ -783,8 +929,7 @@ size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const Veri
   *lse32 = ws.take<float>(2 * N);
   *pb = ws.take<double>(P * pl.I_cap * V);
   *qb = ws.take<double>(P * pl.I_cap * V);
-  *red = ws.take<double>(P * 2 * pl.G * pl.red_w);
-  *bar = ws.take<unsigned int>(P);
+  *red = ws.take<double>(P * 2 * pl.G * pl.red_w * 2);
   return ws.total();
 }
 
@@ -794,8 +939,8 @@ extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32
   if (check_verify(f, V, p) != DSBD_OK) return 0;
   const VerifyPlan pl = make_verify_plan(f, V, p);
   WorkspaceCarver ws(nullptr);
-  int32_t* d; uint64_t* an; float2* pt; float *rm, *ls; double *pb, *qb, *red; unsigned int* bar;
-  return carve_verify(ws, f, V, pl, &d, &an, &pt, &rm, &ls, &pb, &qb, &red, &bar) + 256;
+  int32_t* d; uint64_t* an; float2* pt; float *rm, *ls; double *pb, *qb, *red;
+  return carve_verify(ws, f, V, pl, &d, &an, &pt, &rm, &ls, &pb, &qb, &red) + 256;
 }
 
 extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
@@ -819,14 +964,16 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
-  int32_t* depth; uint64_t* anc; float2* part; float *rowmax, *lse32; double *pb, *qb, *red; unsigned int* bar;
-  carve_verify(ws, f, in->V, pl, &depth, &anc, &part, &rowmax, &lse32, &pb, &qb, &red, &bar);
+  int32_t* depth; uint64_t* anc; float2* part; float *rowmax, *lse32; double *pb, *qb, *red;
+  carve_verify(ws, f, in->V, pl, &depth, &anc, &part, &rowmax, &lse32, &pb, &qb, &red);
 
   // the persistent kernel needs all its workgroups resident at once
   static int max_blocks_per_cu = -1;
   if (max_blocks_per_cu < 0) {
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel, VL_BLOCK, 0) != hipSuccess || nb < 1)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel, VL_BLOCK, 96 * 1024) != hipSuccess || nb < 1)
       nb = 1;
     max_blocks_per_cu = nb;
   }
@@ -847,9 +994,12 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
 
   FinalizeArgs fa;
   fa.part = part; fa.n_nodes = f->n_nodes; fa.nchunk = pl.nchunk; fa.n_prompts = f->n_prompts;
-  fa.rowmax = rowmax; fa.lse32 = lse32; fa.out_lse[0] = out->lse_target; fa.out_lse[1] = out->lse_draft; fa.bar = bar;
-  const int fthreads = 2 * f->n_nodes > f->n_prompts ? 2 * f->n_nodes : f->n_prompts;
-  hipLaunchKernelGGL(vocab_stats_finalize_kernel, dim3((fthreads + 255) / 256), dim3(256), 0, stream, fa);
+  fa.rowmax = rowmax; fa.lse32 = lse32; fa.out_lse[0] = out->lse_target; fa.out_lse[1] = out->lse_draft;
+  fa.slots = reinterpret_cast<unsigned long long*>(red);
+  fa.n_slot_words = (long long)f->n_prompts * 2 * pl.G * pl.red_w * 2;
+  int fblocks = (2 * f->n_nodes + 255) / 256;
+  if (fblocks < 64) fblocks = 64;          // enough threads to clear the slots quickly
+  hipLaunchKernelGGL(vocab_stats_finalize_kernel, dim3(fblocks), dim3(256), 0, stream, fa);
   DSBD_HIP_LAUNCH_CHECK();
 
   LayersArgs la;
@@ -861,12 +1011,14 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.u_acc = in->u_accept; la.u_res = in->u_resid; la.u_fill = in->u_fill;
   la.W_L = p->W_L; la.W_min = p->W_min; la.W_cap = p->W_cap; la.t = p->t;
   la.out = *out; la.depth = depth; la.rowmax = rowmax; la.lse32 = lse32;
-  la.pb = pb; la.qb = qb; la.red = red; la.bar = bar;
-  la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.fault = fault;
+  la.pb = pb; la.qb = qb; la.red = red;
+  la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
+  la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;
   void* kargs[] = {&la};
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, true, stream);
   const hipError_t le = hipLaunchCooperativeKernel(reinterpret_cast<void*>(verify_layers_kernel),
-                                                   dim3((unsigned)grid3), dim3(VL_BLOCK), kargs, 0, stream);
+                                                   dim3((unsigned)grid3), dim3(VL_BLOCK), kargs,
+                                                   (size_t)pl.lds_elems * 16, stream);
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, false, stream);
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
 }

@@ -19,11 +19,13 @@
 // node and tests bits while handling the (at most two) steps that cover the tree's own rows.
 // Partial (m, l, O) of the KV splits go to the workspace; a second kernel merges them.
 #include "common.h"
+#include <stdlib.h>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 #define NEG_BIG (-1.0e30f)
+#define REF_SLACK 40.0f          // log2 headroom of the softmax reference before it is raised
 #define STEP 32                 // tokens per wave step (two 16-token MFMA tiles)
 #define VT_PITCH 36             // bf16 elements per row of the transposed V tile (32 + pad, multiple of 4)
 
@@ -46,7 +48,22 @@ struct AttnArgs {
   float* part_o;                // [nsplit][n_nodes*Hq][D]
   float* part_ml;               // [nsplit][n_nodes*Hq][2]
   int32_t* fault;
+  long long* trace;             // optional timeline of workgroup 0 (diagnostics): pairs (label, wall clock)
 };
+
+// 16-byte load through the GLOBAL address space.  The cache pointers come out of a pointer table in
+// memory, so the compiler only knows them as generic pointers and would emit FLAT loads, which count on
+// the LDS counter as well: every wait for an LDS read would then also wait for all K/V loads in flight.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_global_16(const void* p) {
+  const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ bf16x8 load_global_bf16x8(const void* p) {
+  union { uint4 u; bf16x8 v; } c;
+  c.u = load_global_16(p);
+  return c.v;
+}
 
 __device__ __forceinline__ void wave_lds_fence() {
   // orders this wave's LDS writes before its later LDS reads (other lanes' data); LDS executes a
@@ -132,7 +149,7 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
 #pragma unroll
     for (int j = 0; j < DS; ++j) {
       if (live) {
-        qf[rt][j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
+        qf[rt][j] = load_global_bf16x8(qp + 32 * j);
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[rt][j][e] = (__bf16)0.0f;
@@ -158,7 +175,7 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
   const bool block_live = rb * ROWS_B < R;
 
   bf16x8 kf[2][DS];
-  bf16x8 vr[VROUNDS][2];
+  uint4 vr[VROUNDS][2];             // raw V rows: 8 channels of one token per register quad
 
   // step -> (segment, first token, tokens in the segment)
   auto locate = [&](int st, const __bf16*& kp, const __bf16*& vp, long long& stride, int& tok0, int& len, bool& tree) {
@@ -174,7 +191,7 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
       const int tok = min(tok0 + 16 * tt + col, len - 1);
       const __bf16* p = kp + (long long)tok * stride + 8 * qd;
 #pragma unroll
-      for (int j = 0; j < DS; ++j) kf[tt][j] = *reinterpret_cast<const bf16x8*>(p + 32 * j);
+      for (int j = 0; j < DS; ++j) kf[tt][j] = load_global_bf16x8(p + 32 * j);
     }
   };
   auto load_v = [&](int st) {
@@ -185,7 +202,7 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int tok = min(tok0 + 2 * TG * k + 2 * v_tg + h, len - 1);
-        vr[k][h] = *reinterpret_cast<const bf16x8*>(vp + (long long)tok * stride + 8 * v_dl);
+        vr[k][h] = load_global_16(vp + (long long)tok * stride + 8 * v_dl);
       }
     }
   };
@@ -194,30 +211,33 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
   const bool active = block_live && st < st_end;
   if (active) { load_k(st); load_v(st); }
 
-  while (active && st < st_end) {
-    const __bf16 *kp_, *vp_; long long stride_; int tok0, seglen; bool is_tree;
+  // One step = 32 tokens of this wave: V goes to LDS transposed (two tokens packed per 32-bit write),
+  // the next step's V and K loads are issued as soon as their registers are free, S^T = K Q^T.
+  int tok0 = 0, nvalid = 0, st_next = 0;
+  bool is_tree = false;
+  floatx4 s[NRT][2];
+  auto step_front = [&]() {
+    const __bf16 *kp_, *vp_; long long stride_; int seglen;
     locate(st, kp_, vp_, stride_, tok0, seglen, is_tree);
-    const int nvalid = min(STEP, seglen - tok0);
-    const int st_next = st + TW;
-
-    // ---- V -> LDS, transposed, two tokens packed per 32-bit write; then its registers are free
+    nvalid = min(STEP, seglen - tok0);
+    st_next = st + TW;
     wave_lds_fence();
 #pragma unroll
     for (int k = 0; k < VROUNDS; ++k) {
       const int tokp = 2 * TG * k + 2 * v_tg;          // even token index within the step
+      const uint32_t ta[4] = {vr[k][0].x, vr[k][0].y, vr[k][0].z, vr[k][0].w};   // token tokp, channels 2c, 2c+1
+      const uint32_t tb[4] = {vr[k][1].x, vr[k][1].y, vr[k][1].z, vr[k][1].w};   // token tokp + 1
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        union { __bf16 h[2]; uint32_t u; } pk;
-        pk.h[0] = vr[k][0][e];
-        pk.h[1] = vr[k][1][e];
-        *reinterpret_cast<uint32_t*>(&vt[(8 * v_dl + e) * VT_PITCH + tokp]) = pk.u;
+      for (int c2 = 0; c2 < 4; ++c2) {
+        // (token, token+1) pairs of channel 2c (low halves) and 2c+1 (high halves)
+        const uint32_t lo = __builtin_amdgcn_perm(tb[c2], ta[c2], 0x05040100u);
+        const uint32_t hi = __builtin_amdgcn_perm(tb[c2], ta[c2], 0x07060302u);
+        *reinterpret_cast<uint32_t*>(&vt[(8 * v_dl + 2 * c2) * VT_PITCH + tokp]) = lo;
+        *reinterpret_cast<uint32_t*>(&vt[(8 * v_dl + 2 * c2 + 1) * VT_PITCH + tokp]) = hi;
       }
     }
     wave_lds_fence();
     if (st_next < st_end) load_v(st_next);
-
-    // ---- S^T tiles: tokens x query rows
-    floatx4 s[NRT][2];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
@@ -228,8 +248,62 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
         s[rt][tt] = acc;
       }
     if (st_next < st_end) load_k(st_next);
+  };
+  // O^T += V^T P^T
+  auto step_pv = [&](const bf16x8 (&pf)[NRT]) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      union { uint2 u[2]; bf16x8 v; } vf;
+      const __bf16* rowp = &vt[(16 * dt + col) * VT_PITCH];
+      vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 4 * qd);
+      vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * qd);
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);
+    }
+  };
 
-    // ---- online softmax, lane-local per query row; P^T becomes the next B operand
+  // Softmax numerators are taken against a per-row reference m_run that is NOT the exact running
+  // maximum: it is set by the first step with a valid score for the row and raised only when a score
+  // exceeds it by more than 2^REF_SLACK.  fp32 (and bf16, for P) have the exponent range for numerators
+  // up to 2^REF_SLACK, and the final division by the row sum removes the reference.  So the hot loop
+  // below is "exp2(s - m_run), accumulate": no rescaling of the output accumulators (which live in
+  // accumulation registers that vector ALU instructions cannot touch), no cross-lane traffic.  Steps
+  // that need a mask (tree rows, ragged tail) or a higher reference leave the hot loop and take the
+  // general path once.
+  while (active && st < st_end) {
+    bool general = false;
+    while (st < st_end) {                      // ---- hot loop
+      step_front();
+      if (is_tree || nvalid < STEP) { general = true; break; }
+      bool raise = false;
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float mx = fmaxf(fmaxf(s[rt][0][0], s[rt][0][1]), fmaxf(s[rt][0][2], s[rt][0][3]));
+        mx = fmaxf(mx, fmaxf(fmaxf(s[rt][1][0], s[rt][1][1]), fmaxf(s[rt][1][2], s[rt][1][3])));
+        raise = raise || (mx * a.scale_log2 > m_run[rt] + REF_SLACK);
+      }
+      if (__builtin_amdgcn_ballot_w64(raise) != 0ull) { general = true; break; }
+      bf16x8 pf[NRT];
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        const float nm = -m_run[rt];
+        float psum = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[rt][tt][i], a.scale_log2, nm));
+            psum += p;
+            pf[rt][4 * tt + i] = (__bf16)p;
+          }
+        l_run[rt] += psum;
+      }
+      step_pv(pf);
+      st = st_next;
+    }
+    if (!general) break;
+
+    // ---- general step: masks, reference raise with rescaling
     const bool need_mask = is_tree || nvalid < STEP;
     bf16x8 pf[NRT];
 #pragma unroll
@@ -252,36 +326,25 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
             if (valid) okbits |= 1u << (4 * tt + i); else sv[4 * tt + i] = NEG_BIG;
           }
       }
-      float mx = sv[0];
-#pragma unroll
-      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+      float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
       mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[rt], mx);
-      const float alpha = exp2f(m_run[rt] - m_new);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));                  // same value in the 4 lane groups of a row
+      const float m_new = (mx > m_run[rt] + REF_SLACK) ? mx : m_run[rt];
+      const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+      l_run[rt] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
+      m_run[rt] = m_new;
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float p = ((okbits >> e) & 1u) ? exp2f(sv[e] - m_new) : 0.f;
+        const float p = ((okbits >> e) & 1u) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
         psum += p;
         pf[rt][e] = (__bf16)p;
       }
-      l_run[rt] = l_run[rt] * alpha + psum;
-      m_run[rt] = m_new;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
+      l_run[rt] += psum;
     }
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      union { uint2 u[2]; bf16x8 v; } vf;
-      const __bf16* rowp = &vt[(16 * dt + col) * VT_PITCH];
-      vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 4 * qd);
-      vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * qd);
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);
-    }
+    step_pv(pf);
     st = st_next;
   }
 
@@ -346,6 +409,291 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Variant for many query rows per K/V stream (large trees and/or grouped-query attention): the RW
+// waves of a workgroup each keep 32 query rows (two 16-row tiles) and ALL consume the same 64-token
+// K/V tile, which is staged once through LDS: K row-major (padded rows, read back as MFMA A operands
+// with 16-byte reads), V transposed with token pairs packed.  Tiles are double-buffered: while tile t
+// is consumed from one buffer, tile t+1 sits in registers on its way to the other buffer and tile t+2
+// is in flight from HBM; one workgroup barrier per tile.  Two workgroups fit a CU (<= 256 registers,
+// < 80 KiB LDS), so one can compute while the other waits on memory.  The V^T tile is written with a
+// token-pair swizzle so that the 64 lanes of a transposing write hit 64 different banks.
+template <int D, int RW, int NRT>
+__global__ __launch_bounds__(64 * RW) __attribute__((amdgpu_waves_per_eu(NRT == 1 ? 4 : 2, NRT == 1 ? 4 : 2)))
+void forest_attention_shared_kernel(AttnArgs a) {
+  constexpr int NT = 64 * RW;
+  constexpr int TILE = 64;
+  constexpr int DS = D / 32, DT = D / 16;
+  constexpr int CG = D / 8;                 // 16-byte channel groups per row
+  constexpr int KP = D + 8;                 // K row pitch in elements (16 bytes of padding)
+  constexpr int VP = TILE + 8;              // V^T row pitch in elements
+  constexpr int KL = TILE * CG / NT;        // K 16-byte loads per thread and tile
+  constexpr int VI = (TILE / 2) * CG / NT;  // V (token pair, channel group) items per thread and tile
+  constexpr int ROWS_W = 16 * NRT, ROWS_B = ROWS_W * RW;
+
+  __shared__ __attribute__((aligned(16))) __bf16 k_lds[2][TILE * KP];
+  __shared__ __attribute__((aligned(16))) __bf16 v_lds[2][D * VP];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, qd = lane >> 4;
+
+  int bid = blockIdx.x;
+  const int split = bid % a.nsplit; bid /= a.nsplit;
+  const int rb = bid % a.n_rowblocks; bid /= a.n_rowblocks;
+  const int g = bid % a.Hkv;
+  const int b = bid / a.Hkv;
+
+  const int base = a.tree_off[b];
+  int n_b = a.tree_off[b + 1] - base;
+  if (base < 0 || n_b <= 0 || base + n_b > a.n_nodes) return;   // reported by the topology kernel
+  n_b = min(n_b, DSBD_MAX_TREE_NODES);
+  const int R = n_b * a.group;
+  if (rb * ROWS_B >= R) return;             // uniform over the workgroup
+  const int row0 = rb * ROWS_B + wave * ROWS_W;
+  const int n_rows_total = a.n_nodes * a.Hq;
+
+  int Ls = (a.shared_len && a.k_shared_ptr) ? a.shared_len[b] : 0;
+  int Lo = a.len[b];
+  Ls = max(Ls, 0); Lo = max(Lo, 0);
+  int bad = 0;
+  if ((long long)Ls + Lo > a.max_len) { bad |= DSBD_FAULT_BOUNDS; Ls = min(Ls, a.max_len); Lo = min(Lo, a.max_len - Ls); }
+  const long long hoff = (long long)g * a.head_stride;
+  const __bf16* k0 = Ls ? (const __bf16*)a.k_shared_ptr[b] : nullptr;
+  const __bf16* v0 = Ls ? (const __bf16*)a.v_shared_ptr[b] : nullptr;
+  const __bf16* k1 = Lo ? (const __bf16*)a.k_ptr[b] : nullptr;
+  const __bf16* v1 = Lo ? (const __bf16*)a.v_ptr[b] : nullptr;
+  if (Ls && (!k0 || !v0 || (((uintptr_t)k0 | (uintptr_t)v0) & 15))) { bad |= DSBD_FAULT_BOUNDS; Ls = 0; }
+  if (Lo && (!k1 || !v1 || (((uintptr_t)k1 | (uintptr_t)v1) & 15))) { bad |= DSBD_FAULT_BOUNDS; Lo = 0; }
+  if (bad && tid == 0) atomicOr(a.fault, bad);
+  k0 += hoff; v0 += hoff; k1 += hoff; v1 += hoff;
+  const __bf16* k2 = a.k_tree + ((long long)base * a.Hkv + g) * D;
+  const __bf16* v2 = a.v_tree + ((long long)base * a.Hkv + g) * D;
+  const long long stride2 = (long long)a.Hkv * D;
+  const int n0 = (Ls + TILE - 1) / TILE, n1 = (Lo + TILE - 1) / TILE, n2 = (n_b + TILE - 1) / TILE;
+  const int total_tiles = n0 + n1 + n2;
+  const int per_split = (total_tiles + a.nsplit - 1) / a.nsplit;
+  const int t_begin = split * per_split;
+  const int t_end = min(total_tiles, t_begin + per_split);
+
+  // resident query fragments and ancestor bitmaps
+  bf16x8 qf[NRT][DS];
+  uint64_t anc[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int r = row0 + rt * 16 + col;
+    const bool live = r < R;
+    const int node = live ? r / a.group : 0;
+    const int head = g * a.group + (live ? r % a.group : 0);
+    anc[rt] = live ? a.anc_mask[base + node] : 0ull;
+    const __bf16* qp = a.q + ((long long)(base + node) * a.Hq + head) * D + 8 * qd;
+#pragma unroll
+    for (int j = 0; j < DS; ++j) {
+      if (live) {
+        qf[rt][j] = load_global_bf16x8(qp + 32 * j);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[rt][j][e] = (__bf16)0.0f;
+      }
+    }
+  }
+  floatx4 o[NRT][DT];
+  float m_run[NRT], l_run[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    m_run[rt] = NEG_BIG; l_run[rt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[rt][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  auto locate = [&](int ti, const __bf16*& kp, const __bf16*& vp, long long& stride, int& tok0, int& len, bool& tree) {
+    if (ti < n0) { kp = k0; vp = v0; stride = a.token_stride; tok0 = ti * TILE; len = Ls; tree = false; }
+    else if (ti < n0 + n1) { kp = k1; vp = v1; stride = a.token_stride; tok0 = (ti - n0) * TILE; len = Lo; tree = false; }
+    else { kp = k2; vp = v2; stride = stride2; tok0 = (ti - n0 - n1) * TILE; len = n_b; tree = true; }
+  };
+
+  uint4 kreg[KL];
+  uint4 vreg[VI][2];
+  auto load_tile = [&](int ti) {
+    const __bf16 *kp, *vp; long long stride; int tok0, len; bool tree;
+    locate(ti, kp, vp, stride, tok0, len, tree);
+#pragma unroll
+    for (int r = 0; r < KL; ++r) {
+      const int c = r * NT + tid;
+      const int tok = min(tok0 + c / CG, len - 1);
+      kreg[r] = load_global_16(kp + (long long)tok * stride + (c % CG) * 8);
+    }
+#pragma unroll
+    for (int r = 0; r < VI; ++r) {
+      const int it = r * NT + tid;
+      const int cg = it % CG;                 // CG consecutive lanes read one whole token row
+      const int tp = it / CG;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int tok = min(tok0 + 2 * tp + h, len - 1);
+        vreg[r][h] = load_global_16(vp + (long long)tok * stride + cg * 8);
+      }
+    }
+  };
+  auto store_tile = [&](int buf) {
+    __bf16* kl = k_lds[buf];
+    __bf16* vl = v_lds[buf];
+#pragma unroll
+    for (int r = 0; r < KL; ++r) {
+      const int c = r * NT + tid;
+      *reinterpret_cast<uint4*>(&kl[(c / CG) * KP + (c % CG) * 8]) = kreg[r];
+    }
+#pragma unroll
+    for (int r = 0; r < VI; ++r) {
+      const int it = r * NT + tid;
+      const int cg = it % CG;
+      const int tp = (it / CG) ^ (4 * (cg >> 1));   // token-pair swizzle: the 64 lanes of a write hit 64 banks
+      const uint32_t ta[4] = {vreg[r][0].x, vreg[r][0].y, vreg[r][0].z, vreg[r][0].w};
+      const uint32_t tb[4] = {vreg[r][1].x, vreg[r][1].y, vreg[r][1].z, vreg[r][1].w};
+#pragma unroll
+      for (int c2 = 0; c2 < 4; ++c2) {
+        const uint32_t lo = __builtin_amdgcn_perm(tb[c2], ta[c2], 0x05040100u);
+        const uint32_t hi = __builtin_amdgcn_perm(tb[c2], ta[c2], 0x07060302u);
+        *reinterpret_cast<uint32_t*>(&vl[(8 * cg + 2 * c2) * VP + 2 * tp]) = lo;
+        *reinterpret_cast<uint32_t*>(&vl[(8 * cg + 2 * c2 + 1) * VP + 2 * tp]) = hi;
+      }
+    }
+  };
+
+  int ti = t_begin;
+  if (ti < t_end) { load_tile(ti); store_tile(0); }
+  __syncthreads();
+  if (ti + 1 < t_end) load_tile(ti + 1);
+  int buf = 0;
+
+  while (ti < t_end) {
+    const __bf16 *kp_, *vp_; long long stride_; int tok0, seglen; bool is_tree;
+    locate(ti, kp_, vp_, stride_, tok0, seglen, is_tree);
+    const int nvalid = min(TILE, seglen - tok0);
+    const __bf16* kl = k_lds[buf];
+    const __bf16* vl = v_lds[buf];
+
+    // ---- S^T = K Q^T for the 4 token tiles and 2 row tiles of this wave
+    floatx4 s[NRT][4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) s[rt][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < DS; ++j) {
+        const bf16x8 kfrag = *reinterpret_cast<const bf16x8*>(&kl[(16 * tt + col) * KP + 32 * j + 8 * qd]);
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+          s[rt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfrag, qf[rt][j], s[rt][tt], 0, 0, 0);
+      }
+    }
+
+    // ---- softmax numerators against the per-row reference (see forest_attention_kernel)
+    const bool need_mask = is_tree || nvalid < TILE;
+    bf16x8 pf[NRT][2];
+    bool raise = false;
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float mx = s[rt][0][0];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[rt][tt][i]);
+      raise = raise || (mx * a.scale_log2 > m_run[rt] + REF_SLACK);
+    }
+    if (!need_mask && __builtin_amdgcn_ballot_w64(raise) == 0ull) {
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        const float nm = -m_run[rt];
+        float psum = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[rt][tt][i], a.scale_log2, nm));
+            psum += p;
+            pf[rt][tt >> 1][4 * (tt & 1) + i] = (__bf16)p;
+          }
+        l_run[rt] += psum;
+      }
+    } else {
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float sv[16];
+        unsigned okbits = 0;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int t = 16 * tt + 4 * qd + i;          // token within the tile
+            bool valid = t < nvalid;
+            if (is_tree) valid = valid && ((anc[rt] >> (tok0 + t)) & 1ull);
+            if (valid) okbits |= 1u << (4 * tt + i);
+            sv[4 * tt + i] = valid ? s[rt][tt][i] * a.scale_log2 : NEG_BIG;
+          }
+        float mx = sv[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sv[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = (mx > m_run[rt] + REF_SLACK) ? mx : m_run[rt];
+        const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+        l_run[rt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
+        m_run[rt] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = ((okbits >> e) & 1u) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
+          psum += p;
+          pf[rt][e >> 3][e & 7] = (__bf16)p;
+        }
+        l_run[rt] += psum;
+      }
+    }
+
+    // ---- O^T += V^T P^T, two 32-token halves
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        // rows 16dt .. 16dt+15 belong to channel groups 2dt, 2dt+1: token pairs are swizzled by 4*dt
+        union { uint2 u[2]; bf16x8 v; } vf;
+        const __bf16* rowp = &vl[(16 * dt + col) * VP];
+        vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 2 * qd) ^ (4 * dt)));
+        vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 8 + 2 * qd) ^ (4 * dt)));
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+          o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt][ks], o[rt][dt], 0, 0, 0);
+      }
+
+    // ---- advance the pipeline
+    if (ti + 1 < t_end) store_tile(buf ^ 1);
+    if (ti + 2 < t_end) load_tile(ti + 2);
+    __syncthreads();
+    buf ^= 1;
+    ++ti;
+  }
+
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    l_run[rt] += __shfl_xor(l_run[rt], 16);
+    l_run[rt] += __shfl_xor(l_run[rt], 32);
+    const int r = row0 + rt * 16 + col;
+    if (r < R) {
+      const int node = r / a.group;
+      const int head = g * a.group + r % a.group;
+      const long long grow = (long long)(base + node) * a.Hq + head;
+      const long long prow = (long long)split * n_rows_total + grow;
+      if (qd == 0) { a.part_ml[prow * 2] = m_run[rt]; a.part_ml[prow * 2 + 1] = l_run[rt]; }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+        *reinterpret_cast<floatx4*>(&a.part_o[prow * D + 16 * dt + 4 * qd]) = o[rt][dt];
+    }
+  }
+}
+
 // Merge the KV splits of every (node, head) row: out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.
 template <int D>
 __global__ __launch_bounds__(256) void forest_attention_combine_kernel(int n_rows_total, int nsplit,
@@ -380,21 +728,25 @@ namespace {
 
 struct AttnPlan {
   int nrt, rw, tw, rows_block, n_rowblocks, nsplit;
+  bool shared;      // LDS-shared K/V tiles (many rows per stream) instead of wave-private streams
+  int step;         // tokens per unit of split work
 };
 
 AttnPlan make_plan(const dsbd_forest* f, const dsbd_kv* kv, int Hq, int Hkv) {
   AttnPlan p;
   const int group = Hq / Hkv;
   const int rmax = f->max_tree_nodes * group;
+  p.shared = false;
+  p.step = STEP;
   if (rmax <= 16) { p.nrt = 1; p.rw = 1; p.tw = 4; }
   else if (rmax <= 32) { p.nrt = 2; p.rw = 1; p.tw = 4; }
-  else if (rmax <= 64) { p.nrt = 2; p.rw = 2; p.tw = 2; }
-  else { p.nrt = 4; p.rw = 2; p.tw = 2; }
+  else { p.nrt = 2; p.rw = 4; p.tw = 1; p.shared = true; p.step = 64; }   // 128 rows per workgroup
+  if (p.shared && getenv("DSBD_ATTN_WAVES8")) { p.nrt = 1; p.rw = 8; }   // tuning knob: 8 waves x 16 rows
   p.rows_block = 16 * p.nrt * p.rw;
   p.n_rowblocks = (rmax + p.rows_block - 1) / p.rows_block;
   // enough workgroups to cover the chip several times, but at least two steps per wave and split
   const long long units = (long long)f->n_trees * Hkv * p.n_rowblocks;
-  const int steps = (kv->max_len + STEP - 1) / STEP + 2;
+  const int steps = (kv->max_len + p.step - 1) / p.step + 2;
   int by_steps = steps / (2 * p.tw);
   if (by_steps < 1) by_steps = 1;
   int want = (int)((1024 + units - 1) / units);
@@ -405,6 +757,10 @@ AttnPlan make_plan(const dsbd_forest* f, const dsbd_kv* kv, int Hq, int Hkv) {
   p.nsplit = want < by_steps ? want : by_steps;
   if (p.nsplit > by_traffic) p.nsplit = by_traffic;
   if (p.nsplit > 64) p.nsplit = 64;
+  if (const char* e = getenv("DSBD_ATTN_NSPLIT")) {      // tuning knob: KV splits per (tree, KV head, row block)
+    const int v = atoi(e);
+    if (v >= 1 && v <= 64) p.nsplit = v;
+  }
   return p;
 }
 
@@ -433,10 +789,19 @@ void launch_attn(const AttnArgs& a, int grid, hipStream_t stream) {
 
 template <int D>
 void dispatch_attn(const AttnPlan& p, const AttnArgs& a, int grid, hipStream_t stream) {
-  if (p.nrt == 1) launch_attn<D, 1, 1, 4>(a, grid, stream);
-  else if (p.nrt == 2 && p.rw == 1) launch_attn<D, 2, 1, 4>(a, grid, stream);
-  else if (p.nrt == 2) launch_attn<D, 2, 2, 2>(a, grid, stream);
-  else launch_attn<D, 4, 2, 2>(a, grid, stream);
+  if (p.shared) {
+    if constexpr (D == 128) {
+      if (p.nrt == 1) {
+        hipLaunchKernelGGL((forest_attention_shared_kernel<D, 8, 1>), dim3(grid), dim3(512), 0, stream, a);
+        return;
+      }
+    }
+    hipLaunchKernelGGL((forest_attention_shared_kernel<D, 4, 2>), dim3(grid), dim3(256), 0, stream, a);
+  } else if (p.nrt == 1) {
+    launch_attn<D, 1, 1, 4>(a, grid, stream);
+  } else {
+    launch_attn<D, 2, 1, 4>(a, grid, stream);
+  }
 }
 
 }  // namespace
@@ -446,6 +811,7 @@ extern "C" size_t dsbd_forest_attention_workspace_bytes(const dsbd_forest* f, co
   if (check_args(f, kv, Hq, Hkv, D) != DSBD_OK) return 0;
   const AttnPlan p = make_plan(f, kv, Hq, Hkv);
   WorkspaceCarver ws(nullptr);
+  ws.take<long long>(512);
   ws.take<uint64_t>((size_t)f->n_nodes);
   ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
   ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
@@ -472,6 +838,7 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
+  long long* trace = ws.take<long long>(512);
   uint64_t* anc = ws.take<uint64_t>((size_t)f->n_nodes);
   float* part_o = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
   float* part_ml = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
@@ -492,6 +859,7 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
   a.scale_log2 = sc * 1.4426950408889634f;
   a.nsplit = p.nsplit; a.n_rowblocks = p.n_rowblocks; a.max_len = kv->max_len;
   a.part_o = part_o; a.part_ml = part_ml; a.fault = fault;
+  a.trace = getenv("DSBD_ATTN_TRACE") ? trace : nullptr;
 
   const long long grid = (long long)f->n_trees * Hkv * p.n_rowblocks * p.nsplit;
   if (grid > 0x7fffffffLL) return DSBD_ERR_UNSUPPORTED;

@@ -431,8 +431,13 @@ void forest_attention_shared_kernel(AttnArgs a) {
   constexpr int VI = (TILE / 2) * CG / NT;  // V (token pair, channel group) items per thread and tile
   constexpr int ROWS_W = 16 * NRT, ROWS_B = ROWS_W * RW;
 
-  __shared__ __attribute__((aligned(16))) __bf16 k_lds[2][TILE * KP];
-  __shared__ __attribute__((aligned(16))) __bf16 v_lds[2][D * VP];
+  constexpr int OP = D + 4;                 // row pitch (floats) of the output staging tile
+  constexpr int TILE_BYTES = 2 * (TILE * KP + D * VP) * 2;
+  constexpr int OUT_BYTES = ROWS_B * OP * 4;
+  __shared__ __attribute__((aligned(16))) char smem[TILE_BYTES > OUT_BYTES ? TILE_BYTES : OUT_BYTES];
+  __bf16 (*k_lds)[TILE * KP] = reinterpret_cast<__bf16 (*)[TILE * KP]>(smem);
+  __bf16 (*v_lds)[D * VP] = reinterpret_cast<__bf16 (*)[D * VP]>(smem + 2 * TILE * KP * 2);
+  float* o_stage = reinterpret_cast<float*>(smem);   // reused after the last tile
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -512,6 +517,19 @@ void forest_attention_shared_kernel(AttnArgs a) {
     else { kp = k2; vp = v2; stride = stride2; tok0 = (ti - n0 - n1) * TILE; len = n_b; tree = true; }
   };
 
+  // optional timeline of workgroup 0 / thread 0 (build with -DDSBD_ATTN_TIMELINE, run with DSBD_ATTN_TRACE
+  // set): stamps are kept in LDS and copied out at the end, so that taking them adds no global-memory
+  // traffic to the waits being measured
+#ifdef DSBD_ATTN_TIMELINE
+  __shared__ long long trace_lds[2 * 120];
+  int trace_n = 0;
+  const bool tracing = a.trace != nullptr && blockIdx.x == 0 && tid == 0;
+  auto stamp = [&](int label) {
+    if (tracing && trace_n < 120) { trace_lds[2 * trace_n] = label; trace_lds[2 * trace_n + 1] = wall_clock64(); ++trace_n; }
+  };
+#else
+  auto stamp = [&](int) {};
+#endif
   uint4 kreg[KL];
   uint4 vreg[VI][2];
   auto load_tile = [&](int ti) {
@@ -573,6 +591,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
     const __bf16* kl = k_lds[buf];
     const __bf16* vl = v_lds[buf];
 
+    stamp(1);
     // ---- S^T = K Q^T for the 4 token tiles and 2 row tiles of this wave
     floatx4 s[NRT][4];
 #pragma unroll
@@ -588,6 +607,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
       }
     }
 
+    stamp(2);
     // ---- softmax numerators against the per-row reference (see forest_attention_kernel)
     const bool need_mask = is_tree || nvalid < TILE;
     bf16x8 pf[NRT][2];
@@ -653,6 +673,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
       }
     }
 
+    stamp(3);
     // ---- O^T += V^T P^T, two 32-token halves
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
@@ -668,30 +689,57 @@ void forest_attention_shared_kernel(AttnArgs a) {
           o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt][ks], o[rt][dt], 0, 0, 0);
       }
 
-    // ---- advance the pipeline
+    // ---- advance the pipeline: tile ti+1 (in registers) goes to the other LDS buffer, whose readers all
+    // passed the barrier that ended the previous iteration; then tile ti+2 is requested.  (Requesting it
+    // before this iteration's arithmetic measured slower: the loads then compete with the LDS traffic of
+    // the products for issue slots.)
+    stamp(4);
     if (ti + 1 < t_end) store_tile(buf ^ 1);
+    stamp(5);
     if (ti + 2 < t_end) load_tile(ti + 2);
+    stamp(6);
     __syncthreads();
     buf ^= 1;
     ++ti;
   }
 
+  // ---- partial results of this split: (m, l) per row, and O^T turned back into rows through LDS so
+  // that every row leaves as one contiguous 4*D-byte write instead of 16-byte pieces
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     l_run[rt] += __shfl_xor(l_run[rt], 16);
     l_run[rt] += __shfl_xor(l_run[rt], 32);
-    const int r = row0 + rt * 16 + col;
+    const int rl = wave * ROWS_W + rt * 16 + col;          // row within the block
+    const int r = rb * ROWS_B + rl;
+    if (r < R && qd == 0) {
+      const int node = r / a.group;
+      const int head = g * a.group + r % a.group;
+      const long long prow = (long long)split * n_rows_total + (long long)(base + node) * a.Hq + head;
+      a.part_ml[prow * 2] = m_run[rt];
+      a.part_ml[prow * 2 + 1] = l_run[rt];
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      *reinterpret_cast<floatx4*>(&o_stage[rl * OP + 16 * dt + 4 * qd]) = o[rt][dt];
+  }
+  __syncthreads();
+  constexpr int LPR_O = D / 4;              // lanes per output row (16 bytes each)
+  for (int c = tid; c < ROWS_B * LPR_O; c += NT) {
+    const int rl = c / LPR_O, part = c % LPR_O;
+    const int r = rb * ROWS_B + rl;
     if (r < R) {
       const int node = r / a.group;
       const int head = g * a.group + r % a.group;
-      const long long grow = (long long)(base + node) * a.Hq + head;
-      const long long prow = (long long)split * n_rows_total + grow;
-      if (qd == 0) { a.part_ml[prow * 2] = m_run[rt]; a.part_ml[prow * 2 + 1] = l_run[rt]; }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-        *reinterpret_cast<floatx4*>(&a.part_o[prow * D + 16 * dt + 4 * qd]) = o[rt][dt];
+      const long long prow = (long long)split * n_rows_total + (long long)(base + node) * a.Hq + head;
+      *reinterpret_cast<floatx4*>(&a.part_o[prow * D + 4 * part]) = *reinterpret_cast<const floatx4*>(&o_stage[rl * OP + 4 * part]);
     }
   }
+#ifdef DSBD_ATTN_TIMELINE
+  if (tracing) {
+    a.trace[0] = trace_n;
+    for (int i = 0; i < 2 * trace_n; ++i) a.trace[2 + i] = trace_lds[i];
+  }
+#endif
 }
 
 // Merge the KV splits of every (node, head) row: out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.

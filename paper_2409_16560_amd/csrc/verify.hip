@@ -429,8 +429,14 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const long long len = e_hi - e_lo;
     // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
     const bool in_lds = ch <= (long long)a.lds_elems;
-    double* ps = in_lds ? dyn_lds : pb + e_lo;
-    double* qs = in_lds ? dyn_lds + a.lds_elems : qb + e_lo;
+    // typed accessors (LDS or global): a generic pointer would turn every access into a FLAT instruction
+    double* const pbg = pb + e_lo;
+    double* const qbg = qb + e_lo;
+    const int qoff = a.lds_elems;
+    auto ldp = [&](long long j) -> double { return in_lds ? dyn_lds[j] : pbg[j]; };
+    auto ldq = [&](long long j) -> double { return in_lds ? dyn_lds[qoff + j] : qbg[j]; };
+    auto stp = [&](long long j, double v) { if (in_lds) dyn_lds[j] = v; else pbg[j] = v; };
+    auto stq = [&](long long j, double v) { if (in_lds) dyn_lds[qoff + j] = v; else qbg[j] = v; };
 
     // ===== p_beam / q_beam over I x V: exponentials, row sums (one exchange), scaling
     if (tid < nI) {
@@ -452,24 +458,26 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         double s_p = 0.0, s_q = 0.0;
         const long long joff = (long long)i * V - e_lo;
         long long x = x_lo + tid;
-        for (; x + 7 * VL_BLOCK < x_hi; x += 8 * VL_BLOCK) {     // eight logits of each model in flight
+        for (; x < x_hi; x += 8 * VL_BLOCK) {     // eight logits of each model in flight, ragged end predicated
           float fp[8], fq[8];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) { fp[k] = zp[x + k * VL_BLOCK]; fq[k] = zq[x + k * VL_BLOCK]; }
+          for (int k = 0; k < 8; ++k) {
+            const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
+            fp[k] = zp[xx]; fq[k] = zq[xx];
+          }
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
-            const double ep = exp((double)fp[k] - mp), eq = exp((double)fq[k] - mq);
-            ps[joff + x + k * VL_BLOCK] = ep; qs[joff + x + k * VL_BLOCK] = eq;
-            s_p += ep; s_q += eq;
+            if (x + k * VL_BLOCK < x_hi) {
+              const double ep = exp((double)fp[k] - mp), eq = exp((double)fq[k] - mq);
+              stp(joff + x + k * VL_BLOCK, ep); stq(joff + x + k * VL_BLOCK, eq);
+              s_p += ep; s_q += eq;
+            }
           }
         }
-        for (; x < x_hi; x += VL_BLOCK) {
-          const double ep = exp((double)zp[x] - mp), eq = exp((double)zq[x] - mq);
-          ps[joff + x] = ep; qs[joff + x] = eq;
-          s_p += ep; s_q += eq;
-        }
+        stamp(100);
         s_p = block_sum(s_p, sh);
         s_q = block_sum(s_q, sh);
+        stamp(101);
         if (tid == 0) { sh.colsum[2 * i] = s_p; sh.colsum[2 * i + 1] = s_q; }
       }
     }
@@ -481,6 +489,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const unsigned long long tag = exchange_tag(epoch);
       Slot* bank = exchange_bank(a, prompt, epoch);
       const int ncols = 2 * nI;
+      stamp(102);
       if (tid < ncols) slot_post(bank + (long long)g * a.red_w + tid, sh.colsum[tid], tag);
       int cpow = 1;
       while (cpow < ncols) cpow <<= 1;
@@ -531,7 +540,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
         const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
         const double fp = sh.sp[i], fq = sh.sq[i];
-        for (long long j = j_lo + tid; j < j_hi; j += VL_BLOCK) { ps[j] *= fp; qs[j] *= fq; }
+        for (long long j = j_lo + tid; j < j_hi; j += VL_BLOCK) { stp(j, ldp(j) * fp); stq(j, ldq(j) * fq); }
       }
     }
     __syncthreads();
@@ -543,17 +552,17 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       long long j = tid;
       if (use_q) {
         for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
-          const double p0 = ps[j], p1 = ps[j + VL_BLOCK], p2 = ps[j + 2 * VL_BLOCK], p3 = ps[j + 3 * VL_BLOCK];
-          const double q0 = qs[j], q1 = qs[j + VL_BLOCK], q2 = qs[j + 2 * VL_BLOCK], q3 = qs[j + 3 * VL_BLOCK];
+          const double p0 = ldp(j), p1 = ldp(j + VL_BLOCK), p2 = ldp(j + 2 * VL_BLOCK), p3 = ldp(j + 3 * VL_BLOCK);
+          const double q0 = ldq(j), q1 = ldq(j + VL_BLOCK), q2 = ldq(j + 2 * VL_BLOCK), q3 = ldq(j + 3 * VL_BLOCK);
           s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
           s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
         }
-        for (; j < len; j += VL_BLOCK) s0 += fmax(ps[j] - c * qs[j], 0.0);
+        for (; j < len; j += VL_BLOCK) s0 += fmax(ldp(j) - c * ldq(j), 0.0);
       } else {
         for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
-          s0 += ps[j]; s1 += ps[j + VL_BLOCK]; s2 += ps[j + 2 * VL_BLOCK]; s3 += ps[j + 3 * VL_BLOCK];
+          s0 += ldp(j); s1 += ldp(j + VL_BLOCK); s2 += ldp(j + 2 * VL_BLOCK); s3 += ldp(j + 3 * VL_BLOCK);
         }
-        for (; j < len; j += VL_BLOCK) s0 += ps[j];
+        for (; j < len; j += VL_BLOCK) s0 += ldp(j);
       }
       return (s0 + s1) + (s2 + s3);
     };
@@ -569,7 +578,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
       const long long t_lo = min(len, per * tid), t_hi = min(len, t_lo + per);   // slice-local
       double ts = 0.0;
-      for (long long j = t_lo; j < t_hi; ++j) ts += use_q ? fmax(ps[j] - c * qs[j], 0.0) : ps[j];
+      for (long long j = t_lo; j < t_hi; ++j) ts += use_q ? fmax(ldp(j) - c * ldq(j), 0.0) : ldp(j);
       {
         const double gp = tid < a.G ? sh.gpart[tid] : 0.0;
         const double gincl = block_inclusive_scan(gp, sh);
@@ -602,7 +611,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           double accl = before + (th > 0 ? sh.tsum[th - 1] : 0.0);
           long long pick = -1, last = -1;
           for (long long jj = t_lo; jj < t_hi; ++jj) {
-            const double v = use_q ? fmax(ps[jj] - c * qs[jj], 0.0) : ps[jj];
+            const double v = use_q ? fmax(ldp(jj) - c * ldq(jj), 0.0) : ldp(jj);
             if (v > 0.0) last = jj;
             accl += v;
             if (accl > target) { pick = jj; break; }

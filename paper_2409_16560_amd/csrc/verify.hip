@@ -8,7 +8,7 @@
 //    softmax work of the beam-sampling joint (Section 2.1) done once for every forest node.
 // 2. vocab_stats_finalize_kernel: merges the chunks into the exact row maximum and an fp32
 //    log-sum-exp per node, writes the per-node outputs and clears the synchronisation counters.
-// 3. verify_layers_kernel (latency-bound, persistent, cooperative launch): G workgroups per prompt walk
+// 3. verify_layers_kernel (latency-bound, persistent; all its workgroups must be resident at once): G workgroups per prompt walk
 //    the layers in order.  Every decision is taken in fp64.  For the layer's input beams I the
 //    workgroups materialise p_beam and q_beam over I x V (their slice each), and every dependent
 //    reduction over I x V is one pass over the slices plus one barrier among the G workgroups.
@@ -1023,11 +1023,13 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.pb = pb; la.qb = qb; la.red = red;
   la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
   la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;
-  void* kargs[] = {&la};
+  // Ordinary launch: the grid was checked above to fit the device at once, the stream's earlier kernels have
+  // drained by the time this one starts, and every wait inside the kernel is bounded.  (A cooperative launch
+  // would also guarantee co-residency against work on other streams, but it made rocprofv3 crash at process
+  // exit on ROCm 7.2 and costs extra launch latency.)
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, true, stream);
-  const hipError_t le = hipLaunchCooperativeKernel(reinterpret_cast<void*>(verify_layers_kernel),
-                                                   dim3((unsigned)grid3), dim3(VL_BLOCK), kargs,
-                                                   (size_t)pl.lds_elems * 16, stream);
+  hipLaunchKernelGGL(verify_layers_kernel, dim3((unsigned)grid3), dim3(VL_BLOCK), (size_t)pl.lds_elems * 16, stream, la);
+  const hipError_t le = hipGetLastError();
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, false, stream);
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
 }

@@ -21,6 +21,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0   # MI355X datasheet
+# HBM bytes per launch on c5 measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the same
+# counter reads for a 256 MiB copy): see profiles/bench_c5_hbm_traffic.md.  Only valid for the default workload.
+MEASURED_TRAFFIC_C5 = {"attention": 286.0e6 + 33.1e6, "vocab_stats": 254.5e6 + 0.06e6, "verify_layers": 48.9e6 + 0.8e6}
 
 
 def cpu_baseline(sample_trees=2):
@@ -143,7 +146,8 @@ def main():
                                   w.Hq, w.Hkv, w.D, w.V, "fixed" if args.t < 0 else "dynamic t=%g" % args.t),
                    "input_copies_rotated": len(sets)},
         "roofline": {"bound": "hbm", "kernel": args.kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_C5.get(args.kernel) if args.config == "c5" else None,
                      "algorithmic_bytes_per_launch": kbytes, "avg_launch_ms": kavg_ms, "launches_timed": len(kms)},
         "step_algorithmic_bytes": attn_bytes + verify_bytes,
         "step_hbm_frac": (attn_bytes + verify_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -21,7 +21,7 @@ def hipcc():
 
 def build(verbose=True):
     """Compile every translation unit and link the shared library. Always rebuilds."""
-    flags = [f for f in FLAGS if f != "-fgpu-rdc-"]
+    flags = [f for f in FLAGS if f != "-fgpu-rdc-"] + os.environ.get("DSBD_EXTRA_HIPCC_FLAGS", "").split()
     objs = []
     procs = []
     for src in SOURCES:

@@ -73,6 +73,14 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a workgroup-scope fence, for
+// which the compiler waits for ALL outstanding memory operations (vmcnt(0)) - including the K/V loads of
+// the next tile that were issued on purpose before the barrier, which would then never overlap with the
+// arithmetic.  Here only the LDS counter is drained; global loads stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int D, int NRT, int RW, int TW>
 __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
   static_assert(RW * TW == 4, "four waves per workgroup");
@@ -521,6 +529,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
   // set): stamps are kept in LDS and copied out at the end, so that taking them adds no global-memory
   // traffic to the waits being measured
 #ifdef DSBD_ATTN_TIMELINE
+  const long long wg_start = wall_clock64();
   __shared__ long long trace_lds[2 * 120];
   int trace_n = 0;
   const bool tracing = a.trace != nullptr && blockIdx.x == 0 && tid == 0;
@@ -579,8 +588,13 @@ void forest_attention_shared_kernel(AttnArgs a) {
   };
 
   int ti = t_begin;
-  if (ti < t_end) { load_tile(ti); store_tile(0); }
-  __syncthreads();
+  if (ti < t_end) load_tile(ti);
+  // Everything requested so far (query fragments, ancestor bitmaps, the first tile) is needed now anyway.
+  // Waiting for it explicitly, at a point that dominates the loop, keeps the compiler from re-waiting for
+  // the query loads at the loop header with a vmcnt(0) that would also drain the prefetched tile.
+  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), other counters untouched
+  if (ti < t_end) store_tile(0);
+  lds_barrier();
   if (ti + 1 < t_end) load_tile(ti + 1);
   int buf = 0;
 
@@ -592,91 +606,88 @@ void forest_attention_shared_kernel(AttnArgs a) {
     const __bf16* vl = v_lds[buf];
 
     stamp(1);
-    // ---- S^T = K Q^T for the 4 token tiles and 2 row tiles of this wave
-    floatx4 s[NRT][4];
-#pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) s[rt][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < DS; ++j) {
-        const bf16x8 kfrag = *reinterpret_cast<const bf16x8*>(&kl[(16 * tt + col) * KP + 32 * j + 8 * qd]);
-#pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-          s[rt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfrag, qf[rt][j], s[rt][tt], 0, 0, 0);
-      }
-    }
-
-    stamp(2);
-    // ---- softmax numerators against the per-row reference (see forest_attention_kernel)
+    // The tile is consumed in two 32-token halves (scores -> numerators -> O^T update per half), which keeps
+    // only 16 score and 8 numerator registers live next to the accumulators, so that the registers holding
+    // the NEXT tile's in-flight loads are never touched (a spill or reuse of them would force a wait for
+    // all outstanding K/V loads before the arithmetic, exposing the memory latency every tile).
     const bool need_mask = is_tree || nvalid < TILE;
-    bf16x8 pf[NRT][2];
-    bool raise = false;
 #pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-      float mx = s[rt][0][0];
+    for (int ks = 0; ks < 2; ++ks) {
+      // ---- S^T = K Q^T: 2 token tiles x NRT row tiles
+      floatx4 s[NRT][2];
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt)
+      for (int t2 = 0; t2 < 2; ++t2) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[rt][tt][i]);
-      raise = raise || (mx * a.scale_log2 > m_run[rt] + REF_SLACK);
-    }
-    if (!need_mask && __builtin_amdgcn_ballot_w64(raise) == 0ull) {
+        for (int rt = 0; rt < NRT; ++rt) s[rt][t2] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) {
-        const float nm = -m_run[rt];
-        float psum = 0.f;
+        for (int j = 0; j < DS; ++j) {
+          const bf16x8 kfrag = *reinterpret_cast<const bf16x8*>(&kl[(32 * ks + 16 * t2 + col) * KP + 32 * j + 8 * qd]);
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[rt][tt][i], a.scale_log2, nm));
-            psum += p;
-            pf[rt][tt >> 1][4 * (tt & 1) + i] = (__bf16)p;
-          }
-        l_run[rt] += psum;
-      }
-    } else {
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) {
-        float sv[16];
-        unsigned okbits = 0;
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int t = 16 * tt + 4 * qd + i;          // token within the tile
-            bool valid = t < nvalid;
-            if (is_tree) valid = valid && ((anc[rt] >> (tok0 + t)) & 1ull);
-            if (valid) okbits |= 1u << (4 * tt + i);
-            sv[4 * tt + i] = valid ? s[rt][tt][i] * a.scale_log2 : NEG_BIG;
-          }
-        float mx = sv[0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sv[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = (mx > m_run[rt] + REF_SLACK) ? mx : m_run[rt];
-        const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
-        l_run[rt] *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
-        m_run[rt] = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = ((okbits >> e) & 1u) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
-          psum += p;
-          pf[rt][e >> 3][e & 7] = (__bf16)p;
+          for (int rt = 0; rt < NRT; ++rt)
+            s[rt][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfrag, qf[rt][j], s[rt][t2], 0, 0, 0);
         }
-        l_run[rt] += psum;
       }
-    }
-
-    stamp(3);
-    // ---- O^T += V^T P^T, two 32-token halves
+      // ---- softmax numerators against the per-row reference (see forest_attention_kernel)
+      bf16x8 pf[NRT];
+      bool raise = false;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+      for (int rt = 0; rt < NRT; ++rt) {
+        float mx = fmaxf(fmaxf(s[rt][0][0], s[rt][0][1]), fmaxf(s[rt][0][2], s[rt][0][3]));
+        mx = fmaxf(mx, fmaxf(fmaxf(s[rt][1][0], s[rt][1][1]), fmaxf(s[rt][1][2], s[rt][1][3])));
+        raise = raise || (mx * a.scale_log2 > m_run[rt] + REF_SLACK);
+      }
+      if (!need_mask && __builtin_amdgcn_ballot_w64(raise) == 0ull) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          const float nm = -m_run[rt];
+          float psum = 0.f;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float p = __builtin_amdgcn_exp2f(fmaf(s[rt][t2][i], a.scale_log2, nm));
+              psum += p;
+              pf[rt][4 * t2 + i] = (__bf16)p;
+            }
+          l_run[rt] += psum;
+        }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          float sv[8];
+          unsigned okbits = 0;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int t = 32 * ks + 16 * t2 + 4 * qd + i;          // token within the tile
+              bool valid = t < nvalid;
+              if (is_tree) valid = valid && ((anc[rt] >> (tok0 + t)) & 1ull);
+              if (valid) okbits |= 1u << (4 * t2 + i);
+              sv[4 * t2 + i] = valid ? s[rt][t2][i] * a.scale_log2 : NEG_BIG;
+            }
+          float mx = sv[0];
+#pragma unroll
+          for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = (mx > m_run[rt] + REF_SLACK) ? mx : m_run[rt];
+          const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+          l_run[rt] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
+          m_run[rt] = m_new;
+          float psum = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float p = ((okbits >> e) & 1u) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
+            psum += p;
+            pf[rt][e] = (__bf16)p;
+          }
+          l_run[rt] += psum;
+        }
+      }
+      // ---- O^T += V^T P^T for this half
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         // rows 16dt .. 16dt+15 belong to channel groups 2dt, 2dt+1: token pairs are swizzled by 4*dt
@@ -686,19 +697,19 @@ void forest_attention_shared_kernel(AttnArgs a) {
         vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 8 + 2 * qd) ^ (4 * dt)));
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
-          o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt][ks], o[rt][dt], 0, 0, 0);
+          o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);
       }
+    }
 
     // ---- advance the pipeline: tile ti+1 (in registers) goes to the other LDS buffer, whose readers all
-    // passed the barrier that ended the previous iteration; then tile ti+2 is requested.  (Requesting it
-    // before this iteration's arithmetic measured slower: the loads then compete with the LDS traffic of
-    // the products for issue slots.)
+    // passed the barrier that ended the previous iteration; then tile ti+2 is requested and travels during
+    // the next tile's arithmetic.  (Requesting it before this iteration's arithmetic measured slower.)
     stamp(4);
     if (ti + 1 < t_end) store_tile(buf ^ 1);
     stamp(5);
     if (ti + 2 < t_end) load_tile(ti + 2);
     stamp(6);
-    __syncthreads();
+    lds_barrier();
     buf ^= 1;
     ++ti;
   }
@@ -735,6 +746,10 @@ void forest_attention_shared_kernel(AttnArgs a) {
     }
   }
 #ifdef DSBD_ATTN_TIMELINE
+  if (a.trace != nullptr && tid == 0 && blockIdx.x < 1024) {     // start / end of every workgroup
+    a.trace[1024 + 2 * blockIdx.x] = wg_start;
+    a.trace[1024 + 2 * blockIdx.x + 1] = wall_clock64();
+  }
   if (tracing) {
     a.trace[0] = trace_n;
     for (int i = 0; i < 2 * trace_n; ++i) a.trace[2 + i] = trace_lds[i];
@@ -859,7 +874,7 @@ extern "C" size_t dsbd_forest_attention_workspace_bytes(const dsbd_forest* f, co
   if (check_args(f, kv, Hq, Hkv, D) != DSBD_OK) return 0;
   const AttnPlan p = make_plan(f, kv, Hq, Hkv);
   WorkspaceCarver ws(nullptr);
-  ws.take<long long>(512);
+  ws.take<long long>(4096);
   ws.take<uint64_t>((size_t)f->n_nodes);
   ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
   ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
@@ -886,7 +901,7 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
-  long long* trace = ws.take<long long>(512);
+  long long* trace = ws.take<long long>(4096);
   uint64_t* anc = ws.take<uint64_t>((size_t)f->n_nodes);
   float* part_o = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
   float* part_ml = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);

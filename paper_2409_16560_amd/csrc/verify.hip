@@ -31,6 +31,7 @@
 #define NODE_CAP 512           // nodes of one prompt (all its trees)
 #define NEAR_TIE 1.0e-6
 #define SYNC_LIMIT_TICKS 300000000LL   // 3 s of the 100 MHz wall clock
+#define VL_DYN_LDS_BYTES (80 * 1024)   // dynamic LDS of the layer kernel (its static LDS takes most of the rest)
 
 // ------------------------------------------------------------------------------------------------ kernel 1
 struct StatsArgs {
@@ -120,11 +121,27 @@ struct FinalizeArgs {
   float* out_lse[2];
   unsigned long long* slots;   // exchange slots of the layer kernel, cleared here
   long long n_slot_words;
+  const int32_t *tree_prompt, *tree_off;
+  int n_trees;
+  int4* prompt_rec;            // [n_prompts] (first tree, end tree, first node, end node) of every prompt
 };
 
 __global__ void vocab_stats_finalize_kernel(FinalizeArgs a) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   for (long long k = i; k < a.n_slot_words; k += (long long)gridDim.x * blockDim.x) a.slots[k] = 0ull;
+  // trees of each prompt (tree_prompt is non-decreasing): the layer kernel starts from this record instead of
+  // searching with dependent loads of its own
+  for (int p = (int)(gridDim.x * blockDim.x) - 1 - i; p < a.n_prompts; p += gridDim.x * blockDim.x) {
+    int lo = 0, hi = a.n_trees;
+    while (lo < hi) { const int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] < p) lo = mid + 1; else hi = mid; }
+    const int t_first = lo;
+    hi = a.n_trees;
+    while (lo < hi) { const int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] <= p) lo = mid + 1; else hi = mid; }
+    const int t_end = lo;
+    int4 rec = make_int4(t_first, t_end, 0, 0);
+    if (t_end > t_first) { rec.z = a.tree_off[t_first]; rec.w = a.tree_off[t_end]; }
+    a.prompt_rec[p] = rec;
+  }
   if (i >= 2 * a.n_nodes) return;
   const float2* p = a.part + (long long)i * a.nchunk;
   float M = p[0].x, S = p[0].y;
@@ -149,6 +166,7 @@ struct LayersArgs {
   float t;
   dsbd_verify_out out;
   const int32_t* depth;
+  const int4* prompt_rec; // [n_prompts] (first tree, end tree, first node, end node)
   const float* rowmax;   // [2][n_nodes]
   const float* lse32;    // [2][n_nodes]
   double* pb;            // [n_prompts][I_cap*V]  p_beam slice storage
@@ -160,6 +178,10 @@ struct LayersArgs {
   int32_t* fault;
 };
 
+#define VL_WAVES (VL_BLOCK / 64)
+static_assert(NODE_CAP <= VL_BLOCK, "one thread per node of a prompt");
+static_assert(VL_WAVES == 8, "the fixed reduction trees below are written for eight waves");
+
 struct LayerShared {
   // input beams of the layer
   int I_node[64];
@@ -167,39 +189,97 @@ struct LayerShared {
   double lse_p[64], lse_q[64];       // fp64 log-sum-exp of their logit rows
   double max_p[64], max_q[64];       // exact row maxima
   double sp[64], sq[64];             // beam weight / row sum: p_beam(i,x) = exp(z - max) * sp[i]
-  // accepted beams of the layer (next layer's inputs)
-  int A_node[64];
+  // accepted beams of the layer (next layer's inputs): node and its position among the candidates
+  int A_node[64], A_idx[64];
   double A_cum_p[64], A_cum_q[64];
   // the prompt's nodes (loaded once: the sequential parts must not wait for global memory)
   int n_parent[NODE_CAP], n_token[NODE_CAP], n_rank[NODE_CAP];
   short n_depth[NODE_CAP];
   float n_u[NODE_CAP];               // accept uniform of each node
+  float n_maxp[NODE_CAP], n_maxq[NODE_CAP];   // exact maxima of each node's logit rows
   // candidates
   short slot_of[NODE_CAP];           // slot in I of a prompt node, -1 if not an input beam
   int S_node[NODE_CAP], S_tmp[NODE_CAP];
+  float S_zp[NODE_CAP], S_zq[NODE_CAP];   // logits at the candidates' (parent, token)
   double S_pb[NODE_CAP], S_qb[NODE_CAP];
   // residual chain and accept-count table
   double cc[NODE_CAP + 2], FF[NODE_CAP + 2];
-  double alpha[NODE_CAP + 2], first[NODE_CAP + 2], Pa[NODE_CAP + 2], Pb[NODE_CAP + 2];
-  double wsum[VL_BLOCK / 64];
+  union {
+    struct { double alpha[NODE_CAP + 2], first[NODE_CAP + 2]; } w;   // dynamic width only
+    double wpart[64 * VL_WAVES * 2];                                   // per-wave row sums of the exponential pass
+  } u;
+  double Pa[NODE_CAP + 2], Pb[NODE_CAP + 2];
+  double wsum[2][VL_WAVES];
+  double scan_w[VL_WAVES];
   double tsum[VL_BLOCK];
-  double colsum[128];                // this workgroup's row sums (p and q interleaved)
   double gpart[256];                 // one partial per workgroup of the prompt (G <= 256)
-  int state, kmax, counter, abort, found;
+  double exp_tab[64];                // 2^(j/64)
+  double d_target[64];               // sampling: u * total of each draw
+  int state[2];                      // outcome of the decision rounds, alternating entries
+  int kmax, counter, abort, found, sbad, sgamma;
   int acc_n, pos, kidx;        // accept loop: accepted so far, next candidate, chain index of p'
-  double bcast;
 };
+static_assert(sizeof(((LayerShared*)0)->u.w) >= sizeof(((LayerShared*)0)->u.wpart), "union sizes");
 
-__device__ __forceinline__ double block_sum(double v, LayerShared& sh) {
+// 2^(j/64), j = 0..63, correctly rounded
+__constant__ double c_exp2_tab[64] = {
+  0x1.0000000000000p+0, 0x1.02c9a3e778061p+0, 0x1.059b0d3158574p+0, 0x1.0874518759bc8p+0,
+  0x1.0b5586cf9890fp+0, 0x1.0e3ec32d3d1a2p+0, 0x1.11301d0125b51p+0, 0x1.1429aaea92de0p+0,
+  0x1.172b83c7d517bp+0, 0x1.1a35beb6fcb75p+0, 0x1.1d4873168b9aap+0, 0x1.2063b88628cd6p+0,
+  0x1.2387a6e756238p+0, 0x1.26b4565e27cddp+0, 0x1.29e9df51fdee1p+0, 0x1.2d285a6e4030bp+0,
+  0x1.306fe0a31b715p+0, 0x1.33c08b26416ffp+0, 0x1.371a7373aa9cbp+0, 0x1.3a7db34e59ff7p+0,
+  0x1.3dea64c123422p+0, 0x1.4160a21f72e2ap+0, 0x1.44e086061892dp+0, 0x1.486a2b5c13cd0p+0,
+  0x1.4bfdad5362a27p+0, 0x1.4f9b2769d2ca7p+0, 0x1.5342b569d4f82p+0, 0x1.56f4736b527dap+0,
+  0x1.5ab07dd485429p+0, 0x1.5e76f15ad2148p+0, 0x1.6247eb03a5585p+0, 0x1.6623882552225p+0,
+  0x1.6a09e667f3bcdp+0, 0x1.6dfb23c651a2fp+0, 0x1.71f75e8ec5f74p+0, 0x1.75feb564267c9p+0,
+  0x1.7a11473eb0187p+0, 0x1.7e2f336cf4e62p+0, 0x1.82589994cce13p+0, 0x1.868d99b4492edp+0,
+  0x1.8ace5422aa0dbp+0, 0x1.8f1ae99157736p+0, 0x1.93737b0cdc5e5p+0, 0x1.97d829fde4e50p+0,
+  0x1.9c49182a3f090p+0, 0x1.a0c667b5de565p+0, 0x1.a5503b23e255dp+0, 0x1.a9e6b5579fdbfp+0,
+  0x1.ae89f995ad3adp+0, 0x1.b33a2b84f15fbp+0, 0x1.b7f76f2fb5e47p+0, 0x1.bcc1e904bc1d2p+0,
+  0x1.c199bdd85529cp+0, 0x1.c67f12e57d14bp+0, 0x1.cb720dcef9069p+0, 0x1.d072d4a07897cp+0,
+  0x1.d5818dcfba487p+0, 0x1.da9e603db3285p+0, 0x1.dfc97337b9b5fp+0, 0x1.e502ee78b3ff6p+0,
+  0x1.ea4afa2a490dap+0, 0x1.efa1bee615a27p+0, 0x1.f50765b6e4540p+0, 0x1.fa7c1819e90d8p+0};
+
+// exp(x) for x <= 0 (about one ulp).  x = (64 m + j) ln2/64 + r with |r| <= ln2/128:
+// exp(x) = 2^m 2^(j/64) (1 + (e^r - 1)), the last factor from its Taylor polynomial of degree 6.  The generic
+// library routine costs about twice the fp64 instructions, and the exponential pass over I x V is bound by them.
+__device__ __forceinline__ double exp_nonpos(double x, const double* tab) {
+  x = fmax(x, -1000.0);                                    // exp underflows to zero long before
+  const double n = rint(x * 0x1.71547652b82fep+6);         // 64 / ln 2
+  double r = fma(n, -0x1.62e42fee00000p-7, x);             // ln2/64, leading 32 bits: n * hi is exact
+  r = fma(n, -0x1.a39ef35793c76p-39, r);
+  const int ni = (int)n;
+  double p = fma(r, 1.0 / 720.0, 1.0 / 120.0);
+  p = fma(r, p, 1.0 / 24.0);
+  p = fma(r, p, 1.0 / 6.0);
+  p = fma(r, p, 0.5);
+  p = fma(r * r, p, r);
+  const double T = tab[ni & 63];
+  return ldexp(fma(T, p, T), ni >> 6);
+}
+
+// floor(a / b) for 0 <= a, 0 < b, both below 2^52, without the 64-bit integer division sequence
+__device__ __forceinline__ long long div_floor(long long a, long long b) {
+  long long q = (long long)((double)a / (double)b);
+  if (q * b > a) --q;
+  else if ((q + 1) * b <= a) ++q;
+  return q;
+}
+
+__device__ __forceinline__ double wave_sum_down(double v) {     // total in lane 0
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sh.wsum[threadIdx.x >> 6] = v;
-  __syncthreads();
-  double tot = 0.0;
+  return v;
+}
+__device__ __forceinline__ double wave_sum_all(double v) {      // same total in every lane (addition commutes)
 #pragma unroll
-  for (int w = 0; w < VL_BLOCK / 64; ++w) tot += sh.wsum[w];
-  return tot;
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+__device__ __forceinline__ double wave_max_all(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
+  return v;
 }
 
 // Inclusive prefix sum over the block's threads in thread order (fixed tree: identical in every workgroup
@@ -212,10 +292,10 @@ __device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh
     if (lane >= off) v += up;
   }
   __syncthreads();
-  if (lane == 63) sh.wsum[wave] = v;
+  if (lane == 63) sh.scan_w[wave] = v;
   __syncthreads();
   double before = 0.0;
-  for (int w = 0; w < wave; ++w) before += sh.wsum[w];
+  for (int w = 0; w < wave; ++w) before += sh.scan_w[w];
   return before + v;
 }
 
@@ -226,7 +306,8 @@ __device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh
 // workgroup polls exactly the slots it needs.  The tag changes with every exchange, so a slot is valid
 // only once both words of the current exchange have landed; slots alternate between two banks, and a
 // workgroup can be at most one exchange ahead of the slowest one, so a bank is never overwritten while
-// somebody may still read it.
+// somebody may still read it.  (An exchange that nobody reads - every workgroup skips it alike - does not
+// change that: to write a bank again a workgroup must have completed the exchange in between.)
 struct Slot { unsigned long long w0, w1; };
 
 __device__ __forceinline__ unsigned long long exchange_tag(unsigned int epoch) {
@@ -252,46 +333,37 @@ __device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, doubl
   }
 }
 
+// One wave collects the first slot of all G workgroups (G <= 256), lane i the slots 4i..4i+3, with the loads of
+// a polling round in flight together.  v[k] = 0 for slots beyond G.  False if the wait gave up.
+__device__ __forceinline__ bool wave_collect4(Slot* bank, int red_w, int G, unsigned long long tag, double (&v)[4]) {
+  const int lane = threadIdx.x & 63;
+  bool have[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) { have[k] = (4 * lane + k >= G); v[k] = 0.0; }
+  long long t0 = 0;
+  for (int spin = 0;; ++spin) {
+    unsigned long long w0[4], w1[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      w0[k] = 0; w1[k] = 0;
+      if (!have[k]) {
+        Slot* s = bank + (long long)(4 * lane + k) * red_w;
+        w0[k] = __hip_atomic_load(&s->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        w1[k] = __hip_atomic_load(&s->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (!have[k] && (w0[k] ^ w1[k]) == tag) { v[k] = __longlong_as_double((long long)w0[k]); have[k] = true; }
+    if (have[0] && have[1] && have[2] && have[3]) return true;
+    if (spin == 0) t0 = wall_clock64();
+    else if ((spin & 63) == 0 && wall_clock64() - t0 > SYNC_LIMIT_TICKS) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
 __device__ __forceinline__ Slot* exchange_bank(const LayersArgs& a, int prompt, unsigned int epoch) {
   return reinterpret_cast<Slot*>(a.red) + ((long long)(prompt * 2 + (epoch & 1)) * a.G) * a.red_w;
-}
-
-// Ends an exchange: makes a failed wait visible to the whole workgroup.
-__device__ __forceinline__ bool exchange_finish(const LayersArgs& a, bool mine_ok, LayerShared& sh) {
-  if (!mine_ok) { sh.abort = 1; atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT); }
-  __syncthreads();
-  return sh.abort == 0;
-}
-
-// Sum over the prompt's G workgroups of one value each; identical result in every workgroup (same
-// values, same reduction tree).
-__device__ double group_sum(const LayersArgs& a, int prompt, int g, double local, unsigned int& epoch,
-                            LayerShared& sh, bool& ok) {
-  epoch += 1;
-  const unsigned long long tag = exchange_tag(epoch);
-  Slot* bank = exchange_bank(a, prompt, epoch);
-  if (threadIdx.x == 0) slot_post(bank + (long long)g * a.red_w, local, tag);
-  double v = 0.0;
-  bool mine = true;
-  if ((int)threadIdx.x < a.G) mine = slot_wait(bank + (long long)threadIdx.x * a.red_w, tag, v);
-  ok = exchange_finish(a, mine, sh);
-  return block_sum(ok ? v : 0.0, sh);
-}
-
-// Gathers one value of every workgroup into sh.gpart[0..G).
-__device__ bool group_gather(const LayersArgs& a, int prompt, int g, double local, unsigned int& epoch,
-                             LayerShared& sh) {
-  epoch += 1;
-  const unsigned long long tag = exchange_tag(epoch);
-  Slot* bank = exchange_bank(a, prompt, epoch);
-  if (threadIdx.x == 0) slot_post(bank + (long long)g * a.red_w, local, tag);
-  bool mine = true;
-  for (int w = threadIdx.x; w < a.G; w += VL_BLOCK) {
-    double v = 0.0;
-    mine = mine && slot_wait(bank + (long long)w * a.red_w, tag, v);
-    sh.gpart[w] = v;
-  }
-  return exchange_finish(a, mine, sh);
 }
 
 __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
@@ -300,8 +372,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   const int prompt = blockIdx.x / a.G;
   const int g = blockIdx.x % a.G;
   const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int V = a.V;
   unsigned int epoch = 0;      // exchanges so far; identical in every workgroup of the prompt
+  unsigned int wsum_round = 0; // alternates the two wsum buffers
+  unsigned int decide_round = 0;
   int trace_n = 0;
   auto stamp = [&](int label) {
     if (a.trace && blockIdx.x == 0 && tid == 0 && trace_n < 255) {
@@ -309,77 +384,74 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
   };
   stamp(0);
-  bool ok = true;
 
-  if (tid == 0) sh.abort = 0;
+  if (tid == 0) { sh.abort = 0; sh.sbad = 0; sh.sgamma = 0; }
+  if (tid < 64) sh.exp_tab[tid] = c_exp2_tab[tid];
 
-  // ---- trees and nodes of this prompt (tree_prompt is non-decreasing)
-  int t_first = 0, t_end = 0;
-  {
-    int lo = 0, hi = a.n_trees;
-    while (lo < hi) { int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] < prompt) lo = mid + 1; else hi = mid; }
-    t_first = lo;
-    hi = a.n_trees;
-    while (lo < hi) { int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] <= prompt) lo = mid + 1; else hi = mid; }
-    t_end = lo;
-  }
-  int n_roots = t_end - t_first;
-  int n_begin = 0, n_end = 0;
+  // ---- trees and nodes of this prompt (found by the statistics kernels' epilogue)
+  const int4 rec = a.prompt_rec[prompt];
+  const int t_first = rec.x;
+  int n_roots = rec.y - rec.x;
+  const int n_begin = rec.z, n_end = rec.w;
   int bad = 0;
-  if (n_roots > 0) { n_begin = a.tree_off[t_first]; n_end = a.tree_off[t_end]; }
+  if (n_roots < 0 || t_first < 0 || rec.y > a.n_trees) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
   if (n_roots > a.max_prompt_trees || n_roots > a.I_cap || n_roots > 64) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
   if (n_begin < 0 || n_end > a.n_nodes || n_end < n_begin) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
   if (n_end - n_begin > NODE_CAP) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
-  for (int b = t_first; b < t_first + n_roots; ++b) {
-    const int r0 = a.tree_off[b], r1 = a.tree_off[b + 1];
-    if (r0 < n_begin || r1 > n_end || r1 <= r0) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; break; }
-  }
-  const int n_pn = n_roots > 0 ? n_end - n_begin : 0;   // nodes of the prompt
+  int n_pn = n_roots > 0 ? n_end - n_begin : 0;          // nodes of the prompt
   const int Lw = a.max_depth + 2;                        // row length of the per-layer arrays
-
-  // ---- per-node outputs and initial statuses (first workgroup of the prompt)
-  int gamma = 0;
-  for (int i = tid; i < n_pn; i += VL_BLOCK) {
-    const int n = n_begin + i;
+  __syncthreads();
+  if (tid < n_roots) {                                   // every tree inside the prompt's node range
+    const int b = t_first + tid;
+    const int r0 = a.tree_off[b], r1 = a.tree_off[b + 1];
+    if (r0 < n_begin || r1 > n_end || r1 <= r0) atomicOr(&sh.sbad, DSBD_FAULT_TOPOLOGY);
+    sh.I_node[tid] = r0;
+    sh.cum_p[tid] = a.blp[b];
+    sh.cum_q[tid] = a.blq[b];
+  }
+  if (tid < n_pn) {
+    const int n = n_begin + tid;
     const int d = a.depth[n];
-    gamma = max(gamma, d);
     int tok = a.token[n];
-    if (tok < 0 || tok >= V) { bad |= DSBD_FAULT_TOKEN; tok = 0; }
-    sh.n_depth[i] = (short)d;
-    sh.n_parent[i] = a.parent[n];
-    sh.n_token[i] = tok;
-    sh.n_rank[i] = a.rank ? a.rank[n] : 0;
-    sh.n_u[i] = a.u_acc[n];
+    if (tok < 0 || tok >= V) { atomicOr(&sh.sbad, DSBD_FAULT_TOKEN); tok = 0; }
+    sh.n_depth[tid] = (short)d;
+    sh.n_parent[tid] = a.parent[n];
+    sh.n_token[tid] = tok;
+    sh.n_rank[tid] = a.rank ? a.rank[n] : 0;
+    sh.n_u[tid] = a.u_acc[n];
+    sh.n_maxp[tid] = a.rowmax[n];
+    sh.n_maxq[tid] = a.rowmax[a.n_nodes + n];
+    sh.slot_of[tid] = -1;
+    atomicMax(&sh.sgamma, d);
   }
-  {  // block max of gamma
-    __shared__ int sgamma;
-    if (tid == 0) sgamma = 0;
-    __syncthreads();
-    atomicMax(&sgamma, gamma);
-    __syncthreads();
-    gamma = min(sgamma, a.max_depth);
-  }
-  if (g == 0) {
-    for (int i = tid; i < n_pn; i += VL_BLOCK) {
-      const int n = n_begin + i;
-      const int par = sh.n_parent[i];
-      const bool root = sh.n_depth[i] == 0;
-      const int tok = sh.n_token[i];
-      float lp = 0.f, lq = 0.f;
-      if (!root && par >= n_begin && par < n) {
-        lp = a.zp[(long long)par * V + tok] - a.lse32[par];
-        lq = a.zq[(long long)par * V + tok] - a.lse32[a.n_nodes + par];
-      }
-      if (a.out.node_logp_target) a.out.node_logp_target[n] = lp;
-      if (a.out.node_logp_draft) a.out.node_logp_draft[n] = lq;
-      a.out.node_status[n] = root ? DSBD_ROOT : DSBD_NOT_REACHED;
+  __syncthreads();
+  bad |= sh.sbad;
+  if (sh.sbad & DSBD_FAULT_TOPOLOGY) { n_roots = 0; n_pn = 0; }
+  const int gamma = min(sh.sgamma, a.max_depth);
+  if (bad && g == 0 && tid == 0) atomicOr(a.fault, bad);
+
+  // ---- per-node log-probabilities: node g, g + G, ... of the prompt belong to this workgroup.  The loads are
+  // issued here and the values stored after the first exponential pass, so nobody waits for them.
+  float node_lp = 0.f, node_lq = 0.f;
+  const int my_node = g + tid * a.G;                     // prompt-local
+  if (my_node < n_pn) {
+    const int n = n_begin + my_node;
+    const int par = sh.n_parent[my_node];
+    if (sh.n_depth[my_node] != 0 && par >= n_begin && par < n) {
+      const int tok = sh.n_token[my_node];
+      node_lp = a.zp[(long long)par * V + tok] - a.lse32[par];
+      node_lq = a.zq[(long long)par * V + tok] - a.lse32[a.n_nodes + par];
     }
-    for (int i = tid; i < Lw; i += VL_BLOCK) a.out.layer_width[(long long)prompt * Lw + i] = 0;
   }
-  if (bad && g == 0) atomicOr(a.fault, bad);
-  // Output slots are written by exactly one workgroup each (sampled beams by the workgroup that owns the
-  // sample, everything else by the prompt's first workgroup): the XCDs' L2 caches are not coherent with
-  // each other, so two workgroups must never write the same word.
+  // ---- initial statuses (first workgroup of the prompt)
+  if (g == 0) {
+    if (tid < n_pn) a.out.node_status[n_begin + tid] = sh.n_depth[tid] == 0 ? DSBD_ROOT : DSBD_NOT_REACHED;
+    for (int i = tid; i < Lw; i += VL_BLOCK) a.out.layer_width[(long long)prompt * Lw + i] = i == 0 ? n_roots : 0;
+  }
+  // Output words are written by exactly one workgroup each (sampled beams by the workgroup that owns the
+  // sample, per-node log-probabilities by the node's workgroup, everything else by the prompt's first
+  // workgroup): the XCDs' L2 caches are not coherent with each other, so two workgroups must never write
+  // the same word.
   auto clear_out_slots = [&](int from) {
     for (int i = from + tid; i < a.W_cap; i += VL_BLOCK) {
       const long long o = (long long)prompt * a.W_cap + i;
@@ -405,17 +477,27 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 
   // ---- layer 1 inputs: the roots
   if (tid < n_roots) {
-    const int b = t_first + tid;
-    sh.I_node[tid] = a.tree_off[b];
-    sh.cum_p[tid] = a.blp[b];
-    sh.cum_q[tid] = a.blq[b];
+    const int i = sh.I_node[tid] - n_begin;
+    sh.max_p[tid] = (double)sh.n_maxp[i];
+    sh.max_q[tid] = (double)sh.n_maxq[i];
+    sh.slot_of[i] = (short)tid;
   }
   int nI = n_roots;
   int near_tie = 0;          // meaningful in thread 0
   int l_last = gamma + 1;
   int n_out = 0;
-  if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw] = n_roots;
   __syncthreads();
+
+  // total over the workgroup of one value per thread: valid in every thread after the barrier inside
+  auto wg_total = [&](double s) -> double {
+    s = wave_sum_down(s);
+    double* ws = sh.wsum[wsum_round & 1];
+    wsum_round += 1;
+    if (lane == 0) ws[wave] = s;
+    __syncthreads();
+    return ((ws[0] + ws[1]) + (ws[2] + ws[3])) + ((ws[4] + ws[5]) + (ws[6] + ws[7]));
+  };
+  auto give_up = [&]() { sh.abort = 1; atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT); };
 
   stamp(1);
   for (int l = 1; l <= gamma + 1; ++l) {
@@ -427,6 +509,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const long long e_lo = min(total, (long long)g * ch);
     const long long e_hi = min(total, e_lo + ch);
     const long long len = e_hi - e_lo;
+    const int i_lo = (int)div_floor(e_lo, V);
+    const int i_hi = e_hi > e_lo ? (int)div_floor(e_hi - 1, V) : i_lo - 1;
     // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
     const bool in_lds = ch <= (long long)a.lds_elems;
     // typed accessors (LDS or global): a generic pointer would turn every access into a FLAT instruction
@@ -438,187 +522,249 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     auto stp = [&](long long j, double v) { if (in_lds) dyn_lds[j] = v; else pbg[j] = v; };
     auto stq = [&](long long j, double v) { if (in_lds) dyn_lds[qoff + j] = v; else qbg[j] = v; };
 
-    // ===== p_beam / q_beam over I x V: exponentials, row sums (one exchange), scaling
-    if (tid < nI) {
-      const int node = sh.I_node[tid];
-      sh.max_p[tid] = (double)a.rowmax[node];
-      sh.max_q[tid] = (double)a.rowmax[a.n_nodes + node];
-    }
-    for (int i = tid; i < 2 * nI; i += VL_BLOCK) sh.colsum[i] = 0.0;
-    __syncthreads();
-    {
-      const int i_lo = (int)(e_lo / V), i_hi = e_hi > e_lo ? (int)((e_hi - 1) / V) : i_lo - 1;
-      for (int i = i_lo; i <= i_hi; ++i) {
-        const int node = sh.I_node[i];
-        const long long x_lo = max(e_lo, (long long)i * V) - (long long)i * V;
-        const long long x_hi = min(e_hi, (long long)(i + 1) * V) - (long long)i * V;
-        const float* zp = a.zp + (long long)node * V;
-        const float* zq = a.zq + (long long)node * V;
-        const double mp = sh.max_p[i], mq = sh.max_q[i];
-        double s_p = 0.0, s_q = 0.0;
-        const long long joff = (long long)i * V - e_lo;
-        long long x = x_lo + tid;
-        for (; x < x_hi; x += 8 * VL_BLOCK) {     // eight logits of each model in flight, ragged end predicated
-          float fp[8], fq[8];
+    // ===== p_beam / q_beam over I x V: exponentials and this workgroup's share of the row sums
+    for (int i = i_lo; i <= i_hi; ++i) {
+      const int node = sh.I_node[i];
+      const long long x_lo = max(e_lo, (long long)i * V) - (long long)i * V;
+      const long long x_hi = min(e_hi, (long long)(i + 1) * V) - (long long)i * V;
+      const float* zp = a.zp + (long long)node * V;
+      const float* zq = a.zq + (long long)node * V;
+      const double mp = sh.max_p[i], mq = sh.max_q[i];
+      double s_p = 0.0, s_q = 0.0;
+      const long long joff = (long long)i * V - e_lo;
+      for (long long x = x_lo + tid; x < x_hi; x += 8 * VL_BLOCK) {   // eight logits of each model in flight, ragged end predicated
+        float fp[8], fq[8];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
-            fp[k] = zp[xx]; fq[k] = zq[xx];
-          }
+        for (int k = 0; k < 8; ++k) {
+          const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
+          fp[k] = zp[xx]; fq[k] = zq[xx];
+        }
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            if (x + k * VL_BLOCK < x_hi) {
-              const double ep = exp((double)fp[k] - mp), eq = exp((double)fq[k] - mq);
-              stp(joff + x + k * VL_BLOCK, ep); stq(joff + x + k * VL_BLOCK, eq);
-              s_p += ep; s_q += eq;
-            }
+        for (int k = 0; k < 8; ++k) {
+          if (x + k * VL_BLOCK < x_hi) {
+            const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab), eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
+            stp(joff + x + k * VL_BLOCK, ep); stq(joff + x + k * VL_BLOCK, eq);
+            s_p += ep; s_q += eq;
           }
         }
-        stamp(100);
-        s_p = block_sum(s_p, sh);
-        s_q = block_sum(s_q, sh);
-        stamp(101);
-        if (tid == 0) { sh.colsum[2 * i] = s_p; sh.colsum[2 * i + 1] = s_q; }
+      }
+      s_p = wave_sum_down(s_p);
+      s_q = wave_sum_down(s_q);
+      if (lane == 0) {
+        sh.u.wpart[((i - i_lo) * VL_WAVES + wave) * 2] = s_p;
+        sh.u.wpart[((i - i_lo) * VL_WAVES + wave) * 2 + 1] = s_q;
       }
     }
+    if (l == 1 && my_node < n_pn) {
+      if (a.out.node_logp_target) a.out.node_logp_target[n_begin + my_node] = node_lp;
+      if (a.out.node_logp_draft) a.out.node_logp_draft[n_begin + my_node] = node_lq;
+    }
+    stamp(100);
     __syncthreads();
+    // ===== all-reduce of the 2|I| row sums.  Row i is spread over the workgroups floor(iV/ch) ..
+    // floor(((i+1)V-1)/ch): only those post its two columns and only those are polled.
+    epoch += 1;
+    const unsigned long long rs_tag = exchange_tag(epoch);
+    Slot* const rs_bank = exchange_bank(a, prompt, epoch);
+    if (tid < 2 * (i_hi - i_lo + 1)) {
+      const double* wp = &sh.u.wpart[(tid >> 1) * VL_WAVES * 2 + (tid & 1)];
+      const double s = ((wp[0] + wp[2]) + (wp[4] + wp[6])) + ((wp[8] + wp[10]) + (wp[12] + wp[14]));
+      slot_post(rs_bank + (long long)g * a.red_w + 2 * i_lo + tid, s, rs_tag);
+    }
+    stamp(102);
+
+    // ===== meanwhile: candidates = depth-l nodes whose parent is an input beam, in (rank, node) order
+    int M = 0;
+    float czp = 0.f, czq = 0.f;
+    if (!bonus) {
+      if (tid == 0) sh.counter = 0;
+      __syncthreads();
+      if (tid < n_pn && sh.n_depth[tid] == l) {
+        const int n = n_begin + tid;
+        const int par = sh.n_parent[tid];
+        const bool cand = par >= n_begin && par < n && sh.slot_of[par - n_begin] >= 0;
+        if (cand) sh.S_tmp[atomicAdd(&sh.counter, 1)] = n;
+        else if (g == 0) a.out.node_status[n] = DSBD_PRUNED;
+      }
+      __syncthreads();
+      M = sh.counter;
+      if (tid < M) {
+        const int n = sh.S_tmp[tid];
+        const int rk = sh.n_rank[n - n_begin];
+        int pos = 0;
+        for (int j = 0; j < M; ++j) {
+          const int n2 = sh.S_tmp[j];
+          const int rk2 = sh.n_rank[n2 - n_begin];
+          pos += (rk2 < rk) || (rk2 == rk && n2 < n);
+        }
+        sh.S_node[pos] = n;
+      }
+      __syncthreads();
+      if (tid < M) {      // logits at the candidate's (parent beam, token): in flight while the row sums arrive
+        const int n = sh.S_node[tid];
+        const int par = sh.n_parent[n - n_begin];
+        const int tok = sh.n_token[n - n_begin];
+        czp = a.zp[(long long)par * V + tok];
+        czq = a.zq[(long long)par * V + tok];
+      }
+    }
+
+    // ===== row sums: thread (r, c) gathers column c from every R-th workgroup that holds part of it
     {
-      // all-reduce of the 2|I| row sums: column c of workgroups w = r, r + R, ... is gathered by thread
-      // (r, c); the R partial sums of a column are then folded by a fixed tree.
-      epoch += 1;
-      const unsigned long long tag = exchange_tag(epoch);
-      Slot* bank = exchange_bank(a, prompt, epoch);
       const int ncols = 2 * nI;
-      stamp(102);
-      if (tid < ncols) slot_post(bank + (long long)g * a.red_w + tid, sh.colsum[tid], tag);
-      int cpow = 1;
-      while (cpow < ncols) cpow <<= 1;
-      const int R = VL_BLOCK / cpow;
-      const int c = tid % cpow, r = tid / cpow;
+      int cshift = 0;
+      while ((1 << cshift) < ncols) ++cshift;
+      const int cpow = 1 << cshift;
+      const int R = min(32, VL_BLOCK / cpow);
+      const int c = tid & (cpow - 1), r = tid >> cshift;
       double acc = 0.0;
       bool mine = true;
-      if (c < ncols)
-        for (int w = r; w < a.G; w += R) {
+      if (c < ncols && r < R) {
+        const int i = c >> 1;
+        const int w_lo = (int)div_floor((long long)i * V, ch);
+        const int w_hi = (int)div_floor((long long)(i + 1) * V - 1, ch);
+        for (int w = w_lo + r; w <= w_hi; w += R) {
           double v = 0.0;
-          mine = mine && slot_wait(bank + (long long)w * a.red_w + c, tag, v);
+          mine = mine && slot_wait(rs_bank + (long long)w * a.red_w + c, rs_tag, v);
           acc += v;
         }
-      sh.tsum[tid] = acc;
+      }
+      if (r < R) sh.tsum[tid] = acc;
       stamp(20);
-      if (!exchange_finish(a, mine, sh)) return;
+      if (!mine) give_up();
+      __syncthreads();
+      if (sh.abort) return;
       stamp(21);
-      for (int st = R >> 1; st >= 1; st >>= 1) {
-        if (r < st) sh.tsum[r * cpow + c] += sh.tsum[(r + st) * cpow + c];
-        __syncthreads();
+      // one wave: row totals, log-sum-exp, beam weights = softmax of the cumulative likelihoods over I
+      // (Section 2.1), scale factors
+      if (wave == 0) {
+        const bool valid = lane < nI;
+        double totp = 0.0, totq = 0.0;
+        if (valid)
+          for (int rr = 0; rr < R; ++rr) { totp += sh.tsum[rr * cpow + 2 * lane]; totq += sh.tsum[rr * cpow + 2 * lane + 1]; }
+        const double cp = valid ? sh.cum_p[lane] : -INFINITY, cq = valid ? sh.cum_q[lane] : -INFINITY;
+        const double mp = wave_max_all(cp), mq = wave_max_all(cq);
+        const double ep = valid ? exp_nonpos(cp - mp, sh.exp_tab) : 0.0, eq = valid ? exp_nonpos(cq - mq, sh.exp_tab) : 0.0;
+        const double zp = wave_sum_all(ep), zq = wave_sum_all(eq);
+        if (valid) {
+          sh.sp[lane] = (ep / zp) / totp;
+          sh.sq[lane] = (eq / zq) / totq;
+          sh.lse_p[lane] = sh.max_p[lane] + log(totp);
+          sh.lse_q[lane] = sh.max_q[lane] + log(totq);
+        }
       }
-      if (tid < ncols) {
-        const double tot = sh.tsum[tid];
-        const int i = tid >> 1;
-        if (tid & 1) { sh.lse_q[i] = sh.max_q[i] + log(tot); sh.sq[i] = tot; }
-        else { sh.lse_p[i] = sh.max_p[i] + log(tot); sh.sp[i] = tot; }
-      }
-    }
-    __syncthreads();
-    {
-      // beam weights: softmax of the cumulative likelihoods over I (Section 2.1); one thread per beam
-      double mp = sh.cum_p[0], mq = sh.cum_q[0];
-      for (int i = 1; i < nI; ++i) { mp = fmax(mp, sh.cum_p[i]); mq = fmax(mq, sh.cum_q[i]); }
-      if (tid < nI) { sh.A_cum_p[tid] = exp(sh.cum_p[tid] - mp); sh.A_cum_q[tid] = exp(sh.cum_q[tid] - mq); }
       __syncthreads();
-      double zp = 0.0, zq = 0.0;
-      for (int i = 0; i < nI; ++i) { zp += sh.A_cum_p[i]; zq += sh.A_cum_q[i]; }
-      __syncthreads();
-      if (tid < nI) {
-        sh.sp[tid] = (sh.A_cum_p[tid] / zp) / sh.sp[tid];
-        sh.sq[tid] = (sh.A_cum_q[tid] / zq) / sh.sq[tid];
-      }
     }
-    __syncthreads();
-    {
-      const int i_lo = (int)(e_lo / V), i_hi = e_hi > e_lo ? (int)((e_hi - 1) / V) : i_lo - 1;
-      for (int i = i_lo; i <= i_hi; ++i) {
-        const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
-        const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
-        const double fp = sh.sp[i], fq = sh.sq[i];
-        for (long long j = j_lo + tid; j < j_hi; j += VL_BLOCK) { stp(j, ldp(j) * fp); stq(j, ldq(j) * fq); }
-      }
+    for (int i = i_lo; i <= i_hi; ++i) {
+      const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
+      const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
+      const double fp = sh.sp[i], fq = sh.sq[i];
+      for (long long j = j_lo + tid; j < j_hi; j += VL_BLOCK) { stp(j, ldp(j) * fp); stq(j, ldq(j) * fq); }
     }
+    // p_beam and q_beam at every candidate's (parent beam, token)
+    if (tid < M) {
+      const int n = sh.S_node[tid];
+      const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
+      sh.S_zp[tid] = czp; sh.S_zq[tid] = czq;
+      sh.S_pb[tid] = exp_nonpos((double)czp - sh.max_p[slot], sh.exp_tab) * sh.sp[slot];
+      sh.S_qb[tid] = exp_nonpos((double)czq - sh.max_q[slot], sh.exp_tab) * sh.sq[slot];
+    }
+    if (tid == 0) { sh.cc[1] = 0.0; sh.FF[1] = 1.0; sh.kmax = 1; sh.acc_n = 0; sh.pos = 0; sh.kidx = 1; }
     __syncthreads();
 
     stamp(22);
-    // sum over the slice of max(p_beam - c q_beam, 0) (or of p_beam); four loads in flight per thread
-    auto slice_sum = [&](double c, bool use_q) -> double {
+    // sum over the slice of max(p_beam - c q_beam, 0); four loads in flight per thread
+    auto slice_sum = [&](double c) -> double {
       double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
       long long j = tid;
-      if (use_q) {
-        for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
-          const double p0 = ldp(j), p1 = ldp(j + VL_BLOCK), p2 = ldp(j + 2 * VL_BLOCK), p3 = ldp(j + 3 * VL_BLOCK);
-          const double q0 = ldq(j), q1 = ldq(j + VL_BLOCK), q2 = ldq(j + 2 * VL_BLOCK), q3 = ldq(j + 3 * VL_BLOCK);
-          s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
-          s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
-        }
-        for (; j < len; j += VL_BLOCK) s0 += fmax(ldp(j) - c * ldq(j), 0.0);
-      } else {
-        for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
-          s0 += ldp(j); s1 += ldp(j + VL_BLOCK); s2 += ldp(j + 2 * VL_BLOCK); s3 += ldp(j + 3 * VL_BLOCK);
-        }
-        for (; j < len; j += VL_BLOCK) s0 += ldp(j);
+      for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
+        const double p0 = ldp(j), p1 = ldp(j + VL_BLOCK), p2 = ldp(j + 2 * VL_BLOCK), p3 = ldp(j + 3 * VL_BLOCK);
+        const double q0 = ldq(j), q1 = ldq(j + VL_BLOCK), q2 = ldq(j + 2 * VL_BLOCK), q3 = ldq(j + 3 * VL_BLOCK);
+        s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
+        s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
       }
+      for (; j < len; j += VL_BLOCK) s0 += fmax(ldp(j) - c * ldq(j), 0.0);
       return (s0 + s1) + (s2 + s3);
     };
 
-    // sampling helper state: partial sums of max(pb - c qb, 0) of every workgroup
-    auto sample_pass = [&](double c, bool use_q) -> double { return block_sum(slice_sum(c, use_q), sh); };
-    // draws `cnt` samples with uniforms u[0..cnt) from weights max(pb - c qb, 0); the workgroup
-    // owning a sample writes output slot out_base + j
+    // Draws `cnt` samples (uniforms u[0..cnt)) from the weights max(p_beam - c q_beam, 0) (use_q) or p_beam over
+    // I x V by inverse CDF in flat order; the workgroup owning a sample writes output slot out_base + j.
     auto draw = [&](double c, bool use_q, const float* u, int cnt, int out_base) -> bool {
-      const double mine = sample_pass(c, use_q);
-      if (!group_gather(a, prompt, g, mine, epoch, sh)) return false;
-      // inclusive prefixes over the workgroups (same order everywhere) and over this workgroup's threads
+      float uj = 0.f;
+      if (tid < cnt) uj = u[tid];
+      // inclusive prefixes over this workgroup's threads (contiguous chunks) ...
       const long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
       const long long t_lo = min(len, per * tid), t_hi = min(len, t_lo + per);   // slice-local
       double ts = 0.0;
       for (long long j = t_lo; j < t_hi; ++j) ts += use_q ? fmax(ldp(j) - c * ldq(j), 0.0) : ldp(j);
-      {
-        const double gp = tid < a.G ? sh.gpart[tid] : 0.0;
-        const double gincl = block_inclusive_scan(gp, sh);
-        const double tincl = block_inclusive_scan(ts, sh);
-        if (tid == 0) sh.found = -1;
-        __syncthreads();
-        if (tid < a.G) { sh.gpart[tid] = gincl; if (gp > 0.0) atomicMax(&sh.found, tid); }
-        sh.tsum[tid] = tincl;
-        __syncthreads();
+      const double tincl = block_inclusive_scan(ts, sh);
+      sh.tsum[tid] = tincl;
+      if (tid == 0) sh.counter = 0;
+      __syncthreads();
+      // ... and over the workgroups (same order everywhere), gathered and scanned by one wave
+      epoch += 1;
+      const unsigned long long tag = exchange_tag(epoch);
+      Slot* bank = exchange_bank(a, prompt, epoch);
+      if (wave == 0) {
+        if (lane == 0) slot_post(bank + (long long)g * a.red_w, sh.tsum[VL_BLOCK - 1], tag);
+        double v[4];
+        if (!wave_collect4(bank, a.red_w, a.G, tag, v)) give_up();
+        int nz = -1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (v[k] > 0.0) nz = 4 * lane + k;
+        v[1] += v[0]; v[2] += v[1]; v[3] += v[2];
+        double incl = v[3];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const double up = __shfl_up(incl, off);
+          if (lane >= off) incl += up;
+        }
+        double excl = __shfl_up(incl, 1);
+        if (lane == 0) excl = 0.0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (4 * lane + k < a.G) sh.gpart[4 * lane + k] = excl + v[k];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) nz = max(nz, __shfl_xor(nz, off));
+        if (lane == 0) sh.found = nz;
       }
+      __syncthreads();
+      if (sh.abort) return false;
       const double Z = sh.gpart[a.G - 1];
       const double before = g > 0 ? sh.gpart[g - 1] : 0.0;
-      const int last_nz = max(sh.found, 0);
-      for (int j = 0; j < cnt; ++j) {
-        const double target = (double)u[j] * Z;
-        // owner: the first workgroup whose inclusive prefix exceeds the target
+      if (tid < cnt) {
+        const double target = (double)uj * Z;
+        sh.d_target[tid] = target;
+        // owner: the first workgroup whose inclusive prefix exceeds the target (rounding: the last one with mass)
         int lo = 0, hi = a.G;
         while (lo < hi) { const int mid = (lo + hi) >> 1; if (sh.gpart[mid] > target) hi = mid; else lo = mid + 1; }
-        const int owner = lo < a.G ? lo : last_nz;
-        if (owner != g) continue;            // uniform over the block
-        // thread whose inclusive prefix exceeds the target (rounding: else the last thread with mass)
-        lo = 0; hi = VL_BLOCK;
-        while (lo < hi) { const int mid = (lo + hi) >> 1; if (before + sh.tsum[mid] > target) hi = mid; else lo = mid + 1; }
-        int th = lo;
-        if (th >= VL_BLOCK) {
-          th = VL_BLOCK - 1;
-          while (th > 0 && !(sh.tsum[th] > sh.tsum[th - 1])) --th;
-        }
-        if (tid == th) {
+        const int owner = lo < a.G ? lo : max(sh.found, 0);
+        if (owner == g) sh.S_tmp[atomicAdd(&sh.counter, 1)] = tid;
+      }
+      __syncthreads();
+      const int n_mine = sh.counter;
+      for (int k = 0; k < n_mine; ++k) {
+        const int j = sh.S_tmp[k];
+        const double target = sh.d_target[j];
+        // the thread whose inclusive prefix is the first to exceed the target (rounding: the last one with mass,
+        // found by the last thread)
+        const bool above = before + sh.tsum[tid] > target;
+        const bool prev_above = tid > 0 && (before + sh.tsum[tid - 1] > target);
+        if ((above && !prev_above) || (tid == VL_BLOCK - 1 && !above)) {
+          int th = tid;
+          if (!above)
+            while (th > 0 && !(sh.tsum[th] > sh.tsum[th - 1])) --th;
+          const long long c_lo = min(len, per * th), c_hi = min(len, c_lo + per);
           double accl = before + (th > 0 ? sh.tsum[th - 1] : 0.0);
           long long pick = -1, last = -1;
-          for (long long jj = t_lo; jj < t_hi; ++jj) {
+          for (long long jj = c_lo; jj < c_hi; ++jj) {
             const double v = use_q ? fmax(ldp(jj) - c * ldq(jj), 0.0) : ldp(jj);
             if (v > 0.0) last = jj;
             accl += v;
             if (accl > target) { pick = jj; break; }
           }
-          if (pick < 0) pick = last >= 0 ? last : t_lo;
-          pick += e_lo;                       // back to the flat index over I x V
-          const int i = (int)(pick / V);
+          if (pick < 0) pick = last >= 0 ? last : c_lo;
+          pick = min(pick + e_lo, total - 1);   // back to the flat index over I x V
+          const int i = (int)div_floor(pick, V);
           const int x = (int)(pick - (long long)i * V);
           const int node = sh.I_node[i];
           const long long o = (long long)prompt * a.W_cap + out_base + j;
@@ -642,69 +788,101 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       break;
     }
 
-    // ===== candidates: depth-l nodes whose parent is an input beam, in (rank, node) order
-    for (int i = tid; i < n_pn; i += VL_BLOCK) sh.slot_of[i] = -1;
-    if (tid == 0) sh.counter = 0;
-    __syncthreads();
-    if (tid < nI) sh.slot_of[sh.I_node[tid] - n_begin] = (short)tid;
-    __syncthreads();
-    for (int i = tid; i < n_pn; i += VL_BLOCK) {
-      const int n = n_begin + i;
-      if (sh.n_depth[i] == l) {
-        const int par = sh.n_parent[i];
-        const bool cand = par >= n_begin && par < n && sh.slot_of[par - n_begin] >= 0;
-        if (cand) sh.S_tmp[atomicAdd(&sh.counter, 1)] = n;
-        else if (g == 0) a.out.node_status[n] = DSBD_PRUNED;
-      }
+    // ===== residual chain.  Entry 2 (c = 1) is needed by the first rejection of nearly every layer: its
+    // partial sums are posted ahead of time and collected only when it is asked for.
+    bool spec = false;
+    Slot* spec_bank = nullptr;
+    unsigned long long spec_tag = 0;
+    if (M > 0) {
+      const double tot = wg_total(slice_sum(1.0));
+      epoch += 1;
+      spec_tag = exchange_tag(epoch);
+      spec_bank = exchange_bank(a, prompt, epoch);
+      if (tid == 0) slot_post(spec_bank + (long long)g * a.red_w, tot, spec_tag);
+      spec = true;
     }
-    __syncthreads();
-    const int M = sh.counter;
-    for (int i = tid; i < M; i += VL_BLOCK) {
-      const int n = sh.S_tmp[i];
-      const int rk = sh.n_rank[n - n_begin];
-      int pos = 0;
-      for (int j = 0; j < M; ++j) {
-        const int n2 = sh.S_tmp[j];
-        const int rk2 = sh.n_rank[n2 - n_begin];
-        pos += (rk2 < rk) || (rk2 == rk && n2 < n);
-      }
-      sh.S_node[pos] = n;
-    }
-    __syncthreads();
-    // p_beam and q_beam at every candidate's (parent beam, token)
-    for (int i = tid; i < M; i += VL_BLOCK) {
-      const int n = sh.S_node[i];
-      const int par = sh.n_parent[n - n_begin];
-      const int slot = sh.slot_of[par - n_begin];
-      const int tok = sh.n_token[n - n_begin];
-      sh.S_pb[i] = exp((double)a.zp[(long long)par * V + tok] - sh.max_p[slot]) * sh.sp[slot];
-      sh.S_qb[i] = exp((double)a.zq[(long long)par * V + tok] - sh.max_q[slot]) * sh.sq[slot];
-    }
-    if (tid == 0) { sh.cc[1] = 0.0; sh.FF[1] = 1.0; sh.kmax = 1; }
-    __syncthreads();
 
-    // evaluates the next entry of the residual chain; returns false if the barrier gave up
-    auto extend_chain = [&]() -> bool {
-      const int k = sh.kmax;
-      const double c = sh.cc[k] + sh.FF[k];
-      const double s = block_sum(slice_sum(c, true), sh);
-      bool okb = true;
-      const double F = group_sum(a, prompt, g, s, epoch, sh, okb);
-      if (!okb) return false;
+    int WL = W_in;             // width of the layer, known before the first decision
+
+    // The accept / reject decisions of Algorithm 1 in candidate order, as far as the chain allows (one thread).
+    // Outcome in sh.state[round & 1]: 0 = finished, 1 = the next chain entry is needed.
+    auto decide = [&](unsigned int round) {
+      int pos = sh.pos, nacc = sh.acc_n, k = sh.kidx;
+      const int kmax = sh.kmax;
+      int state = 0;
+      while (true) {
+        if (pos >= M || nacc >= WL) { state = 0; break; }
+        if (k > kmax) { state = 1; break; }
+        if (k > 1 && !(sh.FF[k] > 0.0)) {
+          // a residual without mass (impossible in exact arithmetic): fall back to p_beam
+          atomicOr(a.fault, DSBD_FAULT_ZERO_RESIDUAL);
+          k = 1;
+        }
+        const int n = sh.S_node[pos];
+        const double pbx = sh.S_pb[pos], qbx = sh.S_qb[pos];
+        const double num = (k == 1) ? pbx : fmax(pbx - sh.cc[k] * qbx, 0.0) / sh.FF[k];
+        const double ratio = (qbx == 0.0) ? INFINITY : num / qbx;
+        const double u = (double)sh.n_u[n - n_begin];
+        if (fabs(ratio - u) <= NEAR_TIE) near_tie++;
+        if (u <= ratio) {
+          sh.A_node[nacc] = n;
+          sh.A_idx[nacc] = pos;
+          nacc++;
+          k = 1;
+          if (g == 0) a.out.node_status[n] = DSBD_ACCEPTED;
+        } else {
+          k++;
+          if (g == 0) a.out.node_status[n] = DSBD_REJECTED;
+        }
+        pos++;
+      }
+      sh.pos = pos; sh.acc_n = nacc; sh.kidx = k; sh.state[round & 1] = state;
+    };
+
+    // Appends entry kmax+1 to the residual chain: every workgroup sums its slice, the first wave exchanges the
+    // partial sums and, if asked to, carries on with the decisions right away.  All threads leave through one
+    // barrier; false = a wait gave up.
+    auto extend_chain = [&](bool then_decide) -> bool {
+      if (spec) {                      // entry 2 is already on its way
+        if (wave == 0) {
+          double v[4];
+          if (!wave_collect4(spec_bank, a.red_w, a.G, spec_tag, v)) give_up();
+          const double F = wave_sum_all((v[0] + v[1]) + (v[2] + v[3]));
+          if (lane == 0) {
+            sh.cc[2] = 1.0; sh.FF[2] = F; sh.kmax = 2;
+            if (then_decide) decide(decide_round);
+          }
+        }
+        spec = false;
+      } else {
+        const int k = sh.kmax;
+        const double c = sh.cc[k] + sh.FF[k];
+        const double tot = wg_total(slice_sum(c));
+        epoch += 1;
+        const unsigned long long tag = exchange_tag(epoch);
+        Slot* bank = exchange_bank(a, prompt, epoch);
+        if (wave == 0) {
+          if (lane == 0) slot_post(bank + (long long)g * a.red_w, tot, tag);
+          double v[4];
+          if (!wave_collect4(bank, a.red_w, a.G, tag, v)) give_up();
+          const double F = wave_sum_all((v[0] + v[1]) + (v[2] + v[3]));
+          if (lane == 0) {
+            sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1;
+            if (then_decide) decide(decide_round);
+          }
+        }
+      }
       __syncthreads();
-      if (tid == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1; }
-      __syncthreads();
-      return true;
+      return sh.abort == 0;
     };
 
     stamp(30);
     // ===== width of the layer
-    int WL = W_in;
     if (dynamic) {
       // alpha_j for j = 1..M (Eq. 3) from the chain; stop early if the residual mass vanishes
       bool dead = false;
       for (int j = 1; j <= M && !dead; ++j) {
-        if (!extend_chain()) return;
+        if (!extend_chain(false)) return;
         dead = !(sh.FF[j + 1] > 0.0);
       }
       const int kdone = sh.kmax;     // entries 1..kdone valid
@@ -713,18 +891,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
         double alpha = 1.0;            // no residual mass left: accepted with certainty
         if (i + 1 <= kdone && sh.FF[i] > 0.0) alpha = 1.0 - sh.FF[i + 1] / sh.FF[i];
-        sh.alpha[i] = alpha;
+        sh.u.w.alpha[i] = alpha;
       }
       __syncthreads();
       for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
-        double f = sh.alpha[i];
-        for (int j = 1; j < i; ++j) f *= (1.0 - sh.alpha[j]);
-        sh.first[i] = f;
+        double f = sh.u.w.alpha[i];
+        for (int j = 1; j < i; ++j) f *= (1.0 - sh.u.w.alpha[j]);
+        sh.u.w.first[i] = f;
       }
       if (tid == 0) {
         double none = 1.0;
         sh.Pa[0] = 1.0;
-        for (int m = 1; m <= M; ++m) { none *= (1.0 - sh.alpha[m]); sh.Pa[m] = none; }
+        for (int m = 1; m <= M; ++m) { none *= (1.0 - sh.u.w.alpha[m]); sh.Pa[m] = none; }
       }
       __syncthreads();
       // W~ = max{K : 1 - sum_{k<K} P(M,k) >= t}; K = 0 always qualifies
@@ -740,7 +918,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         for (int m = tid; m <= M; m += VL_BLOCK) {
           double tot = 0.0;
           if (m >= K)
-            for (int i = 1; i <= m; ++i) tot += sh.first[i] * ((m - i >= K - 1) ? sh.Pa[m - i] : 0.0);
+            for (int i = 1; i <= m; ++i) tot += sh.u.w.first[i] * ((m - i >= K - 1) ? sh.Pa[m - i] : 0.0);
           sh.Pb[m] = tot;
         }
         __syncthreads();
@@ -754,59 +932,27 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw + l] = WL;
 
     stamp(40);
-    // ===== sequential accept / reject (thread 0 decides; everybody helps when F is needed)
-    if (tid == 0) { sh.acc_n = 0; sh.pos = 0; sh.kidx = 1; }
+    // ===== sequential accept / reject
+    if (tid == 0) decide(decide_round);
     __syncthreads();
-    while (true) {
-      if (tid == 0) {
-        int pos = sh.pos, nacc = sh.acc_n, k = sh.kidx;
-        int state = 0;                   // 0 = finished, 1 = need the next chain entry
-        while (true) {
-          if (pos >= M || nacc >= WL) { state = 0; break; }
-          if (k > sh.kmax) { state = 1; break; }
-          if (k > 1 && !(sh.FF[k] > 0.0)) {
-            // a residual without mass (impossible in exact arithmetic): fall back to p_beam
-            atomicOr(a.fault, DSBD_FAULT_ZERO_RESIDUAL);
-            k = 1;
-          }
-          const int n = sh.S_node[pos];
-          const double pbx = sh.S_pb[pos], qbx = sh.S_qb[pos];
-          const double num = (k == 1) ? pbx : fmax(pbx - sh.cc[k] * qbx, 0.0) / sh.FF[k];
-          const double ratio = (qbx == 0.0) ? INFINITY : num / qbx;
-          const double u = (double)sh.n_u[n - n_begin];
-          if (fabs(ratio - u) <= NEAR_TIE) near_tie++;
-          if (u <= ratio) {
-            sh.A_node[nacc] = n;
-            nacc++;
-            k = 1;
-            if (g == 0) a.out.node_status[n] = DSBD_ACCEPTED;
-          } else {
-            k++;
-            if (g == 0) a.out.node_status[n] = DSBD_REJECTED;
-          }
-          pos++;
-        }
-        sh.pos = pos; sh.acc_n = nacc; sh.kidx = k; sh.state = state;
-      }
-      __syncthreads();
-      if (sh.state == 0) break;
+    while (sh.state[decide_round & 1] == 1) {
+      decide_round += 1;               // the next outcome goes to the other entry: nobody still reads it
       stamp(41);
-      if (!extend_chain()) return;
+      if (!extend_chain(true)) return;
       stamp(42);
     }
-    const int nacc = sh.acc_n, pos_end = sh.pos, kcur = sh.kidx;
-    __syncthreads();
+    decide_round += 1;
+    const int nacc = sh.acc_n, pos_end = sh.pos, kcur = sh.kidx, kmax_end = sh.kmax;
     if (g == 0)
       for (int i = pos_end + tid; i < M; i += VL_BLOCK) a.out.node_status[sh.S_node[i]] = DSBD_REJECTED;
 
     // cumulative likelihoods of the accepted beams (fp64)
     if (tid < nacc) {
       const int n = sh.A_node[tid];
-      const int par = sh.n_parent[n - n_begin];
-      const int slot = sh.slot_of[par - n_begin];
-      const int tok = sh.n_token[n - n_begin];
-      sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)a.zp[(long long)par * V + tok] - sh.lse_p[slot]);
-      sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)a.zq[(long long)par * V + tok] - sh.lse_q[slot]);
+      const int ci = sh.A_idx[tid];
+      const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
+      sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)sh.S_zp[ci] - sh.lse_p[slot]);
+      sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)sh.S_zq[ci] - sh.lse_q[slot]);
     }
     __syncthreads();
 
@@ -824,8 +970,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
       // p' = p'_kcur; its chain entry may still be missing if the last candidate was rejected
       int k = kcur;
-      if (k > sh.kmax) {
-        if (!extend_chain()) return;
+      if (k > kmax_end) {
+        if (!extend_chain(false)) return;
       }
       if (k > 1 && !(sh.FF[k] > 0.0)) {
         if (g == 0 && tid == 0) atomicOr(a.fault, DSBD_FAULT_ZERO_RESIDUAL);
@@ -842,11 +988,16 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
 
     // ===== the layer passed: its accepted beams are the next layer's inputs
+    if (tid < nI) sh.slot_of[sh.I_node[tid] - n_begin] = -1;
     __syncthreads();
     if (tid < nacc) {
+      const int i = sh.A_node[tid] - n_begin;
       sh.I_node[tid] = sh.A_node[tid];
       sh.cum_p[tid] = sh.A_cum_p[tid];
       sh.cum_q[tid] = sh.A_cum_q[tid];
+      sh.max_p[tid] = (double)sh.n_maxp[i];
+      sh.max_q[tid] = (double)sh.n_maxq[i];
+      sh.slot_of[i] = (short)tid;
     }
     nI = nacc;
     __syncthreads();
@@ -918,17 +1069,17 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   if (G > 256) G = 256;
   pl.G = G;
   pl.red_w = 2 * pl.I_cap;
-  // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most 96 KiB for the two arrays
+  // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most VL_DYN_LDS_BYTES for the two arrays
   long long need = (joint + G - 1) / G;
   need = (need + 1) & ~1LL;
-  const long long cap = 96 * 1024 / 16;
+  const long long cap = VL_DYN_LDS_BYTES / 16;
   pl.lds_elems = (int)(need < cap ? need : cap);
   return pl;
 }
 
 size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const VerifyPlan& pl, int32_t** depth,
                     uint64_t** anc, float2** part, float** rowmax, float** lse32, double** pb, double** qb,
-                    double** red) {
+                    double** red, int4** prompt_rec) {
   const size_t N = (size_t)f->n_nodes, P = (size_t)f->n_prompts;
   ws.take<long long>(512);                 // timeline of the layer kernel (diagnostics), first in the workspace
   *depth = ws.take<int32_t>(N);
@@ -939,6 +1090,7 @@ size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const Veri
   *pb = ws.take<double>(P * pl.I_cap * V);
   *qb = ws.take<double>(P * pl.I_cap * V);
   *red = ws.take<double>(P * 2 * pl.G * pl.red_w * 2);
+  *prompt_rec = ws.take<int4>(P);
   return ws.total();
 }
 
@@ -948,8 +1100,8 @@ extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32
   if (check_verify(f, V, p) != DSBD_OK) return 0;
   const VerifyPlan pl = make_verify_plan(f, V, p);
   WorkspaceCarver ws(nullptr);
-  int32_t* d; uint64_t* an; float2* pt; float *rm, *ls; double *pb, *qb, *red;
-  return carve_verify(ws, f, V, pl, &d, &an, &pt, &rm, &ls, &pb, &qb, &red) + 256;
+  int32_t* d; uint64_t* an; float2* pt; float *rm, *ls; double *pb, *qb, *red; int4* pr;
+  return carve_verify(ws, f, V, pl, &d, &an, &pt, &rm, &ls, &pb, &qb, &red, &pr) + 256;
 }
 
 extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
@@ -973,16 +1125,16 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
-  int32_t* depth; uint64_t* anc; float2* part; float *rowmax, *lse32; double *pb, *qb, *red;
-  carve_verify(ws, f, in->V, pl, &depth, &anc, &part, &rowmax, &lse32, &pb, &qb, &red);
+  int32_t* depth; uint64_t* anc; float2* part; float *rowmax, *lse32; double *pb, *qb, *red; int4* prompt_rec;
+  carve_verify(ws, f, in->V, pl, &depth, &anc, &part, &rowmax, &lse32, &pb, &qb, &red, &prompt_rec);
 
   // the persistent kernel needs all its workgroups resident at once
   static int max_blocks_per_cu = -1;
   if (max_blocks_per_cu < 0) {
     int nb = 0;
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel, VL_BLOCK, 96 * 1024) != hipSuccess || nb < 1)
+                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
       nb = 1;
     max_blocks_per_cu = nb;
   }
@@ -1006,6 +1158,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   fa.rowmax = rowmax; fa.lse32 = lse32; fa.out_lse[0] = out->lse_target; fa.out_lse[1] = out->lse_draft;
   fa.slots = reinterpret_cast<unsigned long long*>(red);
   fa.n_slot_words = (long long)f->n_prompts * 2 * pl.G * pl.red_w * 2;
+  fa.tree_prompt = f->tree_prompt; fa.tree_off = f->tree_off; fa.n_trees = f->n_trees; fa.prompt_rec = prompt_rec;
   int fblocks = (2 * f->n_nodes + 255) / 256;
   if (fblocks < 64) fblocks = 64;          // enough threads to clear the slots quickly
   hipLaunchKernelGGL(vocab_stats_finalize_kernel, dim3(fblocks), dim3(256), 0, stream, fa);
@@ -1019,7 +1172,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.blp = in->beam_logp_target; la.blq = in->beam_logp_draft;
   la.u_acc = in->u_accept; la.u_res = in->u_resid; la.u_fill = in->u_fill;
   la.W_L = p->W_L; la.W_min = p->W_min; la.W_cap = p->W_cap; la.t = p->t;
-  la.out = *out; la.depth = depth; la.rowmax = rowmax; la.lse32 = lse32;
+  la.out = *out; la.depth = depth; la.prompt_rec = prompt_rec; la.rowmax = rowmax; la.lse32 = lse32;
   la.pb = pb; la.qb = qb; la.red = red;
   la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
   la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;

@@ -189,6 +189,7 @@ struct LayerShared {
   double lse_p[64], lse_q[64];       // fp64 log-sum-exp of their logit rows
   double max_p[64], max_q[64];       // exact row maxima
   double sp[64], sq[64];             // beam weight / row sum: p_beam(i,x) = exp(z - max) * sp[i]
+  double bw_p[64], bw_q[64];         // beam weights
   // accepted beams of the layer (next layer's inputs): node and its position among the candidates
   int A_node[64], A_idx[64];
   double A_cum_p[64], A_cum_q[64];
@@ -202,6 +203,8 @@ struct LayerShared {
   int S_node[NODE_CAP], S_tmp[NODE_CAP];
   float S_zp[NODE_CAP], S_zq[NODE_CAP];   // logits at the candidates' (parent, token)
   double S_pb[NODE_CAP], S_qb[NODE_CAP];
+  float S_u[NODE_CAP];               // accept uniform of each candidate
+  unsigned char S_flag[NODE_CAP];    // test against p_beam itself: bit 0 = accepted, bit 1 = near tie
   // residual chain and accept-count table
   double cc[NODE_CAP + 2], FF[NODE_CAP + 2];
   union {
@@ -266,20 +269,39 @@ __device__ __forceinline__ long long div_floor(long long a, long long b) {
   return q;
 }
 
-__device__ __forceinline__ double wave_sum_down(double v) {     // total in lane 0
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off);
-  return v;
+// Wave-wide sum through the data-parallel-primitive lane moves (no LDS round trips as with shuffles): quads,
+// rows of 16, then the row totals across the four rows; lane 63 ends up with the total, which is handed to every
+// lane as a uniform value.  The order of the additions is fixed, so equal inputs give equal bits everywhere.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_move_f64(double v) {       // lanes without a source lane read 0.0
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
 }
-__device__ __forceinline__ double wave_sum_all(double v) {      // same total in every lane (addition commutes)
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
+__device__ __forceinline__ double wave_sum(double v) {
+  v += dpp_move_f64<0xB1, 0xf>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move_f64<0x4E, 0xf>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move_f64<0x124, 0xf>(v);   // row_ror:4
+  v += dpp_move_f64<0x128, 0xf>(v);   // row_ror:8: every lane holds the total of its row
+  v += dpp_move_f64<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_move_f64<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+  return __hiloint2double(hi, lo);
 }
 __device__ __forceinline__ double wave_max_all(double v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
   return v;
+}
+
+// Lanes of one wave handing values to each other through LDS: the hardware executes a wave's LDS instructions
+// in order, but the compiler reasons per thread and would otherwise be free to reuse a value it loaded before
+// another lane's store (or to forward only its own store).  This fence makes it reload.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Inclusive prefix sum over the block's threads in thread order (fixed tree: identical in every workgroup
@@ -333,13 +355,29 @@ __device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, doubl
   }
 }
 
-// One wave collects the first slot of all G workgroups (G <= 256), lane i the slots 4i..4i+3, with the loads of
-// a polling round in flight together.  v[k] = 0 for slots beyond G.  False if the wait gave up.
-__device__ __forceinline__ bool wave_collect4(Slot* bank, int red_w, int G, unsigned long long tag, double (&v)[4]) {
+// Single-value exchanges use a dense layout inside the bank: word w of workgroup w's value at words[w], its
+// tagged copy at words[G + w].  A polling wave then reads consecutive words (a few cache lines per round instead
+// of one line per slot), which matters because every workgroup polls every other one.
+__device__ __forceinline__ void dense_post(Slot* bank, int G, int g, double v, unsigned long long tag) {
+  unsigned long long* w = reinterpret_cast<unsigned long long*>(bank);
+  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+  __hip_atomic_store(&w[g], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&w[G + g], b ^ tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One wave collects the values of all G workgroups (G <= 256): lane i gets those of workgroups i, i + 64, i + 128,
+// i + 192 in v[0..3] (0 beyond G), with the loads of a polling round in flight together; `own` is the value this
+// workgroup posted.  False if the wait gave up.
+__device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double own, unsigned long long tag,
+                                              double (&v)[4]) {
   const int lane = threadIdx.x & 63;
+  unsigned long long* w = reinterpret_cast<unsigned long long*>(bank);
   bool have[4];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) { have[k] = (4 * lane + k >= G); v[k] = 0.0; }
+  for (int k = 0; k < 4; ++k) {
+    have[k] = (lane + 64 * k >= G); v[k] = 0.0;
+    if (lane + 64 * k == g) { have[k] = true; v[k] = own; }   // the workgroup's own value needs no round trip
+  }
   long long t0 = 0;
   for (int spin = 0;; ++spin) {
     unsigned long long w0[4], w1[4];
@@ -347,9 +385,8 @@ __device__ __forceinline__ bool wave_collect4(Slot* bank, int red_w, int G, unsi
     for (int k = 0; k < 4; ++k) {
       w0[k] = 0; w1[k] = 0;
       if (!have[k]) {
-        Slot* s = bank + (long long)(4 * lane + k) * red_w;
-        w0[k] = __hip_atomic_load(&s->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        w1[k] = __hip_atomic_load(&s->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        w0[k] = __hip_atomic_load(&w[lane + 64 * k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        w1[k] = __hip_atomic_load(&w[G + lane + 64 * k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
 #pragma unroll
@@ -490,7 +527,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 
   // total over the workgroup of one value per thread: valid in every thread after the barrier inside
   auto wg_total = [&](double s) -> double {
-    s = wave_sum_down(s);
+    s = wave_sum(s);
     double* ws = sh.wsum[wsum_round & 1];
     wsum_round += 1;
     if (lane == 0) ws[wave] = s;
@@ -548,8 +585,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           }
         }
       }
-      s_p = wave_sum_down(s_p);
-      s_q = wave_sum_down(s_q);
+      s_p = wave_sum(s_p);
+      s_q = wave_sum(s_q);
       if (lane == 0) {
         sh.u.wpart[((i - i_lo) * VL_WAVES + wave) * 2] = s_p;
         sh.u.wpart[((i - i_lo) * VL_WAVES + wave) * 2 + 1] = s_q;
@@ -573,7 +610,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
     stamp(102);
 
-    // ===== meanwhile: candidates = depth-l nodes whose parent is an input beam, in (rank, node) order
+    // ===== meanwhile: beam weights = softmax of the cumulative likelihoods over I (Section 2.1), by one wave
+    if (wave == 1) {
+      const bool valid = lane < nI;
+      double mp = -INFINITY, mq = -INFINITY;
+      for (int i = 0; i < nI; ++i) { mp = fmax(mp, sh.cum_p[i]); mq = fmax(mq, sh.cum_q[i]); }
+      const double ep = valid ? exp_nonpos(sh.cum_p[lane] - mp, sh.exp_tab) : 0.0;
+      const double eq = valid ? exp_nonpos(sh.cum_q[lane] - mq, sh.exp_tab) : 0.0;
+      const double zp = wave_sum(ep), zq = wave_sum(eq);
+      if (valid) { sh.bw_p[lane] = ep / zp; sh.bw_q[lane] = eq / zq; }
+    }
+
+    // ===== and candidates = depth-l nodes whose parent is an input beam, in (rank, node) order
     int M = 0;
     float czp = 0.f, czq = 0.f;
     if (!bonus) {
@@ -629,48 +677,93 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           acc += v;
         }
       }
-      if (r < R) sh.tsum[tid] = acc;
+      // fold the parts held by this wave (lanes c, c + cpow, ...), the waves' results through LDS
+      for (int off = cpow; off < 64; off <<= 1) acc += __shfl_xor(acc, off);
+      sh.tsum[tid] = acc;
       stamp(20);
       if (!mine) give_up();
       __syncthreads();
       if (sh.abort) return;
       stamp(21);
-      // one wave: row totals, log-sum-exp, beam weights = softmax of the cumulative likelihoods over I
-      // (Section 2.1), scale factors
-      if (wave == 0) {
-        const bool valid = lane < nI;
+      // row totals; one wave turns them into the scale factors, another into the fp64 log-sum-exp
+      if (wave < 2 && lane < nI) {
         double totp = 0.0, totq = 0.0;
-        if (valid)
-          for (int rr = 0; rr < R; ++rr) { totp += sh.tsum[rr * cpow + 2 * lane]; totq += sh.tsum[rr * cpow + 2 * lane + 1]; }
-        const double cp = valid ? sh.cum_p[lane] : -INFINITY, cq = valid ? sh.cum_q[lane] : -INFINITY;
-        const double mp = wave_max_all(cp), mq = wave_max_all(cq);
-        const double ep = valid ? exp_nonpos(cp - mp, sh.exp_tab) : 0.0, eq = valid ? exp_nonpos(cq - mq, sh.exp_tab) : 0.0;
-        const double zp = wave_sum_all(ep), zq = wave_sum_all(eq);
-        if (valid) {
-          sh.sp[lane] = (ep / zp) / totp;
-          sh.sq[lane] = (eq / zq) / totq;
+#pragma unroll
+        for (int w = 0; w < VL_WAVES; ++w) {     // with 128 columns a column lives in every other wave
+          const int ip = w * 64 + ((2 * lane) & 63), iq = w * 64 + ((2 * lane + 1) & 63);
+          const double vp = sh.tsum[ip], vq = sh.tsum[iq];
+          if ((ip & (cpow - 1)) == 2 * lane) totp += vp;
+          if ((iq & (cpow - 1)) == 2 * lane + 1) totq += vq;
+        }
+        if (wave == 0) {
+          sh.sp[lane] = sh.bw_p[lane] / totp;
+          sh.sq[lane] = sh.bw_q[lane] / totq;
+        } else {
           sh.lse_p[lane] = sh.max_p[lane] + log(totp);
           sh.lse_q[lane] = sh.max_q[lane] + log(totq);
         }
       }
       __syncthreads();
     }
+    stamp(24);
+    // scaling, fused with this thread's part of F(1) = sum max(p_beam - q_beam, 0) (second entry of the chain)
+    double f1 = 0.0;
     for (int i = i_lo; i <= i_hi; ++i) {
       const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
       const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
       const double fp = sh.sp[i], fq = sh.sq[i];
-      for (long long j = j_lo + tid; j < j_hi; j += VL_BLOCK) { stp(j, ldp(j) * fp); stq(j, ldq(j) * fq); }
+      long long j = j_lo + tid;
+      for (; j + 3 * VL_BLOCK < j_hi; j += 4 * VL_BLOCK) {      // four elements of each array in flight
+        double pv[4], qv[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { pv[k] = ldp(j + k * VL_BLOCK); qv[k] = ldq(j + k * VL_BLOCK); }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          pv[k] *= fp; qv[k] *= fq;
+          stp(j + k * VL_BLOCK, pv[k]); stq(j + k * VL_BLOCK, qv[k]);
+          f1 += fmax(pv[k] - qv[k], 0.0);
+        }
+      }
+      for (; j < j_hi; j += VL_BLOCK) {
+        const double pv = ldp(j) * fp, qv = ldq(j) * fq;
+        stp(j, pv); stq(j, qv);
+        f1 += fmax(pv - qv, 0.0);
+      }
     }
+    stamp(25);
     // p_beam and q_beam at every candidate's (parent beam, token)
     if (tid < M) {
       const int n = sh.S_node[tid];
       const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
       sh.S_zp[tid] = czp; sh.S_zq[tid] = czq;
-      sh.S_pb[tid] = exp_nonpos((double)czp - sh.max_p[slot], sh.exp_tab) * sh.sp[slot];
-      sh.S_qb[tid] = exp_nonpos((double)czq - sh.max_q[slot], sh.exp_tab) * sh.sq[slot];
+      const double pbx = exp_nonpos((double)czp - sh.max_p[slot], sh.exp_tab) * sh.sp[slot];
+      const double qbx = exp_nonpos((double)czq - sh.max_q[slot], sh.exp_tab) * sh.sq[slot];
+      const float uf = sh.n_u[n - n_begin];
+      // the test with p' = p_beam (first candidate, and every candidate right after an acceptance) needs no chain
+      const double ratio = (qbx == 0.0) ? INFINITY : pbx / qbx;
+      sh.S_pb[tid] = pbx; sh.S_qb[tid] = qbx; sh.S_u[tid] = uf;
+      sh.S_flag[tid] = (unsigned char)(((double)uf <= ratio ? 1 : 0) | (fabs(ratio - (double)uf) <= NEAR_TIE ? 2 : 0));
     }
     if (tid == 0) { sh.cc[1] = 0.0; sh.FF[1] = 1.0; sh.kmax = 1; sh.acc_n = 0; sh.pos = 0; sh.kidx = 1; }
-    __syncthreads();
+    // Entry 2 of the residual chain (c = 1) is needed by the first rejection of nearly every layer: its partial
+    // sums are posted ahead of time and collected only when it is asked for.
+    bool spec = false;
+    Slot* spec_bank = nullptr;
+    unsigned long long spec_tag = 0;
+    double spec_own = 0.0;
+    stamp(26);
+    if (M > 0) {
+      const double tot = wg_total(f1);      // barrier inside: also publishes the scaled slices
+      stamp(27);
+      epoch += 1;
+      spec_tag = exchange_tag(epoch);
+      spec_bank = exchange_bank(a, prompt, epoch);
+      if (tid == 0) dense_post(spec_bank, a.G, g, tot, spec_tag);
+      spec_own = tot;
+      spec = true;
+    } else {
+      __syncthreads();
+    }
 
     stamp(22);
     // sum over the slice of max(p_beam - c q_beam, 0); four loads in flight per thread
@@ -706,9 +799,15 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const unsigned long long tag = exchange_tag(epoch);
       Slot* bank = exchange_bank(a, prompt, epoch);
       if (wave == 0) {
-        if (lane == 0) slot_post(bank + (long long)g * a.red_w, sh.tsum[VL_BLOCK - 1], tag);
+        const double mine = sh.tsum[VL_BLOCK - 1];
+        if (lane == 0) dense_post(bank, a.G, g, mine, tag);
         double v[4];
-        if (!wave_collect4(bank, a.red_w, a.G, tag, v)) give_up();
+        if (!wave_collect4(bank, a.G, g, mine, tag, v)) give_up();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (lane + 64 * k < a.G) sh.gpart[lane + 64 * k] = v[k];
+        wave_lds_fence();          // now four consecutive workgroups per lane
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = 4 * lane + k < a.G ? sh.gpart[4 * lane + k] : 0.0;
         int nz = -1;
 #pragma unroll
         for (int k = 0; k < 4; ++k) if (v[k] > 0.0) nz = 4 * lane + k;
@@ -788,25 +887,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       break;
     }
 
-    // ===== residual chain.  Entry 2 (c = 1) is needed by the first rejection of nearly every layer: its
-    // partial sums are posted ahead of time and collected only when it is asked for.
-    bool spec = false;
-    Slot* spec_bank = nullptr;
-    unsigned long long spec_tag = 0;
-    if (M > 0) {
-      const double tot = wg_total(slice_sum(1.0));
-      epoch += 1;
-      spec_tag = exchange_tag(epoch);
-      spec_bank = exchange_bank(a, prompt, epoch);
-      if (tid == 0) slot_post(spec_bank + (long long)g * a.red_w, tot, spec_tag);
-      spec = true;
-    }
-
     int WL = W_in;             // width of the layer, known before the first decision
 
-    // The accept / reject decisions of Algorithm 1 in candidate order, as far as the chain allows (one thread).
+    // The accept / reject decisions of Algorithm 1 in candidate order, as far as the chain allows.
     // Outcome in sh.state[round & 1]: 0 = finished, 1 = the next chain entry is needed.
-    auto decide = [&](unsigned int round) {
+    // Plain sequential form (one thread): only used when a residual without mass turns up.
+    auto decide_serial = [&](unsigned int round) {
       int pos = sh.pos, nacc = sh.acc_n, k = sh.kidx;
       const int kmax = sh.kmax;
       int state = 0;
@@ -822,7 +908,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const double pbx = sh.S_pb[pos], qbx = sh.S_qb[pos];
         const double num = (k == 1) ? pbx : fmax(pbx - sh.cc[k] * qbx, 0.0) / sh.FF[k];
         const double ratio = (qbx == 0.0) ? INFINITY : num / qbx;
-        const double u = (double)sh.n_u[n - n_begin];
+        const double u = (double)sh.S_u[pos];
         if (fabs(ratio - u) <= NEAR_TIE) near_tie++;
         if (u <= ratio) {
           sh.A_node[nacc] = n;
@@ -838,6 +924,73 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
       sh.pos = pos; sh.acc_n = nacc; sh.kidx = k; sh.state[round & 1] = state;
     };
+    // The same decisions taken by the first wave, a run at a time.  With p' = p_beam (chain index 1) consecutive
+    // candidates are independent tests (precomputed flags): all acceptances up to the first rejection are taken
+    // at once.  After a rejection candidate pos + j meets chain entry k + j for as long as the rejections last:
+    // those tests run side by side and the first acceptance ends the streak.
+    auto decide = [&](unsigned int round, int kmax) {    // kmax: entries of the chain that exist (uniform)
+      wave_lds_fence();                                    // the newest entry was written by lane 0 a moment ago
+      int pos = sh.pos, nacc = sh.acc_n, k = sh.kidx;      // uniform over the wave
+      int state = 0, near_add = 0;
+      while (true) {
+        if (pos >= M || nacc >= WL) { state = 0; break; }
+        const int cand = pos + lane;
+        if (k == 1) {
+          const int nv = min(64, M - pos);
+          const int fl = lane < nv ? sh.S_flag[cand] : 0;
+          const unsigned long long rej = __ballot(lane < nv && !(fl & 1));
+          const int run = rej ? min(nv, (int)__ffsll((long long)rej) - 1) : nv;   // acceptances in a row from pos
+          const int take = min(run, WL - nacc);
+          if (lane < take) {
+            const int n = sh.S_node[cand];
+            sh.A_node[nacc + lane] = n;
+            sh.A_idx[nacc + lane] = cand;
+            if (g == 0) a.out.node_status[n] = DSBD_ACCEPTED;
+          }
+          const bool fails = take == run && run < nv && nacc + take < WL;   // candidate pos + run is tested and rejected
+          near_add += __popcll(__ballot((lane < take || (fails && lane == run)) && (fl & 2)));
+          nacc += take; pos += take;
+          if (fails) {
+            if (lane == run && g == 0) a.out.node_status[sh.S_node[cand]] = DSBD_REJECTED;
+            pos += 1; k = 2;
+          }
+          continue;
+        }
+        const int navail = kmax - k + 1;                   // chain entries k .. kmax exist
+        if (navail <= 0) { state = 1; break; }
+        const int nv = min(min(64, navail), M - pos);
+        bool acc = false, nr = false, dead = false;
+        if (lane < nv) {
+          const int kk = k + lane;
+          const double F = sh.FF[kk];
+          dead = !(F > 0.0);
+          const double pbx = sh.S_pb[cand], qbx = sh.S_qb[cand];
+          const double num = fmax(pbx - sh.cc[kk] * qbx, 0.0) / F;
+          const double ratio = (qbx == 0.0) ? INFINITY : num / qbx;
+          const double u = (double)sh.S_u[cand];
+          acc = u <= ratio;
+          nr = fabs(ratio - u) <= NEAR_TIE;
+        }
+        const unsigned long long accm = __ballot(lane < nv && acc);
+        const int last = accm ? (int)__ffsll((long long)accm) - 1 : nv - 1;     // last candidate tested in this step
+        if (__ballot(lane <= last && dead)) {
+          // a residual without mass: hand the rest to the sequential form, which knows what to do about it
+          if (lane == 0) { near_tie += near_add; sh.pos = pos; sh.acc_n = nacc; sh.kidx = k; decide_serial(round); }
+          wave_lds_fence();
+          return;
+        }
+        near_add += __popcll(__ballot(lane <= last && nr));
+        if (lane <= last) {
+          const int n = sh.S_node[cand];
+          const bool a_here = accm && lane == last;
+          if (a_here) { sh.A_node[nacc] = n; sh.A_idx[nacc] = cand; }
+          if (g == 0) a.out.node_status[n] = a_here ? DSBD_ACCEPTED : DSBD_REJECTED;
+        }
+        pos += last + 1;
+        if (accm) { nacc += 1; k = 1; } else { k += nv; }
+      }
+      if (lane == 0) { near_tie += near_add; sh.pos = pos; sh.acc_n = nacc; sh.kidx = k; sh.state[round & 1] = state; }
+    };
 
     // Appends entry kmax+1 to the residual chain: every workgroup sums its slice, the first wave exchanges the
     // partial sums and, if asked to, carries on with the decisions right away.  All threads leave through one
@@ -846,30 +999,31 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       if (spec) {                      // entry 2 is already on its way
         if (wave == 0) {
           double v[4];
-          if (!wave_collect4(spec_bank, a.red_w, a.G, spec_tag, v)) give_up();
-          const double F = wave_sum_all((v[0] + v[1]) + (v[2] + v[3]));
-          if (lane == 0) {
-            sh.cc[2] = 1.0; sh.FF[2] = F; sh.kmax = 2;
-            if (then_decide) decide(decide_round);
-          }
+          if (!wave_collect4(spec_bank, a.G, g, spec_own, spec_tag, v)) give_up();
+          const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+          if (lane == 0) { sh.cc[2] = 1.0; sh.FF[2] = F; sh.kmax = 2; }
+          if (then_decide) decide(decide_round, 2);
         }
         spec = false;
       } else {
         const int k = sh.kmax;
         const double c = sh.cc[k] + sh.FF[k];
-        const double tot = wg_total(slice_sum(c));
+        const double sl = slice_sum(c);
+        stamp(43);
+        const double tot = wg_total(sl);
+        stamp(44);
         epoch += 1;
         const unsigned long long tag = exchange_tag(epoch);
         Slot* bank = exchange_bank(a, prompt, epoch);
         if (wave == 0) {
-          if (lane == 0) slot_post(bank + (long long)g * a.red_w, tot, tag);
+          if (lane == 0) dense_post(bank, a.G, g, tot, tag);
           double v[4];
-          if (!wave_collect4(bank, a.red_w, a.G, tag, v)) give_up();
-          const double F = wave_sum_all((v[0] + v[1]) + (v[2] + v[3]));
-          if (lane == 0) {
-            sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1;
-            if (then_decide) decide(decide_round);
-          }
+          if (!wave_collect4(bank, a.G, g, tot, tag, v)) give_up();
+          stamp(45);
+          const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+          stamp(46);
+          if (lane == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1; }
+          if (then_decide) decide(decide_round, k + 1);
         }
       }
       __syncthreads();
@@ -933,7 +1087,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 
     stamp(40);
     // ===== sequential accept / reject
-    if (tid == 0) decide(decide_round);
+    if (wave == 0) decide(decide_round, sh.kmax);
     __syncthreads();
     while (sh.state[decide_round & 1] == 1) {
       decide_round += 1;               // the next outcome goes to the other entry: nobody still reads it

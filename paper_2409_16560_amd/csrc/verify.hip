@@ -550,14 +550,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const int i_hi = e_hi > e_lo ? (int)div_floor(e_hi - 1, V) : i_lo - 1;
     // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
     const bool in_lds = ch <= (long long)a.lds_elems;
-    // typed accessors (LDS or global): a generic pointer would turn every access into a FLAT instruction
-    double* const pbg = pb + e_lo;
-    double* const qbg = qb + e_lo;
-    const int qoff = a.lds_elems;
-    auto ldp = [&](long long j) -> double { return in_lds ? dyn_lds[j] : pbg[j]; };
-    auto ldq = [&](long long j) -> double { return in_lds ? dyn_lds[qoff + j] : qbg[j]; };
-    auto stp = [&](long long j, double v) { if (in_lds) dyn_lds[j] = v; else pbg[j] = v; };
-    auto stq = [&](long long j, double v) { if (in_lds) dyn_lds[qoff + j] = v; else qbg[j] = v; };
+    // Accessors with explicit address spaces (LDS or global): through generic pointers the compiler merges the two
+    // cases into one FLAT access with a selected address, which is slower than either.
+    typedef __attribute__((address_space(3))) double lds_f64;
+    typedef __attribute__((address_space(1))) double glb_f64;
+    lds_f64* const pl = (lds_f64*)dyn_lds;
+    lds_f64* const ql = pl + a.lds_elems;
+    glb_f64* const pbg = (glb_f64*)(pb + e_lo);
+    glb_f64* const qbg = (glb_f64*)(qb + e_lo);
+    auto ldp = [&](long long j) -> double { double v; if (in_lds) v = pl[(int)j]; else v = pbg[j]; return v; };
+    auto ldq = [&](long long j) -> double { double v; if (in_lds) v = ql[(int)j]; else v = qbg[j]; return v; };
+    auto stp = [&](long long j, double v) { if (in_lds) pl[(int)j] = v; else pbg[j] = v; };
+    auto stq = [&](long long j, double v) { if (in_lds) ql[(int)j] = v; else qbg[j] = v; };
 
     // ===== p_beam / q_beam over I x V: exponentials and this workgroup's share of the row sums
     for (int i = i_lo; i <= i_hi; ++i) {
@@ -685,7 +689,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       __syncthreads();
       if (sh.abort) return;
       stamp(21);
-      // row totals; one wave turns them into the scale factors, another into the fp64 log-sum-exp
+      // row totals; one wave turns them into the scale factors, another keeps them for the fp64 log-sum-exp
       if (wave < 2 && lane < nI) {
         double totp = 0.0, totq = 0.0;
 #pragma unroll
@@ -698,9 +702,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (wave == 0) {
           sh.sp[lane] = sh.bw_p[lane] / totp;
           sh.sq[lane] = sh.bw_q[lane] / totq;
-        } else {
-          sh.lse_p[lane] = sh.max_p[lane] + log(totp);
-          sh.lse_q[lane] = sh.max_q[lane] + log(totq);
+        } else {             // the logarithms wait until the other waves have nothing to do (below)
+          sh.lse_p[lane] = totp;
+          sh.lse_q[lane] = totq;
         }
       }
       __syncthreads();
@@ -765,6 +769,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       __syncthreads();
     }
 
+    // fp64 log-sum-exp of the input beams' rows: needed at the end of the layer only, so one wave takes the
+    // logarithms while the first wave is busy with the decisions (or the others with the sampling prefix sums)
+    if (wave == 1 && lane < nI) {
+      sh.lse_p[lane] = sh.max_p[lane] + log(sh.lse_p[lane]);
+      sh.lse_q[lane] = sh.max_q[lane] + log(sh.lse_q[lane]);
+    }
     stamp(22);
     // sum over the slice of max(p_beam - c q_beam, 0); four loads in flight per thread
     auto slice_sum = [&](double c) -> double {

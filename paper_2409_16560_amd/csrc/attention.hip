@@ -56,7 +56,9 @@ struct AttnArgs {
 // the LDS counter as well: every wait for an LDS read would then also wait for all K/V loads in flight.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_global_16(const void* p) {
-  const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(p);
+  // non-temporal: the caches are streamed through once per call and should not be kept in preference to
+  // anything else
+  const u32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ bf16x8 load_global_bf16x8(const void* p) {

@@ -5,6 +5,7 @@
 // thread per node, each walking its parent chain; the walk validates the parent array so that
 // no later kernel ever follows a bad index.
 #include "common.h"
+#include "topology_device.h"
 
 __global__ __launch_bounds__(64) void topology_kernel(int n_trees, int n_nodes, const int32_t* __restrict__ tree_off,
                                                       const int32_t* __restrict__ parent, int max_tree_nodes,
@@ -12,52 +13,7 @@ __global__ __launch_bounds__(64) void topology_kernel(int n_trees, int n_nodes, 
                                                       uint64_t* __restrict__ anc_mask, int32_t* __restrict__ fault) {
   const int b = blockIdx.x;
   if (b >= n_trees) return;
-  int base = tree_off[b];
-  int end = tree_off[b + 1];
-  int bad = 0;
-  if (base < 0 || end > n_nodes || end <= base) {
-    if (threadIdx.x == 0) atomicOr(fault, DSBD_FAULT_TOPOLOGY);
-    return;
-  }
-  const int n_all = end - base;
-  int n = n_all;
-  if (n > max_tree_nodes || n > DSBD_MAX_TREE_NODES) {
-    bad |= DSBD_FAULT_BOUNDS;
-    n = min(n, min(max_tree_nodes, DSBD_MAX_TREE_NODES));
-  }
-  // nodes beyond the supported tree size: defined (empty) outputs, never followed
-  for (int j = n + threadIdx.x; j < n_all; j += blockDim.x) {
-    anc_mask[base + j] = 0;
-    if (depth) depth[base + j] = 0;
-  }
-  const int j = threadIdx.x;
-  if (j < n) {
-    uint64_t m = 0;
-    int a = j;                      // local index
-    bool ok = true;
-    for (int it = 0; it < DSBD_MAX_TREE_NODES; ++it) {
-      m |= 1ull << a;
-      int p = parent[base + a];
-      if (a == 0) {
-        if (p != -1) ok = false;
-        break;
-      }
-      int pl = p - base;
-      if (pl < 0 || pl >= a) {      // outside the tree, or not before the child
-        ok = false;
-        break;
-      }
-      a = pl;
-    }
-    if (!ok) {
-      bad |= DSBD_FAULT_TOPOLOGY;
-      m = 1ull << j;                // fall back to "sees only itself"
-    }
-    int d = __popcll(m) - 1;
-    if (d > max_depth) bad |= DSBD_FAULT_BOUNDS;
-    anc_mask[base + j] = m;
-    if (depth) depth[base + j] = d;
-  }
+  const int bad = dsbd_tree_topology(b, threadIdx.x, n_nodes, tree_off, parent, max_tree_nodes, max_depth, depth, anc_mask);
   if (bad) atomicOr(fault, bad);
 }
 

@@ -1,14 +1,14 @@
 // Layer-wise verification of a draft forest on gfx950 (paper Section 3.1 "Details", Algorithm 1,
 // and the dynamic layer width of Section 3.2, Eq. 1-6).
 //
-// Three kernels on the caller's stream:
+// Two kernels on the caller's stream:
 //
 // 1. vocab_stats_kernel (bandwidth-bound, all nodes, both models): one pass over the fp32 logits with
 //    a per-thread online max / sum-of-exponentials, reduced per row chunk.  This is the O(W |V|)
-//    softmax work of the beam-sampling joint (Section 2.1) done once for every forest node.
-// 2. vocab_stats_finalize_kernel: merges the chunks into the exact row maximum and an fp32
-//    log-sum-exp per node, writes the per-node outputs and clears the synchronisation counters.
-// 3. verify_layers_kernel (latency-bound, persistent; all its workgroups must be resident at once): G workgroups per prompt walk
+//    softmax work of the beam-sampling joint (Section 2.1) done once for every forest node.  A few extra
+//    workgroups of the same launch do the small jobs the next kernel depends on: forest topology (node
+//    depths, validation), the tree range of every prompt, clearing the exchange slots.
+// 2. verify_layers_kernel (latency-bound, persistent; all its workgroups must be resident at once): G workgroups per prompt walk
 //    the layers in order.  Every decision is taken in fp64.  For the layer's input beams I the
 //    workgroups materialise p_beam and q_beam over I x V (their slice each), and every dependent
 //    reduction over I x V is one pass over the slices plus one barrier among the G workgroups.
@@ -23,6 +23,7 @@
 // All G workgroups of a prompt run the same sequential program on the same reduced values (summed in
 // the same order), so their control flow stays identical without any broadcast.
 #include "common.h"
+#include "topology_device.h"
 #include <float.h>
 #include <stdlib.h>
 
@@ -39,6 +40,13 @@ struct StatsArgs {
   int n_nodes, V, nchunk, chunk;
   float2* part;      // [2][n_nodes][nchunk] (max, sum of exp(x - max))
   int32_t* fault;
+  // service workgroups (blockIdx.y == n_nodes)
+  int n_trees, n_prompts, max_tree_nodes, max_depth;
+  const int32_t *tree_prompt, *tree_off, *parent;
+  int32_t* depth;              // [n_nodes]
+  int4* prompt_rec;            // [n_prompts] (first tree, end tree, first node, end node) of every prompt
+  unsigned long long* slots;   // exchange slots of the layer kernel, cleared here
+  long long n_slot_words;
 };
 
 __device__ __forceinline__ void online_add4(float& m, float& s, bool& bad, float x0, float x1, float x2, float x3) {
@@ -94,8 +102,42 @@ __device__ __forceinline__ void online_merge(float& m, float& s, float m2, float
   m = mn;
 }
 
+// The small jobs done by the extra row of workgroups (blockIdx.y == n_nodes) while the others stream.
+__device__ void stats_service(const StatsArgs& a, int sidx, int n_service) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // exchange slots of the layer kernel: a slot is valid only with the tag of its exchange, so zeros never are
+  for (long long k = (long long)sidx * VS_BLOCK + tid; k < a.n_slot_words; k += (long long)n_service * VS_BLOCK)
+    a.slots[k] = 0ull;
+  // forest topology, one wave per tree
+  for (int b = sidx * (VS_BLOCK / 64) + wave; b < a.n_trees; b += n_service * (VS_BLOCK / 64)) {
+    const int bad = dsbd_tree_topology(b, lane, a.n_nodes, a.tree_off, a.parent, a.max_tree_nodes, a.max_depth,
+                                       a.depth, nullptr);
+    if (bad) atomicOr(a.fault, bad);
+  }
+  // trees of each prompt (tree_prompt is non-decreasing): counted by one wave, so that the layer kernel starts
+  // from this record instead of searching with dependent loads of its own
+  for (int p = sidx * (VS_BLOCK / 64) + wave; p < a.n_prompts; p += n_service * (VS_BLOCK / 64)) {
+    int lt = 0, le = 0;
+    for (int t = lane; t < a.n_trees; t += 64) {
+      const int tp = a.tree_prompt[t];
+      lt += tp < p; le += tp <= p;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { lt += __shfl_xor(lt, off); le += __shfl_xor(le, off); }
+    if (lane == 0) {
+      int4 rec = make_int4(lt, le, 0, 0);
+      if (le > lt) { rec.z = a.tree_off[lt]; rec.w = a.tree_off[le]; }
+      a.prompt_rec[p] = rec;
+    }
+  }
+}
+
 __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
   const int c = blockIdx.x, n = blockIdx.y, which = blockIdx.z;
+  if (n == a.n_nodes) {       // uniform over the workgroup
+    stats_service(a, which * gridDim.x + c, 2 * gridDim.x);
+    return;
+  }
   const int lo = c * a.chunk;
   const int hi = min(a.V, lo + a.chunk);
   const float* row = a.z[which] + (long long)n * a.V;
@@ -150,47 +192,6 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------ kernel 2
-struct FinalizeArgs {
-  const float2* part;
-  int n_nodes, nchunk, n_prompts;
-  float* rowmax;      // [2][n_nodes]
-  float* lse32;       // [2][n_nodes]
-  float* out_lse[2];
-  unsigned long long* slots;   // exchange slots of the layer kernel, cleared here
-  long long n_slot_words;
-  const int32_t *tree_prompt, *tree_off;
-  int n_trees;
-  int4* prompt_rec;            // [n_prompts] (first tree, end tree, first node, end node) of every prompt
-};
-
-__global__ void vocab_stats_finalize_kernel(FinalizeArgs a) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  for (long long k = i; k < a.n_slot_words; k += (long long)gridDim.x * blockDim.x) a.slots[k] = 0ull;
-  // trees of each prompt (tree_prompt is non-decreasing): the layer kernel starts from this record instead of
-  // searching with dependent loads of its own
-  for (int p = (int)(gridDim.x * blockDim.x) - 1 - i; p < a.n_prompts; p += gridDim.x * blockDim.x) {
-    int lo = 0, hi = a.n_trees;
-    while (lo < hi) { const int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] < p) lo = mid + 1; else hi = mid; }
-    const int t_first = lo;
-    hi = a.n_trees;
-    while (lo < hi) { const int mid = (lo + hi) >> 1; if (a.tree_prompt[mid] <= p) lo = mid + 1; else hi = mid; }
-    const int t_end = lo;
-    int4 rec = make_int4(t_first, t_end, 0, 0);
-    if (t_end > t_first) { rec.z = a.tree_off[t_first]; rec.w = a.tree_off[t_end]; }
-    a.prompt_rec[p] = rec;
-  }
-  if (i >= 2 * a.n_nodes) return;
-  const float2* p = a.part + (long long)i * a.nchunk;
-  float M = p[0].x, S = p[0].y;
-  for (int c = 1; c < a.nchunk; ++c) online_merge(M, S, p[c].x, p[c].y);
-  const float lse = M + logf(S);
-  a.rowmax[i] = M;
-  a.lse32[i] = lse;
-  const int which = i / a.n_nodes, n = i % a.n_nodes;
-  if (a.out_lse[which]) a.out_lse[which][n] = lse;
-}
-
-// ------------------------------------------------------------------------------------------------ kernel 3
 struct LayersArgs {
   int n_prompts, n_trees, n_nodes;
   const int32_t *tree_prompt, *tree_off, *parent, *token, *rank;
@@ -204,8 +205,8 @@ struct LayersArgs {
   dsbd_verify_out out;
   const int32_t* depth;
   const int4* prompt_rec; // [n_prompts] (first tree, end tree, first node, end node)
-  const float* rowmax;   // [2][n_nodes]
-  const float* lse32;    // [2][n_nodes]
+  const float2* part;    // [2][n_nodes][nchunk] row statistics per chunk (max, sum of exp(x - max))
+  int nchunk;
   double* pb;            // [n_prompts][I_cap*V]  p_beam slice storage
   double* qb;            // [n_prompts][I_cap*V]
   double* red;           // exchange slots [n_prompts][2 banks][G][red_w] of 16 bytes each
@@ -235,6 +236,7 @@ struct LayerShared {
   short n_depth[NODE_CAP];
   float n_u[NODE_CAP];               // accept uniform of each node
   float n_maxp[NODE_CAP], n_maxq[NODE_CAP];   // exact maxima of each node's logit rows
+  float n_lsep[NODE_CAP], n_lseq[NODE_CAP];   // fp32 log-sum-exp of each node's logit rows
   // candidates
   short slot_of[NODE_CAP];           // slot in I of a prompt node, -1 if not an input beam
   int S_node[NODE_CAP], S_tmp[NODE_CAP];
@@ -493,10 +495,20 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     sh.n_token[tid] = tok;
     sh.n_rank[tid] = a.rank ? a.rank[n] : 0;
     sh.n_u[tid] = a.u_acc[n];
-    sh.n_maxp[tid] = a.rowmax[n];
-    sh.n_maxq[tid] = a.rowmax[a.n_nodes + n];
     sh.slot_of[tid] = -1;
     atomicMax(&sh.sgamma, d);
+    // row statistics: the chunks of the statistics pass merged into the exact maximum and an fp32 log-sum-exp
+    const float2* pp = a.part + (long long)n * a.nchunk;
+    const float2* pq = a.part + ((long long)a.n_nodes + n) * a.nchunk;
+    float Mp = pp[0].x, Sp = pp[0].y, Mq = pq[0].x, Sq = pq[0].y;
+    for (int c = 1; c < a.nchunk; ++c) { online_merge(Mp, Sp, pp[c].x, pp[c].y); online_merge(Mq, Sq, pq[c].x, pq[c].y); }
+    const float lp = Mp + logf(Sp), lq = Mq + logf(Sq);
+    sh.n_maxp[tid] = Mp; sh.n_maxq[tid] = Mq;
+    sh.n_lsep[tid] = lp; sh.n_lseq[tid] = lq;
+    if (g == 0) {
+      if (a.out.lse_target) a.out.lse_target[n] = lp;
+      if (a.out.lse_draft) a.out.lse_draft[n] = lq;
+    }
   }
   __syncthreads();
   bad |= sh.sbad;
@@ -513,8 +525,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const int par = sh.n_parent[my_node];
     if (sh.n_depth[my_node] != 0 && par >= n_begin && par < n) {
       const int tok = sh.n_token[my_node];
-      node_lp = a.zp[(long long)par * V + tok] - a.lse32[par];
-      node_lq = a.zq[(long long)par * V + tok] - a.lse32[a.n_nodes + par];
+      node_lp = a.zp[(long long)par * V + tok] - sh.n_lsep[par - n_begin];
+      node_lq = a.zq[(long long)par * V + tok] - sh.n_lseq[par - n_begin];
     }
   }
   // ---- initial statuses (first workgroup of the prompt)
@@ -1284,15 +1296,11 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
 }
 
 size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const VerifyPlan& pl, int32_t** depth,
-                    uint64_t** anc, float2** part, float** rowmax, float** lse32, double** pb, double** qb,
-                    double** red, int4** prompt_rec) {
+                    float2** part, double** pb, double** qb, double** red, int4** prompt_rec) {
   const size_t N = (size_t)f->n_nodes, P = (size_t)f->n_prompts;
   ws.take<long long>(512);                 // timeline of the layer kernel (diagnostics), first in the workspace
   *depth = ws.take<int32_t>(N);
-  *anc = ws.take<uint64_t>(N);
   *part = ws.take<float2>(2 * N * pl.nchunk);
-  *rowmax = ws.take<float>(2 * N);
-  *lse32 = ws.take<float>(2 * N);
   *pb = ws.take<double>(P * pl.I_cap * V);
   *qb = ws.take<double>(P * pl.I_cap * V);
   *red = ws.take<double>(P * 2 * pl.G * pl.red_w * 2);
@@ -1306,8 +1314,8 @@ extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32
   if (check_verify(f, V, p) != DSBD_OK) return 0;
   const VerifyPlan pl = make_verify_plan(f, V, p);
   WorkspaceCarver ws(nullptr);
-  int32_t* d; uint64_t* an; float2* pt; float *rm, *ls; double *pb, *qb, *red; int4* pr;
-  return carve_verify(ws, f, V, pl, &d, &an, &pt, &rm, &ls, &pb, &qb, &red, &pr) + 256;
+  int32_t* d; float2* pt; double *pb, *qb, *red; int4* pr;
+  return carve_verify(ws, f, V, pl, &d, &pt, &pb, &qb, &red, &pr) + 256;
 }
 
 extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
@@ -1331,8 +1339,8 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
-  int32_t* depth; uint64_t* anc; float2* part; float *rowmax, *lse32; double *pb, *qb, *red; int4* prompt_rec;
-  carve_verify(ws, f, in->V, pl, &depth, &anc, &part, &rowmax, &lse32, &pb, &qb, &red, &prompt_rec);
+  int32_t* depth; float2* part; double *pb, *qb, *red; int4* prompt_rec;
+  carve_verify(ws, f, in->V, pl, &depth, &part, &pb, &qb, &red, &prompt_rec);
 
   // the persistent kernel needs all its workgroups resident at once
   static int max_blocks_per_cu = -1;
@@ -1347,27 +1355,19 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   const long long grid3 = (long long)f->n_prompts * pl.G;
   if (grid3 > (long long)max_blocks_per_cu * cached_cu_count()) return DSBD_ERR_UNSUPPORTED;
 
-  rc = dsbd_launch_topology(f, depth, anc, fault, stream);
-  if (rc != DSBD_OK) return rc;
-
   StatsArgs sa;
   sa.z[0] = in->logits_target; sa.z[1] = in->logits_draft;
   sa.n_nodes = f->n_nodes; sa.V = in->V; sa.nchunk = pl.nchunk; sa.chunk = pl.chunk;
   sa.part = part; sa.fault = fault;
+  sa.n_trees = f->n_trees; sa.n_prompts = f->n_prompts; sa.max_tree_nodes = f->max_tree_nodes; sa.max_depth = f->max_depth;
+  sa.tree_prompt = f->tree_prompt; sa.tree_off = f->tree_off; sa.parent = f->parent;
+  sa.depth = depth; sa.prompt_rec = prompt_rec;
+  sa.slots = reinterpret_cast<unsigned long long*>(red);
+  sa.n_slot_words = (long long)f->n_prompts * 2 * pl.G * pl.red_w * 2;
+  // one extra row of workgroups (blockIdx.y == n_nodes) for the small jobs
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, true, stream);
-  hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes, 2), dim3(VS_BLOCK), 0, stream, sa);
+  hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, 2), dim3(VS_BLOCK), 0, stream, sa);
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, false, stream);
-  DSBD_HIP_LAUNCH_CHECK();
-
-  FinalizeArgs fa;
-  fa.part = part; fa.n_nodes = f->n_nodes; fa.nchunk = pl.nchunk; fa.n_prompts = f->n_prompts;
-  fa.rowmax = rowmax; fa.lse32 = lse32; fa.out_lse[0] = out->lse_target; fa.out_lse[1] = out->lse_draft;
-  fa.slots = reinterpret_cast<unsigned long long*>(red);
-  fa.n_slot_words = (long long)f->n_prompts * 2 * pl.G * pl.red_w * 2;
-  fa.tree_prompt = f->tree_prompt; fa.tree_off = f->tree_off; fa.n_trees = f->n_trees; fa.prompt_rec = prompt_rec;
-  int fblocks = (2 * f->n_nodes + 255) / 256;
-  if (fblocks < 64) fblocks = 64;          // enough threads to clear the slots quickly
-  hipLaunchKernelGGL(vocab_stats_finalize_kernel, dim3(fblocks), dim3(256), 0, stream, fa);
   DSBD_HIP_LAUNCH_CHECK();
 
   LayersArgs la;
@@ -1378,7 +1378,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.blp = in->beam_logp_target; la.blq = in->beam_logp_draft;
   la.u_acc = in->u_accept; la.u_res = in->u_resid; la.u_fill = in->u_fill;
   la.W_L = p->W_L; la.W_min = p->W_min; la.W_cap = p->W_cap; la.t = p->t;
-  la.out = *out; la.depth = depth; la.prompt_rec = prompt_rec; la.rowmax = rowmax; la.lse32 = lse32;
+  la.out = *out; la.depth = depth; la.prompt_rec = prompt_rec; la.part = part; la.nchunk = pl.nchunk;
   la.pb = pb; la.qb = qb; la.red = red;
   la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
   la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;

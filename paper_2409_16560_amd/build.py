@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsbd.so")
-SOURCES = ["topology.hip", "attention.hip", "verify.hip", "select.hip", "timing.hip"]
+SOURCES = ["attention.hip", "verify.hip", "select.hip", "timing.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fgpu-rdc-", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

@@ -15,10 +15,13 @@
 //                 one query row (column l%16), its scores and its slice of the output accumulators;
 //   O^T += V^T P^T  MFMA 16x16x32, B = P^T built in registers from the S^T tile, A = V^T read from a
 //                 wave-private LDS tile into which V was written transposed (token pairs packed).
-// The ancestor mask never exists in memory: each lane keeps the 64-bit ancestor bitmap of its row's
-// node and tests bits while handling the (at most two) steps that cover the tree's own rows.
+// The ancestor mask never exists in memory: every wave derives the tree's topology itself (the parent array of
+// a tree is one load per lane, the parent chains are walked with lane shuffles), each lane keeps the 64-bit
+// ancestor bitmap of its row's node and tests bits while handling the (at most two) steps that cover the
+// tree's own rows.  The first workgroup of a tree also reports what the walk found wrong with the parent array.
 // Partial (m, l, O) of the KV splits go to the workspace; a second kernel merges them.
 #include "common.h"
+#include "topology_device.h"
 #include <stdlib.h>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -31,7 +34,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 struct AttnArgs {
   const int32_t* tree_off;
-  const uint64_t* anc_mask;
+  const int32_t* parent;
+  int max_tree_nodes, max_depth;
+  uint64_t* anc_out;            // [n_nodes] ancestor-or-self bitmaps, written once per tree if not null
   const void* const* k_ptr;
   const void* const* v_ptr;
   const int32_t* len;
@@ -111,10 +116,15 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
   const int g = bid % a.Hkv;
   const int b = bid / a.Hkv;
 
-  const int base = a.tree_off[b];
-  int n_b = a.tree_off[b + 1] - base;
-  if (base < 0 || n_b <= 0 || base + n_b > a.n_nodes) return;   // reported by the topology kernel
-  n_b = min(n_b, DSBD_MAX_TREE_NODES);
+  const dsbd_tree_range tr = dsbd_tree_range_of(b, a.n_nodes, a.tree_off, a.max_tree_nodes);
+  const bool reporter = split == 0 && rb == 0 && g == 0 && wave == 0;   // one wave per tree speaks for it
+  if (!tr.valid) {
+    if (reporter && lane == 0) atomicOr(a.fault, tr.bad);
+    return;
+  }
+  const int base = tr.base;
+  const int n_b = min(tr.n_all, DSBD_MAX_TREE_NODES);
+  const int p_mine = dsbd_tree_parent_of(tr, lane, a.parent);   // used once the first loads are on their way
   const int R = n_b * a.group;       // query rows of this (tree, KV head)
   const int row0 = rb * ROWS_B + rw * ROWS_W;
   const int n_rows_total = a.n_nodes * a.Hq;
@@ -154,7 +164,7 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
     const bool live = r < R;
     const int node = live ? r / a.group : 0;
     const int head = g * a.group + (live ? r % a.group : 0);
-    anc[rt] = live ? a.anc_mask[base + node] : 0ull;
+    anc[rt] = 0ull;
     const __bf16* qp = a.q + ((long long)(base + node) * a.Hq + head) * D + 8 * qd;
 #pragma unroll
     for (int j = 0; j < DS; ++j) {
@@ -220,6 +230,19 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
   int st = st_begin + tw;
   const bool active = block_live && st < st_end;
   if (active) { load_k(st); load_v(st); }
+  // ---- topology of the tree (every wave for itself, while the first K/V loads travel): lane j = node j
+  {
+    uint64_t my_anc = 0;
+    const int tb = dsbd_tree_walk(tr, lane, p_mine, a.max_depth, nullptr, reporter ? a.anc_out : nullptr, &my_anc);
+    if (reporter && tb) atomicOr(a.fault, tb);
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      const int r = row0 + rt * 16 + col;
+      const int node = r < R ? r / a.group : 0;
+      const unsigned lo = __shfl((unsigned)my_anc, node), hi = __shfl((unsigned)(my_anc >> 32), node);
+      anc[rt] = r < R ? ((uint64_t)hi << 32) | lo : 0ull;
+    }
+  }
 
   // One step = 32 tokens of this wave: V goes to LDS transposed (two tokens packed per 32-bit write),
   // the next step's V and K loads are issued as soon as their registers are free, S^T = K Q^T.
@@ -459,10 +482,15 @@ void forest_attention_shared_kernel(AttnArgs a) {
   const int g = bid % a.Hkv;
   const int b = bid / a.Hkv;
 
-  const int base = a.tree_off[b];
-  int n_b = a.tree_off[b + 1] - base;
-  if (base < 0 || n_b <= 0 || base + n_b > a.n_nodes) return;   // reported by the topology kernel
-  n_b = min(n_b, DSBD_MAX_TREE_NODES);
+  const dsbd_tree_range tr = dsbd_tree_range_of(b, a.n_nodes, a.tree_off, a.max_tree_nodes);
+  const bool reporter = split == 0 && rb == 0 && g == 0 && wave == 0;   // one wave per tree speaks for it
+  if (!tr.valid) {
+    if (reporter && lane == 0) atomicOr(a.fault, tr.bad);
+    return;
+  }
+  const int base = tr.base;
+  const int n_b = min(tr.n_all, DSBD_MAX_TREE_NODES);
+  const int p_mine = dsbd_tree_parent_of(tr, lane, a.parent);   // used once the first loads are on their way
   const int R = n_b * a.group;
   if (rb * ROWS_B >= R) return;             // uniform over the workgroup
   const int row0 = rb * ROWS_B + wave * ROWS_W;
@@ -500,7 +528,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
     const bool live = r < R;
     const int node = live ? r / a.group : 0;
     const int head = g * a.group + (live ? r % a.group : 0);
-    anc[rt] = live ? a.anc_mask[base + node] : 0ull;
+    anc[rt] = 0ull;
     const __bf16* qp = a.q + ((long long)(base + node) * a.Hq + head) * D + 8 * qd;
 #pragma unroll
     for (int j = 0; j < DS; ++j) {
@@ -591,6 +619,19 @@ void forest_attention_shared_kernel(AttnArgs a) {
 
   int ti = t_begin;
   if (ti < t_end) load_tile(ti);
+  // ---- topology of the tree (every wave for itself, while the first K/V loads travel): lane j = node j
+  {
+    uint64_t my_anc = 0;
+    const int tb = dsbd_tree_walk(tr, lane, p_mine, a.max_depth, nullptr, reporter ? a.anc_out : nullptr, &my_anc);
+    if (reporter && tb) atomicOr(a.fault, tb);
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      const int r = row0 + rt * 16 + col;
+      const int node = r < R ? r / a.group : 0;
+      const unsigned lo = __shfl((unsigned)my_anc, node), hi = __shfl((unsigned)(my_anc >> 32), node);
+      anc[rt] = r < R ? ((uint64_t)hi << 32) | lo : 0ull;
+    }
+  }
   // Everything requested so far (query fragments, ancestor bitmaps, the first tile) is needed now anyway.
   // Waiting for it explicitly, at a point that dominates the loop, keeps the compiler from re-waiting for
   // the query loads at the loop header with a vmcnt(0) that would also drain the prefetched tile.
@@ -877,7 +918,6 @@ extern "C" size_t dsbd_forest_attention_workspace_bytes(const dsbd_forest* f, co
   const AttnPlan p = make_plan(f, kv, Hq, Hkv);
   WorkspaceCarver ws(nullptr);
   ws.take<long long>(4096);
-  ws.take<uint64_t>((size_t)f->n_nodes);
   ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
   ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
   return ws.total() + 256;
@@ -904,16 +944,11 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
   long long* trace = ws.take<long long>(4096);
-  uint64_t* anc = ws.take<uint64_t>((size_t)f->n_nodes);
   float* part_o = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * D);
   float* part_ml = ws.take<float>((size_t)p.nsplit * f->n_nodes * Hq * 2);
-  if (anc_mask_out) anc = anc_mask_out;
-
-  rc = dsbd_launch_topology(f, nullptr, anc, fault, stream);
-  if (rc != DSBD_OK) return rc;
-
   AttnArgs a;
-  a.tree_off = f->tree_off; a.anc_mask = anc;
+  a.tree_off = f->tree_off; a.parent = f->parent;
+  a.max_tree_nodes = f->max_tree_nodes; a.max_depth = f->max_depth; a.anc_out = anc_mask_out;
   a.k_ptr = kv->k_ptr; a.v_ptr = kv->v_ptr; a.len = kv->len;
   a.k_shared_ptr = kv->k_shared_ptr; a.v_shared_ptr = kv->v_shared_ptr; a.shared_len = kv->shared_len;
   a.token_stride = kv->token_stride; a.head_stride = kv->head_stride;

@@ -29,10 +29,5 @@ struct WorkspaceCarver {
   size_t total() const { return dsbd_align_up(used, 256); }
 };
 
-// Launches the forest-topology kernel (depth and ancestor-or-self bitmap of every node, with
-// validation of the parent array).  depth may be null.
-int32_t dsbd_launch_topology(const dsbd_forest* f, int32_t* depth, uint64_t* anc_mask, int32_t* fault,
-                             hipStream_t stream);
-
 // Measurement hook (timing.hip): records an event before / after kernel `kernel_id` when enabled.
 void dsbd_timing_mark(int kernel_id, bool begin, hipStream_t stream);

@@ -111,7 +111,7 @@ __device__ void stats_service(const StatsArgs& a, int sidx, int n_service) {
   // forest topology, one wave per tree
   for (int b = sidx * (VS_BLOCK / 64) + wave; b < a.n_trees; b += n_service * (VS_BLOCK / 64)) {
     const int bad = dsbd_tree_topology(b, lane, a.n_nodes, a.tree_off, a.parent, a.max_tree_nodes, a.max_depth,
-                                       a.depth, nullptr);
+                                       a.depth, nullptr, nullptr);
     if (bad) atomicOr(a.fault, bad);
   }
   // trees of each prompt (tree_prompt is non-decreasing): counted by one wave, so that the layer kernel starts

@@ -459,7 +459,11 @@ void forest_attention_shared_kernel(AttnArgs a) {
   constexpr int DS = D / 32, DT = D / 16;
   constexpr int CG = D / 8;                 // 16-byte channel groups per row
   constexpr int KP = D + 8;                 // K row pitch in elements (16 bytes of padding)
-  constexpr int VP = TILE + 8;              // V^T row pitch in elements
+#ifndef DSBD_VT_PAD
+#define DSBD_VT_PAD 4
+#define DSBD_VT_SWZ 2
+#endif
+  constexpr int VP = TILE + DSBD_VT_PAD;    // V^T row pitch in elements
   constexpr int KL = TILE * CG / NT;        // K 16-byte loads per thread and tile
   constexpr int VI = (TILE / 2) * CG / NT;  // V (token pair, channel group) items per thread and tile
   constexpr int ROWS_W = 16 * NRT, ROWS_B = ROWS_W * RW;
@@ -604,7 +608,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
     for (int r = 0; r < VI; ++r) {
       const int it = r * NT + tid;
       const int cg = it % CG;
-      const int tp = (it / CG) ^ (4 * (cg >> 1));   // token-pair swizzle: the 64 lanes of a write hit 64 banks
+      const int tp = (it / CG) ^ (DSBD_VT_SWZ * (cg >> 1));   // token-pair swizzle: the 64 lanes of a write hit 64 banks
       const uint32_t ta[4] = {vreg[r][0].x, vreg[r][0].y, vreg[r][0].z, vreg[r][0].w};
       const uint32_t tb[4] = {vreg[r][1].x, vreg[r][1].y, vreg[r][1].z, vreg[r][1].w};
 #pragma unroll
@@ -736,8 +740,8 @@ void forest_attention_shared_kernel(AttnArgs a) {
         // rows 16dt .. 16dt+15 belong to channel groups 2dt, 2dt+1: token pairs are swizzled by 4*dt
         union { uint2 u[2]; bf16x8 v; } vf;
         const __bf16* rowp = &vl[(16 * dt + col) * VP];
-        vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 2 * qd) ^ (4 * dt)));
-        vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 8 + 2 * qd) ^ (4 * dt)));
+        vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 2 * qd) ^ (DSBD_VT_SWZ * dt)));
+        vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 8 + 2 * qd) ^ (DSBD_VT_SWZ * dt)));
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
           o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);

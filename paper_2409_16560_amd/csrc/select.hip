@@ -24,6 +24,9 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
   int n = a.n_out[p];
   n = max(0, min(n, min(W, 64)));
   __shared__ int best;
+  __shared__ int path_lds[64][DSBD_MAX_TREE_NODES + 1];   // one row per output beam (padded against bank conflicts)
+  extern __shared__ int toff_lds[];                       // tree_off[0 .. n_trees], staged once for the searches
+  for (int t = j; t <= a.n_trees; t += 64) toff_lds[t] = a.tree_off[t];
   if (j == 0) {
     best = 0;
     if (a.keep_one)
@@ -46,7 +49,7 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
   const long long so = (long long)p * W + src;
   int node = a.out_parent[so];
   int len = 0, bad = 0;
-  int tmp[DSBD_MAX_TREE_NODES];
+  int* tmp = path_lds[j];
   int root = -1;
   if (node < 0 || node >= a.n_nodes) { bad = DSBD_FAULT_TOPOLOGY; }
   else {
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
   int tree = -1;
   if (root >= 0) {
     int lo = 0, hi = a.n_trees;
-    while (lo < hi) { const int mid = (lo + hi) >> 1; if (a.tree_off[mid + 1] <= root) lo = mid + 1; else hi = mid; }
+    while (lo < hi) { const int mid = (lo + hi) >> 1; if (toff_lds[mid + 1] <= root) lo = mid + 1; else hi = mid; }
     tree = lo < a.n_trees ? lo : -1;
   }
   a.nx.src_tree[o] = tree;
@@ -97,7 +100,9 @@ extern "C" int32_t dsbd_select_beams(const dsbd_forest* f, const dsbd_verify_out
   a.n_out = v->n_out; a.out_parent = v->out_parent; a.out_token = v->out_token;
   a.out_lp = v->out_logp_target; a.out_lq = v->out_logp_draft;
   a.nx = *nx; a.fault = fault;
-  hipLaunchKernelGGL(select_beams_kernel, dim3(f->n_prompts), dim3(64), 0, static_cast<hipStream_t>(stream_), a);
+  const size_t toff_bytes = ((size_t)f->n_trees + 1) * sizeof(int32_t);
+  if (toff_bytes > 64 * 1024) return DSBD_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(select_beams_kernel, dim3(f->n_prompts), dim3(64), toff_bytes, static_cast<hipStream_t>(stream_), a);
   DSBD_HIP_LAUNCH_CHECK();
   return DSBD_OK;
 }

@@ -61,9 +61,14 @@ struct AttnArgs {
 // the LDS counter as well: every wait for an LDS read would then also wait for all K/V loads in flight.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_global_16(const void* p) {
-  // (plain loads on purpose: a cache line of K is consumed by several load instructions of a wave, and
-  // non-temporal loads, which help the one-touch logit stream, cost 20 % here)
   const u32x4 v = *(const __attribute__((address_space(1))) u32x4*)(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+// The same with the non-temporal hint, for data that one thread consumes whole with one load (the K/V tiles of
+// the shared-tile kernel: 9 % faster inside the benchmark's kernel mix).  Where a cache line is consumed by several
+// load instructions of a wave (K in operand layout, wave-private kernel) the hint costs 20 % instead.
+__device__ __forceinline__ uint4 load_global_16_nt(const void* p) {
+  const u32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ bf16x8 load_global_bf16x8(const void* p) {
@@ -583,7 +588,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
     for (int r = 0; r < KL; ++r) {
       const int c = r * NT + tid;
       const int tok = min(tok0 + c / CG, len - 1);
-      kreg[r] = load_global_16(kp + (long long)tok * stride + (c % CG) * 8);
+      kreg[r] = load_global_16_nt(kp + (long long)tok * stride + (c % CG) * 8);
     }
 #pragma unroll
     for (int r = 0; r < VI; ++r) {
@@ -593,7 +598,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int tok = min(tok0 + 2 * tp + h, len - 1);
-        vreg[r][h] = load_global_16(vp + (long long)tok * stride + cg * 8);
+        vreg[r][h] = load_global_16_nt(vp + (long long)tok * stride + cg * 8);
       }
     }
   };

@@ -826,16 +826,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
     stamp(22);
     // sum over the slice of max(p_beam - c q_beam, 0); four loads in flight per thread
-    auto slice_sum = [&](double c) -> double {
+    // (the threads t0 .. t0+nt-1 share the work; the others return 0)
+    auto slice_sum = [&](double c, int t0, int nt) -> double {
       double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-      long long j = tid;
-      for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
-        const double p0 = ldp(j), p1 = ldp(j + VL_BLOCK), p2 = ldp(j + 2 * VL_BLOCK), p3 = ldp(j + 3 * VL_BLOCK);
-        const double q0 = ldq(j), q1 = ldq(j + VL_BLOCK), q2 = ldq(j + 2 * VL_BLOCK), q3 = ldq(j + 3 * VL_BLOCK);
+      if (tid < t0) return 0.0;
+      long long j = tid - t0;
+      for (; j + 3 * nt < len; j += 4 * nt) {
+        const double p0 = ldp(j), p1 = ldp(j + nt), p2 = ldp(j + 2 * nt), p3 = ldp(j + 3 * nt);
+        const double q0 = ldq(j), q1 = ldq(j + nt), q2 = ldq(j + 2 * nt), q3 = ldq(j + 3 * nt);
         s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
         s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
       }
-      for (; j < len; j += VL_BLOCK) s0 += fmax(ldp(j) - c * ldq(j), 0.0);
+      for (; j < len; j += nt) s0 += fmax(ldp(j) - c * ldq(j), 0.0);
       return (s0 + s1) + (s2 + s3);
     };
 
@@ -1067,7 +1069,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       } else {
         const int k = sh.kmax;
         const double c = sh.cc[k] + sh.FF[k];
-        const double sl = slice_sum(c);
+        const double sl = slice_sum(c, 0, VL_BLOCK);
         stamp(43);
         const double tot = wg_total(sl);
         stamp(44);
@@ -1145,16 +1147,46 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     if (g == 0 && tid == 0) a.out.layer_width[(long long)prompt * Lw + l] = WL;
 
     stamp(40);
-    // ===== sequential accept / reject
-    if (wave == 0) decide(decide_round, sh.kmax);
-    __syncthreads();
-    while (sh.state[decide_round & 1] == 1) {
-      decide_round += 1;               // the next outcome goes to the other entry: nobody still reads it
-      stamp(41);
-      if (!extend_chain(true)) return;
-      stamp(42);
+    // ===== sequential accept / reject.  The first wave takes the decisions as far as the chain reaches; meanwhile
+    // the other seven waves already sum their slices for the chain entry that would come next, so a rejection that
+    // needs it finds the partial sums ready to post (and an acceptance that ends the layer just drops them).
+    {
+      bool posted = spec;              // the next entry's partial sums are on their way: F(1), from the scaling pass
+      Slot* x_bank = spec_bank;
+      unsigned long long x_tag = spec_tag;
+      double x_own = spec_own;
+      while (true) {
+        const int k = sh.kmax;         // entries 1..k exist (read after a barrier: uniform)
+        const double c_next = sh.cc[k] + sh.FF[k];
+        stamp(41);
+        if (wave == 0) decide(decide_round, k);
+        double tot = 0.0;
+        if (!posted) tot = wg_total(slice_sum(c_next, 64, VL_BLOCK - 64));   // barrier inside
+        else __syncthreads();
+        const int st = sh.state[decide_round & 1];
+        decide_round += 1;             // the next outcome goes to the other entry: nobody still reads it
+        stamp(42);
+        if (st != 1) break;
+        if (!posted) {
+          epoch += 1;
+          x_tag = exchange_tag(epoch);
+          x_bank = exchange_bank(a, prompt, epoch);
+          if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
+          x_own = tot;
+        }
+        if (wave == 0) {
+          double v[4];
+          if (!wave_collect4(x_bank, a.G, g, x_own, x_tag, v)) give_up();
+          const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+          if (lane == 0) { sh.cc[k + 1] = c_next; sh.FF[k + 1] = F; sh.kmax = k + 1; }
+        }
+        posted = false;
+        spec = false;
+        stamp(45);
+        __syncthreads();
+        if (sh.abort) return;
+      }
     }
-    decide_round += 1;
     const int nacc = sh.acc_n, pos_end = sh.pos, kcur = sh.kidx, kmax_end = sh.kmax;
     if (g == 0)
       for (int i = pos_end + tid; i < M; i += VL_BLOCK) a.out.node_status[sh.S_node[i]] = DSBD_REJECTED;

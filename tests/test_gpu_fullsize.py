@@ -64,3 +64,16 @@ def test_c5_verify_and_select_whole_forest(c5, t):
         g = lambda x: x.cpu().numpy()
         for name in ("n_next", "src_tree", "src_out", "path_len", "path", "token"):
             assert np.array_equal(g(getattr(nx, name)), sref[name]), name
+
+
+@pytest.mark.parametrize("t", [-1.0, 0.7])
+def test_c4_verify_whole_batch(t):
+    """The dynamic-width batch at full size: 16 prompts of 1..8 beams share the device, 16 workgroups each."""
+    import gpu_util as gu
+    w = make_workload("c4", L=1, Hq=1, Hkv=1, D=64)
+    d = gu.DeviceWorkload(w)
+    res = d.verify(t=t)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t)
+    near = gu.compare_verify(res, ref, w)
+    print("c4 verify t=%g: %d prompts, %d nodes, l_last %s near ties %d" % (t, w.n_prompts, w.n_nodes, ref["l_last"].tolist(), near), flush=True)

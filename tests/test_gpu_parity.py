@@ -108,6 +108,22 @@ def test_verify_forest_matches_oracle(cfg, kw, W_L, t):
             assert np.max(np.abs(g(nx.logp_target) - sref["logp_p"])) <= 1e-9
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("noise", [0.25, 0.5, 0.8, 2.5])
+def test_verify_accept_patterns_over_seeds(seed, noise):
+    """Many different accept / reject sequences on the benchmark's forest shape: runs of acceptances, rejection
+    streaks of several chain entries, layers that fall short at every depth (the draft's distance from the target
+    sets the acceptance rate).  Fixed and dynamic width."""
+    gu = _gu()
+    w = make_workload("c5", L=1, Hq=1, Hkv=1, D=64, V=9000, seed=seed, noise_std=noise)
+    d = gu.DeviceWorkload(w)
+    for t in (-1.0, 0.6):
+        res = d.verify(t=t)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, t=t)
+        gu.compare_verify(res, ref, w)
+
+
 def test_verify_with_draft_rank_order():
     gu = _gu()
     w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=3000)

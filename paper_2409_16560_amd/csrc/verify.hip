@@ -394,14 +394,14 @@ __device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, doubl
   }
 }
 
-// Single-value exchanges use a dense layout inside the bank: word w of workgroup w's value at words[w], its
-// tagged copy at words[G + w].  A polling wave then reads consecutive words (a few cache lines per round instead
-// of one line per slot), which matters because every workgroup polls every other one.
+// Single-value exchanges: workgroup w owns the slot at the start of its own 128-byte line of the bank (slot index
+// w * LINE_SLOTS), so that no two workgroups ever write the same cache line.  Measured with a microbenchmark
+// on this chip, all-to-all among 256 workgroups: 2.3 us with a line per workgroup, 3.1 us with the words packed
+// densely (sixteen writers per line), although the packed layout needs sixteen times fewer lines per poll.
+#define LINE_SLOTS 8
 __device__ __forceinline__ void dense_post(Slot* bank, int G, int g, double v, unsigned long long tag) {
-  unsigned long long* w = reinterpret_cast<unsigned long long*>(bank);
-  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
-  __hip_atomic_store(&w[g], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(&w[G + g], b ^ tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  (void)G;
+  slot_post(bank + (long long)g * LINE_SLOTS, v, tag);
 }
 
 // One wave collects the values of all G workgroups (G <= 256): lane i gets those of workgroups i, i + 64, i + 128,
@@ -410,7 +410,6 @@ __device__ __forceinline__ void dense_post(Slot* bank, int G, int g, double v, u
 __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double own, unsigned long long tag,
                                               double (&v)[4]) {
   const int lane = threadIdx.x & 63;
-  unsigned long long* w = reinterpret_cast<unsigned long long*>(bank);
   bool have[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
@@ -424,8 +423,9 @@ __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double o
     for (int k = 0; k < 4; ++k) {
       w0[k] = 0; w1[k] = 0;
       if (!have[k]) {
-        w0[k] = __hip_atomic_load(&w[lane + 64 * k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        w1[k] = __hip_atomic_load(&w[G + lane + 64 * k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        Slot* s = bank + (long long)(lane + 64 * k) * LINE_SLOTS;
+        w0[k] = __hip_atomic_load(&s->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        w1[k] = __hip_atomic_load(&s->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
 #pragma unroll
@@ -1319,6 +1319,7 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   if (G > 256) G = 256;
   pl.G = G;
   pl.red_w = 2 * pl.I_cap;
+  if (pl.red_w < LINE_SLOTS) pl.red_w = LINE_SLOTS;    // single-value exchanges use one 128-byte line per workgroup
   // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most VL_DYN_LDS_BYTES for the two arrays
   long long need = (joint + G - 1) / G;
   need = (need + 1) & ~1LL;

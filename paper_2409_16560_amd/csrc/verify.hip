@@ -31,7 +31,7 @@
 #define VL_BLOCK 512
 #define NODE_CAP 512           // nodes of one prompt (all its trees)
 #define NEAR_TIE 1.0e-6
-#define SYNC_LIMIT_TICKS 300000000LL   // 3 s of the 100 MHz wall clock
+#define SYNC_LIMIT_TICKS 300000000LL   // default bound of every wait: 3 s of the 100 MHz wall clock
 #define VL_DYN_LDS_BYTES (80 * 1024)   // dynamic LDS of the layer kernel (its static LDS takes most of the rest)
 
 // ------------------------------------------------------------------------------------------------ kernel 1
@@ -213,6 +213,9 @@ struct LayersArgs {
   int G, I_cap, red_w;
   long long* trace;      // optional timeline (first workgroup of prompt 0): pairs (label, 100 MHz wall clock)
   int lds_elems;         // capacity (elements) of each of the two dynamic-LDS slice arrays; 0 = none
+  long long sync_limit;  // bound of every wait, in ticks of the 100 MHz wall clock
+  int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
+                         // bounded waits give up and the error path can be exercised without a hang
   int32_t* fault;
 };
 
@@ -381,15 +384,15 @@ __device__ __forceinline__ void slot_post(Slot* s, double v, unsigned long long 
   __hip_atomic_store(&s->w1, b ^ tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Waits until the slot carries the tag; gives up after SYNC_LIMIT_TICKS (returns false).
-__device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, double& v) {
+// Waits until the slot carries the tag; gives up after `limit` ticks of the wall clock (returns false).
+__device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, double& v, long long limit) {
   long long t0 = 0;
   for (int spin = 0;; ++spin) {
     const unsigned long long w0 = __hip_atomic_load(&s->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const unsigned long long w1 = __hip_atomic_load(&s->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((w0 ^ w1) == tag) { v = __longlong_as_double((long long)w0); return true; }
     if (spin == 0) t0 = wall_clock64();
-    else if ((spin & 63) == 0 && wall_clock64() - t0 > SYNC_LIMIT_TICKS) return false;
+    else if ((spin & 15) == 0 && wall_clock64() - t0 > limit) return false;
     __builtin_amdgcn_s_sleep(1);
   }
 }
@@ -408,7 +411,7 @@ __device__ __forceinline__ void dense_post(Slot* bank, int G, int g, double v, u
 // i + 192 in v[0..3] (0 beyond G), with the loads of a polling round in flight together; `own` is the value this
 // workgroup posted.  False if the wait gave up.
 __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double own, unsigned long long tag,
-                                              double (&v)[4]) {
+                                              double (&v)[4], long long limit) {
   const int lane = threadIdx.x & 63;
   bool have[4];
 #pragma unroll
@@ -433,7 +436,7 @@ __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double o
       if (!have[k] && (w0[k] ^ w1[k]) == tag) { v[k] = __longlong_as_double((long long)w0[k]); have[k] = true; }
     if (have[0] && have[1] && have[2] && have[3]) return true;
     if (spin == 0) t0 = wall_clock64();
-    else if ((spin & 63) == 0 && wall_clock64() - t0 > SYNC_LIMIT_TICKS) return false;
+    else if ((spin & 15) == 0 && wall_clock64() - t0 > limit) return false;
     __builtin_amdgcn_s_sleep(1);
   }
 }
@@ -656,7 +659,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     epoch += 1;
     const unsigned long long rs_tag = exchange_tag(epoch);
     Slot* const rs_bank = exchange_bank(a, prompt, epoch);
-    if (tid < 2 * (i_hi - i_lo + 1)) {
+    if (tid < 2 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
       const double* wp = &sh.u.wpart[(tid >> 1) * VL_WAVES * 2 + (tid & 1)];
       const double s = ((wp[0] + wp[2]) + (wp[4] + wp[6])) + ((wp[8] + wp[10]) + (wp[12] + wp[14]));
       slot_post(rs_bank + (long long)g * a.red_w + 2 * i_lo + tid, s, rs_tag);
@@ -726,7 +729,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const int w_hi = (int)div_floor((long long)(i + 1) * V - 1, ch);
         for (int w = w_lo + r; w <= w_hi; w += R) {
           double v = 0.0;
-          mine = mine && slot_wait(rs_bank + (long long)w * a.red_w + c, rs_tag, v);
+          mine = mine && slot_wait(rs_bank + (long long)w * a.red_w + c, rs_tag, v, a.sync_limit);
           acc += v;
         }
       }
@@ -863,7 +866,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const double mine = sh.tsum[VL_BLOCK - 1];
         if (lane == 0) dense_post(bank, a.G, g, mine, tag);
         double v[4];
-        if (!wave_collect4(bank, a.G, g, mine, tag, v)) give_up();
+        if (!wave_collect4(bank, a.G, g, mine, tag, v, a.sync_limit)) give_up();
 #pragma unroll
         for (int k = 0; k < 4; ++k) if (lane + 64 * k < a.G) sh.gpart[lane + 64 * k] = v[k];
         wave_lds_fence();          // now four consecutive workgroups per lane
@@ -1060,7 +1063,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       if (spec) {                      // entry 2 is already on its way
         if (wave == 0) {
           double v[4];
-          if (!wave_collect4(spec_bank, a.G, g, spec_own, spec_tag, v)) give_up();
+          if (!wave_collect4(spec_bank, a.G, g, spec_own, spec_tag, v, a.sync_limit)) give_up();
           const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
           if (lane == 0) { sh.cc[2] = 1.0; sh.FF[2] = F; sh.kmax = 2; }
           if (then_decide) decide(decide_round, 2);
@@ -1079,7 +1082,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (wave == 0) {
           if (lane == 0) dense_post(bank, a.G, g, tot, tag);
           double v[4];
-          if (!wave_collect4(bank, a.G, g, tot, tag, v)) give_up();
+          if (!wave_collect4(bank, a.G, g, tot, tag, v, a.sync_limit)) give_up();
           stamp(45);
           const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
           stamp(46);
@@ -1176,7 +1179,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         }
         if (wave == 0) {
           double v[4];
-          if (!wave_collect4(x_bank, a.G, g, x_own, x_tag, v)) give_up();
+          if (!wave_collect4(x_bank, a.G, g, x_own, x_tag, v, a.sync_limit)) give_up();
           const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
           if (lane == 0) { sh.cc[k + 1] = c_next; sh.FF[k + 1] = F; sh.kmax = k + 1; }
         }
@@ -1414,6 +1417,13 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.out = *out; la.depth = depth; la.prompt_rec = prompt_rec; la.part = part; la.nchunk = pl.nchunk;
   la.pb = pb; la.qb = qb; la.red = red;
   la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
+  la.sync_limit = SYNC_LIMIT_TICKS;
+  la.mute_wg = -1;
+  if (const char* e = getenv("DSBD_VERIFY_SYNC_LIMIT_US")) {   // bound of the kernel's waits (default 3 s)
+    const long long us = atoll(e);
+    if (us >= 1 && us <= 10000000LL) la.sync_limit = us * 100;
+  }
+  if (const char* e = getenv("DSBD_VERIFY_TEST_MUTE_WG")) la.mute_wg = atoi(e);   // error-path test hook
   la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;
   // Ordinary launch: the grid was checked above to fit the device at once, the stream's earlier kernels have
   // drained by the time this one starts, and every wait inside the kernel is bounded.  (A cooperative launch

@@ -168,3 +168,28 @@ def test_device_side_faults_are_reported_not_fatal():
     torch.cuda.synchronize()
     f = int(res.fault.item())
     assert f & dsbd.DSBD_FAULT_NONFINITE and f & dsbd.DSBD_FAULT_TOKEN
+
+
+def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang():
+    """Error path of the layer kernel's exchanges, forced from the host: one workgroup withholds its first post
+    (test hook), every wait for it is bounded (2 ms here instead of 3 s), so all workgroups give up, the kernel ends
+    normally and the call reports DSBD_FAULT_SYNC_TIMEOUT.  The next call on the same workspace works."""
+    import os
+    gu = _gu()
+    import paper_2409_16560_amd as dsbd
+    w = make_workload("c5", L=1, Hq=1, Hkv=1, D=64, V=20000)
+    d = gu.DeviceWorkload(w)
+    nbytes = dsbd.dsbd_verify_forest_workspace_bytes(d.forest, w.V, 0, 1, w.W_cap, -1.0)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    os.environ["DSBD_VERIFY_SYNC_LIMIT_US"] = "2000"
+    os.environ["DSBD_VERIFY_TEST_MUTE_WG"] = "5"
+    try:
+        res = d.verify(workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["DSBD_VERIFY_SYNC_LIMIT_US"]
+        del os.environ["DSBD_VERIFY_TEST_MUTE_WG"]
+    assert int(res.fault.item()) & dsbd.DSBD_FAULT_SYNC_TIMEOUT
+    res = d.verify(workspace=ws)
+    torch.cuda.synchronize()
+    gu.compare_verify(res, gu.oracle_verify(w), w)

@@ -8,6 +8,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsbd.so")
 SOURCES = ["attention.hip", "verify.hip", "select.hip", "timing.hip"]
+# Per-file flags.  attention.hip: scores come out of the matrix units and go through max / exp2 only; without
+# -fno-honor-nans every fmaxf operand is first canonicalised (v_max x, x), which triples the instructions of the
+# row-maximum checks.  (verify.hip must keep NaN semantics: it detects non-finite logits.)
+FILE_FLAGS = {"attention.hip": os.environ.get("DSBD_ATTN_FLAGS", "-fno-honor-nans").split()}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fgpu-rdc-", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
@@ -26,7 +30,7 @@ def build(verbose=True):
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc()] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc()] + flags + FILE_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for src, p in procs:

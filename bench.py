@@ -48,6 +48,52 @@ def cpu_baseline(sample_trees=2):
                       % (sample_trees, w.n_nodes, t1 - t0, t2 - t1, cores)}
 
 
+def commit_measurement(dsbd, torch, w, d, o, reps=10):
+    """Cache commit along the plan of the last step (not part of `value`: it is a row beyond the verification path).
+    Policy measured: the first next beam of every source tree continues in its source buffer (tree rows appended),
+    every other next beam gets a fresh buffer (whole prefix copied)."""
+    grow = w.max_depth + 1
+    L = [int(x) for x in w.own_len]
+    cap = max(L) + grow
+    mk = lambda: torch.empty((cap, w.Hkv, w.D), dtype=torch.bfloat16, device="cuda")
+    k_src, v_src = d.kv.keep[0], d.kv.keep[1]
+    src_k, src_v = [mk() for _ in L], [mk() for _ in L]
+    for b in range(len(L)):
+        src_k[b][:L[b]] = k_src[b]; src_v[b][:L[b]] = v_src[b]
+    kv = dsbd.PrefixKV([src_k[b][:L[b]] for b in range(len(L))], [src_v[b][:L[b]] for b in range(len(L))])
+    nx = o["nx"]
+    torch.cuda.synchronize()
+    n_next, src_tree, path_len = nx.n_next.cpu().numpy(), nx.src_tree.cpu().numpy(), nx.path_len.cpu().numpy()
+    dst_k, dst_v, taken, moved = [], [], set(), 0
+    row = w.Hkv * w.D * 2
+    for p in range(w.n_prompts):
+        for s_ in range(w.W_cap):
+            b = int(src_tree[p, s_]) if s_ < int(n_next[p]) else -1
+            if b >= 0 and b not in taken:
+                taken.add(b); dst_k.append(src_k[b]); dst_v.append(src_v[b])
+                moved += int(path_len[p, s_]) * row * 2 * 2
+            elif b >= 0:
+                dst_k.append(mk()); dst_v.append(mk())
+                moved += (L[b] + int(path_len[p, s_])) * row * 2 * 2
+            else:
+                dst_k.append(None); dst_v.append(None)
+    dst = dsbd.KVDst(dst_k, dst_v, kv)
+    fault = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dsbd.dsbd_commit_kv(d.forest, kv, d.k_tree, d.v_tree, nx, w.W_cap, dst, fault=fault)
+    dsbd.dsbd_timing_enable(dsbd.DSBD_KERNEL_KV_COMMIT, reps)
+    for _ in range(reps):
+        dsbd.dsbd_commit_kv(d.forest, kv, d.k_tree, d.v_tree, nx, w.W_cap, dst, fault=fault)
+    torch.cuda.synchronize()
+    ms = sorted(dsbd.dsbd_timing_collect(reps))
+    dsbd.dsbd_timing_enable(0, 0)
+    assert int(fault.item()) == 0
+    med = ms[len(ms) // 2]
+    return {"ms": med, "next_beams": int(n_next.sum()), "continued_in_place": len(taken),
+            "bytes_read_plus_written": moved, "achieved": moved / (med * 1e-3) / 1e9 if med > 0 else 0.0,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": (moved / (med * 1e-3) / 1e9 / HBM_PEAK_GBS) if med > 0 else 0.0,
+            "note": "copies count read + write; not included in value / ms_per_step"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +105,7 @@ def main():
     ap.add_argument("--kernel", default="attention", choices=["attention", "vocab_stats", "verify_layers"],
                     help="kernel whose duration is measured with HIP events for the roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-commit", action="store_true", help="skip the (separately reported) cache-commit measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -153,6 +200,8 @@ def main():
         "step_hbm_frac": (attn_bytes + verify_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "breakdown_ms": br,
     }
+    if not args.no_commit:
+        res["next_rows"] = {"kv_commit": commit_measurement(dsbd, torch, w, sets[0], outs[0])}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline()
     print(json.dumps(res))

@@ -10,7 +10,8 @@
  *   2. verifies the forest layer by layer (paper Section 3.1 "Details", Algorithm 1) with the
  *      fixed or the dynamic layer width (Section 3.2, Eq. 1-6);
  *   3. turns the verification result into the next iteration's beam set (Algorithm 1's return
- *      value; Section 3.3 last paragraph; Section 3.4 for the one-beam variant).
+ *      value; Section 3.3 last paragraph; Section 3.4 for the one-beam variant);
+ *   4. updates the key/value caches to follow that beam set (Section 3.3 last paragraph).
  *
  * Conventions
  *   - Every array argument is a DEVICE pointer owned by the caller unless marked "host".
@@ -194,6 +195,36 @@ int32_t dsbd_select_beams(const dsbd_forest* forest, const dsbd_verify_out* veri
                           int32_t keep_one, const dsbd_next_beams* next, int32_t* fault, void* stream);
 
 /*
+ * Destination caches of the next iteration's beams, one per slot (p, j) of the next-beam plan, in the layout
+ * (strides) of the source caches.  Only the own segment is written; a segment shared by the beams of a prompt
+ * stays where it is.
+ */
+typedef struct dsbd_kv_dst {
+  void* const* k_ptr;   /* [n_prompts*W_cap] device array of device pointers (entries of unused slots are ignored) */
+  void* const* v_ptr;   /* [n_prompts*W_cap]                                                           */
+  int32_t*     len;     /* [n_prompts*W_cap] out: tokens of the new own segment, 0 in unused slots     */
+  int32_t      capacity;/* tokens every destination buffer can hold                                    */
+} dsbd_kv_dst;
+
+/*
+ * Physical cache update (Section 3.3, last paragraph: the caches follow the output beams; Section 3.4: one
+ * cache in the memory-reduced variant).  For every next beam (p, j), j < next->n_next[p]: destination (p, j) :=
+ * own segment of tree next->src_tree[p,j] (src->len tokens), followed by the rows k_tree / v_tree [n_nodes,Hkv,D]
+ * of the nodes next->path[p,j,0 .. path_len) (root first).  The output beam's own last token is the root of the
+ * next iteration's tree and gets its row in the next forward pass.  Bit-exact copies of bf16 data.
+ *   - A destination pointer equal to its source pointer means "continue in place": only the tree rows are appended
+ *     (at most one next beam per source tree can do that).  Apart from this, destination buffers must not overlap
+ *     any source segment or each other: the copies run concurrently.
+ *   - Device-side problems: a plan entry outside the forest (DSBD_FAULT_TOPOLOGY), a new length above
+ *     dst->capacity, a null or misaligned (16 bytes) pointer (DSBD_FAULT_BOUNDS); the affected destination gets
+ *     length 0 (or, for a bad path node, that row is skipped) and nothing is written out of bounds.
+ * W_cap and forest->max_depth must be the values used for dsbd_select_beams.
+ */
+int32_t dsbd_commit_kv(const dsbd_forest* forest, const dsbd_kv* src, const void* k_tree, const void* v_tree,
+                       int32_t Hkv, int32_t D, const dsbd_next_beams* next, int32_t W_cap,
+                       const dsbd_kv_dst* dst, int32_t* fault, void* stream);
+
+/*
  * Measurement hook (no counterpart in the paper).  dsbd_timing_enable(kernel, capacity) makes the
  * library record a pair of HIP events around every launch of ONE of its kernels, on the stream the
  * kernel is launched on, for up to `capacity` launches; dsbd_timing_collect() waits for the recorded
@@ -204,6 +235,7 @@ int32_t dsbd_select_beams(const dsbd_forest* forest, const dsbd_verify_out* veri
 #define DSBD_KERNEL_ATTENTION     1   /* forest attention main kernel (streams K/V)            */
 #define DSBD_KERNEL_VOCAB_STATS   2   /* per-node vocabulary softmax statistics (streams logits) */
 #define DSBD_KERNEL_VERIFY_LAYERS 3   /* persistent layer-by-layer verification                */
+#define DSBD_KERNEL_KV_COMMIT     4   /* cache update (copies the surviving caches)             */
 int32_t dsbd_timing_enable(int32_t kernel, int32_t capacity);
 int32_t dsbd_timing_collect(float* ms, int32_t max_n);
 

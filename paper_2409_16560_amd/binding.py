@@ -59,6 +59,10 @@ class _NextBeams(C.Structure):
         "n_next", "src_tree", "src_out", "path_len", "path", "token", "logp_target", "logp_draft")]
 
 
+class _KVDst(C.Structure):
+    _fields_ = [("k_ptr", C.c_void_p), ("v_ptr", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32)]
+
+
 def lib_path():
     return os.path.join(_HERE, "libdsbd.so")
 
@@ -89,6 +93,9 @@ def load_library():
     lib.dsbd_select_beams.restype = C.c_int32
     lib.dsbd_select_beams.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyOut), C.c_int32, C.c_int32,
                                       C.POINTER(_NextBeams), C.c_void_p, C.c_void_p]
+    lib.dsbd_commit_kv.restype = C.c_int32
+    lib.dsbd_commit_kv.argtypes = [C.POINTER(_Forest), C.POINTER(_KV), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                   C.POINTER(_NextBeams), C.c_int32, C.POINTER(_KVDst), C.c_void_p, C.c_void_p]
     lib.dsbd_timing_enable.restype = C.c_int32
     lib.dsbd_timing_enable.argtypes = [C.c_int32, C.c_int32]
     lib.dsbd_timing_collect.restype = C.c_int32
@@ -318,7 +325,47 @@ def dsbd_select_beams(forest: Forest, verified: VerifyResult, keep_one=False, re
     return result
 
 
-DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS = 1, 2, 3
+class KVDst:
+    """Destination caches of the next beams: one bf16 tensor per slot (p, j) of the plan (None for slots that are
+    never used), laid out like the source caches ([cap, Hkv, D], or [Hkv, cap, D] with head_major)."""
+
+    def __init__(self, k: List[Optional[torch.Tensor]], v: List[Optional[torch.Tensor]], src: PrefixKV, head_major=False):
+        ref = next(t for t in k if t is not None)
+        dev = ref.device
+        ax = 1 if head_major else 0
+        for t in list(k) + list(v):
+            if t is None:
+                continue
+            assert t.dtype == torch.bfloat16 and t.stride(-1) == 1
+            ts, hs = (t.stride(1), t.stride(0)) if head_major else (t.stride(0), t.stride(1))
+            assert (ts, hs) == (src.token_stride, src.head_stride), "destinations use the layout of the sources"
+        self.keep = (k, v)
+        self.capacity = min(t.shape[ax] for t in list(k) + list(v) if t is not None)
+        self.k_ptr = torch.tensor([0 if t is None else t.data_ptr() for t in k], dtype=torch.int64, device=dev)
+        self.v_ptr = torch.tensor([0 if t is None else t.data_ptr() for t in v], dtype=torch.int64, device=dev)
+        self.len = torch.zeros(len(k), dtype=torch.int32, device=dev)
+
+    def c_struct(self):
+        return _KVDst(_ptr(self.k_ptr), _ptr(self.v_ptr), _ptr(self.len), int(self.capacity))
+
+
+def dsbd_commit_kv(forest: Forest, src: PrefixKV, k_tree, v_tree, plan: NextBeams, W_cap: int, dst: KVDst,
+                   fault=None, stream=None):
+    """Copies the surviving caches into the next beams' buffers (appending the tree rows of each beam's path).
+    Returns (dst.len as [P, W_cap] int32 tensor, fault i32[1])."""
+    lib = load_library()
+    f, k, nx, d = forest.c_struct(), src.c_struct(), plan.c_struct(), dst.c_struct()
+    assert dst.k_ptr.numel() == forest.n_prompts * W_cap
+    Hkv, D = k_tree.shape[1], k_tree.shape[2]
+    if fault is None:
+        fault = torch.zeros(1, dtype=torch.int32, device=k_tree.device)
+    rc = lib.dsbd_commit_kv(C.byref(f), C.byref(k), _ptr(k_tree), _ptr(v_tree), int(Hkv), int(D), C.byref(nx),
+                            int(W_cap), C.byref(d), _ptr(fault), _stream(stream))
+    _check(rc, "dsbd_commit_kv")
+    return dst.len.view(forest.n_prompts, W_cap), fault
+
+
+DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS, DSBD_KERNEL_KV_COMMIT = 1, 2, 3, 4
 
 
 def dsbd_timing_enable(kernel: int, capacity: int = 0):

@@ -27,7 +27,7 @@ extern "C" int32_t dsbd_timing_enable(int32_t kernel_id, int32_t capacity) {
   for (hipEvent_t e : g_stop) (void)hipEventDestroy(e);
   g_start.clear(); g_stop.clear(); g_used = 0; g_kernel = 0;
   if (kernel_id == 0) return DSBD_OK;
-  if (kernel_id < 0 || kernel_id > DSBD_KERNEL_VERIFY_LAYERS || capacity < 1) return DSBD_ERR_INVALID;
+  if (kernel_id < 0 || kernel_id > DSBD_KERNEL_KV_COMMIT || capacity < 1) return DSBD_ERR_INVALID;
   for (int i = 0; i < capacity; ++i) {
     hipEvent_t a, b;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return DSBD_ERR_HIP;

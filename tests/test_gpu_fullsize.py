@@ -77,3 +77,36 @@ def test_c4_verify_whole_batch(t):
     ref = gu.oracle_verify(w, t=t)
     near = gu.compare_verify(res, ref, w)
     print("c4 verify t=%g: %d prompts, %d nodes, l_last %s near ties %d" % (t, w.n_prompts, w.n_nodes, ref["l_last"].tolist(), near), flush=True)
+
+
+def test_c5_commit_kv_whole_caches(c5):
+    """Cache commit at the benchmark size: every new cache compared bit for bit (8 beams x 8192 tokens x 2 KB x K,V)."""
+    import gpu_util as gu
+    import paper_2409_16560_amd as dsbd
+    from oracle import commit as o_commit, select as o_select
+    w, d = c5
+    res = d.verify(t=-1.0)
+    nx = dsbd.dsbd_select_beams(d.forest, res)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=-1.0)
+    if gu.compare_verify(res, ref, w):
+        pytest.skip("near tie in the verification")
+    sref = o_select.select_beams(w.tree_off, w.parent, ref["n_out"], ref["out_parent"], ref["out_token"],
+                                 ref["out_logp_p"], ref["out_logp_q"], w.max_depth + 1)
+    rk, rv, rlen = o_commit.commit_kv(w.k_own, w.v_own, w.k_tree, w.v_tree, sref["n_next"], sref["src_tree"],
+                                      sref["path_len"], sref["path"])
+    cap = int(w.own_len.max()) + w.max_depth + 1
+    n = w.n_prompts * w.W_cap
+    mk = lambda: torch.full((cap, w.Hkv, w.D), -1.0, dtype=torch.bfloat16, device="cuda")
+    used = int(sref["n_next"].sum())
+    dst_k = [mk() if j < used else None for j in range(n)]
+    dst_v = [mk() if j < used else None for j in range(n)]
+    dst = dsbd.KVDst(dst_k, dst_v, d.kv)
+    dlen, fault = dsbd.dsbd_commit_kv(d.forest, d.kv, d.k_tree, d.v_tree, nx, w.W_cap, dst)
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0 and np.array_equal(dlen.cpu().numpy(), rlen)
+    bits = lambda t_: t_.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    for (p, s_), want in rk.items():
+        j = p * w.W_cap + s_
+        assert np.array_equal(bits(dst_k[j][:want.shape[0]]), want) and np.array_equal(bits(dst_v[j][:want.shape[0]]), rv[(p, s_)])
+        assert bool((dst_k[j][want.shape[0]:] == -1.0).all())

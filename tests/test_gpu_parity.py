@@ -193,3 +193,100 @@ def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang():
     res = d.verify(workspace=ws)
     torch.cuda.synchronize()
     gu.compare_verify(res, gu.oracle_verify(w), w)
+
+
+def _commit_case(cfg, kw, keep_one, t, head_major=False, in_place=True):
+    """Runs verify -> select -> commit on the device and the oracle chain on the CPU; compares the new caches
+    bit for bit.  With in_place the first next beam of every source tree continues in its source buffer."""
+    gu = _gu()
+    import paper_2409_16560_amd as dsbd
+    from oracle import commit as o_commit, select as o_select
+    w = make_workload(cfg, **kw)
+    d = gu.DeviceWorkload(w, share_prefix=True)
+    res = d.verify(t=t)
+    nx = dsbd.dsbd_select_beams(d.forest, res, keep_one=keep_one)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t)
+    near = gu.compare_verify(res, ref, w)
+    if near:
+        pytest.skip("near tie in the verification: plans may differ")
+    sref = o_select.select_beams(w.tree_off, w.parent, ref["n_out"], ref["out_parent"], ref["out_token"],
+                                 ref["out_logp_p"], ref["out_logp_q"], w.max_depth + 1, keep_one=keep_one)
+    rk, rv, rlen = o_commit.commit_kv(w.k_own, w.v_own, w.k_tree, w.v_tree, sref["n_next"], sref["src_tree"],
+                                      sref["path_len"], sref["path"])
+    # source caches with room to grow (so that a beam can continue in place), destination buffers for the rest
+    grow = w.max_depth + 1
+    cap = max(k.shape[0] for k in w.k_own) + grow
+    def buf():
+        t_ = torch.full((cap, w.Hkv, w.D), -1.0, dtype=torch.bfloat16, device="cuda")
+        return t_.permute(1, 0, 2).contiguous().permute(1, 0, 2) if head_major else t_
+    src_k, src_v = [], []
+    for b in range(w.n_trees):
+        kb, vb = buf(), buf()
+        kb[:w.k_own[b].shape[0]] = gu.bf16_dev(w.k_own[b]); vb[:w.v_own[b].shape[0]] = gu.bf16_dev(w.v_own[b])
+        src_k.append(kb); src_v.append(vb)
+    L = [k.shape[0] for k in w.k_own]
+    view = lambda t_, n: (t_.permute(1, 0, 2)[:, :n] if head_major else t_[:n])
+    kv = dsbd.PrefixKV([view(src_k[b], L[b]) for b in range(w.n_trees)], [view(src_v[b], L[b]) for b in range(w.n_trees)],
+                       head_major=head_major)
+    dst_k, dst_v, taken = [], [], set()
+    for p in range(w.n_prompts):
+        for s_ in range(w.W_cap):
+            b = int(sref["src_tree"][p, s_]) if s_ < int(sref["n_next"][p]) else -1
+            if b >= 0 and in_place and b not in taken:
+                taken.add(b); dst_k.append(src_k[b]); dst_v.append(src_v[b])
+            else:
+                dst_k.append(buf()); dst_v.append(buf())
+    to_view = (lambda t_: t_.permute(1, 0, 2)) if head_major else (lambda t_: t_)
+    dst = dsbd.KVDst([to_view(t_) for t_ in dst_k], [to_view(t_) for t_ in dst_v], kv, head_major=head_major)
+    dlen, fault = dsbd.dsbd_commit_kv(d.forest, kv, d.k_tree, d.v_tree, nx, w.W_cap, dst)
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0
+    assert np.array_equal(dlen.cpu().numpy(), rlen)
+    bits = lambda t_: t_.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    n_checked = 0
+    for (p, s_), want in rk.items():
+        j = p * w.W_cap + s_
+        n = want.shape[0]
+        assert np.array_equal(bits(dst_k[j][:n]), want), ("K", p, s_)
+        assert np.array_equal(bits(dst_v[j][:n]), rv[(p, s_)]), ("V", p, s_)
+        assert bool((dst_k[j][n:] == -1.0).all()) and bool((dst_v[j][n:] == -1.0).all())   # nothing beyond the new length
+        n_checked += 1
+    assert n_checked == int(sref["n_next"].sum())
+    return n_checked
+
+
+@pytest.mark.parametrize("cfg,kw", [
+    ("c1", {}),
+    ("c2", dict(L=100, V=500, Hq=8, Hkv=4)),
+    ("c3", dict(L=300, V=700, Hq=8, Hkv=2, D=64)),              # shared leading segment stays shared
+    ("c4", dict(L=(40, 200), V=300, n_prompts=5, Hq=4, Hkv=4)), # ragged lengths, several prompts
+    ("c5", dict(L=333, V=2000)),                                 # GQA 32/8, 31-node trees
+])
+@pytest.mark.parametrize("keep_one", [False, True])
+def test_commit_kv_matches_oracle(cfg, kw, keep_one):
+    _commit_case(cfg, kw, keep_one, t=-1.0)
+
+
+def test_commit_kv_head_major_and_copy_only():
+    _commit_case("c2", dict(L=100, V=500, Hq=8, Hkv=4), False, t=0.7, head_major=True)
+    _commit_case("c5", dict(L=130, V=2000), False, t=-1.0, in_place=False)
+
+
+def test_commit_kv_reports_what_does_not_fit():
+    gu = _gu()
+    import paper_2409_16560_amd as dsbd
+    w = make_workload("c2", L=50, V=500, Hq=4, Hkv=4)
+    d = gu.DeviceWorkload(w)
+    res = d.verify()
+    nx = dsbd.dsbd_select_beams(d.forest, res)
+    small = [torch.full((52, w.Hkv, w.D), -1.0, dtype=torch.bfloat16, device="cuda") for _ in range(2 * w.n_prompts * w.W_cap)]
+    n = w.n_prompts * w.W_cap
+    dst = dsbd.KVDst(small[:n], small[n:], d.kv)              # capacity 52 < 50 + path length for deeper beams
+    dlen, fault = dsbd.dsbd_commit_kv(d.forest, d.kv, d.k_tree, d.v_tree, nx, w.W_cap, dst)
+    torch.cuda.synchronize()
+    pl = nx.path_len.cpu().numpy(); nn = nx.n_next.cpu().numpy()
+    too_long = [(p, s_) for p in range(w.n_prompts) for s_ in range(int(nn[p])) if 50 + pl[p, s_] > 52]
+    assert (int(fault.item()) & dsbd.DSBD_FAULT_BOUNDS != 0) == bool(too_long)
+    for p, s_ in too_long:
+        assert int(dlen[p, s_]) == 0 and bool((small[p * w.W_cap + s_] == -1.0).all())

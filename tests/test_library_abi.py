@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     import paper_2409_16560_amd as dsbd
     lib = dsbd.load_library()
     names = header_functions()
-    assert {"dsbd_forest_attention", "dsbd_verify_forest", "dsbd_select_beams"} <= set(names)
+    assert {"dsbd_forest_attention", "dsbd_verify_forest", "dsbd_select_beams", "dsbd_commit_kv"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert "gfx950" in dsbd.dsbd_version()
@@ -31,7 +31,7 @@ def test_binding_structs_match_header_field_order():
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     for cname, cls in (("dsbd_forest", b._Forest), ("dsbd_kv", b._KV), ("dsbd_params", b._Params),
                        ("dsbd_verify_in", b._VerifyIn), ("dsbd_verify_out", b._VerifyOut),
-                       ("dsbd_next_beams", b._NextBeams)):
+                       ("dsbd_next_beams", b._NextBeams), ("dsbd_kv_dst", b._KVDst)):
         body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (cname, cname), src, flags=re.S).group(1)
         fields = []
         for decl in body.split(";"):
@@ -69,6 +69,10 @@ def test_host_side_argument_checks_need_no_gpu():
     nb = b._NextBeams(*([None] * 8))
     assert lib.dsbd_select_beams(C.byref(f), C.byref(vout), 4, 0, C.byref(nb), None, None) == -1
     assert lib.dsbd_select_beams(C.byref(f), C.byref(vout), 65, 0, C.byref(nb), C.c_void_p(8), None) == -2
+    kd = b._KVDst(None, None, None, 16)
+    assert lib.dsbd_commit_kv(C.byref(f), C.byref(kv), None, None, 8, 128, C.byref(nb), 4, C.byref(kd), None, None) == -1
+    assert lib.dsbd_commit_kv(C.byref(f), C.byref(kv), None, None, 8, 100, C.byref(nb), 4, C.byref(kd), C.c_void_p(8), None) == -2
+    assert lib.dsbd_commit_kv(C.byref(f), C.byref(kv), None, None, 8, 128, C.byref(nb), 4, C.byref(kd), C.c_void_p(8), None) == -1
 
 
 def test_workspace_sizes_scale_with_the_problem():

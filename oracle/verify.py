@@ -11,7 +11,10 @@ Readings taken where the text is ambiguous (each is restated in the design notes
     ratio printed in Section 3.1 / Algorithm 1 is the inverse and contradicts them);
   * p_beam^(l), q_beam^(l) are normalised over I^(l) x V with I^(l) the accepted beams of layer l-1;
   * candidates of a layer are tested in ascending (draft rank, node index);
-  * warping T is the identity;
+  * warping T acts on the joint over I x V, as the formulas of Section 3.1 are written (T applied to p/P and
+    q/Q): top-k keeps the k largest joint entries (ties: lower flat index first), top-p then keeps the smallest
+    leading part of those, in descending order, whose share of the kept mass exceeds p; the result is
+    renormalised.  top_k = 0 and top_p >= 1 switch the respective step off (both off: T is the identity);
   * the bonus layer samples W_L beams with W_L the call's input width;
   * P(m,0) = prod_{j<=m}(1 - alpha_j); the "at least K" tail sums k = 0..K-1 (Eq. 6);
   * W_L^(l) is additionally capped by the output capacity W_cap.
@@ -71,6 +74,37 @@ def beam_joint(cum_I, z_I):
     rows = np.exp(z_I - z_I.max(axis=1, keepdims=True))
     rows = rows / rows.sum(axis=1, keepdims=True)
     return w[:, None] * rows
+
+
+def warp_joint(d, top_k=0, top_p=1.0):
+    """T o d for a joint d over I x V (Section 2.1 "warping operation"; Section 3.1 "Details": p_beam = T o p/P,
+    q_beam = T o q/Q; the experiments use top-k then top-p, appendix "Experiment Configuration").
+    Entries are ranked by descending value, equal values by ascending flat index (beam-major, token-minor)."""
+    d = np.asarray(d, dtype=np.float64)
+    if top_k <= 0 and top_p >= 1.0:
+        return d
+    flat = d.ravel()
+    order = sorted(range(len(flat)), key=lambda j: (-flat[j], j))
+    if top_k > 0:
+        order = order[:top_k]
+    if top_p < 1.0:
+        mass = 0.0
+        for j in order:
+            mass += flat[j]
+        cum, keep = 0.0, []
+        for j in order:
+            keep.append(j)
+            cum += flat[j]
+            if cum / mass > top_p:
+                break
+        order = keep
+    out = np.zeros_like(flat)
+    z = 0.0
+    for j in order:
+        z += flat[j]
+    for j in order:
+        out[j] = flat[j] / z
+    return out.reshape(d.shape)
 
 
 def residual(p_prime, q_beam):
@@ -153,7 +187,7 @@ def dynamic_width(p_beam, q_beam, M, t, W_min, W_cap):
 
 # ----------------------------------------------------------------------------- Algorithm 1
 def verify_prompt(nodes, roots, parent, token, depth, rank, z_p, z_q, lse_p, lse_q, cum_p, cum_q,
-                  u_accept, u_resid, u_fill, W_L, W_min, W_cap, t, status, trace=None):
+                  u_accept, u_resid, u_fill, W_L, W_min, W_cap, t, status, trace=None, top_k=0, top_p=1.0):
     """Verify the draft layers of one prompt.
 
     nodes: node ids of the prompt (ascending); roots: its input beams.
@@ -182,8 +216,8 @@ def verify_prompt(nodes, roots, parent, token, depth, rank, z_p, z_q, lse_p, lse
                 status[n] = PRUNED
         S.sort(key=lambda n: (int(rank[n]) if rank is not None else 0, n))
         M = len(S)
-        p_beam = beam_joint([cum_p[i] for i in I], z_p[I])
-        q_beam = beam_joint([cum_q[i] for i in I], z_q[I])
+        p_beam = warp_joint(beam_joint([cum_p[i] for i in I], z_p[I]), top_k, top_p)
+        q_beam = warp_joint(beam_joint([cum_q[i] for i in I], z_q[I]), top_k, top_p)
         if t < 0:
             WL = W_in
         else:
@@ -236,7 +270,7 @@ def verify_prompt(nodes, roots, parent, token, depth, rank, z_p, z_q, lse_p, lse
         I = acc
 
     if l_last == gamma + 1:
-        p_beam = beam_joint([cum_p[i] for i in I], z_p[I])
+        p_beam = warp_joint(beam_joint([cum_p[i] for i in I], z_p[I]), top_k, top_p)
         layer_width[gamma + 1] = W_in
         rec = {"l": gamma + 1, "I": list(I), "S": [], "p_beam": p_beam, "q_beam": None, "W_L": W_in,
                "tests": [], "samples": []}
@@ -254,7 +288,7 @@ def verify_prompt(nodes, roots, parent, token, depth, rank, z_p, z_q, lse_p, lse
 
 
 def verify_forest(tree_prompt, tree_off, parent, token, logits_p, logits_q, beam_logp_p, beam_logp_q,
-                  u_accept, u_resid, u_fill, W_L, W_min, W_cap, t, rank=None, traces=None):
+                  u_accept, u_resid, u_fill, W_L, W_min, W_cap, t, rank=None, traces=None, top_k=0, top_p=1.0):
     """Whole-forest verification: per-node softmax statistics, cumulative beam likelihoods, then
     Algorithm 1 independently for every prompt.  Returns a dict of arrays shaped like the
     library's outputs (output slots beyond n_out hold -1 / 0)."""
@@ -291,7 +325,8 @@ def verify_forest(tree_prompt, tree_off, parent, token, logits_p, logits_q, beam
         nodes = list(range(int(tree_off[trees[0]]), int(tree_off[trees[-1] + 1])))
         tr = [] if traces is not None else None
         r = verify_prompt(nodes, roots, parent, token, depth, rank, z_p, z_q, lse_p, lse_q, cum_p, cum_q,
-                          u_accept, u_resid[p], u_fill[p], W_L, W_min, W_cap, t, status, trace=tr)
+                          u_accept, u_resid[p], u_fill[p], W_L, W_min, W_cap, t, status, trace=tr,
+                          top_k=top_k, top_p=top_p)
         if traces is not None:
             traces.append(tr)
         res["l_last"][p] = r["l_last"]

@@ -45,7 +45,7 @@ def build_forest(W_in, layer1, layer2=()):
                 node1=node1, node2=node2)
 
 
-def run(fr, z_p, z_q, blp, blq, u_accept, W_L, t, W_min=1, W_cap=8):
+def run(fr, z_p, z_q, blp, blq, u_accept, W_L, t, W_min=1, W_cap=8, top_k=0, top_p=1.0):
     """One oracle call on forest `fr`; z_p/z_q are per-node logit rows. Returns (result, trace)."""
     N = len(fr["parent"])
     T = len(fr["tree_off"]) - 1
@@ -54,12 +54,12 @@ def run(fr, z_p, z_q, blp, blq, u_accept, W_L, t, W_min=1, W_cap=8):
     res = verify.verify_forest(np.zeros(T, dtype=np.int32), fr["tree_off"], fr["parent"], fr["token"], z_p, z_q,
                                blp, blq, u_accept, np.full((1, Lmax + 2), 0.5, dtype=np.float32),
                                np.full((1, Lmax + 2, W_cap), 0.5, dtype=np.float32), W_L, W_min, W_cap, t,
-                               rank=fr["rank"], traces=traces)
+                               rank=fr["rank"], traces=traces, top_k=top_k, top_p=top_p)
     assert N == len(u_accept)
     return res, traces[0]
 
 
-def layer_outcome_distribution(fr, z_p, z_q, blp, blq, W_L, t, layer, free_nodes, fixed_u, W_cap=8):
+def layer_outcome_distribution(fr, z_p, z_q, blp, blq, W_L, t, layer, free_nodes, fixed_u, W_cap=8, top_k=0, top_p=1.0):
     """Exact distribution of the beams that layer `layer` hands on (accepted drafts, then the
     residual sample, then fills), over flat indices slot*V + token of I^(layer) x V.
 
@@ -77,7 +77,7 @@ def layer_outcome_distribution(fr, z_p, z_q, blp, blq, W_L, t, layer, free_nodes
             u[n] = val
         for n, a in zip(free_nodes, pattern):
             u[n] = U_ACC if a else U_REJ
-        res, trace = run(fr, z_p, z_q, blp, blq, u, W_L, t, W_cap=W_cap)
+        res, trace = run(fr, z_p, z_q, blp, blq, u, W_L, t, W_cap=W_cap, top_k=top_k, top_p=top_p)
         rec = [r for r in trace if r["l"] == layer]
         if not rec:
             return None, None, None, None

@@ -38,6 +38,7 @@ class Spec:
     draft: str                    # 'indep' (independent N(0,std)) or 'noise' (target + N(0,noise_std))
     noise_std: float = 0.5
     seed: int = 0
+    draft_top_k: int = 0          # > 0: draft tokens come from the draft_top_k largest draft logits of the parent's row
 
 
 CONFIGS = {
@@ -217,12 +218,18 @@ def make_workload(config: Union[str, Spec], W_cap: Optional[int] = None, **overr
         raise ValueError(spec.draft)
     logits_q = np.ascontiguousarray(logits_q, dtype=np.float32)
 
-    # draft tokens: token[n] ~ softmax(logits_q[parent[n]]) iid (Gumbel-max draw); roots arbitrary
+    # draft tokens: token[n] ~ softmax(logits_q[parent[n]]) iid (Gumbel-max draw), optionally restricted to the
+    # row's draft_top_k largest logits (a draft model that samples with a top-k cut); roots arbitrary
     tr = np.random.Generator(np.random.Philox(key=[seed, 4]))
     token = np.zeros(N, dtype=np.int32)
     for n in range(N):
         if parent[n] < 0:
             token[n] = int(tr.integers(0, V))
+        elif spec.draft_top_k > 0:
+            row = logits_q[parent[n]].astype(np.float64)
+            best = np.argsort(-row, kind="stable")[:spec.draft_top_k]
+            g = tr.gumbel(size=len(best))
+            token[n] = int(best[np.argmax(row[best] + g)])
         else:
             g = tr.gumbel(size=V)
             token[n] = int(np.argmax(logits_q[parent[n]].astype(np.float64) + g))

@@ -125,6 +125,13 @@ typedef struct dsbd_params {
   int32_t W_min;   /* floor of the dynamic width (Eq. 5), >= 1                                      */
   int32_t W_cap;   /* capacity of the per-prompt output arrays; also caps every layer's width       */
   float   t;       /* threshold of Eq. 6 in [0,1]; t < 0 selects the fixed width W_L for all layers */
+  /* Warping operation T of beam sampling (Section 2.1; Section 3.1 "Details": p_beam = T o p/P), applied to   */
+  /* both joints over I x V in every layer and to p_beam of the bonus layer.  Entries are ranked by value,     */
+  /* equal values by lower flat index (beam-major, token-minor).                                               */
+  int32_t top_k;   /* keep the top_k largest entries; 0: keep all.  1..32 supported; > 32: UNSUPPORTED         */
+  float   top_p;   /* of those kept, the shortest leading part whose share of their mass exceeds top_p, then   */
+                   /* renormalise; 0 or >= 1: no cut (a zeroed struct means no warping).  A value in (0,1)     */
+                   /* needs top_k >= 1 (else UNSUPPORTED); < 0: INVALID                                        */
 } dsbd_params;
 
 /* Inputs of the verification that are not part of the forest. Lmax = forest->max_depth. */

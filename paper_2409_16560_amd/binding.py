@@ -39,7 +39,8 @@ class _KV(C.Structure):
 
 
 class _Params(C.Structure):
-    _fields_ = [("W_L", C.c_int32), ("W_min", C.c_int32), ("W_cap", C.c_int32), ("t", C.c_float)]
+    _fields_ = [("W_L", C.c_int32), ("W_min", C.c_int32), ("W_cap", C.c_int32), ("t", C.c_float),
+                ("top_k", C.c_int32), ("top_p", C.c_float)]
 
 
 class _VerifyIn(C.Structure):
@@ -250,22 +251,23 @@ class VerifyResult:
             torch.zeros(1, dtype=torch.int32, device=dev), W_cap)
 
 
-def _params(W_L, W_min, W_cap, t):
-    return _Params(int(W_L), int(W_min), int(W_cap), float(t))
+def _params(W_L, W_min, W_cap, t, top_k=0, top_p=1.0):
+    return _Params(int(W_L), int(W_min), int(W_cap), float(t), int(top_k), float(top_p))
 
 
-def dsbd_verify_forest_workspace_bytes(forest: Forest, V, W_L=0, W_min=1, W_cap=16, t=-1.0):
-    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t)
+def dsbd_verify_forest_workspace_bytes(forest: Forest, V, W_L=0, W_min=1, W_cap=16, t=-1.0, top_k=0, top_p=1.0):
+    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t, top_k, top_p)
     return int(load_library().dsbd_verify_forest_workspace_bytes(C.byref(f), int(V), C.byref(p)))
 
 
 def dsbd_verify_forest(forest: Forest, logits_target, logits_draft, beam_logp_target, beam_logp_draft,
                        u_accept, u_resid, u_fill, W_L=0, W_min=1, W_cap=16, t=-1.0, result: VerifyResult = None,
-                       workspace=None, stream=None):
-    """Layer-wise verification; logits [N,V] f32, beam_logp [T] f64, uniforms f32.  Returns VerifyResult."""
+                       workspace=None, stream=None, top_k=0, top_p=1.0):
+    """Layer-wise verification; logits [N,V] f32, beam_logp [T] f64, uniforms f32.  top_k / top_p: the warping
+    operation on the joints (0 / 1.0: none).  Returns VerifyResult."""
     lib = load_library()
     N, V = logits_target.shape
-    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t)
+    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t, top_k, top_p)
     for t_, dt in ((logits_target, torch.float32), (logits_draft, torch.float32), (beam_logp_target, torch.float64),
                    (beam_logp_draft, torch.float64), (u_accept, torch.float32), (u_resid, torch.float32),
                    (u_fill, torch.float32)):

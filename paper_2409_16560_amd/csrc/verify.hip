@@ -25,6 +25,7 @@
 #include "common.h"
 #include "topology_device.h"
 #include <float.h>
+#include <limits.h>
 #include <stdlib.h>
 
 #define VS_BLOCK 256
@@ -40,7 +41,7 @@ struct StatsArgs {
   int n_nodes, V, nchunk, chunk;
   float2* part;      // [2][n_nodes][nchunk] (max, sum of exp(x - max))
   int32_t* fault;
-  // service workgroups (blockIdx.y == n_nodes)
+  // service workgroups (blockIdx.y == 0)
   int n_trees, n_prompts, max_tree_nodes, max_depth;
   const int32_t *tree_prompt, *tree_off, *parent;
   int32_t* depth;              // [n_nodes]
@@ -102,12 +103,13 @@ __device__ __forceinline__ void online_merge(float& m, float& s, float m2, float
   m = mn;
 }
 
-// The small jobs done by the extra row of workgroups (blockIdx.y == n_nodes) while the others stream.
+// The small jobs done by the extra row of workgroups (blockIdx.y == 0) while the others stream.
 __device__ void stats_service(const StatsArgs& a, int sidx, int n_service) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // exchange slots of the layer kernel: a slot is valid only with the tag of its exchange, so zeros never are
-  for (long long k = (long long)sidx * VS_BLOCK + tid; k < a.n_slot_words; k += (long long)n_service * VS_BLOCK)
-    a.slots[k] = 0ull;
+  ulonglong2* const s2 = reinterpret_cast<ulonglong2*>(a.slots);     // the slot array is 256-byte aligned
+  for (long long k = (long long)sidx * VS_BLOCK + tid; k < a.n_slot_words / 2; k += (long long)n_service * VS_BLOCK)
+    s2[k] = make_ulonglong2(0ull, 0ull);
   // forest topology, one wave per tree
   for (int b = sidx * (VS_BLOCK / 64) + wave; b < a.n_trees; b += n_service * (VS_BLOCK / 64)) {
     const int bad = dsbd_tree_topology(b, lane, a.n_nodes, a.tree_off, a.parent, a.max_tree_nodes, a.max_depth,
@@ -133,8 +135,9 @@ __device__ void stats_service(const StatsArgs& a, int sidx, int n_service) {
 }
 
 __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
-  const int c = blockIdx.x, n = blockIdx.y, which = blockIdx.z;
-  if (n == a.n_nodes) {       // uniform over the workgroup
+  // row 0 of the grid does the small jobs (dispatched first: done long before the streaming rows are)
+  const int c = blockIdx.x, n = (int)blockIdx.y - 1, which = blockIdx.z;
+  if (n < 0) {                // uniform over the workgroup
     stats_service(a, which * gridDim.x + c, 2 * gridDim.x);
     return;
   }
@@ -202,6 +205,8 @@ struct LayersArgs {
   const float *u_acc, *u_res, *u_fill;
   int W_L, W_min, W_cap;
   float t;
+  int top_k;             // warping T (Section 2.1): keep the top_k largest entries of each joint (0: T is the identity) ...
+  float top_p;           // ... then the smallest leading part of those whose share of the kept mass exceeds top_p
   dsbd_verify_out out;
   const int32_t* depth;
   const int4* prompt_rec; // [n_prompts] (first tree, end tree, first node, end node)
@@ -209,7 +214,7 @@ struct LayersArgs {
   int nchunk;
   double* pb;            // [n_prompts][I_cap*V]  p_beam slice storage
   double* qb;            // [n_prompts][I_cap*V]
-  double* red;           // exchange slots [n_prompts][2 banks][G][red_w] of 16 bytes each
+  double* red;           // exchange slots [n_prompts][banks][G][red_w] of 16 bytes each
   int G, I_cap, red_w;
   long long* trace;      // optional timeline (first workgroup of prompt 0): pairs (label, 100 MHz wall clock)
   int lds_elems;         // capacity (elements) of each of the two dynamic-LDS slice arrays; 0 = none
@@ -260,6 +265,11 @@ struct LayerShared {
   double gpart[256];                 // one partial per workgroup of the prompt (G <= 256)
   double exp_tab[64];                // 2^(j/64)
   double d_target[64];               // sampling: u * total of each draw
+  // warped joints (top-k / top-p): union of the two supports, ascending flat index over I x V
+  int U_idx[64];
+  double U_p[64], U_q[64];
+  int nU;
+  int W_cnt[2];                      // entries kept per model after the merge
   int state[2];                      // outcome of the decision rounds, alternating entries
   int kmax, counter, abort, found, sbad, sgamma;
   int acc_n, pos, kidx;        // accept loop: accepted so far, next candidate, chain index of p'
@@ -368,10 +378,14 @@ __device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh
 // No grid-wide barrier and no cache-wide fence: a workgroup publishes each partial value in its own
 // 16-byte slot as two agent-scope atomic words (value bits, value bits XOR tag) and every other
 // workgroup polls exactly the slots it needs.  The tag changes with every exchange, so a slot is valid
-// only once both words of the current exchange have landed; slots alternate between two banks, and a
-// workgroup can be at most one exchange ahead of the slowest one, so a bank is never overwritten while
-// somebody may still read it.  (An exchange that nobody reads - every workgroup skips it alike - does not
-// change that: to write a bank again a workgroup must have completed the exchange in between.)
+// only once both words of the current exchange have landed.  A bank of slots is never overwritten while
+// somebody may still read it:
+//  * exchanges that every workgroup posts and then collects at once from all the others (chain entries,
+//    sampling prefixes, warping candidates) alternate between banks 0 and 1: whoever posts exchange n + 2 has
+//    collected n + 1, so everybody had posted n + 1 and was therefore done collecting n;
+//  * the row-sum exchange (collected only from the workgroups that share a row) and the early post of the
+//    chain's second entry (collected later, or never) give no such guarantee, so each layer has a bank of its
+//    own for either of them, written once per launch.
 struct Slot { unsigned long long w0, w1; };
 
 __device__ __forceinline__ unsigned long long exchange_tag(unsigned int epoch) {
@@ -441,10 +455,29 @@ __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double o
   }
 }
 
-__device__ __forceinline__ Slot* exchange_bank(const LayersArgs& a, int prompt, unsigned int epoch) {
-  return reinterpret_cast<Slot*>(a.red) + ((long long)(prompt * 2 + (epoch & 1)) * a.G) * a.red_w;
+// banks of one prompt: two alternating ones, then a pair (row sums, early chain entry) per layer
+__host__ __device__ __forceinline__ int exchange_banks(int max_depth) { return 2 + 2 * (max_depth + 1); }
+__device__ __forceinline__ Slot* exchange_bank(const LayersArgs& a, int prompt, int bank) {
+  return reinterpret_cast<Slot*>(a.red) + ((long long)(prompt * exchange_banks(a.max_depth) + bank) * a.G) * a.red_w;
 }
 
+// ---- selection of the largest joint entries (warping T).  Entries are ranked by descending value, equal values by
+// ascending flat index; a candidate is (value, index), "none" is (-1, INT_MAX).
+#define WARP_K_MAX 32
+__device__ __forceinline__ bool cand_before(double va, int ia, double vb, int ib) {
+  return va > vb || (va == vb && ia < ib);
+}
+// first candidate in rank order among one per lane; the same result in every lane
+__device__ __forceinline__ void wave_first(double& v, int& i) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const double ov = __shfl_xor(v, off);
+    const int oi = __shfl_xor(i, off);
+    if (cand_before(ov, oi, v, i)) { v = ov; i = oi; }
+  }
+}
+
+template <bool WARP>
 __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   __shared__ LayerShared sh;
   extern __shared__ __attribute__((aligned(16))) double dyn_lds[];
@@ -453,7 +486,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int V = a.V;
-  unsigned int epoch = 0;      // exchanges so far; identical in every workgroup of the prompt
+  unsigned int epoch = 0;      // exchanges so far (sets the tag); identical in every workgroup of the prompt
+  unsigned int xchg = 0;       // of those, the ones on the two alternating banks
   unsigned int wsum_round = 0; // alternates the two wsum buffers
   unsigned int decide_round = 0;
   int trace_n = 0;
@@ -658,7 +692,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // floor(((i+1)V-1)/ch): only those post its two columns and only those are polled.
     epoch += 1;
     const unsigned long long rs_tag = exchange_tag(epoch);
-    Slot* const rs_bank = exchange_bank(a, prompt, epoch);
+    Slot* const rs_bank = exchange_bank(a, prompt, 2 + 2 * (l - 1));
     if (tid < 2 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
       const double* wp = &sh.u.wpart[(tid >> 1) * VL_WAVES * 2 + (tid & 1)];
       const double s = ((wp[0] + wp[2]) + (wp[4] + wp[6])) + ((wp[8] + wp[10]) + (wp[12] + wp[14]));
@@ -786,14 +820,191 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         f1 += fmax(pv - qv, 0.0);
       }
     }
+    if constexpr (WARP) {
+      // ===== warping T: top-k / top-p on the two joints (Section 2.1; Section 3.1 "Details": p_beam = T o p/P).
+      // Every workgroup finds the K first entries of its slice, all exchange them, every workgroup merges the
+      // G*K candidates into the same global list, cuts it by top-p and renormalises.  From here on the layer works
+      // on the (at most 2K) surviving entries, which every workgroup holds: no further exchange is needed.
+      __syncthreads();                       // the scaled slices are complete
+      const int K = a.top_k;
+      // scratch (all rewritten later in the layer): per-wave lists in S_pb/S_qb (values) and S_zp/S_zq (indices),
+      // merged lists in Pa (values: p then q) and Pb (indices)
+      double* const cvp = sh.S_pb; double* const cvq = sh.S_qb;
+      int* const cip = reinterpret_cast<int*>(sh.S_zp); int* const ciq = reinterpret_cast<int*>(sh.S_zq);
+      double* const lv = sh.Pa; int* const li = reinterpret_cast<int*>(sh.Pb);
+      {  // (1) every wave: the K first entries among the slice elements its lanes own
+        double pv_prev = INFINITY, qv_prev = INFINITY;
+        int pi_prev = -1, qi_prev = -1;
+        for (int r = 0; r < K; ++r) {
+          double bp = -1.0, bq = -1.0;
+          int ip = INT_MAX, iq = INT_MAX;
+          for (long long j = tid; j < len; j += VL_BLOCK) {
+            const int fi = (int)(e_lo + j);
+            const double vp = ldp(j), vq = ldq(j);
+            if (cand_before(pv_prev, pi_prev, vp, fi) && cand_before(vp, fi, bp, ip)) { bp = vp; ip = fi; }
+            if (cand_before(qv_prev, qi_prev, vq, fi) && cand_before(vq, fi, bq, iq)) { bq = vq; iq = fi; }
+          }
+          wave_first(bp, ip);
+          wave_first(bq, iq);
+          if (lane == 0) { cvp[wave * K + r] = bp; cip[wave * K + r] = ip; cvq[wave * K + r] = bq; ciq[wave * K + r] = iq; }
+          pv_prev = bp; pi_prev = ip; qv_prev = bq; qi_prev = iq;
+        }
+      }
+      // one wave: the K first of a candidate list, in rank order ("none" entries sort last)
+      auto wave_select = [&](const double* vals, const int* idx, int n, double* ov, int* oi) {
+        double v_prev = INFINITY;
+        int i_prev = -1;
+        for (int r = 0; r < K; ++r) {
+          double b = -1.0;
+          int bi = INT_MAX;
+          for (int c = lane; c < n; c += 64) {
+            const double v = vals[c];
+            const int fi = idx[c];
+            if (cand_before(v_prev, i_prev, v, fi) && cand_before(v, fi, b, bi)) { b = v; bi = fi; }
+          }
+          wave_first(b, bi);
+          if (lane == 0) { ov[r] = b; oi[r] = bi; }
+          v_prev = b; i_prev = bi;
+        }
+      };
+      __syncthreads();
+      if (wave == 0) { wave_select(cvp, cip, VL_WAVES * K, lv, li); wave_select(cvq, ciq, VL_WAVES * K, lv + K, li + K); }
+      __syncthreads();
+      // (2) exchange: workgroup g posts 4K words (model, rank, value | index)
+      epoch += 1;
+      const unsigned long long w_tag = exchange_tag(epoch);
+      Slot* const w_bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
+      if (tid < 4 * K) {
+        const int m = tid / (2 * K), r = (tid % (2 * K)) >> 1;
+        const double payload = (tid & 1) ? (double)li[m * K + r] : lv[m * K + r];
+        slot_post(w_bank + (long long)g * a.red_w + tid, payload, w_tag);
+      }
+      // (3) everybody collects all G*4K words into the dynamic LDS (the slices are not needed any more):
+      // values [model][workgroup*K + rank], then the indices
+      const int GK = a.G * K;
+      double* const gv = dyn_lds;
+      int* const gi = reinterpret_cast<int*>(dyn_lds + 2 * GK);
+      {
+        const int nS = a.G * 4 * K;
+        bool okc = true;
+        for (int s0 = tid; s0 < nS && okc; s0 += 4 * VL_BLOCK) {
+          bool have[4];
+          double val[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) { have[k] = s0 + k * VL_BLOCK >= nS; val[k] = 0.0; }
+          long long t0 = 0;
+          for (int spin = 0;; ++spin) {
+            unsigned long long w0[4], w1[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              w0[k] = 0; w1[k] = 0;
+              if (!have[k]) {
+                const int sk = s0 + k * VL_BLOCK;
+                Slot* sl = w_bank + (long long)(sk / (4 * K)) * a.red_w + sk % (4 * K);
+                w0[k] = __hip_atomic_load(&sl->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                w1[k] = __hip_atomic_load(&sl->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              if (!have[k] && (w0[k] ^ w1[k]) == w_tag) { val[k] = __longlong_as_double((long long)w0[k]); have[k] = true; }
+            if (have[0] && have[1] && have[2] && have[3]) break;
+            if (spin == 0) t0 = wall_clock64();
+            else if ((spin & 15) == 0 && wall_clock64() - t0 > a.sync_limit) { okc = false; break; }
+            __builtin_amdgcn_s_sleep(1);
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int sk = s0 + k * VL_BLOCK;
+            if (sk < nS && okc) {
+              const int w = sk / (4 * K), c = sk % (4 * K);
+              const int m = c / (2 * K), r = (c % (2 * K)) >> 1;
+              if (c & 1) gi[m * GK + w * K + r] = (int)val[k];
+              else gv[m * GK + w * K + r] = val[k];
+            }
+          }
+        }
+        if (!okc) give_up();
+      }
+      __syncthreads();
+      if (sh.abort) return;
+      {  // (4) merge: every wave selects from an eighth of the G*K candidates, the first wave from the 8K winners
+        const int n8 = (GK + VL_WAVES - 1) / VL_WAVES;
+        const int lo = min(GK, wave * n8), cnt = min(GK, lo + n8) - lo;
+        wave_select(gv + lo, gi + lo, cnt, cvp + wave * K, cip + wave * K);
+        wave_select(gv + GK + lo, gi + GK + lo, cnt, cvq + wave * K, ciq + wave * K);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        wave_select(cvp, cip, VL_WAVES * K, lv, li);
+        wave_select(cvq, ciq, VL_WAVES * K, lv + K, li + K);
+        wave_lds_fence();
+        // (5) top-p on the kept entries (descending order: the smallest leading part whose share exceeds top_p),
+        // renormalisation; lane 0 for p_beam, lane 1 for q_beam, sums taken in list order
+        if (lane < 2) {
+          double* v = lv + lane * K;
+          const int* ix = li + lane * K;
+          int n = 0;
+          while (n < K && ix[n] != INT_MAX) ++n;         // fewer than K exist when I x V is smaller
+          int keep = n;
+          if (a.top_p < 1.0f) {
+            double mass = 0.0;
+            for (int r = 0; r < n; ++r) mass += v[r];
+            double cum = 0.0;
+            keep = 0;
+            for (int r = 0; r < n; ++r) {
+              keep = r + 1;
+              cum += v[r];
+              if (cum / mass > (double)a.top_p) break;
+            }
+          }
+          double z = 0.0;
+          for (int r = 0; r < keep; ++r) z += v[r];
+          for (int r = 0; r < keep; ++r) v[r] = v[r] / z;
+          sh.W_cnt[lane] = keep;
+        }
+        wave_lds_fence();
+        // (6) union of the two supports, ascending flat index: lanes 0..31 carry the p entries, 32..63 the q entries
+        const int mp = sh.W_cnt[0], mq = sh.W_cnt[1];
+        const int r = lane & 31;
+        const bool is_q = lane >= 32;
+        bool valid = is_q ? r < mq : r < mp;
+        int idx = valid ? li[(is_q ? K : 0) + r] : INT_MAX;
+        double wp = 0.0, wq = 0.0;
+        if (valid && !is_q) {
+          wp = lv[r];
+          for (int c = 0; c < mq; ++c) if (li[K + c] == idx) wq = lv[K + c];
+        } else if (valid) {
+          wq = lv[K + r];
+          for (int c = 0; c < mp; ++c) if (li[c] == idx) valid = false;     // already carried by a p entry
+        }
+        int rank = 0;
+        for (int c = 0; c < 64; ++c) {
+          const int oidx = __shfl(idx, c);
+          const int oval = __shfl((int)valid, c);
+          rank += (oval && oidx < idx) ? 1 : 0;
+        }
+        if (valid) { sh.U_idx[rank] = idx; sh.U_p[rank] = wp; sh.U_q[rank] = wq; }
+        const unsigned long long vm = __ballot(valid);
+        if (lane == 0) sh.nU = __popcll(vm);
+      }
+      __syncthreads();
+    }
     stamp(25);
     // p_beam and q_beam at every candidate's (parent beam, token)
     if (tid < M) {
       const int n = sh.S_node[tid];
       const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
       sh.S_zp[tid] = czp; sh.S_zq[tid] = czq;
-      const double pbx = exp_nonpos((double)czp - sh.max_p[slot], sh.exp_tab) * sh.sp[slot];
-      const double qbx = exp_nonpos((double)czq - sh.max_q[slot], sh.exp_tab) * sh.sq[slot];
+      double pbx, qbx;
+      if constexpr (WARP) {       // warped joints: the surviving entries, zero elsewhere
+        const int flat = slot * V + sh.n_token[n - n_begin];
+        pbx = 0.0; qbx = 0.0;
+        for (int c = 0; c < sh.nU; ++c) if (sh.U_idx[c] == flat) { pbx = sh.U_p[c]; qbx = sh.U_q[c]; }
+      } else {
+        pbx = exp_nonpos((double)czp - sh.max_p[slot], sh.exp_tab) * sh.sp[slot];
+        qbx = exp_nonpos((double)czq - sh.max_q[slot], sh.exp_tab) * sh.sq[slot];
+      }
       const float uf = sh.n_u[n - n_begin];
       // the test with p' = p_beam (first candidate, and every candidate right after an acceptance) needs no chain
       const double ratio = (qbx == 0.0) ? INFINITY : pbx / qbx;
@@ -808,12 +1019,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     unsigned long long spec_tag = 0;
     double spec_own = 0.0;
     stamp(26);
-    if (M > 0) {
+    if (!WARP && M > 0) {
       const double tot = wg_total(f1);      // barrier inside: also publishes the scaled slices
       stamp(27);
       epoch += 1;
       spec_tag = exchange_tag(epoch);
-      spec_bank = exchange_bank(a, prompt, epoch);
+      spec_bank = exchange_bank(a, prompt, 3 + 2 * (l - 1));
       if (tid == 0) dense_post(spec_bank, a.G, g, tot, spec_tag);
       spec_own = tot;
       spec = true;
@@ -833,6 +1044,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     auto slice_sum = [&](double c, int t0, int nt) -> double {
       double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
       if (tid < t0) return 0.0;
+      if constexpr (WARP) {       // the whole (warped) joint is the short list every workgroup holds
+        const int c2 = tid - t0;
+        return c2 < sh.nU ? fmax(sh.U_p[c2] - c * sh.U_q[c2], 0.0) : 0.0;
+      }
       long long j = tid - t0;
       for (; j + 3 * nt < len; j += 4 * nt) {
         const double p0 = ldp(j), p1 = ldp(j + nt), p2 = ldp(j + 2 * nt), p3 = ldp(j + 3 * nt);
@@ -847,6 +1062,43 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // Draws `cnt` samples (uniforms u[0..cnt)) from the weights max(p_beam - c q_beam, 0) (use_q) or p_beam over
     // I x V by inverse CDF in flat order; the workgroup owning a sample writes output slot out_base + j.
     auto draw = [&](double c, bool use_q, const float* u, int cnt, int out_base) -> bool {
+      if constexpr (WARP) {
+        // the weights live on the short list (ascending flat index) that every workgroup holds: one wave scans
+        // it, the first workgroup writes the samples
+        if (wave == 0) {
+          const int nU = sh.nU;
+          double w = 0.0;
+          if (lane < nU) w = use_q ? fmax(sh.U_p[lane] - c * sh.U_q[lane], 0.0) : sh.U_p[lane];
+          double incl = w;
+#pragma unroll
+          for (int off = 1; off < 64; off <<= 1) {
+            const double up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+          }
+          const double Z = __shfl(incl, 63);
+          const unsigned long long mass = __ballot(w > 0.0);
+          for (int j = 0; j < cnt; ++j) {
+            const double target = (double)u[j] * Z;
+            const unsigned long long above = __ballot(incl > target);
+            // the first entry whose inclusive prefix exceeds the target (rounding: the last one with mass)
+            const int pl_ = above ? (int)__ffsll((long long)above) - 1 : (mass ? 63 - __clzll((long long)mass) : 0);
+            if (g == 0 && lane == pl_) {
+              const long long pick = sh.U_idx[pl_];
+              const int i = (int)div_floor(pick, V);
+              const int x = (int)(pick - (long long)i * V);
+              const int node = sh.I_node[i];
+              const long long o = (long long)prompt * a.W_cap + out_base + j;
+              a.out.out_parent[o] = node;
+              a.out.out_token[o] = x;
+              a.out.out_node[o] = -1;
+              a.out.out_logp_target[o] = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
+              a.out.out_logp_draft[o] = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+            }
+          }
+        }
+        __syncthreads();
+        return true;
+      }
       float uj = 0.f;
       if (tid < cnt) uj = u[tid];
       // inclusive prefixes over this workgroup's threads (contiguous chunks) ...
@@ -861,7 +1113,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       // ... and over the workgroups (same order everywhere), gathered and scanned by one wave
       epoch += 1;
       const unsigned long long tag = exchange_tag(epoch);
-      Slot* bank = exchange_bank(a, prompt, epoch);
+      Slot* bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
       if (wave == 0) {
         const double mine = sh.tsum[VL_BLOCK - 1];
         if (lane == 0) dense_post(bank, a.G, g, mine, tag);
@@ -1076,9 +1328,17 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         stamp(43);
         const double tot = wg_total(sl);
         stamp(44);
+        if constexpr (WARP) {          // every workgroup holds the whole warped joint: the total is F itself
+          if (wave == 0) {
+            if (lane == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = tot; sh.kmax = k + 1; }
+            if (then_decide) decide(decide_round, k + 1);
+          }
+          __syncthreads();
+          return true;
+        }
         epoch += 1;
         const unsigned long long tag = exchange_tag(epoch);
-        Slot* bank = exchange_bank(a, prompt, epoch);
+        Slot* bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
         if (wave == 0) {
           if (lane == 0) dense_post(bank, a.G, g, tot, tag);
           double v[4];
@@ -1170,10 +1430,15 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         decide_round += 1;             // the next outcome goes to the other entry: nobody still reads it
         stamp(42);
         if (st != 1) break;
+        if constexpr (WARP) {
+          if (tid == 0) { sh.cc[k + 1] = c_next; sh.FF[k + 1] = tot; sh.kmax = k + 1; }
+          __syncthreads();
+          continue;
+        }
         if (!posted) {
           epoch += 1;
           x_tag = exchange_tag(epoch);
-          x_bank = exchange_bank(a, prompt, epoch);
+          x_bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
           if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
           x_own = tot;
         }
@@ -1279,6 +1544,14 @@ int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
   if (p->W_L <= 0 && f->max_prompt_trees > p->W_cap) return DSBD_ERR_INVALID;
   if ((long long)f->max_prompt_trees * f->max_tree_nodes > NODE_CAP) return DSBD_ERR_UNSUPPORTED;
   if (f->max_depth < 0 || f->max_depth >= DSBD_MAX_TREE_NODES) return DSBD_ERR_INVALID;
+  // warping T: top_k = 0 and top_p >= 1 is the identity; otherwise the joint is cut to its top_k <= WARP_K_MAX
+  // entries first (top-p alone would need an unbounded candidate list)
+  if (p->top_k < 0 || !(p->top_p >= 0.0f)) return DSBD_ERR_INVALID;
+  if (p->top_k > WARP_K_MAX || (p->top_k == 0 && p->top_p > 0.0f && p->top_p < 1.0f)) return DSBD_ERR_UNSUPPORTED;
+  if (p->top_k > 0) {
+    const long long cap = p->W_cap > f->max_prompt_trees ? p->W_cap : f->max_prompt_trees;
+    if (cap * V > 0x7fffffffLL) return DSBD_ERR_UNSUPPORTED;     // flat indices travel as 32-bit integers
+  }
   return DSBD_OK;
 }
 
@@ -1320,14 +1593,21 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   }
   if (G < 1) G = 1;
   if (G > 256) G = 256;
+  const long long cap = VL_DYN_LDS_BYTES / 16;
+  // warping: all G * top_k candidates of both models (value + index: 3 doubles a pair) sit in the dynamic LDS
+  if (p->top_k > 0 && (long long)G * p->top_k * 3 > 2 * cap) G = (int)(2 * cap / (3LL * p->top_k));
   pl.G = G;
   pl.red_w = 2 * pl.I_cap;
   if (pl.red_w < LINE_SLOTS) pl.red_w = LINE_SLOTS;    // single-value exchanges use one 128-byte line per workgroup
+  if (pl.red_w < 4 * p->top_k) pl.red_w = 4 * p->top_k;
   // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most VL_DYN_LDS_BYTES for the two arrays
   long long need = (joint + G - 1) / G;
   need = (need + 1) & ~1LL;
-  const long long cap = VL_DYN_LDS_BYTES / 16;
   pl.lds_elems = (int)(need < cap ? need : cap);
+  if (p->top_k > 0) {
+    const long long w_need = ((long long)G * p->top_k * 3 + 1) / 2 + 1;
+    if (pl.lds_elems < w_need) pl.lds_elems = (int)w_need;
+  }
   return pl;
 }
 
@@ -1339,7 +1619,7 @@ size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const Veri
   *part = ws.take<float2>(2 * N * pl.nchunk);
   *pb = ws.take<double>(P * pl.I_cap * V);
   *qb = ws.take<double>(P * pl.I_cap * V);
-  *red = ws.take<double>(P * 2 * pl.G * pl.red_w * 2);
+  *red = ws.take<double>(P * exchange_banks(f->max_depth) * pl.G * pl.red_w * 2);
   *prompt_rec = ws.take<int4>(P);
   return ws.total();
 }
@@ -1382,11 +1662,16 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   static int max_blocks_per_cu = -1;
   if (max_blocks_per_cu < 0) {
     int nb = 0;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
+    int nb2 = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel<false>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
       nb = 1;
-    max_blocks_per_cu = nb;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb2, verify_layers_kernel<true>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb2 < 1)
+      nb2 = 1;
+    max_blocks_per_cu = nb < nb2 ? nb : nb2;
   }
   const long long grid3 = (long long)f->n_prompts * pl.G;
   if (grid3 > (long long)max_blocks_per_cu * cached_cu_count()) return DSBD_ERR_UNSUPPORTED;
@@ -1399,8 +1684,8 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   sa.tree_prompt = f->tree_prompt; sa.tree_off = f->tree_off; sa.parent = f->parent;
   sa.depth = depth; sa.prompt_rec = prompt_rec;
   sa.slots = reinterpret_cast<unsigned long long*>(red);
-  sa.n_slot_words = (long long)f->n_prompts * 2 * pl.G * pl.red_w * 2;
-  // one extra row of workgroups (blockIdx.y == n_nodes) for the small jobs
+  sa.n_slot_words = (long long)f->n_prompts * exchange_banks(f->max_depth) * pl.G * pl.red_w * 2;
+  // one extra row of workgroups (blockIdx.y == 0) for the small jobs
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, true, stream);
   hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, 2), dim3(VS_BLOCK), 0, stream, sa);
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, false, stream);
@@ -1425,12 +1710,16 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   }
   if (const char* e = getenv("DSBD_VERIFY_TEST_MUTE_WG")) la.mute_wg = atoi(e);   // error-path test hook
   la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;
+  la.top_k = p->top_k; la.top_p = (p->top_p > 0.0f && p->top_p < 1.0f) ? p->top_p : 1.0f;
   // Ordinary launch: the grid was checked above to fit the device at once, the stream's earlier kernels have
   // drained by the time this one starts, and every wait inside the kernel is bounded.  (A cooperative launch
   // would also guarantee co-residency against work on other streams, but it made rocprofv3 crash at process
   // exit on ROCm 7.2 and costs extra launch latency.)
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, true, stream);
-  hipLaunchKernelGGL(verify_layers_kernel, dim3((unsigned)grid3), dim3(VL_BLOCK), (size_t)pl.lds_elems * 16, stream, la);
+  if (p->top_k > 0)
+    hipLaunchKernelGGL(verify_layers_kernel<true>, dim3((unsigned)grid3), dim3(VL_BLOCK), (size_t)pl.lds_elems * 16, stream, la);
+  else
+    hipLaunchKernelGGL(verify_layers_kernel<false>, dim3((unsigned)grid3), dim3(VL_BLOCK), (size_t)pl.lds_elems * 16, stream, la);
   const hipError_t le = hipGetLastError();
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, false, stream);
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;

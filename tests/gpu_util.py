@@ -75,10 +75,12 @@ def oracle_attention(w):
     return o_attn.forest_attention(w.parent, w.tree_off, f64(w.q), f64(w.k_tree), f64(w.v_tree), list(pk), list(pv))
 
 
-def oracle_verify(w, W_L=0, W_min=1, t=-1.0, rank=None):
+def oracle_verify(w, W_L=0, W_min=1, t=-1.0, rank=None, top_k=0, top_p=1.0):
+    # top_p reaches the library as a 32-bit float: the oracle takes the same value
     return o_verify.verify_forest(w.tree_prompt, w.tree_off, w.parent, w.token, w.logits_p, w.logits_q,
                                   w.beam_logp_p, w.beam_logp_q, w.u_accept, w.u_resid, w.u_fill,
-                                  W_L, W_min, w.W_cap, np.float32(t), rank=rank)
+                                  W_L, W_min, w.W_cap, np.float32(t), rank=rank, top_k=top_k,
+                                  top_p=float(np.float32(top_p)))
 
 
 def compare_attention(w, out, lse, ref_out, ref_lse, rows=None):

@@ -124,6 +124,62 @@ def test_verify_accept_patterns_over_seeds(seed, noise):
         gu.compare_verify(res, ref, w)
 
 
+WARP_CASES = [
+    # (config, overrides, top_k, top_p)
+    ("c3", dict(V=5000, draft_top_k=4), 16, 1.0),
+    ("c3", dict(V=5000, draft_top_k=4), 16, 0.8),
+    ("c3", dict(V=5000, draft_top_k=2), 5, 0.6),
+    ("c3", dict(V=4001, draft_top_k=8), 32, 0.95),
+    ("c2", dict(V=32000, draft_top_k=3), 8, 0.9),
+    ("c5", dict(V=20000, draft_top_k=4), 32, 0.9),
+    ("c5", dict(V=20000, draft_top_k=4, draft="indep"), 12, 1.0),    # supports that barely overlap
+    ("c4", dict(V=3000, n_prompts=6, draft_top_k=4), 10, 0.85),      # several prompts, ragged widths
+    ("c1", dict(V=9, draft_top_k=3), 32, 0.9),                       # fewer than top_k entries in I x V
+    ("c3", dict(V=5000, draft_top_k=1), 1, 1.0),                     # top_k = 1: one-point joints
+]
+
+
+@pytest.mark.parametrize("t", [-1.0, 0.6])
+@pytest.mark.parametrize("cfg,kw,top_k,top_p", WARP_CASES)
+def test_verify_with_warping_matches_oracle(cfg, kw, top_k, top_p, t):
+    """Warping operation T (top-k, then top-p) on the joints: the decisions, widths and samples agree with the oracle's."""
+    gu = _gu()
+    w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
+    print("case", cfg, kw, "top_k", top_k, "top_p", top_p, "t", t, flush=True)
+    d = gu.DeviceWorkload(w)
+    res = d.verify(t=t, top_k=top_k, top_p=top_p)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+    near = gu.compare_verify(res, ref, w)
+    st = ref["node_status"]
+    print("l_last", ref["l_last"].tolist(), "accepted", int((st == 1).sum()), "rejected", int((st == 2).sum()),
+          "near ties", near, flush=True)
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23, 24])
+def test_verify_with_warping_over_seeds(seed):
+    gu = _gu()
+    w = make_workload("c5", L=1, Hq=1, Hkv=1, D=64, V=9000, seed=seed, noise_std=0.8, draft_top_k=3)
+    d = gu.DeviceWorkload(w)
+    for top_k, top_p, t in ((8, 1.0, -1.0), (8, 0.7, 0.6), (24, 0.9, -1.0), (3, 0.5, 0.3)):
+        print("seed", seed, "top_k", top_k, "top_p", top_p, "t", t, flush=True)
+        res = d.verify(t=t, top_k=top_k, top_p=top_p)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+        gu.compare_verify(res, ref, w)
+
+
+def test_warping_switched_off_is_the_plain_path():
+    gu = _gu()
+    w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=5000)
+    d = gu.DeviceWorkload(w)
+    a = d.verify(t=0.7)
+    b = d.verify(t=0.7, top_k=0, top_p=1.0)
+    torch.cuda.synchronize()
+    for name in ("node_status", "out_parent", "out_token", "out_node", "l_last", "layer_width", "out_logp_target"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+
+
 def test_verify_with_draft_rank_order():
     gu = _gu()
     w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=3000)

@@ -63,6 +63,12 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(p)) == 0
     p = b._Params(2, 1, 4, -1.0)
     assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 0, C.byref(p)) == 0     # V < 1
+    assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(p)) > 0
+    for top_k, top_p in ((33, 1.0), (0, 0.5), (-1, 1.0), (4, -0.5)):      # warping outside what is supported
+        pw = b._Params(2, 1, 4, -1.0, top_k, top_p)
+        assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(pw)) == 0
+    pw = b._Params(2, 1, 4, -1.0, 32, 0.9)
+    assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(pw)) > 0
     vin = b._VerifyIn(100, None, None, None, None, None, None, None)
     vout = b._VerifyOut(*([None] * 14))
     assert lib.dsbd_verify_forest(C.byref(f), C.byref(vin), C.byref(p), C.byref(vout), None, 0, None, None) == -1

@@ -106,6 +106,9 @@ def main():
                     help="kernel whose duration is measured with HIP events for the roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-commit", action="store_true", help="skip the (separately reported) cache-commit measurement")
+    ap.add_argument("--no-warp", action="store_true", help="skip the (separately reported) warped verification")
+    ap.add_argument("--warp-top-k", type=int, default=32)
+    ap.add_argument("--warp-top-p", type=float, default=0.9)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -202,6 +205,25 @@ def main():
     }
     if not args.no_commit:
         res["next_rows"] = {"kv_commit": commit_measurement(dsbd, torch, w, sets[0], outs[0])}
+    if not args.no_warp:
+        # the same verification with the warping operation on the joints (reported apart from the headline)
+        k, p_ = args.warp_top_k, args.warp_top_p
+        wws = torch.empty(dsbd.dsbd_verify_forest_workspace_bytes(sets[0].forest, w.V, 0, 1, w.W_cap, args.t, k, p_),
+                          dtype=torch.uint8, device="cuda")
+        call = lambda i: sets[i % len(sets)].verify(t=args.t, result=outs[i % len(sets)]["vres"], workspace=wws,
+                                                    top_k=k, top_p=p_)
+        for i in range(5):
+            call(i)
+        torch.cuda.synchronize()
+        reps = 20
+        dsbd.dsbd_timing_enable(dsbd.DSBD_KERNEL_VERIFY_LAYERS, reps)
+        call_ms = timed_calls(call, reps)
+        lk = dsbd.dsbd_timing_collect(reps)
+        dsbd.dsbd_timing_enable(0, 0)
+        assert int(outs[0]["vres"].fault.item()) == 0
+        res.setdefault("next_rows", {})["warped_verify"] = {
+            "top_k": k, "top_p": p_, "verify_ms": call_ms, "verify_layers_kernel_ms": sum(lk) / max(1, len(lk)),
+            "plain_verify_ms": br["verify_ms"], "note": "dsbd_verify_forest with top_k / top_p set; not part of value"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline()
     print(json.dumps(res))

@@ -195,6 +195,18 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------ kernel 2
+// Where the exchanges of one prompt keep their 16-byte slots (offsets in slots from the prompt's first one).
+struct SlotLayout {
+  int x[2];              // the two alternating banks of the post-then-collect-from-all exchanges: G lines
+  int r, r_w, r_stride;  // row sums of layer l: r + (l - 1) * r_stride, r_w slots per workgroup
+  int s, s_stride;       // early chain entry of layer l: s + (l - 1) * s_stride, a line per workgroup
+  int b, b_w;            // warping: every workgroup's candidate list, b_w slots each
+  int c;                 // warping: the groups' merged lists (b_w slots each)
+  int d;                 // warping: the final entries, posted by the prompt's first workgroup
+  int prompt_stride;
+};
+#define WARP_RESULT_SLOTS 193     // count + 64 x (index, p, q)
+
 struct LayersArgs {
   int n_prompts, n_trees, n_nodes;
   const int32_t *tree_prompt, *tree_off, *parent, *token, *rank;
@@ -212,12 +224,15 @@ struct LayersArgs {
   const int4* prompt_rec; // [n_prompts] (first tree, end tree, first node, end node)
   const float2* part;    // [2][n_nodes][nchunk] row statistics per chunk (max, sum of exp(x - max))
   int nchunk;
-  double* pb;            // [n_prompts][I_cap*V]  p_beam slice storage
-  double* qb;            // [n_prompts][I_cap*V]
-  double* red;           // exchange slots [n_prompts][banks][G][red_w] of 16 bytes each
-  int G, I_cap, red_w;
+  double* pb;            // [n_prompts][G][slice_cap]  p_beam slice storage, a private region per workgroup
+  double* qb;            // the same for q_beam
+  long long slice_cap;   // elements of a workgroup's region
+  double* red;           // exchange slots of 16 bytes each, n_prompts regions laid out as in `sl`
+  SlotLayout sl;
+  int G, I_cap;
   long long* trace;      // optional timeline (first workgroup of prompt 0): pairs (label, 100 MHz wall clock)
   int lds_elems;         // capacity (elements) of each of the two dynamic-LDS slice arrays; 0 = none
+  int lds_slice;         // slices of up to this many elements are kept in the LDS (<= lds_elems)
   long long sync_limit;  // bound of every wait, in ticks of the 100 MHz wall clock
   int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
                          // bounded waits give up and the error path can be exercised without a hang
@@ -269,6 +284,7 @@ struct LayerShared {
   int U_idx[64];
   double U_p[64], U_q[64];
   int nU;
+  double W_tau[2];                   // lower bounds of the slice's K-th entries
   int W_cnt[2];                      // entries kept per model after the merge
   int state[2];                      // outcome of the decision rounds, alternating entries
   int kmax, counter, abort, found, sbad, sgamma;
@@ -385,7 +401,10 @@ __device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh
 //    collected n + 1, so everybody had posted n + 1 and was therefore done collecting n;
 //  * the row-sum exchange (collected only from the workgroups that share a row) and the early post of the
 //    chain's second entry (collected later, or never) give no such guarantee, so each layer has a bank of its
-//    own for either of them, written once per launch.
+//    own for either of them, written once per launch;
+//  * the three hops of the warping merge (every workgroup -> its group's first -> the prompt's first -> every
+//    workgroup) have a bank each: nobody posts a hop of the next layer before having received the result of
+//    this one, which exists only after every reader of the earlier hops is done.
 struct Slot { unsigned long long w0, w1; };
 
 __device__ __forceinline__ unsigned long long exchange_tag(unsigned int epoch) {
@@ -455,17 +474,22 @@ __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double o
   }
 }
 
-// banks of one prompt: two alternating ones, then a pair (row sums, early chain entry) per layer
-__host__ __device__ __forceinline__ int exchange_banks(int max_depth) { return 2 + 2 * (max_depth + 1); }
-__device__ __forceinline__ Slot* exchange_bank(const LayersArgs& a, int prompt, int bank) {
-  return reinterpret_cast<Slot*>(a.red) + ((long long)(prompt * exchange_banks(a.max_depth) + bank) * a.G) * a.red_w;
+__device__ __forceinline__ Slot* prompt_slots(const LayersArgs& a, int prompt) {
+  return reinterpret_cast<Slot*>(a.red) + (long long)prompt * a.sl.prompt_stride;
 }
 
 // ---- selection of the largest joint entries (warping T).  Entries are ranked by descending value, equal values by
 // ascending flat index; a candidate is (value, index), "none" is (-1, INT_MAX).
 #define WARP_K_MAX 32
+#define WARP_CAND 512          // candidates per model a merge can hold (WARP_GROUP lists of WARP_K_MAX entries)
+#define WARP_GROUP 16          // workgroups whose lists one workgroup merges
 __device__ __forceinline__ bool cand_before(double va, int ia, double vb, int ib) {
-  return va > vb || (va == vb && ia < ib);
+  // no short circuit: the operands are loaded side by side instead of one after a branch on the other
+  return (va > vb) | ((va == vb) & (ia < ib));
+}
+__device__ __forceinline__ double readlane_f64(double v, int l) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), l), hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+  return __hiloint2double(hi, lo);
 }
 // first candidate in rank order among one per lane; the same result in every lane
 __device__ __forceinline__ void wave_first(double& v, int& i) {
@@ -488,6 +512,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   const int V = a.V;
   unsigned int epoch = 0;      // exchanges so far (sets the tag); identical in every workgroup of the prompt
   unsigned int xchg = 0;       // of those, the ones on the two alternating banks
+  Slot* const slots = prompt_slots(a, prompt);
   unsigned int wsum_round = 0; // alternates the two wsum buffers
   unsigned int decide_round = 0;
   int trace_n = 0;
@@ -593,8 +618,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   const int W_in = a.W_L > 0 ? a.W_L : n_roots;
   const bool dynamic = a.t >= 0.f;
   const double thr = (double)a.t;
-  double* pb = a.pb + (long long)prompt * a.I_cap * V;
-  double* qb = a.qb + (long long)prompt * a.I_cap * V;
+  // Slices that do not fit the LDS live in the workspace, each workgroup's in a region of its own: the layers
+  // cut I x V differently, and an address written by workgroups of two XCDs in turn (whose L2 caches write back
+  // in no particular order) could later be read back stale.
+  double* pb = a.pb + ((long long)prompt * a.G + g) * a.slice_cap;
+  double* qb = a.qb + ((long long)prompt * a.G + g) * a.slice_cap;
   const float* u_res = a.u_res + (long long)prompt * Lw;
   const float* u_fill = a.u_fill + (long long)prompt * Lw * a.W_cap;
 
@@ -635,15 +663,15 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const int i_lo = (int)div_floor(e_lo, V);
     const int i_hi = e_hi > e_lo ? (int)div_floor(e_hi - 1, V) : i_lo - 1;
     // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
-    const bool in_lds = ch <= (long long)a.lds_elems;
+    const bool in_lds = ch <= (long long)a.lds_slice;
     // Accessors with explicit address spaces (LDS or global): through generic pointers the compiler merges the two
     // cases into one FLAT access with a selected address, which is slower than either.
     typedef __attribute__((address_space(3))) double lds_f64;
     typedef __attribute__((address_space(1))) double glb_f64;
     lds_f64* const pl = (lds_f64*)dyn_lds;
     lds_f64* const ql = pl + a.lds_elems;
-    glb_f64* const pbg = (glb_f64*)(pb + e_lo);
-    glb_f64* const qbg = (glb_f64*)(qb + e_lo);
+    glb_f64* const pbg = (glb_f64*)pb;
+    glb_f64* const qbg = (glb_f64*)qb;
     auto ldp = [&](long long j) -> double { double v; if (in_lds) v = pl[(int)j]; else v = pbg[j]; return v; };
     auto ldq = [&](long long j) -> double { double v; if (in_lds) v = ql[(int)j]; else v = qbg[j]; return v; };
     auto stp = [&](long long j, double v) { if (in_lds) pl[(int)j] = v; else pbg[j] = v; };
@@ -692,11 +720,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // floor(((i+1)V-1)/ch): only those post its two columns and only those are polled.
     epoch += 1;
     const unsigned long long rs_tag = exchange_tag(epoch);
-    Slot* const rs_bank = exchange_bank(a, prompt, 2 + 2 * (l - 1));
+    Slot* const rs_bank = slots + a.sl.r + (long long)(l - 1) * a.sl.r_stride;
     if (tid < 2 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
       const double* wp = &sh.u.wpart[(tid >> 1) * VL_WAVES * 2 + (tid & 1)];
       const double s = ((wp[0] + wp[2]) + (wp[4] + wp[6])) + ((wp[8] + wp[10]) + (wp[12] + wp[14]));
-      slot_post(rs_bank + (long long)g * a.red_w + 2 * i_lo + tid, s, rs_tag);
+      slot_post(rs_bank + (long long)g * a.sl.r_w + 2 * i_lo + tid, s, rs_tag);
     }
     stamp(102);
 
@@ -763,7 +791,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const int w_hi = (int)div_floor((long long)(i + 1) * V - 1, ch);
         for (int w = w_lo + r; w <= w_hi; w += R) {
           double v = 0.0;
-          mine = mine && slot_wait(rs_bank + (long long)w * a.red_w + c, rs_tag, v, a.sync_limit);
+          mine = mine && slot_wait(rs_bank + (long long)w * a.sl.r_w + c, rs_tag, v, a.sync_limit);
           acc += v;
         }
       }
@@ -798,6 +826,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     stamp(24);
     // scaling, fused with this thread's part of F(1) = sum max(p_beam - q_beam, 0) (second entry of the chain)
     double f1 = 0.0;
+    double tmax_p = -1.0, tmax_q = -1.0;     // warping: the largest scaled entries this thread has seen
     for (int i = i_lo; i <= i_hi; ++i) {
       const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
       const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
@@ -811,28 +840,114 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         for (int k = 0; k < 4; ++k) {
           pv[k] *= fp; qv[k] *= fq;
           stp(j + k * VL_BLOCK, pv[k]); stq(j + k * VL_BLOCK, qv[k]);
-          f1 += fmax(pv[k] - qv[k], 0.0);
+          if constexpr (WARP) { tmax_p = fmax(tmax_p, pv[k]); tmax_q = fmax(tmax_q, qv[k]); }
+          else f1 += fmax(pv[k] - qv[k], 0.0);
         }
       }
       for (; j < j_hi; j += VL_BLOCK) {
         const double pv = ldp(j) * fp, qv = ldq(j) * fq;
         stp(j, pv); stq(j, qv);
-        f1 += fmax(pv - qv, 0.0);
+        if constexpr (WARP) { tmax_p = fmax(tmax_p, pv); tmax_q = fmax(tmax_q, qv); }
+        else f1 += fmax(pv - qv, 0.0);
       }
     }
     if constexpr (WARP) {
       // ===== warping T: top-k / top-p on the two joints (Section 2.1; Section 3.1 "Details": p_beam = T o p/P).
-      // Every workgroup finds the K first entries of its slice, all exchange them, every workgroup merges the
-      // G*K candidates into the same global list, cuts it by top-p and renormalises.  From here on the layer works
-      // on the (at most 2K) surviving entries, which every workgroup holds: no further exchange is needed.
+      // Every workgroup finds the K first entries of its slice.  The lists travel up a tree: the first workgroup
+      // of every group of WARP_GROUP merges its group's lists, the prompt's first workgroup merges the groups'
+      // lists, cuts the result by top-p, renormalises and posts the surviving entries (at most 2K), which every
+      // workgroup then holds: the rest of the layer needs no further exchange.
       __syncthreads();                       // the scaled slices are complete
       const int K = a.top_k;
-      // scratch (all rewritten later in the layer): per-wave lists in S_pb/S_qb (values) and S_zp/S_zq (indices),
-      // merged lists in Pa (values: p then q) and Pb (indices)
-      double* const cvp = sh.S_pb; double* const cvq = sh.S_qb;
-      int* const cip = reinterpret_cast<int*>(sh.S_zp); int* const ciq = reinterpret_cast<int*>(sh.S_zq);
-      double* const lv = sh.Pa; int* const li = reinterpret_cast<int*>(sh.Pb);
-      {  // (1) every wave: the K first entries among the slice elements its lanes own
+      typedef __attribute__((address_space(3))) int lds_i32;
+      // scratch (all rewritten later in the layer): candidates in S_pb/S_qb (values) and S_zp/S_zq (indices),
+      // lists in Pa (values: p then q) and Pb (indices); collected lists in the dynamic LDS (the slices are not
+      // needed any more by then): values [model][source * K + rank], then the indices
+      lds_f64* const cvp = (lds_f64*)sh.S_pb; lds_f64* const cvq = (lds_f64*)sh.S_qb;
+      lds_i32* const cip = (lds_i32*)sh.S_zp; lds_i32* const ciq = (lds_i32*)sh.S_zq;
+      lds_f64* const lv = (lds_f64*)sh.Pa; lds_i32* const li = (lds_i32*)sh.Pb;
+      lds_f64* const gv = (lds_f64*)dyn_lds;
+      lds_i32* const gi = (lds_i32*)(dyn_lds + 2 * WARP_CAND);
+      // The K first of na candidates by counting for each those ahead of it, eight threads per candidate and 64
+      // candidates per pass; ranks nobody takes keep what the caller put there.
+      auto rank_cands = [&](lds_f64* va, lds_i32* ia, int na, lds_f64* ov, lds_i32* oi) {
+        const int part = tid & 7;
+        for (int t0 = 0; t0 < na; t0 += VL_BLOCK / 8) {
+          const int t = t0 + (tid >> 3);
+          const bool has = t < na;
+          const double v = has ? va[t] : 0.0;
+          const int ix = has ? ia[t] : 0;
+          int rank = 0;
+          if (has)
+            for (int c = part; c < na; c += 8) rank += cand_before(va[c], ia[c], v, ix) ? 1 : 0;
+          rank += __shfl_xor(rank, 1);
+          rank += __shfl_xor(rank, 2);
+          rank += __shfl_xor(rank, 4);
+          if (has && part == 0 && rank < K) { ov[rank] = v; oi[rank] = ix; }
+        }
+      };
+      // candidates (counts in W_cnt) -> lists; missing ranks are "none" (-1, INT_MAX), which sorts last
+      auto rank_select = [&]() {
+        if (tid < 2 * K) { lv[tid] = -1.0; li[tid] = INT_MAX; }
+        __syncthreads();
+        rank_cands(cvp, cip, min(sh.W_cnt[0], WARP_CAND), lv, li);
+        rank_cands(cvq, ciq, min(sh.W_cnt[1], WARP_CAND), lv + K, li + K);
+      };
+      // (1) a lower bound of the slice's K-th entry: the K-th largest of the maxima of 64 groups of eight threads
+      // (K of the slice's entries, from different groups, are at or above it)
+      {
+        double gp = tmax_p, gq = tmax_q;
+#pragma unroll
+        for (int off = 1; off <= 4; off <<= 1) { gp = fmax(gp, __shfl_xor(gp, off)); gq = fmax(gq, __shfl_xor(gq, off)); }
+        if ((lane & 7) == 0) { sh.tsum[wave * 8 + (lane >> 3)] = gp; sh.tsum[64 + wave * 8 + (lane >> 3)] = gq; }
+        if (tid < 2) sh.W_cnt[tid] = 0;
+      }
+      __syncthreads();
+      stamp(57);
+      {  // four threads count, for one of the 2 x 64 maxima, those ahead of it; the one with K - 1 ahead is the bound
+        const int m = tid >> 8, i = (tid >> 2) & 63, part = tid & 3;
+        const double v = sh.tsum[m * 64 + i];
+        int rank = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int c = part + 4 * j;
+          const double o = sh.tsum[m * 64 + c];
+          rank += (o > v || (o == v && c < i)) ? 1 : 0;
+        }
+        rank += __shfl_xor(rank, 1);
+        rank += __shfl_xor(rank, 2);
+        if (part == 0 && rank == K - 1) sh.W_tau[m] = v;    // -1 when fewer than K groups hold anything: everything passes
+      }
+      __syncthreads();
+      stamp(58);
+      {  // (2) everything at or above the bound is a candidate
+        const double tp = sh.W_tau[0], tq = sh.W_tau[1];
+        auto offer = [&](long long j, double vp, double vq) {
+          if (vp >= tp) {
+            const int c = atomicAdd(&sh.W_cnt[0], 1);
+            if (c < WARP_CAND) { cvp[c] = vp; cip[c] = (int)(e_lo + j); }
+          }
+          if (vq >= tq) {
+            const int c = atomicAdd(&sh.W_cnt[1], 1);
+            if (c < WARP_CAND) { cvq[c] = vq; ciq[c] = (int)(e_lo + j); }
+          }
+        };
+        long long j = tid;
+        for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
+          double pv[4], qv[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) { pv[k] = ldp(j + k * VL_BLOCK); qv[k] = ldq(j + k * VL_BLOCK); }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) offer(j + k * VL_BLOCK, pv[k], qv[k]);
+        }
+        for (; j < len; j += VL_BLOCK) offer(j, ldp(j), ldq(j));
+      }
+      __syncthreads();
+      stamp(60);
+      if (sh.W_cnt[0] > WARP_CAND || sh.W_cnt[1] > WARP_CAND) {
+        // too many entries at or above the bound (many equal values, or a vocabulary of a few hundred tokens):
+        // every wave extracts the K first of its lanes' elements a rank at a time; those become the candidates
+        __syncthreads();                     // everybody has read the counts
         double pv_prev = INFINITY, qv_prev = INFINITY;
         int pi_prev = -1, qi_prev = -1;
         for (int r = 0; r < K; ++r) {
@@ -849,43 +964,22 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           if (lane == 0) { cvp[wave * K + r] = bp; cip[wave * K + r] = ip; cvq[wave * K + r] = bq; ciq[wave * K + r] = iq; }
           pv_prev = bp; pi_prev = ip; qv_prev = bq; qi_prev = iq;
         }
+        if (tid < 2) sh.W_cnt[tid] = VL_WAVES * K;
       }
-      // one wave: the K first of a candidate list, in rank order ("none" entries sort last)
-      auto wave_select = [&](const double* vals, const int* idx, int n, double* ov, int* oi) {
-        double v_prev = INFINITY;
-        int i_prev = -1;
-        for (int r = 0; r < K; ++r) {
-          double b = -1.0;
-          int bi = INT_MAX;
-          for (int c = lane; c < n; c += 64) {
-            const double v = vals[c];
-            const int fi = idx[c];
-            if (cand_before(v_prev, i_prev, v, fi) && cand_before(v, fi, b, bi)) { b = v; bi = fi; }
-          }
-          wave_first(b, bi);
-          if (lane == 0) { ov[r] = b; oi[r] = bi; }
-          v_prev = b; i_prev = bi;
+      rank_select();                         // barrier inside, after the counts are final
+      __syncthreads();
+      stamp(61);
+      // (3) up the tree.  A list travels as 4K words (model, rank, value | index).
+      auto post_list = [&](Slot* where, unsigned long long tag) {
+        if (tid < 4 * K) {
+          const int m = tid / (2 * K), r = (tid % (2 * K)) >> 1;
+          const double payload = (tid & 1) ? (double)li[m * K + r] : lv[m * K + r];
+          slot_post(where + tid, payload, tag);
         }
       };
-      __syncthreads();
-      if (wave == 0) { wave_select(cvp, cip, VL_WAVES * K, lv, li); wave_select(cvq, ciq, VL_WAVES * K, lv + K, li + K); }
-      __syncthreads();
-      // (2) exchange: workgroup g posts 4K words (model, rank, value | index)
-      epoch += 1;
-      const unsigned long long w_tag = exchange_tag(epoch);
-      Slot* const w_bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
-      if (tid < 4 * K) {
-        const int m = tid / (2 * K), r = (tid % (2 * K)) >> 1;
-        const double payload = (tid & 1) ? (double)li[m * K + r] : lv[m * K + r];
-        slot_post(w_bank + (long long)g * a.red_w + tid, payload, w_tag);
-      }
-      // (3) everybody collects all G*4K words into the dynamic LDS (the slices are not needed any more):
-      // values [model][workgroup*K + rank], then the indices
-      const int GK = a.G * K;
-      double* const gv = dyn_lds;
-      int* const gi = reinterpret_cast<int*>(dyn_lds + 2 * GK);
-      {
-        const int nS = a.G * 4 * K;
+      // n_src lists, b_w slots apart from `from` on, into gv / gi; up to four slots in flight per thread
+      auto collect_lists = [&](Slot* from, unsigned long long tag, int n_src) {
+        const int nS = n_src * 4 * K;
         bool okc = true;
         for (int s0 = tid; s0 < nS && okc; s0 += 4 * VL_BLOCK) {
           bool have[4];
@@ -900,14 +994,14 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
               w0[k] = 0; w1[k] = 0;
               if (!have[k]) {
                 const int sk = s0 + k * VL_BLOCK;
-                Slot* sl = w_bank + (long long)(sk / (4 * K)) * a.red_w + sk % (4 * K);
+                Slot* sl = from + (long long)(sk / (4 * K)) * a.sl.b_w + sk % (4 * K);
                 w0[k] = __hip_atomic_load(&sl->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 w1[k] = __hip_atomic_load(&sl->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               }
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-              if (!have[k] && (w0[k] ^ w1[k]) == w_tag) { val[k] = __longlong_as_double((long long)w0[k]); have[k] = true; }
+              if (!have[k] && (w0[k] ^ w1[k]) == tag) { val[k] = __longlong_as_double((long long)w0[k]); have[k] = true; }
             if (have[0] && have[1] && have[2] && have[3]) break;
             if (spin == 0) t0 = wall_clock64();
             else if ((spin & 15) == 0 && wall_clock64() - t0 > a.sync_limit) { okc = false; break; }
@@ -917,78 +1011,175 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           for (int k = 0; k < 4; ++k) {
             const int sk = s0 + k * VL_BLOCK;
             if (sk < nS && okc) {
-              const int w = sk / (4 * K), c = sk % (4 * K);
+              const int src = sk / (4 * K), c = sk % (4 * K);
               const int m = c / (2 * K), r = (c % (2 * K)) >> 1;
-              if (c & 1) gi[m * GK + w * K + r] = (int)val[k];
-              else gv[m * GK + w * K + r] = val[k];
+              if (c & 1) gi[m * WARP_CAND + src * K + r] = (int)val[k];
+              else gv[m * WARP_CAND + src * K + r] = val[k];
             }
           }
         }
         if (!okc) give_up();
-      }
-      __syncthreads();
-      if (sh.abort) return;
-      {  // (4) merge: every wave selects from an eighth of the G*K candidates, the first wave from the 8K winners
-        const int n8 = (GK + VL_WAVES - 1) / VL_WAVES;
-        const int lo = min(GK, wave * n8), cnt = min(GK, lo + n8) - lo;
-        wave_select(gv + lo, gi + lo, cnt, cvp + wave * K, cip + wave * K);
-        wave_select(gv + GK + lo, gi + GK + lo, cnt, cvq + wave * K, ciq + wave * K);
-      }
-      __syncthreads();
-      if (wave == 0) {
-        wave_select(cvp, cip, VL_WAVES * K, lv, li);
-        wave_select(cvq, ciq, VL_WAVES * K, lv + K, li + K);
-        wave_lds_fence();
-        // (5) top-p on the kept entries (descending order: the smallest leading part whose share exceeds top_p),
-        // renormalisation; lane 0 for p_beam, lane 1 for q_beam, sums taken in list order
-        if (lane < 2) {
-          double* v = lv + lane * K;
-          const int* ix = li + lane * K;
-          int n = 0;
-          while (n < K && ix[n] != INT_MAX) ++n;         // fewer than K exist when I x V is smaller
-          int keep = n;
-          if (a.top_p < 1.0f) {
-            double mass = 0.0;
-            for (int r = 0; r < n; ++r) mass += v[r];
-            double cum = 0.0;
-            keep = 0;
-            for (int r = 0; r < n; ++r) {
-              keep = r + 1;
-              cum += v[r];
-              if (cum / mass > (double)a.top_p) break;
+      };
+      // The K first of n_src collected lists, each in rank order: a tree of four-way merges.  In a merge an
+      // entry's rank is its own rank plus the numbers of entries of the three partner lists ahead of it (binary
+      // searches, side by side); ranks K and beyond drop out.  The lists alternate between the dynamic LDS and
+      // the candidate arrays; the last merge writes lv / li.  Ends after a barrier.
+      auto merge_lists = [&](int n_src) {
+        int n = n_src;
+        bool in_g = true;
+        while (true) {
+          const int n4 = (n + 3) >> 2;
+          const bool last = n4 == 1;
+          lds_f64* const sv0 = in_g ? gv : cvp;
+          lds_f64* const sv1 = in_g ? gv + WARP_CAND : cvq;
+          lds_i32* const si0 = in_g ? gi : cip;
+          lds_i32* const si1 = in_g ? gi + WARP_CAND : ciq;
+          lds_f64* const dv0 = last ? lv : (in_g ? cvp : gv);
+          lds_f64* const dv1 = last ? lv + K : (in_g ? cvq : gv + WARP_CAND);
+          lds_i32* const di0 = last ? li : (in_g ? cip : gi);
+          lds_i32* const di1 = last ? li + K : (in_g ? ciq : gi + WARP_CAND);
+          for (int t = tid; t < 2 * n4 * K; t += VL_BLOCK) {
+            const int m = t >= n4 * K ? 1 : 0, e = t - m * n4 * K;
+            (m ? dv1 : dv0)[e] = -1.0;
+            (m ? di1 : di0)[e] = INT_MAX;
+          }
+          __syncthreads();
+          for (int t = tid; t < 2 * n * K; t += VL_BLOCK) {
+            const int m = t >= n * K ? 1 : 0, e = t - m * n * K;
+            const int src = e / K, r = e - src * K;
+            lds_f64* const sv = m ? sv1 : sv0;
+            lds_i32* const si = m ? si1 : si0;
+            const double v = sv[e];
+            const int ix = si[e];
+            // entries of a partner list ahead of this one: the longest leading part of which all are (branch-free:
+            // steps 32, 16, .. 1; a partner that does not exist has length 0 and is read at this entry's own list)
+            int po[3], len_j[3], cnt[3];
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+              const int o = (src & ~3) + ((src + 1 + j) & 3);
+              po[j] = (o < n ? o : src) * K; len_j[j] = o < n ? K : 0; cnt[j] = 0;
+            }
+#pragma unroll
+            for (int step = 32; step >= 1; step >>= 1) {
+              double pv3[3];
+              int pi3[3];
+#pragma unroll
+              for (int j = 0; j < 3; ++j) {
+                const int at = min(cnt[j] + step - 1, K - 1);
+                pv3[j] = sv[po[j] + at]; pi3[j] = si[po[j] + at];
+              }
+#pragma unroll
+              for (int j = 0; j < 3; ++j)
+                cnt[j] += ((cnt[j] + step - 1 < len_j[j]) & cand_before(pv3[j], pi3[j], v, ix)) ? step : 0;
+            }
+            const int rank = r + cnt[0] + cnt[1] + cnt[2];
+            if (rank < K && ix != INT_MAX) {
+              (m ? dv1 : dv0)[(src >> 2) * K + rank] = v;
+              (m ? di1 : di0)[(src >> 2) * K + rank] = ix;
             }
           }
-          double z = 0.0;
-          for (int r = 0; r < keep; ++r) z += v[r];
-          for (int r = 0; r < keep; ++r) v[r] = v[r] / z;
-          sh.W_cnt[lane] = keep;
+          __syncthreads();
+          if (last) break;
+          n = n4;
+          in_g = !in_g;
         }
-        wave_lds_fence();
-        // (6) union of the two supports, ascending flat index: lanes 0..31 carry the p entries, 32..63 the q entries
-        const int mp = sh.W_cnt[0], mq = sh.W_cnt[1];
-        const int r = lane & 31;
-        const bool is_q = lane >= 32;
-        bool valid = is_q ? r < mq : r < mp;
-        int idx = valid ? li[(is_q ? K : 0) + r] : INT_MAX;
-        double wp = 0.0, wq = 0.0;
-        if (valid && !is_q) {
-          wp = lv[r];
-          for (int c = 0; c < mq; ++c) if (li[K + c] == idx) wq = lv[K + c];
-        } else if (valid) {
-          wq = lv[K + r];
-          for (int c = 0; c < mp; ++c) if (li[c] == idx) valid = false;     // already carried by a p entry
+      };
+      unsigned long long tag_d = 0;
+      if (a.G > 1) {
+        const int first = g - g % WARP_GROUP;
+        const int n_mem = min(WARP_GROUP, a.G - first);
+        const int n_groups = (a.G + WARP_GROUP - 1) / WARP_GROUP;
+        const unsigned long long tag_b = exchange_tag(epoch + 1), tag_c = exchange_tag(epoch + 2);
+        tag_d = exchange_tag(epoch + 3);
+        epoch += 3;
+        post_list(slots + a.sl.b + (long long)g * a.sl.b_w, tag_b);
+        if (g == first) {                    // the group's first workgroup merges the group's lists
+          collect_lists(slots + a.sl.b + (long long)first * a.sl.b_w, tag_b, n_mem);
+          __syncthreads();
+          stamp(62);
+          if (sh.abort) return;
+          merge_lists(n_mem);
+          stamp(63);
+          if (n_groups > 1) post_list(slots + a.sl.c + (long long)(g / WARP_GROUP) * a.sl.b_w, tag_c);
         }
-        int rank = 0;
-        for (int c = 0; c < 64; ++c) {
-          const int oidx = __shfl(idx, c);
-          const int oval = __shfl((int)valid, c);
-          rank += (oval && oidx < idx) ? 1 : 0;
+        if (g == 0 && n_groups > 1) {        // the prompt's first workgroup merges the groups' lists
+          collect_lists(slots + a.sl.c, tag_c, n_groups);
+          __syncthreads();
+          stamp(64);
+          if (sh.abort) return;
+          merge_lists(n_groups);
         }
-        if (valid) { sh.U_idx[rank] = idx; sh.U_p[rank] = wp; sh.U_q[rank] = wq; }
-        const unsigned long long vm = __ballot(valid);
-        if (lane == 0) sh.nU = __popcll(vm);
       }
-      __syncthreads();
+      stamp(65);
+      if (g == 0) {
+        if (wave == 0) {
+          // (4) top-p on the kept entries (rank order: the shortest leading part whose share exceeds top_p) and
+          // renormalisation; lanes 0..31 carry p_beam's list, lanes 32..63 q_beam's, one rank each.  The running
+          // sums add the entries one by one in rank order.
+          const int r = lane & 31, half = lane & 32;
+          const bool is_q = half != 0;
+          const int ix = r < K ? li[(is_q ? K : 0) + r] : INT_MAX;
+          const bool real = ix != INT_MAX;
+          const double v = real ? lv[(is_q ? K : 0) + r] : 0.0;
+          double cum = 0.0;
+          int partner = -1;                  // lane of the other list's entry with the same index
+          for (int c = 0; c < K; ++c) {
+            const double vp_c = readlane_f64(v, c), vq_c = readlane_f64(v, 32 + c);
+            if (c <= r) cum += is_q ? vq_c : vp_c;
+            const int ip_c = __builtin_amdgcn_readlane(ix, c), iq_c = __builtin_amdgcn_readlane(ix, 32 + c);
+            if ((is_q ? ip_c : iq_c) == ix) partner = (is_q ? 0 : 32) + c;
+          }
+          const unsigned long long real_m = __ballot(real);
+          const int n = __popcll(is_q ? (real_m >> 32) : (real_m & 0xffffffffull));     // real entries lead the list
+          int keep = n;
+          if (a.top_p < 1.0f) {
+            const double mass = __shfl(cum, half + max(n - 1, 0));
+            const unsigned long long over_m = __ballot(real && cum / mass > (double)a.top_p);
+            const unsigned int mine = (unsigned int)(is_q ? (over_m >> 32) : (over_m & 0xffffffffull));
+            if (mine) keep = __ffs((int)mine);
+          }
+          const double z = __shfl(cum, half + max(keep - 1, 0));
+          const bool kept = r < keep;
+          const double w = kept ? v / z : 0.0;
+          // (5) union of the two supports, ascending flat index: a q entry whose index p_beam also keeps is
+          // carried by the p entry
+          const double w_partner = __shfl(w, max(partner, 0));       // 0 when the partner was cut
+          const int kept_partner = __shfl((int)kept, max(partner, 0));
+          const bool both = real && partner >= 0 && kept_partner;
+          const double other = (both && !is_q) ? w_partner : 0.0;
+          const bool valid = kept && !(is_q && both);
+          int rank = 0;
+#pragma unroll
+          for (int c = 0; c < 64; ++c) {
+            const int oidx = __builtin_amdgcn_readlane(ix, c);
+            const int oval = __builtin_amdgcn_readlane((int)valid, c);
+            rank += (oval && oidx < ix) ? 1 : 0;
+          }
+          if (valid) { sh.U_idx[rank] = ix; sh.U_p[rank] = is_q ? 0.0 : w; sh.U_q[rank] = is_q ? w : other; }
+          const unsigned long long vm = __ballot(valid);
+          if (lane == 0) sh.nU = __popcll(vm);
+        }
+        __syncthreads();
+        if (a.G > 1 && tid < WARP_RESULT_SLOTS) {          // (6) ... and down again: the count, then (index, p, q) each
+          const int u = (tid - 1) / 3, f = (tid - 1) % 3;
+          double payload = 0.0;
+          if (tid == 0) payload = (double)sh.nU;
+          else if (u < sh.nU) payload = f == 0 ? (double)sh.U_idx[u] : (f == 1 ? sh.U_p[u] : sh.U_q[u]);
+          slot_post(slots + a.sl.d + tid, payload, tag_d);
+        }
+      } else {
+        if (tid < WARP_RESULT_SLOTS) {
+          double v = 0.0;
+          if (!slot_wait(slots + a.sl.d + tid, tag_d, v, a.sync_limit)) give_up();
+          const int u = (tid - 1) / 3, f = (tid - 1) % 3;
+          if (tid == 0) sh.nU = (int)v;
+          else if (f == 0) sh.U_idx[u] = (int)v;
+          else if (f == 1) sh.U_p[u] = v;
+          else sh.U_q[u] = v;
+        }
+        __syncthreads();
+        if (sh.abort) return;
+      }
     }
     stamp(25);
     // p_beam and q_beam at every candidate's (parent beam, token)
@@ -999,8 +1190,15 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       double pbx, qbx;
       if constexpr (WARP) {       // warped joints: the surviving entries, zero elsewhere
         const int flat = slot * V + sh.n_token[n - n_begin];
-        pbx = 0.0; qbx = 0.0;
-        for (int c = 0; c < sh.nU; ++c) if (sh.U_idx[c] == flat) { pbx = sh.U_p[c]; qbx = sh.U_q[c]; }
+        int at = 0;                                  // entries with a smaller index (the list is in index order)
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1) {
+          const int probe = at + step - 1;
+          at += (probe < sh.nU && sh.U_idx[min(probe, 63)] < flat) ? step : 0;
+        }
+        const bool hit = at < sh.nU && sh.U_idx[min(at, 63)] == flat;
+        pbx = hit ? sh.U_p[min(at, 63)] : 0.0;
+        qbx = hit ? sh.U_q[min(at, 63)] : 0.0;
       } else {
         pbx = exp_nonpos((double)czp - sh.max_p[slot], sh.exp_tab) * sh.sp[slot];
         qbx = exp_nonpos((double)czq - sh.max_q[slot], sh.exp_tab) * sh.sq[slot];
@@ -1024,7 +1222,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       stamp(27);
       epoch += 1;
       spec_tag = exchange_tag(epoch);
-      spec_bank = exchange_bank(a, prompt, 3 + 2 * (l - 1));
+      spec_bank = slots + a.sl.s + (long long)(l - 1) * a.sl.s_stride;
       if (tid == 0) dense_post(spec_bank, a.G, g, tot, spec_tag);
       spec_own = tot;
       spec = true;
@@ -1113,7 +1311,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       // ... and over the workgroups (same order everywhere), gathered and scanned by one wave
       epoch += 1;
       const unsigned long long tag = exchange_tag(epoch);
-      Slot* bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
+      Slot* bank = slots + a.sl.x[xchg++ & 1];
       if (wave == 0) {
         const double mine = sh.tsum[VL_BLOCK - 1];
         if (lane == 0) dense_post(bank, a.G, g, mine, tag);
@@ -1338,7 +1536,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         }
         epoch += 1;
         const unsigned long long tag = exchange_tag(epoch);
-        Slot* bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
+        Slot* bank = slots + a.sl.x[xchg++ & 1];
         if (wave == 0) {
           if (lane == 0) dense_post(bank, a.G, g, tot, tag);
           double v[4];
@@ -1438,7 +1636,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (!posted) {
           epoch += 1;
           x_tag = exchange_tag(epoch);
-          x_bank = exchange_bank(a, prompt, (int)(xchg++ & 1));
+          x_bank = slots + a.sl.x[xchg++ & 1];
           if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
           x_own = tot;
         }
@@ -1529,7 +1727,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 namespace {
 
 struct VerifyPlan {
-  int nchunk, chunk, I_cap, G, red_w, lds_elems;
+  int nchunk, chunk, I_cap, G, lds_elems;
+  SlotLayout sl;
+  long long slice_cap;     // elements of the largest slice of I x V a workgroup can get
 };
 
 int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
@@ -1594,20 +1794,34 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   if (G < 1) G = 1;
   if (G > 256) G = 256;
   const long long cap = VL_DYN_LDS_BYTES / 16;
-  // warping: all G * top_k candidates of both models (value + index: 3 doubles a pair) sit in the dynamic LDS
-  if (p->top_k > 0 && (long long)G * p->top_k * 3 > 2 * cap) G = (int)(2 * cap / (3LL * p->top_k));
   pl.G = G;
-  pl.red_w = 2 * pl.I_cap;
-  if (pl.red_w < LINE_SLOTS) pl.red_w = LINE_SLOTS;    // single-value exchanges use one 128-byte line per workgroup
-  if (pl.red_w < 4 * p->top_k) pl.red_w = 4 * p->top_k;
+  // exchange slots: every workgroup's slots of an exchange start a 128-byte line (no two writers per line)
+  {
+    auto up8 = [](int v) { return (v + LINE_SLOTS - 1) / LINE_SLOTS * LINE_SLOTS; };
+    const int layers = f->max_depth + 1;
+    SlotLayout& sl = pl.sl;
+    int off = 0;
+    sl.x[0] = off; off += G * LINE_SLOTS;
+    sl.x[1] = off; off += G * LINE_SLOTS;
+    sl.r_w = up8(2 * pl.I_cap);
+    sl.r = off; sl.r_stride = G * sl.r_w; off += layers * sl.r_stride;
+    sl.s = off; sl.s_stride = G * LINE_SLOTS; off += layers * sl.s_stride;
+    sl.b = sl.c = sl.d = off; sl.b_w = 0;
+    if (p->top_k > 0) {
+      sl.b_w = up8(4 * p->top_k);
+      sl.b = off; off += G * sl.b_w;
+      sl.c = off; off += (G + WARP_GROUP - 1) / WARP_GROUP * sl.b_w;
+      sl.d = off; off += up8(WARP_RESULT_SLOTS);
+    }
+    sl.prompt_stride = off;
+  }
   // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most VL_DYN_LDS_BYTES for the two arrays
   long long need = (joint + G - 1) / G;
   need = (need + 1) & ~1LL;
+  pl.slice_cap = need;
   pl.lds_elems = (int)(need < cap ? need : cap);
-  if (p->top_k > 0) {
-    const long long w_need = ((long long)G * p->top_k * 3 + 1) / 2 + 1;
-    if (pl.lds_elems < w_need) pl.lds_elems = (int)w_need;
-  }
+  // warping: the candidate lists of a merge (2 x WARP_CAND values and indices) sit in the dynamic LDS
+  if (p->top_k > 0 && pl.lds_elems < (3 * WARP_CAND + 1) / 2) pl.lds_elems = (3 * WARP_CAND + 1) / 2;
   return pl;
 }
 
@@ -1617,9 +1831,9 @@ size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const Veri
   ws.take<long long>(512);                 // timeline of the layer kernel (diagnostics), first in the workspace
   *depth = ws.take<int32_t>(N);
   *part = ws.take<float2>(2 * N * pl.nchunk);
-  *pb = ws.take<double>(P * pl.I_cap * V);
-  *qb = ws.take<double>(P * pl.I_cap * V);
-  *red = ws.take<double>(P * exchange_banks(f->max_depth) * pl.G * pl.red_w * 2);
+  *pb = ws.take<double>(P * pl.G * (size_t)pl.slice_cap);
+  *qb = ws.take<double>(P * pl.G * (size_t)pl.slice_cap);
+  *red = ws.take<double>(P * (size_t)pl.sl.prompt_stride * 2);
   *prompt_rec = ws.take<int4>(P);
   return ws.total();
 }
@@ -1684,7 +1898,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   sa.tree_prompt = f->tree_prompt; sa.tree_off = f->tree_off; sa.parent = f->parent;
   sa.depth = depth; sa.prompt_rec = prompt_rec;
   sa.slots = reinterpret_cast<unsigned long long*>(red);
-  sa.n_slot_words = (long long)f->n_prompts * exchange_banks(f->max_depth) * pl.G * pl.red_w * 2;
+  sa.n_slot_words = (long long)f->n_prompts * pl.sl.prompt_stride * 2;
   // one extra row of workgroups (blockIdx.y == 0) for the small jobs
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, true, stream);
   hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, 2), dim3(VS_BLOCK), 0, stream, sa);
@@ -1700,7 +1914,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.u_acc = in->u_accept; la.u_res = in->u_resid; la.u_fill = in->u_fill;
   la.W_L = p->W_L; la.W_min = p->W_min; la.W_cap = p->W_cap; la.t = p->t;
   la.out = *out; la.depth = depth; la.prompt_rec = prompt_rec; la.part = part; la.nchunk = pl.nchunk;
-  la.pb = pb; la.qb = qb; la.red = red;
+  la.pb = pb; la.qb = qb; la.red = red; la.slice_cap = pl.slice_cap;
   la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
   la.sync_limit = SYNC_LIMIT_TICKS;
   la.mute_wg = -1;
@@ -1709,7 +1923,12 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
     if (us >= 1 && us <= 10000000LL) la.sync_limit = us * 100;
   }
   if (const char* e = getenv("DSBD_VERIFY_TEST_MUTE_WG")) la.mute_wg = atoi(e);   // error-path test hook
-  la.G = pl.G; la.I_cap = pl.I_cap; la.red_w = pl.red_w; la.lds_elems = pl.lds_elems; la.fault = fault;
+  la.G = pl.G; la.I_cap = pl.I_cap; la.sl = pl.sl; la.lds_elems = pl.lds_elems; la.fault = fault;
+  la.lds_slice = pl.lds_elems;
+  if (const char* e = getenv("DSBD_VERIFY_LDS_SLICE")) {   // tuning / test knob: largest slice kept in the LDS
+    const int v = atoi(e);
+    if (v >= 0 && v < la.lds_slice) la.lds_slice = v;
+  }
   la.top_k = p->top_k; la.top_p = (p->top_p > 0.0f && p->top_p < 1.0f) ? p->top_p : 1.0f;
   // Ordinary launch: the grid was checked above to fit the device at once, the stream's earlier kernels have
   // drained by the time this one starts, and every wait inside the kernel is bounded.  (A cooperative launch

@@ -111,7 +111,11 @@ def compare_verify(res, ref, w):
     assert np.array_equal(g(res.node_status)[node_ok], ref["node_status"][node_ok])
     for name, key in (("l_last", "l_last"), ("layer_width", "layer_width"), ("n_out", "n_out"),
                       ("out_parent", "out_parent"), ("out_token", "out_token"), ("out_node", "out_node")):
-        assert np.array_equal(g(getattr(res, name))[clean], ref[key][clean]), name
+        got, want = g(getattr(res, name))[clean], ref[key][clean]
+        if not np.array_equal(got, want):
+            bad = np.argwhere(got != want)
+            raise AssertionError("%s differs at (clean prompt, ...) %s: got %s, expected %s"
+                                 % (name, bad[:8].tolist(), got[got != want][:8].tolist(), want[got != want][:8].tolist()))
     for name, key in (("lse_target", "lse_p"), ("lse_draft", "lse_q"), ("node_logp_target", "node_logp_p"),
                       ("node_logp_draft", "node_logp_q")):
         err = np.max(np.abs(g(getattr(res, name)).astype(np.float64) - ref[key]))

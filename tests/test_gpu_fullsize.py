@@ -66,6 +66,27 @@ def test_c5_verify_and_select_whole_forest(c5, t):
             assert np.array_equal(g(getattr(nx, name)), sref[name]), name
 
 
+@pytest.mark.parametrize("top_k,top_p,t", [(32, 0.9, -1.0), (32, 0.9, 0.6), (8, 1.0, -1.0)])
+def test_c5_verify_with_warping_whole_forest(c5, top_k, top_p, t):
+    """Warped joints at the full vocabulary: the benchmark's forest (draft tokens from the whole row: most lie
+    outside the kept entries) and one whose draft tokens come from the rows' largest logits."""
+    import gpu_util as gu
+    w, d = c5
+    res = d.verify(t=t, top_k=top_k, top_p=top_p)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+    gu.compare_verify(res, ref, w)
+    w2 = make_workload("c5", L=1, Hq=1, Hkv=1, D=64, draft_top_k=4, seed=3)
+    d2 = gu.DeviceWorkload(w2)
+    res = d2.verify(t=t, top_k=top_k, top_p=top_p)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w2, t=t, top_k=top_k, top_p=top_p)
+    near = gu.compare_verify(res, ref, w2)
+    st = ref["node_status"]
+    print("c5 warped top_k=%d top_p=%g t=%g: l_last %s accepted %d rejected %d near ties %d"
+          % (top_k, top_p, t, ref["l_last"].tolist(), int((st == 1).sum()), int((st == 2).sum()), near), flush=True)
+
+
 @pytest.mark.parametrize("t", [-1.0, 0.7])
 def test_c4_verify_whole_batch(t):
     """The dynamic-width batch at full size: 16 prompts of 1..8 beams share the device, 16 workgroups each."""

@@ -169,6 +169,42 @@ def test_verify_with_warping_over_seeds(seed):
         gu.compare_verify(res, ref, w)
 
 
+@pytest.mark.parametrize("cfg,kw", [("c3", dict(V=5000)), ("c2", dict(V=700)), ("c4", dict(V=3000, n_prompts=3))])
+def test_warping_with_many_equal_entries(cfg, kw):
+    """Rows of equal logits: thousands of joint entries tie, the order of equal values (lower flat index first)
+    decides which are kept, and the selection has to leave its fast path (more candidates than it can hold)."""
+    import dataclasses
+    gu = _gu()
+    w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
+    zp, zq = np.zeros_like(w.logits_p), np.zeros_like(w.logits_q)
+    zp[1::3] = np.round(w.logits_p[1::3])            # some rows with a few distinct levels instead
+    zq[1::3] = np.round(w.logits_q[1::3])
+    w = dataclasses.replace(w, logits_p=zp, logits_q=zq)
+    d = gu.DeviceWorkload(w)
+    for top_k, top_p, t in ((16, 1.0, -1.0), (32, 0.7, 0.5), (3, 0.9, -1.0)):
+        print("case", cfg, kw, "top_k", top_k, "top_p", top_p, "t", t, flush=True)
+        res = d.verify(t=t, top_k=top_k, top_p=top_p)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+        gu.compare_verify(res, ref, w)
+
+
+@pytest.mark.parametrize("cfg,kw,top_k", [("c3", dict(V=5000), 0), ("c4", dict(V=3000, n_prompts=6), 0),
+                                          ("c5", dict(V=20000, draft_top_k=4), 16), ("c5", dict(V=20000), 0)])
+def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, monkeypatch):
+    """The same results when the joint slices live in the workspace instead of the LDS (as they do at large
+    I x V per workgroup): each workgroup's region is private, whatever way the layers cut I x V."""
+    gu = _gu()
+    monkeypatch.setenv("DSBD_VERIFY_LDS_SLICE", "0")
+    w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
+    d = gu.DeviceWorkload(w)
+    for t in (-1.0, 0.6):
+        res = d.verify(t=t, top_k=top_k, top_p=0.9 if top_k else 1.0)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=0.9 if top_k else 1.0)
+        gu.compare_verify(res, ref, w)
+
+
 def test_warping_switched_off_is_the_plain_path():
     gu = _gu()
     w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=5000)

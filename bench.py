@@ -107,8 +107,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-commit", action="store_true", help="skip the (separately reported) cache-commit measurement")
     ap.add_argument("--no-warp", action="store_true", help="skip the (separately reported) warped verification")
-    ap.add_argument("--warp-top-k", type=int, default=32)
-    ap.add_argument("--warp-top-p", type=float, default=0.9)
+    ap.add_argument("--no-draft", action="store_true", help="skip the (separately reported) draft-side sampling step")
+    ap.add_argument("--warp-top-k", type=int, default=10, help="warping of the separately reported runs (the paper's setting)")
+    ap.add_argument("--warp-top-p", type=float, default=0.8)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -224,6 +225,24 @@ def main():
         res.setdefault("next_rows", {})["warped_verify"] = {
             "top_k": k, "top_p": p_, "verify_ms": call_ms, "verify_layers_kernel_ms": sum(lk) / max(1, len(lk)),
             "plain_verify_ms": br["verify_ms"], "note": "dsbd_verify_forest with top_k / top_p set; not part of value"}
+    if not args.no_draft:
+        # one beam-sampling step of the small model at the benchmark's shape: 16 beams in, 16 draws out (per prompt)
+        W_S = 16
+        d0 = sets[0]
+        zq = d0.logits_q[:W_S].contiguous()
+        cum = torch.linspace(-3.0, 0.0, W_S, dtype=torch.float64, device="cuda")
+        off = torch.tensor([0, W_S], dtype=torch.int32, device="cuda")
+        uu = d0.u_fill.reshape(-1)[:W_S].contiguous()
+        dr = {}
+        for name, (k, p_) in (("plain", (0, 1.0)), ("warped", (args.warp_top_k, args.warp_top_p))):
+            call = lambda i: dsbd.dsbd_draft_layer(off, zq, cum, uu, W_S, max_prompt_beams=W_S, top_k=k, top_p=p_)
+            for i in range(3):
+                call(i)
+            torch.cuda.synchronize()
+            dr[name + "_ms"] = timed_calls(call, 20)
+        dr.update({"beams_in": W_S, "draws": W_S, "V": w.V, "top_k": args.warp_top_k, "top_p": args.warp_top_p,
+                   "note": "dsbd_draft_layer (statistics + sampling kernels, workspace allocated per call); not part of value"})
+        res.setdefault("next_rows", {})["draft_layer"] = dr
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline()
     print(json.dumps(res))

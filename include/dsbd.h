@@ -232,6 +232,72 @@ int32_t dsbd_commit_kv(const dsbd_forest* forest, const dsbd_kv* src, const void
                        const dsbd_kv_dst* dst, int32_t* fault, void* stream);
 
 /*
+ * Draft stage, one step (Section 3.1 "Overview": the small model performs beam sampling of width W_S for gamma
+ * steps; "Details": a draft beam of the next layer is a sample of q_beam = T o q/Q over (beams of the current
+ * layer) x V, the W_S draft beams of a layer drawn independently).  The beams of the current layer are rows:
+ * the input beams for the first step, the W_S draws of the step before afterwards.
+ */
+typedef struct dsbd_draft_in {
+  int32_t n_prompts;
+  int32_t n_beams;                 /* rows of the current layer, all prompts                                 */
+  int32_t max_prompt_beams;        /* host-side bound: most beams of one prompt (<= 64)                      */
+  int32_t V;
+  const int32_t* beam_off;         /* [n_prompts+1] device: beams of prompt p are rows beam_off[p] .. beam_off[p+1]-1 */
+  const float*   logits_draft;     /* [n_beams,V] small model's logits at those beams                        */
+  const double*  beam_logp_draft;  /* [n_beams] their stored log-likelihoods under the small model           */
+  const float*   u;                /* [n_prompts,W_S] uniforms in [0,1), one per draw                        */
+} dsbd_draft_in;
+
+typedef struct dsbd_draft_out {    /* device arrays [n_prompts,W_S]; draw j of prompt p at p*W_S + j          */
+  int32_t* parent;                 /* row (0 .. n_beams-1) of the beam the draw continues                    */
+  int32_t* token;
+  double*  logp_draft;             /* log-likelihood of the new beam under the (unwarped) small model        */
+} dsbd_draft_out;
+
+size_t dsbd_draft_layer_workspace_bytes(const dsbd_draft_in* in, int32_t W_S, int32_t top_k, float top_p);
+
+/*
+ * W_S independent inverse-CDF draws per prompt from q_beam over (the prompt's beams) x V, flat order beam-major /
+ * token-minor, warped by top_k / top_p as in dsbd_params (0 / 1: no warping).  Decisions in fp64; the same
+ * kernels as the verification's sampling of its additional layer.  W_S in 1..64.  A prompt without beams gets
+ * parent = token = -1.  Faults as for dsbd_verify_forest (non-finite logits, inconsistent beam_off).
+ */
+int32_t dsbd_draft_layer(const dsbd_draft_in* in, int32_t W_S, int32_t top_k, float top_p,
+                         const dsbd_draft_out* out, void* workspace, size_t workspace_bytes,
+                         int32_t* fault, void* stream);
+
+/*
+ * Lays the sampled layers out as the draft forest (Section 3.1 "Overview": one tree per input beam, every layer
+ * from the second on holds the W_S intermediate beams of a step).  Layer l = 1..gamma: draw j of prompt p is row
+ * p*W_S + j with parent row layer_parent[(l-1)*n_prompts*W_S + p*W_S + j] in layer l-1 (a row of
+ * dsbd_draft_layer's input at that step) and token layer_token[...].
+ * Layout written: trees contiguous in input-beam order; inside a tree the root, then its nodes by (layer, draw
+ * index), so parent < child; draft_rank = draw index within the layer (the order dsbd_verify_forest must test a
+ * layer's candidates in); n_nodes = n_roots + gamma*n_prompts*W_S.
+ * Device-side problems (fault bits): a parent row outside its prompt's rows of the layer before
+ * (DSBD_FAULT_TOPOLOGY; the node is hung under the first valid row), a tree of more than 64 nodes or a prompt of
+ * more than 512 (DSBD_FAULT_BOUNDS; the arrays are still consistent, but the forest is not usable by the other
+ * calls).
+ */
+typedef struct dsbd_forest_out {   /* device arrays, caller-allocated */
+  int32_t* tree_prompt;            /* [n_roots]                                                              */
+  int32_t* tree_off;               /* [n_roots+1]                                                            */
+  int32_t* parent;                 /* [n_nodes]                                                              */
+  int32_t* token;                  /* [n_nodes]                                                              */
+  int32_t* draft_rank;             /* [n_nodes]                                                              */
+  int32_t* node_of_root;           /* [n_roots] forest node of every input beam (= tree_off[b])              */
+  int32_t* node_of;                /* [gamma*n_prompts*W_S] forest node of every draw, layer-major           */
+  int32_t* max_tree_nodes;         /* [1] nodes of the largest tree                                          */
+} dsbd_forest_out;
+
+int32_t dsbd_build_forest(int32_t n_prompts, int32_t n_roots, int32_t gamma, int32_t W_S,
+                          const int32_t* root_off,      /* [n_prompts+1] device: input beams of prompt p    */
+                          const int32_t* root_token,    /* [n_roots] device or NULL (roots then get token 0) */
+                          const int32_t* layer_parent,  /* [gamma,n_prompts*W_S] device                      */
+                          const int32_t* layer_token,   /* [gamma,n_prompts*W_S] device                      */
+                          const dsbd_forest_out* out, int32_t* fault, void* stream);
+
+/*
  * Measurement hook (no counterpart in the paper).  dsbd_timing_enable(kernel, capacity) makes the
  * library record a pair of HIP events around every launch of ONE of its kernels, on the stream the
  * kernel is launched on, for up to `capacity` launches; dsbd_timing_collect() waits for the recorded

@@ -38,6 +38,22 @@ class _KV(C.Structure):
                 ("token_stride", C.c_int64), ("head_stride", C.c_int64), ("max_len", C.c_int32)]
 
 
+class _DraftIn(C.Structure):
+    _fields_ = [("n_prompts", C.c_int32), ("n_beams", C.c_int32), ("max_prompt_beams", C.c_int32), ("V", C.c_int32),
+                ("beam_off", C.c_void_p), ("logits_draft", C.c_void_p), ("beam_logp_draft", C.c_void_p),
+                ("u", C.c_void_p)]
+
+
+class _DraftOut(C.Structure):
+    _fields_ = [("parent", C.c_void_p), ("token", C.c_void_p), ("logp_draft", C.c_void_p)]
+
+
+class _ForestOut(C.Structure):
+    _fields_ = [("tree_prompt", C.c_void_p), ("tree_off", C.c_void_p), ("parent", C.c_void_p), ("token", C.c_void_p),
+                ("draft_rank", C.c_void_p), ("node_of_root", C.c_void_p), ("node_of", C.c_void_p),
+                ("max_tree_nodes", C.c_void_p)]
+
+
 class _Params(C.Structure):
     _fields_ = [("W_L", C.c_int32), ("W_min", C.c_int32), ("W_cap", C.c_int32), ("t", C.c_float),
                 ("top_k", C.c_int32), ("top_p", C.c_float)]
@@ -97,6 +113,14 @@ def load_library():
     lib.dsbd_commit_kv.restype = C.c_int32
     lib.dsbd_commit_kv.argtypes = [C.POINTER(_Forest), C.POINTER(_KV), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                    C.POINTER(_NextBeams), C.c_int32, C.POINTER(_KVDst), C.c_void_p, C.c_void_p]
+    lib.dsbd_draft_layer_workspace_bytes.restype = C.c_size_t
+    lib.dsbd_draft_layer_workspace_bytes.argtypes = [C.POINTER(_DraftIn), C.c_int32, C.c_int32, C.c_float]
+    lib.dsbd_draft_layer.restype = C.c_int32
+    lib.dsbd_draft_layer.argtypes = [C.POINTER(_DraftIn), C.c_int32, C.c_int32, C.c_float, C.POINTER(_DraftOut),
+                                     C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.dsbd_build_forest.restype = C.c_int32
+    lib.dsbd_build_forest.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.POINTER(_ForestOut), C.c_void_p, C.c_void_p]
     lib.dsbd_timing_enable.restype = C.c_int32
     lib.dsbd_timing_enable.argtypes = [C.c_int32, C.c_int32]
     lib.dsbd_timing_collect.restype = C.c_int32
@@ -368,6 +392,67 @@ def dsbd_commit_kv(forest: Forest, src: PrefixKV, k_tree, v_tree, plan: NextBeam
 
 
 DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS, DSBD_KERNEL_KV_COMMIT = 1, 2, 3, 4
+
+
+def dsbd_draft_layer(beam_off, logits_draft, beam_logp_draft, u, W_S, *, max_prompt_beams, top_k=0, top_p=1.0,
+                     workspace=None, fault=None, stream=None):
+    """One beam-sampling step of the small model.  beam_off i32[P+1] (device), logits_draft f32[n_beams,V],
+    beam_logp_draft f64[n_beams], u f32[P,W_S].  Returns (parent i32[P,W_S] rows of the input, token i32[P,W_S],
+    logp f64[P,W_S], fault i32[1])."""
+    lib = load_library()
+    n_beams, V = logits_draft.shape
+    P = beam_off.numel() - 1
+    dev = logits_draft.device
+    assert beam_off.dtype == torch.int32 and logits_draft.dtype == torch.float32 and logits_draft.is_contiguous()
+    assert beam_logp_draft.dtype == torch.float64 and u.dtype == torch.float32 and u.is_contiguous()
+    assert u.numel() == P * W_S and beam_logp_draft.numel() == n_beams
+    din = _DraftIn(int(P), int(n_beams), int(max_prompt_beams), int(V), _ptr(beam_off), _ptr(logits_draft),
+                   _ptr(beam_logp_draft), _ptr(u))
+    parent = torch.empty((P, W_S), dtype=torch.int32, device=dev)
+    token = torch.empty((P, W_S), dtype=torch.int32, device=dev)
+    logp = torch.empty((P, W_S), dtype=torch.float64, device=dev)
+    dout = _DraftOut(_ptr(parent), _ptr(token), _ptr(logp))
+    if fault is None:
+        fault = torch.zeros(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        nbytes = int(lib.dsbd_draft_layer_workspace_bytes(C.byref(din), int(W_S), int(top_k), float(top_p)))
+        if nbytes == 0:
+            raise DsbdError(-2, "dsbd_draft_layer_workspace_bytes")
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    rc = lib.dsbd_draft_layer(C.byref(din), int(W_S), int(top_k), float(top_p), C.byref(dout), _ptr(workspace),
+                              workspace.numel(), _ptr(fault), _stream(stream))
+    _check(rc, "dsbd_draft_layer")
+    return parent, token, logp, fault
+
+
+def dsbd_build_forest(root_off, layer_parent, layer_token, root_token=None, *, n_roots, max_prompt_trees,
+                      fault=None, stream=None):
+    """Forest layout of gamma sampled layers.  root_off i32[P+1] (device), layer_parent / layer_token
+    i32[gamma, P*W_S] (device), root_token i32[n_roots] or None.  Returns (Forest, node_of_root i32[n_roots],
+    node_of i32[gamma, P*W_S], max_tree_nodes i32[1] (device), fault i32[1]); the Forest carries the bound of 64
+    nodes per tree, the device value says what the largest tree really holds."""
+    lib = load_library()
+    dev = root_off.device
+    P = root_off.numel() - 1
+    gamma = int(layer_parent.shape[0]) if layer_parent is not None and layer_parent.numel() > 0 else 0
+    W_S = int(layer_parent.shape[1]) // P if gamma else 0
+    N = int(n_roots) + gamma * P * W_S
+    i32 = lambda n: torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    tree_prompt, tree_off, parent, token, rank = i32(n_roots), i32(n_roots + 1), i32(N), i32(N), i32(N)
+    node_of_root, node_of, mx = i32(n_roots), i32(gamma * P * W_S), i32(1)
+    fo = _ForestOut(_ptr(tree_prompt), _ptr(tree_off), _ptr(parent), _ptr(token), _ptr(rank), _ptr(node_of_root),
+                    _ptr(node_of), _ptr(mx))
+    if fault is None:
+        fault = torch.zeros(1, dtype=torch.int32, device=dev)
+    for t_ in (root_off, layer_parent, layer_token, root_token):
+        assert t_ is None or (t_.dtype == torch.int32 and t_.is_contiguous())
+    rc = lib.dsbd_build_forest(int(P), int(n_roots), gamma, W_S, _ptr(root_off), _ptr(root_token),
+                               _ptr(layer_parent) if gamma else None, _ptr(layer_token) if gamma else None,
+                               C.byref(fo), _ptr(fault), _stream(stream))
+    _check(rc, "dsbd_build_forest")
+    f = Forest(tree_prompt[:n_roots], tree_off[:n_roots + 1], parent[:N], token[:N], rank[:N], n_prompts=P,
+               max_tree_nodes=64, max_depth=gamma, max_prompt_trees=int(max_prompt_trees), device=dev)
+    return f, node_of_root[:n_roots], node_of[:gamma * P * W_S].view(gamma, P * W_S) if gamma else node_of[:0], mx, fault
 
 
 def dsbd_timing_enable(kernel: int, capacity: int = 0):

@@ -19,7 +19,8 @@ def test_library_exports_every_declared_symbol():
     import paper_2409_16560_amd as dsbd
     lib = dsbd.load_library()
     names = header_functions()
-    assert {"dsbd_forest_attention", "dsbd_verify_forest", "dsbd_select_beams", "dsbd_commit_kv"} <= set(names)
+    assert {"dsbd_forest_attention", "dsbd_verify_forest", "dsbd_select_beams", "dsbd_commit_kv", "dsbd_draft_layer",
+            "dsbd_build_forest"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert "gfx950" in dsbd.dsbd_version()
@@ -31,7 +32,8 @@ def test_binding_structs_match_header_field_order():
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     for cname, cls in (("dsbd_forest", b._Forest), ("dsbd_kv", b._KV), ("dsbd_params", b._Params),
                        ("dsbd_verify_in", b._VerifyIn), ("dsbd_verify_out", b._VerifyOut),
-                       ("dsbd_next_beams", b._NextBeams), ("dsbd_kv_dst", b._KVDst)):
+                       ("dsbd_next_beams", b._NextBeams), ("dsbd_kv_dst", b._KVDst), ("dsbd_draft_in", b._DraftIn),
+                       ("dsbd_draft_out", b._DraftOut), ("dsbd_forest_out", b._ForestOut)):
         body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (cname, cname), src, flags=re.S).group(1)
         fields = []
         for decl in body.split(";"):
@@ -79,6 +81,17 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.dsbd_commit_kv(C.byref(f), C.byref(kv), None, None, 8, 128, C.byref(nb), 4, C.byref(kd), None, None) == -1
     assert lib.dsbd_commit_kv(C.byref(f), C.byref(kv), None, None, 8, 100, C.byref(nb), 4, C.byref(kd), C.c_void_p(8), None) == -2
     assert lib.dsbd_commit_kv(C.byref(f), C.byref(kv), None, None, 8, 128, C.byref(nb), 4, C.byref(kd), C.c_void_p(8), None) == -1
+    di = b._DraftIn(1, 2, 2, 100, None, None, None, None)
+    do = b._DraftOut(None, None, None)
+    assert lib.dsbd_draft_layer_workspace_bytes(C.byref(di), 4, 0, 1.0) > 0
+    assert lib.dsbd_draft_layer_workspace_bytes(C.byref(di), 65, 0, 1.0) == 0          # W_S above 64
+    assert lib.dsbd_draft_layer_workspace_bytes(C.byref(di), 4, 33, 1.0) == 0          # top_k above 32
+    assert lib.dsbd_draft_layer(C.byref(di), 4, 0, 1.0, C.byref(do), None, 0, C.c_void_p(8), None) == -1   # null arrays
+    assert lib.dsbd_draft_layer(C.byref(di), 0, 0, 1.0, C.byref(do), None, 0, C.c_void_p(8), None) == -2
+    fo = b._ForestOut(*([None] * 8))
+    assert lib.dsbd_build_forest(1, 2, 3, 4, None, None, None, None, C.byref(fo), C.c_void_p(8), None) == -1
+    assert lib.dsbd_build_forest(1, 2, 3, 65, None, None, None, None, C.byref(fo), C.c_void_p(8), None) == -2
+    assert lib.dsbd_build_forest(0, 0, 0, 0, None, None, None, None, C.byref(fo), C.c_void_p(8), None) == 0
 
 
 def test_workspace_sizes_scale_with_the_problem():

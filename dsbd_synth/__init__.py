@@ -7,3 +7,4 @@ oracle's tests and the HIP path's tests may import it.
 from .philox import philox4x32_10, uniform01_f32            # noqa: F401
 from .bf16 import f32_to_bf16_bits, bf16_bits_to_f32       # noqa: F401
 from .workloads import CONFIGS, make_workload, Workload    # noqa: F401
+from .models import SyntheticModels                        # noqa: F401

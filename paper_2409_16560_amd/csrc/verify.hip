@@ -501,6 +501,23 @@ __device__ __forceinline__ void wave_first(double& v, int& i) {
   }
 }
 
+// How a layer's joint over nI rows of V entries is cut among G workgroups (host and device use the same rule).
+struct SliceCut {
+  int rows_per_wg;       // > 0: every workgroup takes this many whole rows (nI >= G)
+  int wg_per_row;        // else: every row is cut into this many pieces of `len` entries (the last ones may be empty)
+  long long len;         // entries of the longest slice
+};
+__host__ __device__ inline SliceCut slice_cut(int nI, int V, int G) {
+  SliceCut c;
+  if (nI >= G) {
+    c.rows_per_wg = (nI + G - 1) / G; c.wg_per_row = 0; c.len = (long long)c.rows_per_wg * V;
+  } else {
+    c.rows_per_wg = 0; c.wg_per_row = G / nI;
+    c.len = (((long long)V + c.wg_per_row - 1) / c.wg_per_row + 1) & ~1LL;
+  }
+  return c;
+}
+
 template <bool WARP>
 __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   __shared__ LayerShared sh;
@@ -655,10 +672,22 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     stamp(10 + l);
     const bool bonus = (l == gamma + 1);
     const long long total = (long long)nI * V;           // elements of I x V
-    long long ch = (total + a.G - 1) / a.G;
-    ch = (ch + 1) & ~1LL;
-    const long long e_lo = min(total, (long long)g * ch);
-    const long long e_hi = min(total, e_lo + ch);
+    // I x V is cut along the rows: with fewer rows than workgroups every row is cut into the same pieces (the
+    // workgroups left over idle for the layer), otherwise every workgroup takes whole rows.  Either way a row's
+    // sum is formed in an order that depends on the row's length only, so beams with equal logits and equal
+    // likelihoods (duplicates are common in beam sampling) get bitwise equal joint entries, and the order of
+    // equal entries (by index) is the same as in a plain row-by-row evaluation.
+    const SliceCut cut = slice_cut(nI, V, a.G);
+    const long long ch = cut.len;            // the longest slice of the layer
+    long long e_lo = total, e_hi = total;
+    if (cut.rows_per_wg > 0) {
+      e_lo = min(total, (long long)g * cut.rows_per_wg * V);
+      e_hi = min(total, e_lo + (long long)cut.rows_per_wg * V);
+    } else if (g / cut.wg_per_row < nI) {
+      const long long r0 = (long long)(g / cut.wg_per_row) * V, k = g % cut.wg_per_row;
+      e_lo = r0 + min((long long)V, k * cut.len);
+      e_hi = r0 + min((long long)V, (k + 1) * cut.len);
+    }
     const long long len = e_hi - e_lo;
     const int i_lo = (int)div_floor(e_lo, V);
     const int i_hi = e_hi > e_lo ? (int)div_floor(e_hi - 1, V) : i_lo - 1;
@@ -716,8 +745,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
     stamp(100);
     __syncthreads();
-    // ===== all-reduce of the 2|I| row sums.  Row i is spread over the workgroups floor(iV/ch) ..
-    // floor(((i+1)V-1)/ch): only those post its two columns and only those are polled.
+    // ===== all-reduce of the 2|I| row sums.  Only the workgroups that hold a piece of row i post its two
+    // columns and only those are polled.
     epoch += 1;
     const unsigned long long rs_tag = exchange_tag(epoch);
     Slot* const rs_bank = slots + a.sl.r + (long long)(l - 1) * a.sl.r_stride;
@@ -787,8 +816,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       bool mine = true;
       if (c < ncols && r < R) {
         const int i = c >> 1;
-        const int w_lo = (int)div_floor((long long)i * V, ch);
-        const int w_hi = (int)div_floor((long long)(i + 1) * V - 1, ch);
+        const int w_lo = cut.rows_per_wg > 0 ? i / cut.rows_per_wg : i * cut.wg_per_row;
+        const int w_hi = cut.rows_per_wg > 0 ? w_lo : w_lo + (int)((V + cut.len - 1) / cut.len) - 1;
         for (int w = w_lo + r; w <= w_hi; w += R) {
           double v = 0.0;
           mine = mine && slot_wait(rs_bank + (long long)w * a.sl.r_w + c, rs_tag, v, a.sync_limit);
@@ -1816,7 +1845,11 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
     sl.prompt_stride = off;
   }
   // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most VL_DYN_LDS_BYTES for the two arrays
-  long long need = (joint + G - 1) / G;
+  long long need = 2;                        // the longest slice any number of input rows can give
+  for (int nI = 1; nI <= pl.I_cap; ++nI) {
+    const long long len = slice_cut(nI, V, G).len;
+    if (len > need) need = len;
+  }
   need = (need + 1) & ~1LL;
   pl.slice_cap = need;
   pl.lds_elems = (int)(need < cap ? need : cap);

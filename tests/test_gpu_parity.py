@@ -205,6 +205,29 @@ def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, monkeypatch):
         gu.compare_verify(res, ref, w)
 
 
+def test_duplicate_beams_tie_exactly_as_in_a_row_by_row_evaluation():
+    """Beam sampling often returns the same beam twice.  Two input beams with equal logits and equal likelihoods
+    have equal joint entries; which of two equal entries the top-k / top-p cut keeps is decided by the index on
+    both sides, which needs the library to form equal rows' sums in the same order."""
+    import dataclasses
+    gu = _gu()
+    for cfg, kw in (("c3", dict(V=5000, draft_top_k=4)), ("c5", dict(V=9000, draft_top_k=3))):
+        w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
+        zp, zq, bp, bq = w.logits_p.copy(), w.logits_q.copy(), w.beam_logp_p.copy(), w.beam_logp_q.copy()
+        n = w.max_tree_nodes                              # all trees have the same shape in these configurations
+        for src, dst in ((0, 2), (0, 5), (1, 3)):
+            zp[dst * n:(dst + 1) * n], zq[dst * n:(dst + 1) * n] = zp[src * n:(src + 1) * n], zq[src * n:(src + 1) * n]
+            bp[dst], bq[dst] = bp[src], bq[src]
+        w = dataclasses.replace(w, logits_p=zp, logits_q=zq, beam_logp_p=bp, beam_logp_q=bq)
+        d = gu.DeviceWorkload(w)
+        for top_k, top_p, t in ((16, 0.8, -1.0), (10, 0.8, 0.6), (7, 1.0, -1.0), (0, 1.0, -1.0)):
+            print("case", cfg, "top_k", top_k, "top_p", top_p, "t", t, flush=True)
+            res = d.verify(t=t, top_k=top_k, top_p=top_p)
+            torch.cuda.synchronize()
+            ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+            gu.compare_verify(res, ref, w)
+
+
 def test_warping_switched_off_is_the_plain_path():
     gu = _gu()
     w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=5000)

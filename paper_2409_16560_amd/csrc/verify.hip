@@ -907,8 +907,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           const double v = has ? va[t] : 0.0;
           const int ix = has ? ia[t] : 0;
           int rank = 0;
-          if (has)
-            for (int c = part; c < na; c += 8) rank += cand_before(va[c], ia[c], v, ix) ? 1 : 0;
+          if (has) {
+            int c = part;
+            for (; c + 24 < na; c += 32) {     // four candidates per round, their loads in flight together
+              double o[4];
+              int oi4[4];
+#pragma unroll
+              for (int k = 0; k < 4; ++k) { o[k] = va[c + 8 * k]; oi4[k] = ia[c + 8 * k]; }
+#pragma unroll
+              for (int k = 0; k < 4; ++k) rank += cand_before(o[k], oi4[k], v, ix) ? 1 : 0;
+            }
+            for (; c < na; c += 8) rank += cand_before(va[c], ia[c], v, ix) ? 1 : 0;
+          }
           rank += __shfl_xor(rank, 1);
           rank += __shfl_xor(rank, 2);
           rank += __shfl_xor(rank, 4);
@@ -1049,69 +1059,69 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         }
         if (!okc) give_up();
       };
-      // The K first of n_src collected lists, each in rank order: a tree of four-way merges.  In a merge an
-      // entry's rank is its own rank plus the numbers of entries of the three partner lists ahead of it (binary
-      // searches, side by side); ranks K and beyond drop out.  The lists alternate between the dynamic LDS and
-      // the candidate arrays; the last merge writes lv / li.  Ends after a barrier.
-      auto merge_lists = [&](int n_src) {
-        int n = n_src;
-        bool in_g = true;
-        while (true) {
-          const int n4 = (n + 3) >> 2;
-          const bool last = n4 == 1;
-          lds_f64* const sv0 = in_g ? gv : cvp;
-          lds_f64* const sv1 = in_g ? gv + WARP_CAND : cvq;
-          lds_i32* const si0 = in_g ? gi : cip;
-          lds_i32* const si1 = in_g ? gi + WARP_CAND : ciq;
-          lds_f64* const dv0 = last ? lv : (in_g ? cvp : gv);
-          lds_f64* const dv1 = last ? lv + K : (in_g ? cvq : gv + WARP_CAND);
-          lds_i32* const di0 = last ? li : (in_g ? cip : gi);
-          lds_i32* const di1 = last ? li + K : (in_g ? ciq : gi + WARP_CAND);
-          for (int t = tid; t < 2 * n4 * K; t += VL_BLOCK) {
-            const int m = t >= n4 * K ? 1 : 0, e = t - m * n4 * K;
-            (m ? dv1 : dv0)[e] = -1.0;
-            (m ? di1 : di0)[e] = INT_MAX;
+      // The K first of n_src <= 16 collected lists, each in rank order: one or two levels of four-way merges.  In
+      // a merge an entry's rank is its own rank plus the numbers of entries of the three partner lists ahead of
+      // it (binary searches, side by side, branch-free); ranks K and beyond drop out.
+      auto merge_pass = [&](lds_f64* sv0, lds_i32* si0, lds_f64* sv1, lds_i32* si1, int n,
+                            lds_f64* dv0, lds_i32* di0, lds_f64* dv1, lds_i32* di1) {
+        for (int t = tid; t < 2 * n * K; t += VL_BLOCK) {
+          const int m = t >= n * K ? 1 : 0, e = t - m * n * K;
+          const int src = e / K, r = e - src * K;
+          lds_f64* const sv = m ? sv1 : sv0;
+          lds_i32* const si = m ? si1 : si0;
+          const double v = sv[e];
+          const int ix = si[e];
+          // entries of a partner list ahead of this one: the longest leading part of which all are (steps 32,
+          // 16, .. 1; a partner that does not exist has length 0 and is read at this entry's own list)
+          int po[3], len_j[3], cnt[3];
+#pragma unroll
+          for (int j = 0; j < 3; ++j) {
+            const int o = (src & ~3) + ((src + 1 + j) & 3);
+            po[j] = (o < n ? o : src) * K; len_j[j] = o < n ? K : 0; cnt[j] = 0;
           }
-          __syncthreads();
-          for (int t = tid; t < 2 * n * K; t += VL_BLOCK) {
-            const int m = t >= n * K ? 1 : 0, e = t - m * n * K;
-            const int src = e / K, r = e - src * K;
-            lds_f64* const sv = m ? sv1 : sv0;
-            lds_i32* const si = m ? si1 : si0;
-            const double v = sv[e];
-            const int ix = si[e];
-            // entries of a partner list ahead of this one: the longest leading part of which all are (branch-free:
-            // steps 32, 16, .. 1; a partner that does not exist has length 0 and is read at this entry's own list)
-            int po[3], len_j[3], cnt[3];
+#pragma unroll
+          for (int step = 32; step >= 1; step >>= 1) {
+            if (step > K) continue;          // uniform: short lists need fewer halvings
+            double pv3[3];
+            int pi3[3];
 #pragma unroll
             for (int j = 0; j < 3; ++j) {
-              const int o = (src & ~3) + ((src + 1 + j) & 3);
-              po[j] = (o < n ? o : src) * K; len_j[j] = o < n ? K : 0; cnt[j] = 0;
+              const int at = min(cnt[j] + step - 1, K - 1);
+              pv3[j] = sv[po[j] + at]; pi3[j] = si[po[j] + at];
             }
 #pragma unroll
-            for (int step = 32; step >= 1; step >>= 1) {
-              double pv3[3];
-              int pi3[3];
-#pragma unroll
-              for (int j = 0; j < 3; ++j) {
-                const int at = min(cnt[j] + step - 1, K - 1);
-                pv3[j] = sv[po[j] + at]; pi3[j] = si[po[j] + at];
-              }
-#pragma unroll
-              for (int j = 0; j < 3; ++j)
-                cnt[j] += ((cnt[j] + step - 1 < len_j[j]) & cand_before(pv3[j], pi3[j], v, ix)) ? step : 0;
-            }
-            const int rank = r + cnt[0] + cnt[1] + cnt[2];
-            if (rank < K && ix != INT_MAX) {
-              (m ? dv1 : dv0)[(src >> 2) * K + rank] = v;
-              (m ? di1 : di0)[(src >> 2) * K + rank] = ix;
-            }
+            for (int j = 0; j < 3; ++j)
+              cnt[j] += ((cnt[j] + step - 1 < len_j[j]) & cand_before(pv3[j], pi3[j], v, ix)) ? step : 0;
           }
-          __syncthreads();
-          if (last) break;
-          n = n4;
-          in_g = !in_g;
+          const int rank = r + cnt[0] + cnt[1] + cnt[2];
+          if (rank < K && ix != INT_MAX) {
+            (m ? dv1 : dv0)[(src >> 2) * K + rank] = v;
+            (m ? di1 : di0)[(src >> 2) * K + rank] = ix;
+          }
         }
+      };
+      auto fill_none = [&](lds_f64* v0, lds_i32* i0, lds_f64* v1, lds_i32* i1, int cnt) {
+        for (int t = tid; t < 2 * cnt; t += VL_BLOCK) {
+          const int m = t >= cnt ? 1 : 0, e = t - m * cnt;
+          (m ? v1 : v0)[e] = -1.0;
+          (m ? i1 : i0)[e] = INT_MAX;
+        }
+      };
+      // gv / gi -> lv / li.  The candidate arrays (first 4K entries per model) must hold "none" on entry: the
+      // caller fills them before it collects, so that the barrier after the collection covers both.
+      auto merge_lists = [&](int n) {
+        if (n <= 4) {
+          fill_none(lv, li, lv + K, li + K, K);
+          __syncthreads();
+          merge_pass(gv, gi, gv + WARP_CAND, gi + WARP_CAND, n, lv, li, lv + K, li + K);
+          __syncthreads();
+          return;
+        }
+        merge_pass(gv, gi, gv + WARP_CAND, gi + WARP_CAND, n, cvp, cip, cvq, ciq);
+        fill_none(lv, li, lv + K, li + K, K);
+        __syncthreads();
+        merge_pass(cvp, cip, cvq, ciq, (n + 3) >> 2, lv, li, lv + K, li + K);
+        __syncthreads();
       };
       unsigned long long tag_d = 0;
       if (a.G > 1) {
@@ -1123,6 +1133,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         epoch += 3;
         post_list(slots + a.sl.b + (long long)g * a.sl.b_w, tag_b);
         if (g == first) {                    // the group's first workgroup merges the group's lists
+          fill_none(cvp, cip, cvq, ciq, 4 * K);
           collect_lists(slots + a.sl.b + (long long)first * a.sl.b_w, tag_b, n_mem);
           __syncthreads();
           stamp(62);
@@ -1132,6 +1143,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           if (n_groups > 1) post_list(slots + a.sl.c + (long long)(g / WARP_GROUP) * a.sl.b_w, tag_c);
         }
         if (g == 0 && n_groups > 1) {        // the prompt's first workgroup merges the groups' lists
+          fill_none(cvp, cip, cvq, ciq, 4 * K);
           collect_lists(slots + a.sl.c, tag_c, n_groups);
           __syncthreads();
           stamp(64);
@@ -1178,11 +1190,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           const double other = (both && !is_q) ? w_partner : 0.0;
           const bool valid = kept && !(is_q && both);
           int rank = 0;
-#pragma unroll
-          for (int c = 0; c < 64; ++c) {
-            const int oidx = __builtin_amdgcn_readlane(ix, c);
-            const int oval = __builtin_amdgcn_readlane((int)valid, c);
-            rank += (oval && oidx < ix) ? 1 : 0;
+          for (int c = 0; c < K; ++c) {      // the lists' lanes: c (p_beam) and 32 + c (q_beam)
+            const int ip_c = __builtin_amdgcn_readlane(ix, c), iq_c = __builtin_amdgcn_readlane(ix, 32 + c);
+            const int vp_c = __builtin_amdgcn_readlane((int)valid, c), vq_c = __builtin_amdgcn_readlane((int)valid, 32 + c);
+            rank += ((vp_c && ip_c < ix) ? 1 : 0) + ((vq_c && iq_c < ix) ? 1 : 0);
           }
           if (valid) { sh.U_idx[rank] = ix; sh.U_p[rank] = is_q ? 0.0 : w; sh.U_q[rank] = is_q ? w : other; }
           const unsigned long long vm = __ballot(valid);

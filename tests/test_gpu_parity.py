@@ -239,6 +239,50 @@ def test_warping_switched_off_is_the_plain_path():
         assert torch.equal(getattr(a, name), getattr(b, name)), name
 
 
+@pytest.mark.parametrize("name,kw,W_cap,top_k", [
+    ("64 beams of 8 nodes: 512 nodes in one prompt", dict(W=64, tree="binary_bfs", tree_nodes=8, V=700), 64, 0),
+    ("64 beams, warped", dict(W=64, tree="fork_chain", tree_nodes=7, V=700, draft_top_k=3), 64, 32),
+    ("one chain of 64 nodes: 63 draft layers", dict(W=1, tree="chain", tree_nodes=64, V=300, noise_std=0.05), 16, 0),
+    ("one 64-node tree, warped", dict(W=2, tree="random", tree_nodes=64, V=300, draft_top_k=2), 16, 4),
+])
+def test_verify_at_the_size_limits(name, kw, W_cap, top_k):
+    gu = _gu()
+    w = make_workload("c3", W_cap=W_cap, L=1, Hq=1, Hkv=1, D=64, **kw)
+    print(name, "nodes", w.n_nodes, "depth", w.max_depth, flush=True)
+    d = gu.DeviceWorkload(w)
+    for t in (-1.0, 0.5):
+        res = d.verify(t=t, top_k=top_k, top_p=0.9 if top_k else 1.0)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=0.9 if top_k else 1.0)
+        gu.compare_verify(res, ref, w)
+        print("  t", t, "l_last", ref["l_last"].tolist(), "widths", ref["layer_width"][0][:8].tolist(), flush=True)
+
+
+def test_a_prompt_without_beams_between_two_others():
+    """tree_prompt may skip a prompt: it gets no output beams, its neighbours are verified as usual."""
+    import dataclasses
+    gu = _gu()
+    w = make_workload("c4", L=1, Hq=1, Hkv=1, D=64, V=900, n_prompts=2, seed=4)
+    tp = w.tree_prompt.copy()
+    tp[tp == 1] = 2                                   # prompts 0 and 2 keep their trees, prompt 1 has none
+    u_res = np.concatenate([w.u_resid[:1], w.u_resid[:1], w.u_resid[1:]])
+    u_fill = np.concatenate([w.u_fill[:1], w.u_fill[:1], w.u_fill[1:]])
+    w3 = dataclasses.replace(w, tree_prompt=tp, n_prompts=3, u_resid=u_res, u_fill=u_fill,
+                             k_shared=[w.k_shared[0], None, w.k_shared[1]], v_shared=[w.v_shared[0], None, w.v_shared[1]])
+    d = gu.DeviceWorkload(w3)
+    res = d.verify(t=0.7)
+    torch.cuda.synchronize()
+    ref2 = gu.oracle_verify(w, t=0.7)                 # the two real prompts, numbered 0 and 1
+    g = lambda x: x.cpu().numpy()
+    assert int(res.fault.item()) == 0
+    assert g(res.n_out).tolist() == [int(ref2["n_out"][0]), 0, int(ref2["n_out"][1])]
+    assert np.array_equal(g(res.node_status), ref2["node_status"])
+    for name, key in (("out_parent", "out_parent"), ("out_token", "out_token"), ("l_last", "l_last")):
+        got = g(getattr(res, name))
+        assert np.array_equal(got[0], ref2[key][0]) and np.array_equal(got[2], ref2[key][1]), name
+    assert np.all(g(res.out_parent)[1] == -1) and g(res.l_last)[1] == 0
+
+
 def test_verify_with_draft_rank_order():
     gu = _gu()
     w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=3000)

@@ -173,6 +173,13 @@ size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, 
  * p' <- norm(max(0, p' - q_beam)) on rejection and p' <- p_beam on acceptance, early stop at
  * W_L^(l) accepted beams, residual + p_beam sampling when a layer falls short, and the bonus
  * layer when every layer passes.  Decisions are taken in fp64.
+ *   - Limits: at most 64 input beams, 512 forest nodes and W_cap <= 64 per prompt; n_prompts times the workgroups
+ *     per prompt must fit the device at once (at most one workgroup per compute unit and prompt: UNSUPPORTED beyond).
+ *   - The layer kernel's workgroups wait for each other, so it needs the device to itself while it runs: work that
+ *     another stream keeps resident at the same time (a second verification in particular) can keep some of its
+ *     workgroups from starting; every wait is bounded (3 s by default) and ends in DSBD_FAULT_SYNC_TIMEOUT with
+ *     unusable outputs, never in a hang.  Calls on one stream are safe.
+ *   - The workspace must not be shared by calls that may overlap.
  */
 int32_t dsbd_verify_forest(const dsbd_forest* forest, const dsbd_verify_in* in, const dsbd_params* params,
                            const dsbd_verify_out* out,

@@ -198,8 +198,10 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
 // Where the exchanges of one prompt keep their 16-byte slots (offsets in slots from the prompt's first one).
 struct SlotLayout {
   int x[2];              // the two alternating banks of the post-then-collect-from-all exchanges: G lines
+  int xc[2];             // ... and of the group sums of their two-hop form: SUM_GROUPS lines
   int r, r_w, r_stride;  // row sums of layer l: r + (l - 1) * r_stride, r_w slots per workgroup
   int s, s_stride;       // early chain entry of layer l: s + (l - 1) * s_stride, a line per workgroup
+  int sc, sc_stride;     // its group sums: sc + (l - 1) * sc_stride, SUM_GROUPS lines
   int b, b_w;            // warping: every workgroup's candidate list, b_w slots each
   int c;                 // warping: the groups' merged lists (b_w slots each)
   int d;                 // warping: the final entries, posted by the prompt's first workgroup
@@ -472,6 +474,42 @@ __device__ __forceinline__ bool wave_collect4(Slot* bank, int G, int g, double o
     else if ((spin & 15) == 0 && wall_clock64() - t0 > limit) return false;
     __builtin_amdgcn_s_sleep(1);
   }
+}
+
+// Sum over the prompt's G workgroups of one value each, for the first wave of every workgroup; the value is already
+// posted (or being posted) in the workgroup's line of `bank`.  With more than SUM_GROUP workgroups the sum takes two
+// hops: the first workgroup of every group of SUM_GROUP adds up its group's values and posts the group sum in
+// `gbank`, and everybody adds up the at most SUM_GROUPS group sums.  Each workgroup then polls 16 + 16 lines instead
+// of 256, and all of them add the same numbers in the same order.  False if a wait gave up.
+#define SUM_GROUP 16
+#define SUM_GROUPS 16
+__device__ __forceinline__ bool wave_sum_groups(Slot* bank, Slot* gbank, int G, int g, double own,
+                                                unsigned long long tag, long long limit, double& total) {
+  const int lane = threadIdx.x & 63;
+  if (G <= SUM_GROUP) {
+    double v[4];
+    const bool ok = wave_collect4(bank, G, g, own, tag, v, limit);
+    total = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+    return ok;
+  }
+  bool ok = true;
+  const int first = g - g % SUM_GROUP, n_groups = (G + SUM_GROUP - 1) / SUM_GROUP;
+  double gs_own = 0.0;
+  if (g == first) {
+    const int n_mem = min(SUM_GROUP, G - first);
+    double v = 0.0;
+    if (lane == 0) v = own;
+    else if (lane < n_mem) ok = slot_wait(bank + (long long)(first + lane) * LINE_SLOTS, tag, v, limit);
+    gs_own = wave_sum(v);
+    if (lane == 0) slot_post(gbank + (long long)(g / SUM_GROUP) * LINE_SLOTS, gs_own, tag);
+  }
+  double c = 0.0;
+  if (lane < n_groups) {
+    if (g == first && lane == g / SUM_GROUP) c = gs_own;          // the workgroup's own group sum needs no round trip
+    else ok = slot_wait(gbank + (long long)lane * LINE_SLOTS, tag, c, limit) && ok;
+  }
+  total = wave_sum(c);
+  return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
 }
 
 __device__ __forceinline__ Slot* prompt_slots(const LayersArgs& a, int prompt) {
@@ -1254,6 +1292,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // sums are posted ahead of time and collected only when it is asked for.
     bool spec = false;
     Slot* spec_bank = nullptr;
+    Slot* spec_gbank = nullptr;
     unsigned long long spec_tag = 0;
     double spec_own = 0.0;
     stamp(26);
@@ -1263,6 +1302,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       epoch += 1;
       spec_tag = exchange_tag(epoch);
       spec_bank = slots + a.sl.s + (long long)(l - 1) * a.sl.s_stride;
+      spec_gbank = slots + a.sl.sc + (long long)(l - 1) * a.sl.sc_stride;
       if (tid == 0) dense_post(spec_bank, a.G, g, tot, spec_tag);
       spec_own = tot;
       spec = true;
@@ -1552,9 +1592,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     auto extend_chain = [&](bool then_decide) -> bool {
       if (spec) {                      // entry 2 is already on its way
         if (wave == 0) {
-          double v[4];
-          if (!wave_collect4(spec_bank, a.G, g, spec_own, spec_tag, v, a.sync_limit)) give_up();
-          const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+          double F;
+          if (!wave_sum_groups(spec_bank, spec_gbank, a.G, g, spec_own, spec_tag, a.sync_limit, F)) give_up();
           if (lane == 0) { sh.cc[2] = 1.0; sh.FF[2] = F; sh.kmax = 2; }
           if (then_decide) decide(decide_round, 2);
         }
@@ -1576,14 +1615,13 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         }
         epoch += 1;
         const unsigned long long tag = exchange_tag(epoch);
-        Slot* bank = slots + a.sl.x[xchg++ & 1];
+        Slot* bank = slots + a.sl.x[xchg & 1];
+        Slot* gbank = slots + a.sl.xc[xchg++ & 1];
         if (wave == 0) {
           if (lane == 0) dense_post(bank, a.G, g, tot, tag);
-          double v[4];
-          if (!wave_collect4(bank, a.G, g, tot, tag, v, a.sync_limit)) give_up();
+          double F;
+          if (!wave_sum_groups(bank, gbank, a.G, g, tot, tag, a.sync_limit, F)) give_up();
           stamp(45);
-          const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
-          stamp(46);
           if (lane == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1; }
           if (then_decide) decide(decide_round, k + 1);
         }
@@ -1654,6 +1692,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     {
       bool posted = spec;              // the next entry's partial sums are on their way: F(1), from the scaling pass
       Slot* x_bank = spec_bank;
+      Slot* x_gbank = spec_gbank;
       unsigned long long x_tag = spec_tag;
       double x_own = spec_own;
       while (true) {
@@ -1676,14 +1715,14 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (!posted) {
           epoch += 1;
           x_tag = exchange_tag(epoch);
-          x_bank = slots + a.sl.x[xchg++ & 1];
+          x_bank = slots + a.sl.x[xchg & 1];
+          x_gbank = slots + a.sl.xc[xchg++ & 1];
           if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
           x_own = tot;
         }
         if (wave == 0) {
-          double v[4];
-          if (!wave_collect4(x_bank, a.G, g, x_own, x_tag, v, a.sync_limit)) give_up();
-          const double F = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+          double F;
+          if (!wave_sum_groups(x_bank, x_gbank, a.G, g, x_own, x_tag, a.sync_limit, F)) give_up();
           if (lane == 0) { sh.cc[k + 1] = c_next; sh.FF[k + 1] = F; sh.kmax = k + 1; }
         }
         posted = false;
@@ -1843,9 +1882,12 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
     int off = 0;
     sl.x[0] = off; off += G * LINE_SLOTS;
     sl.x[1] = off; off += G * LINE_SLOTS;
+    sl.xc[0] = off; off += SUM_GROUPS * LINE_SLOTS;
+    sl.xc[1] = off; off += SUM_GROUPS * LINE_SLOTS;
     sl.r_w = up8(2 * pl.I_cap);
     sl.r = off; sl.r_stride = G * sl.r_w; off += layers * sl.r_stride;
     sl.s = off; sl.s_stride = G * LINE_SLOTS; off += layers * sl.s_stride;
+    sl.sc = off; sl.sc_stride = SUM_GROUPS * LINE_SLOTS; off += layers * sl.sc_stride;
     sl.b = sl.c = sl.d = off; sl.b_w = 0;
     if (p->top_k > 0) {
       sl.b_w = up8(4 * p->top_k);

@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--t", type=float, default=-1.0, help="threshold of the dynamic width; < 0 = fixed width")
     ap.add_argument("--kernel", default="attention", choices=["attention", "vocab_stats", "verify_layers"],
                     help="kernel whose duration is measured with HIP events for the roofline")
+    ap.add_argument("--shared-len", type=int, default=None,
+                    help="control run: leading prefix tokens shared by the beams of a prompt (the caches then serve most K/V)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-commit", action="store_true", help="skip the (separately reported) cache-commit measurement")
     ap.add_argument("--no-warp", action="store_true", help="skip the (separately reported) warped verification")
@@ -124,7 +126,7 @@ def main():
     import gpu_util as gu
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = make_workload(args.config)
+    w = make_workload(args.config) if args.shared_len is None else make_workload(args.config, shared_len=args.shared_len)
     attn_bytes, verify_bytes = algorithmic_bytes(w, share_prefix=True)
     sets = [gu.DeviceWorkload(w)]
     for _ in range(args.copies - 1):
@@ -195,7 +197,8 @@ def main():
         "config": {"workload": "%s: %d beams, %d forest nodes, prefix %d, Hq/Hkv %d/%d, D %d, V %d, %s width"
                                % (args.config, w.n_trees, w.n_nodes, int(w.own_len.max() + w.shared_len.max()),
                                   w.Hq, w.Hkv, w.D, w.V, "fixed" if args.t < 0 else "dynamic t=%g" % args.t),
-                   "input_copies_rotated": len(sets)},
+                   "input_copies_rotated": len(sets),
+                   **({} if args.shared_len is None else {"control_shared_prefix_tokens": args.shared_len})},
         "roofline": {"bound": "hbm", "kernel": args.kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_C5.get(args.kernel) if args.config == "c5" else None,

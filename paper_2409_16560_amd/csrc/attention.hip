@@ -26,6 +26,8 @@
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
 
 #define NEG_BIG (-1.0e30f)
 #define REF_SLACK 40.0f          // log2 headroom of the softmax reference before it is raised
@@ -450,8 +452,9 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------------------
 // Variant for many query rows per K/V stream (large trees and/or grouped-query attention): the RW
 // waves of a workgroup each keep 32 query rows (two 16-row tiles) and ALL consume the same 64-token
-// K/V tile, which is staged once through LDS: K row-major (padded rows, read back as MFMA A operands
-// with 16-byte reads), V transposed with token pairs packed.  Tiles are double-buffered: while tile t
+// K/V tile, which is staged once through LDS, both row-major with padded rows: K is read back as MFMA A operands
+// with 16-byte reads, V through the transposing LDS read of gfx950 (ds_read_b64_tr_b16), which hands a lane four
+// tokens of one channel.  Tiles are double-buffered: while tile t
 // is consumed from one buffer, tile t+1 sits in registers on its way to the other buffer and tile t+2
 // is in flight from HBM; one workgroup barrier per tile.  Two workgroups fit a CU (<= 256 registers,
 // < 80 KiB LDS), so one can compute while the other waits on memory.  The V^T tile is written with a
@@ -464,21 +467,16 @@ void forest_attention_shared_kernel(AttnArgs a) {
   constexpr int DS = D / 32, DT = D / 16;
   constexpr int CG = D / 8;                 // 16-byte channel groups per row
   constexpr int KP = D + 8;                 // K row pitch in elements (16 bytes of padding)
-#ifndef DSBD_VT_PAD
-#define DSBD_VT_PAD 4
-#define DSBD_VT_SWZ 2
-#endif
-  constexpr int VP = TILE + DSBD_VT_PAD;    // V^T row pitch in elements
   constexpr int KL = TILE * CG / NT;        // K 16-byte loads per thread and tile
   constexpr int VI = (TILE / 2) * CG / NT;  // V (token pair, channel group) items per thread and tile
   constexpr int ROWS_W = 16 * NRT, ROWS_B = ROWS_W * RW;
 
   constexpr int OP = D + 4;                 // row pitch (floats) of the output staging tile
-  constexpr int TILE_BYTES = 2 * (TILE * KP + D * VP) * 2;
+  constexpr int TILE_BYTES = 2 * (TILE * KP + TILE * KP) * 2;
   constexpr int OUT_BYTES = ROWS_B * OP * 4;
   __shared__ __attribute__((aligned(16))) char smem[TILE_BYTES > OUT_BYTES ? TILE_BYTES : OUT_BYTES];
   __bf16 (*k_lds)[TILE * KP] = reinterpret_cast<__bf16 (*)[TILE * KP]>(smem);
-  __bf16 (*v_lds)[D * VP] = reinterpret_cast<__bf16 (*)[D * VP]>(smem + 2 * TILE * KP * 2);
+  __bf16 (*v_lds)[TILE * KP] = reinterpret_cast<__bf16 (*)[TILE * KP]>(smem + 2 * TILE * KP * 2);
   float* o_stage = reinterpret_cast<float*>(smem);   // reused after the last tile
 
   const int tid = threadIdx.x;
@@ -613,17 +611,10 @@ void forest_attention_shared_kernel(AttnArgs a) {
 #pragma unroll
     for (int r = 0; r < VI; ++r) {
       const int it = r * NT + tid;
-      const int cg = it % CG;
-      const int tp = (it / CG) ^ (DSBD_VT_SWZ * (cg >> 1));   // token-pair swizzle: the 64 lanes of a write hit 64 banks
-      const uint32_t ta[4] = {vreg[r][0].x, vreg[r][0].y, vreg[r][0].z, vreg[r][0].w};
-      const uint32_t tb[4] = {vreg[r][1].x, vreg[r][1].y, vreg[r][1].z, vreg[r][1].w};
+      const int cg = it % CG, tp = it / CG;
 #pragma unroll
-      for (int c2 = 0; c2 < 4; ++c2) {
-        const uint32_t lo = __builtin_amdgcn_perm(tb[c2], ta[c2], 0x05040100u);
-        const uint32_t hi = __builtin_amdgcn_perm(tb[c2], ta[c2], 0x07060302u);
-        *reinterpret_cast<uint32_t*>(&vl[(8 * cg + 2 * c2) * VP + 2 * tp]) = lo;
-        *reinterpret_cast<uint32_t*>(&vl[(8 * cg + 2 * c2 + 1) * VP + 2 * tp]) = hi;
-      }
+      for (int h = 0; h < 2; ++h)
+        *reinterpret_cast<uint4*>(&vl[(2 * tp + h) * KP + cg * 8]) = vreg[r][h];
     }
   };
 
@@ -743,11 +734,14 @@ void forest_attention_shared_kernel(AttnArgs a) {
       // ---- O^T += V^T P^T for this half
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        // rows 16dt .. 16dt+15 belong to channel groups 2dt, 2dt+1: token pairs are swizzled by 4*dt
-        union { uint2 u[2]; bf16x8 v; } vf;
-        const __bf16* rowp = &vl[(16 * dt + col) * VP];
-        vf.u[0] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 2 * qd) ^ (DSBD_VT_SWZ * dt)));
-        vf.u[1] = *reinterpret_cast<const uint2*>(rowp + 2 * ((16 * ks + 8 + 2 * qd) ^ (DSBD_VT_SWZ * dt)));
+        // A operand = V^T: lane (channel 16dt + col, qd) needs tokens 4qd .. 4qd+3 of both 16-token blocks of the
+        // half, the order the numerators have in pf.  A transposing read returns, to lane i of a group of 16, the
+        // element i % 4 of the four lanes i / 4, 4 + i / 4, ...: so lane i points at token 4qd + i / 4, channels
+        // 16dt + 4 (i % 4) .. + 3, and receives channel 16dt + i of tokens 4qd .. 4qd+3.
+        union { v4i16 h[2]; bf16x8 v; } vf;
+        const __bf16* rowp = &vl[(32 * ks + 4 * qd + (col >> 2)) * KP + 16 * dt + 4 * (col & 3)];
+        vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(rowp));
+        vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(rowp + 16 * KP));
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
           o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);

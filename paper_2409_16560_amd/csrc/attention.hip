@@ -468,7 +468,6 @@ void forest_attention_shared_kernel(AttnArgs a) {
   constexpr int CG = D / 8;                 // 16-byte channel groups per row
   constexpr int KP = D + 8;                 // K row pitch in elements (16 bytes of padding)
   constexpr int KL = TILE * CG / NT;        // K 16-byte loads per thread and tile
-  constexpr int VI = (TILE / 2) * CG / NT;  // V (token pair, channel group) items per thread and tile
   constexpr int ROWS_W = 16 * NRT, ROWS_B = ROWS_W * RW;
 
   constexpr int OP = D + 4;                 // row pitch (floats) of the output staging tile
@@ -578,26 +577,17 @@ void forest_attention_shared_kernel(AttnArgs a) {
   auto stamp = [&](int) {};
 #endif
   uint4 kreg[KL];
-  uint4 vreg[VI][2];
+  uint4 vreg[KL];
   auto load_tile = [&](int ti) {
     const __bf16 *kp, *vp; long long stride; int tok0, len; bool tree;
     locate(ti, kp, vp, stride, tok0, len, tree);
 #pragma unroll
-    for (int r = 0; r < KL; ++r) {
+    for (int r = 0; r < KL; ++r) {            // CG consecutive lanes read one whole token row of K and of V
       const int c = r * NT + tid;
       const int tok = min(tok0 + c / CG, len - 1);
-      kreg[r] = load_global_16_nt(kp + (long long)tok * stride + (c % CG) * 8);
-    }
-#pragma unroll
-    for (int r = 0; r < VI; ++r) {
-      const int it = r * NT + tid;
-      const int cg = it % CG;                 // CG consecutive lanes read one whole token row
-      const int tp = it / CG;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int tok = min(tok0 + 2 * tp + h, len - 1);
-        vreg[r][h] = load_global_16_nt(vp + (long long)tok * stride + cg * 8);
-      }
+      const long long off = (long long)tok * stride + (c % CG) * 8;
+      kreg[r] = load_global_16_nt(kp + off);
+      vreg[r] = load_global_16_nt(vp + off);
     }
   };
   auto store_tile = [&](int buf) {
@@ -607,14 +597,7 @@ void forest_attention_shared_kernel(AttnArgs a) {
     for (int r = 0; r < KL; ++r) {
       const int c = r * NT + tid;
       *reinterpret_cast<uint4*>(&kl[(c / CG) * KP + (c % CG) * 8]) = kreg[r];
-    }
-#pragma unroll
-    for (int r = 0; r < VI; ++r) {
-      const int it = r * NT + tid;
-      const int cg = it % CG, tp = it / CG;
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        *reinterpret_cast<uint4*>(&vl[(2 * tp + h) * KP + cg * 8]) = vreg[r][h];
+      *reinterpret_cast<uint4*>(&vl[(c / CG) * KP + (c % CG) * 8]) = vreg[r];
     }
   };
 

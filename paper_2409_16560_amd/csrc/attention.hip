@@ -457,8 +457,7 @@ __global__ __launch_bounds__(256) void forest_attention_kernel(AttnArgs a) {
 // tokens of one channel.  Tiles are double-buffered: while tile t
 // is consumed from one buffer, tile t+1 sits in registers on its way to the other buffer and tile t+2
 // is in flight from HBM; one workgroup barrier per tile.  Two workgroups fit a CU (<= 256 registers,
-// < 80 KiB LDS), so one can compute while the other waits on memory.  The V^T tile is written with a
-// token-pair swizzle so that the 64 lanes of a transposing write hit 64 different banks.
+// < 80 KiB LDS), so one can compute while the other waits on memory.
 template <int D, int RW, int NRT>
 __global__ __launch_bounds__(64 * RW) __attribute__((amdgpu_waves_per_eu(NRT == 1 ? 4 : 2, NRT == 1 ? 4 : 2)))
 void forest_attention_shared_kernel(AttnArgs a) {
@@ -798,15 +797,32 @@ __global__ __launch_bounds__(256) void forest_attention_combine_kernel(int n_row
   const long long row = gid / QPR;
   const int quad = (int)(gid % QPR);
   if (row >= n_rows_total) return;
-  float M = NEG_BIG;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[((long long)s * n_rows_total + row) * 2]);
-  float L = 0.f;
+  // Eight splits at a time with all their loads in flight (a loop of one load and one use per split is bound by
+  // memory latency); the running reference M is raised batch by batch.
+  float M = NEG_BIG, L = 0.f;
   floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < nsplit; ++s) {
-    const long long prow = (long long)s * n_rows_total + row;
-    const float w = exp2f(part_ml[prow * 2] - M);
-    L += w * part_ml[prow * 2 + 1];
-    acc += w * *reinterpret_cast<const floatx4*>(&part_o[prow * D + 4 * quad]);
+  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+    float2 ml[8];
+    floatx4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const long long prow = (long long)min(s0 + j, nsplit - 1) * n_rows_total + row;
+      ml[j] = *reinterpret_cast<const float2*>(&part_ml[prow * 2]);
+      v[j] = *reinterpret_cast<const floatx4*>(&part_o[prow * D + 4 * quad]);
+    }
+    float Mb = M;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < nsplit) Mb = fmaxf(Mb, ml[j].x);
+    const float keep = exp2f(M - Mb);                   // 1 when the reference stays
+    L *= keep; acc *= keep; M = Mb;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < nsplit) {
+        const float w = exp2f(ml[j].x - M);
+        L += w * ml[j].y;
+        acc += w * v[j];
+      }
   }
   const float inv = L > 0.f ? 1.f / L : 0.f;
   union { __bf16 h[4]; uint2 u; } pk;

@@ -374,6 +374,13 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a workgroup-scope fence, for which the
+// compiler also drains the wave's outstanding global loads and stores: where the waves exchange nothing but LDS
+// values, this form lets the first wave's status stores and slot posts stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Inclusive prefix sum over the block's threads in thread order (fixed tree: identical in every workgroup
 // that scans the same values).
 __device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh) {
@@ -617,8 +624,20 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // row statistics: the chunks of the statistics pass merged into the exact maximum and an fp32 log-sum-exp
     const float2* pp = a.part + (long long)n * a.nchunk;
     const float2* pq = a.part + ((long long)a.n_nodes + n) * a.nchunk;
-    float Mp = pp[0].x, Sp = pp[0].y, Mq = pq[0].x, Sq = pq[0].y;
-    for (int c = 1; c < a.nchunk; ++c) { online_merge(Mp, Sp, pp[c].x, pp[c].y); online_merge(Mq, Sq, pq[c].x, pq[c].y); }
+    // (the chunks' loads all leave before the first merge: one after the other they cost a memory latency each)
+    float Mp, Sp, Mq, Sq;
+    if (a.nchunk <= 4) {
+      float2 vp[4], vq[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) { const int cc = min(c, a.nchunk - 1); vp[c] = pp[cc]; vq[c] = pq[cc]; }
+      Mp = vp[0].x; Sp = vp[0].y; Mq = vq[0].x; Sq = vq[0].y;
+#pragma unroll
+      for (int c = 1; c < 4; ++c)
+        if (c < a.nchunk) { online_merge(Mp, Sp, vp[c].x, vp[c].y); online_merge(Mq, Sq, vq[c].x, vq[c].y); }
+    } else {
+      Mp = pp[0].x; Sp = pp[0].y; Mq = pq[0].x; Sq = pq[0].y;
+      for (int c = 1; c < a.nchunk; ++c) { online_merge(Mp, Sp, pp[c].x, pp[c].y); online_merge(Mq, Sq, pq[c].x, pq[c].y); }
+    }
     const float lp = Mp + logf(Sp), lq = Mq + logf(Sq);
     sh.n_maxp[tid] = Mp; sh.n_maxq[tid] = Mq;
     sh.n_lsep[tid] = lp; sh.n_lseq[tid] = lq;
@@ -695,12 +714,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   __syncthreads();
 
   // total over the workgroup of one value per thread: valid in every thread after the barrier inside
-  auto wg_total = [&](double s) -> double {
+  auto wg_total = [&](double s, bool lds_only = false) -> double {
     s = wave_sum(s);
     double* ws = sh.wsum[wsum_round & 1];
     wsum_round += 1;
     if (lane == 0) ws[wave] = s;
-    __syncthreads();
+    if (lds_only) lds_barrier(); else __syncthreads();
     return ((ws[0] + ws[1]) + (ws[2] + ws[3])) + ((ws[4] + ws[5]) + (ws[6] + ws[7]));
   };
   auto give_up = [&]() { sh.abort = 1; atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT); };
@@ -743,6 +762,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     auto ldq = [&](long long j) -> double { double v; if (in_lds) v = ql[(int)j]; else v = qbg[j]; return v; };
     auto stp = [&](long long j, double v) { if (in_lds) pl[(int)j] = v; else pbg[j] = v; };
     auto stq = [&](long long j, double v) { if (in_lds) ql[(int)j] = v; else qbg[j] = v; };
+    // The hot loops are written once and instantiated for both homes of the slices, with the choice taken outside
+    // the loop (left per access, it becomes a pair of branches around every load and store).
+    auto with_slices = [&](auto&& body) { if (in_lds) body(pl, ql); else body(pbg, qbg); };
 
     // ===== p_beam / q_beam over I x V: exponentials and this workgroup's share of the row sums
     for (int i = i_lo; i <= i_hi; ++i) {
@@ -754,22 +776,24 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const double mp = sh.max_p[i], mq = sh.max_q[i];
       double s_p = 0.0, s_q = 0.0;
       const long long joff = (long long)i * V - e_lo;
-      for (long long x = x_lo + tid; x < x_hi; x += 8 * VL_BLOCK) {   // eight logits of each model in flight, ragged end predicated
-        float fp[8], fq[8];
+      with_slices([&](auto P, auto Q) {
+        for (long long x = x_lo + tid; x < x_hi; x += 8 * VL_BLOCK) {   // eight logits of each model in flight, ragged end predicated
+          float fp[8], fq[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
-          fp[k] = zp[xx]; fq[k] = zq[xx];
-        }
+          for (int k = 0; k < 8; ++k) {
+            const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
+            fp[k] = zp[xx]; fq[k] = zq[xx];
+          }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          if (x + k * VL_BLOCK < x_hi) {
-            const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab), eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
-            stp(joff + x + k * VL_BLOCK, ep); stq(joff + x + k * VL_BLOCK, eq);
-            s_p += ep; s_q += eq;
+          for (int k = 0; k < 8; ++k) {
+            if (x + k * VL_BLOCK < x_hi) {
+              const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab), eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
+              P[joff + x + k * VL_BLOCK] = ep; Q[joff + x + k * VL_BLOCK] = eq;
+              s_p += ep; s_q += eq;
+            }
           }
         }
-      }
+      });
       s_p = wave_sum(s_p);
       s_q = wave_sum(s_q);
       if (lane == 0) {
@@ -898,25 +922,27 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
       const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
       const double fp = sh.sp[i], fq = sh.sq[i];
-      long long j = j_lo + tid;
-      for (; j + 3 * VL_BLOCK < j_hi; j += 4 * VL_BLOCK) {      // four elements of each array in flight
-        double pv[4], qv[4];
+      with_slices([&](auto P, auto Q) {
+        long long j = j_lo + tid;
+        for (; j + 3 * VL_BLOCK < j_hi; j += 4 * VL_BLOCK) {      // four elements of each array in flight
+          double pv[4], qv[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { pv[k] = ldp(j + k * VL_BLOCK); qv[k] = ldq(j + k * VL_BLOCK); }
+          for (int k = 0; k < 4; ++k) { pv[k] = P[j + k * VL_BLOCK]; qv[k] = Q[j + k * VL_BLOCK]; }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          pv[k] *= fp; qv[k] *= fq;
-          stp(j + k * VL_BLOCK, pv[k]); stq(j + k * VL_BLOCK, qv[k]);
-          if constexpr (WARP) { tmax_p = fmax(tmax_p, pv[k]); tmax_q = fmax(tmax_q, qv[k]); }
-          else f1 += fmax(pv[k] - qv[k], 0.0);
+          for (int k = 0; k < 4; ++k) {
+            pv[k] *= fp; qv[k] *= fq;
+            P[j + k * VL_BLOCK] = pv[k]; Q[j + k * VL_BLOCK] = qv[k];
+            if constexpr (WARP) { tmax_p = fmax(tmax_p, pv[k]); tmax_q = fmax(tmax_q, qv[k]); }
+            else f1 += fmax(pv[k] - qv[k], 0.0);
+          }
         }
-      }
-      for (; j < j_hi; j += VL_BLOCK) {
-        const double pv = ldp(j) * fp, qv = ldq(j) * fq;
-        stp(j, pv); stq(j, qv);
-        if constexpr (WARP) { tmax_p = fmax(tmax_p, pv); tmax_q = fmax(tmax_q, qv); }
-        else f1 += fmax(pv - qv, 0.0);
-      }
+        for (; j < j_hi; j += VL_BLOCK) {
+          const double pv = P[j] * fp, qv = Q[j] * fq;
+          P[j] = pv; Q[j] = qv;
+          if constexpr (WARP) { tmax_p = fmax(tmax_p, pv); tmax_q = fmax(tmax_q, qv); }
+          else f1 += fmax(pv - qv, 0.0);
+        }
+      });
     }
     if constexpr (WARP) {
       // ===== warping T: top-k / top-p on the two joints (Section 2.1; Section 3.1 "Details": p_beam = T o p/P).
@@ -1009,15 +1035,17 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
             if (c < WARP_CAND) { cvq[c] = vq; ciq[c] = (int)(e_lo + j); }
           }
         };
-        long long j = tid;
-        for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
-          double pv[4], qv[4];
+        with_slices([&](auto P, auto Q) {
+          long long j = tid;
+          for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
+            double pv[4], qv[4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) { pv[k] = ldp(j + k * VL_BLOCK); qv[k] = ldq(j + k * VL_BLOCK); }
+            for (int k = 0; k < 4; ++k) { pv[k] = P[j + k * VL_BLOCK]; qv[k] = Q[j + k * VL_BLOCK]; }
 #pragma unroll
-          for (int k = 0; k < 4; ++k) offer(j + k * VL_BLOCK, pv[k], qv[k]);
-        }
-        for (; j < len; j += VL_BLOCK) offer(j, ldp(j), ldq(j));
+            for (int k = 0; k < 4; ++k) offer(j + k * VL_BLOCK, pv[k], qv[k]);
+          }
+          for (; j < len; j += VL_BLOCK) offer(j, P[j], Q[j]);
+        });
       }
       __syncthreads();
       stamp(60);
@@ -1326,14 +1354,16 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const int c2 = tid - t0;
         return c2 < sh.nU ? fmax(sh.U_p[c2] - c * sh.U_q[c2], 0.0) : 0.0;
       }
-      long long j = tid - t0;
-      for (; j + 3 * nt < len; j += 4 * nt) {
-        const double p0 = ldp(j), p1 = ldp(j + nt), p2 = ldp(j + 2 * nt), p3 = ldp(j + 3 * nt);
-        const double q0 = ldq(j), q1 = ldq(j + nt), q2 = ldq(j + 2 * nt), q3 = ldq(j + 3 * nt);
-        s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
-        s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
-      }
-      for (; j < len; j += nt) s0 += fmax(ldp(j) - c * ldq(j), 0.0);
+      with_slices([&](auto P, auto Q) {
+        long long j = tid - t0;
+        for (; j + 3 * nt < len; j += 4 * nt) {
+          const double p0 = P[j], p1 = P[j + nt], p2 = P[j + 2 * nt], p3 = P[j + 3 * nt];
+          const double q0 = Q[j], q1 = Q[j + nt], q2 = Q[j + 2 * nt], q3 = Q[j + 3 * nt];
+          s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
+          s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
+        }
+        for (; j < len; j += nt) s0 += fmax(P[j] - c * Q[j], 0.0);
+      });
       return (s0 + s1) + (s2 + s3);
     };
 
@@ -1383,7 +1413,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
       const long long t_lo = min(len, per * tid), t_hi = min(len, t_lo + per);   // slice-local
       double ts = 0.0;
-      for (long long j = t_lo; j < t_hi; ++j) ts += use_q ? fmax(ldp(j) - c * ldq(j), 0.0) : ldp(j);
+      with_slices([&](auto P, auto Q) {
+        if (use_q) for (long long j = t_lo; j < t_hi; ++j) ts += fmax(P[j] - c * Q[j], 0.0);
+        else for (long long j = t_lo; j < t_hi; ++j) ts += P[j];
+      });
       const double tincl = block_inclusive_scan(ts, sh);
       sh.tsum[tid] = tincl;
       if (tid == 0) sh.counter = 0;
@@ -1701,8 +1734,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         stamp(41);
         if (wave == 0) decide(decide_round, k);
         double tot = 0.0;
-        if (!posted) tot = wg_total(slice_sum(c_next, 64, VL_BLOCK - 64));   // barrier inside
-        else __syncthreads();
+        // (the barriers of this loop order LDS values only: chain entries, decisions, wave totals; slices are
+        // read-only here and the outputs written meanwhile are read by nobody in this kernel)
+        if (!posted) tot = wg_total(slice_sum(c_next, 64, VL_BLOCK - 64), true);   // barrier inside
+        else lds_barrier();
         const int st = sh.state[decide_round & 1];
         decide_round += 1;             // the next outcome goes to the other entry: nobody still reads it
         stamp(42);
@@ -1728,7 +1763,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         posted = false;
         spec = false;
         stamp(45);
-        __syncthreads();
+        lds_barrier();
         if (sh.abort) return;
       }
     }

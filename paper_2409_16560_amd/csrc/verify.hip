@@ -724,6 +724,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   };
   auto give_up = [&]() { sh.abort = 1; atomicOr(a.fault, DSBD_FAULT_SYNC_TIMEOUT); };
 
+  // this workgroup's share of I x V, as a function of the number of rows
+  int geo_nI = -1, geo_ilo = 0, geo_ihi = -1, geo_pieces = 1;
+  SliceCut geo_cut = {0, 1, 0};
+  long long geo_lo = 0, geo_hi = 0;
+
   stamp(1);
   for (int l = 1; l <= gamma + 1; ++l) {
     stamp(10 + l);
@@ -734,20 +739,29 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // sum is formed in an order that depends on the row's length only, so beams with equal logits and equal
     // likelihoods (duplicates are common in beam sampling) get bitwise equal joint entries, and the order of
     // equal entries (by index) is the same as in a plain row-by-row evaluation.
-    const SliceCut cut = slice_cut(nI, V, a.G);
-    const long long ch = cut.len;            // the longest slice of the layer
-    long long e_lo = total, e_hi = total;
-    if (cut.rows_per_wg > 0) {
-      e_lo = min(total, (long long)g * cut.rows_per_wg * V);
-      e_hi = min(total, e_lo + (long long)cut.rows_per_wg * V);
-    } else if (g / cut.wg_per_row < nI) {
-      const long long r0 = (long long)(g / cut.wg_per_row) * V, k = g % cut.wg_per_row;
-      e_lo = r0 + min((long long)V, k * cut.len);
-      e_hi = r0 + min((long long)V, (k + 1) * cut.len);
+    // (worked out when the number of rows changes: a handful of 64-bit divisions, on every workgroup's critical
+    // path, that a fixed layer width repeats unchanged layer after layer)
+    if (nI != geo_nI) {
+      geo_nI = nI;
+      geo_cut = slice_cut(nI, V, a.G);
+      geo_lo = total; geo_hi = total;
+      if (geo_cut.rows_per_wg > 0) {
+        geo_lo = min(total, (long long)g * geo_cut.rows_per_wg * V);
+        geo_hi = min(total, geo_lo + (long long)geo_cut.rows_per_wg * V);
+      } else if (g / geo_cut.wg_per_row < nI) {
+        const long long r0 = (long long)(g / geo_cut.wg_per_row) * V, k = g % geo_cut.wg_per_row;
+        geo_lo = r0 + min((long long)V, k * geo_cut.len);
+        geo_hi = r0 + min((long long)V, (k + 1) * geo_cut.len);
+      }
+      geo_ilo = (int)div_floor(geo_lo, V);
+      geo_ihi = geo_hi > geo_lo ? (int)div_floor(geo_hi - 1, V) : geo_ilo - 1;
+      geo_pieces = (int)((V + geo_cut.len - 1) / geo_cut.len);
     }
+    const SliceCut cut = geo_cut;
+    const long long ch = cut.len;            // the longest slice of the layer
+    const long long e_lo = geo_lo, e_hi = geo_hi;
     const long long len = e_hi - e_lo;
-    const int i_lo = (int)div_floor(e_lo, V);
-    const int i_hi = e_hi > e_lo ? (int)div_floor(e_hi - 1, V) : i_lo - 1;
+    const int i_lo = geo_ilo, i_hi = geo_ihi;
     // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
     const bool in_lds = ch <= (long long)a.lds_slice;
     // Accessors with explicit address spaces (LDS or global): through generic pointers the compiler merges the two
@@ -879,7 +893,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       if (c < ncols && r < R) {
         const int i = c >> 1;
         const int w_lo = cut.rows_per_wg > 0 ? i / cut.rows_per_wg : i * cut.wg_per_row;
-        const int w_hi = cut.rows_per_wg > 0 ? w_lo : w_lo + (int)((V + cut.len - 1) / cut.len) - 1;
+        const int w_hi = cut.rows_per_wg > 0 ? w_lo : w_lo + geo_pieces - 1;
         for (int w = w_lo + r; w <= w_hi; w += R) {
           double v = 0.0;
           mine = mine && slot_wait(rs_bank + (long long)w * a.sl.r_w + c, rs_tag, v, a.sync_limit);

@@ -1903,8 +1903,12 @@ int cached_cu_count() {
 
 VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   VerifyPlan pl;
-  // row chunks of about 32k logits: a few thousand workgroups at the large configurations
-  int target = 32768;
+  // about four chunks per row, of 8k to 32k logits each: a few thousand workgroups at the large configurations,
+  // and at most four chunk statistics per row for the layer kernel's prologue to merge (measured: a 32000-token
+  // vocabulary in one chunk per row ran the 16-prompt batch at 45 % of the HBM peak, in four at 57 %)
+  int target = V / 4;
+  if (target < 8192) target = 8192;
+  if (target > 32768) target = 32768;
   if (const char* e = getenv("DSBD_STATS_CHUNK")) {   // tuning knob: logits per workgroup of the statistics pass
     const int v = atoi(e);
     if (v >= 1024) target = v;

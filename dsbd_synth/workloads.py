@@ -116,7 +116,7 @@ def tree_parents(kind: str, n: int, rng) -> List[int]:
         return [-1] + list(range(n - 1))
     if kind == "fork_chain":
         # root, two children, each child continued as a chain
-        return [-1, 0, 0] + [i - 2 for i in range(3, n)]
+        return ([-1, 0, 0] + [i - 2 for i in range(3, n)])[:n]
     if kind == "binary_bfs":
         return [-1] + [(i - 1) // 2 for i in range(1, n)]
     if kind == "binary_dfs":

@@ -124,6 +124,37 @@ def test_verify_accept_patterns_over_seeds(seed, noise):
         gu.compare_verify(res, ref, w)
 
 
+@pytest.mark.parametrize("sweep", [0, 1, 2])
+def test_verify_random_forests_and_parameters(sweep):
+    """Randomized sweep: prompts, beams, tree shapes and sizes, vocabulary sizes (one workgroup per prompt up to
+    several per row), draft distance, fixed / dynamic width, W_L above and below the number of beams, warping."""
+    from dsbd_synth.workloads import Spec
+    gu = _gu()
+    rng = np.random.default_rng(1000 + sweep)
+    for case in range(25):
+        tree = str(rng.choice(["random", "binary_dfs", "chain", "fork_chain"]))
+        nodes = int(rng.choice([3, 7, 15, 31])) if tree == "binary_dfs" else (2, int(rng.integers(3, 32)))
+        spec = Spec("sweep", int(rng.integers(1, 5)), (1, int(rng.integers(1, 9))), tree, nodes, 1, 0, 1, 1, 64,
+                    int(rng.choice([17, 130, 1000, 4097, 12000, 33000])), float(rng.choice([1.0, 3.0])),
+                    str(rng.choice(["noise", "indep"])), float(rng.choice([0.25, 0.5, 1.0, 2.5])),
+                    int(rng.integers(0, 1 << 30)), int(rng.choice([0, 0, 4])))
+        t = float(rng.choice([-1.0, -1.0, 0.3, 0.6, 0.9]))
+        W_L = int(rng.choice([0, 0, 2, 5]))
+        top_k, top_p = 0, 1.0
+        if spec.draft_top_k and rng.random() < 0.7:
+            top_k, top_p = int(rng.choice([1, 5, 16, 32])), float(rng.choice([1.0, 0.9, 0.6]))
+        w = make_workload(spec)
+        d = gu.DeviceWorkload(w)
+        res = d.verify(W_L=W_L, t=t, top_k=top_k, top_p=top_p)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, W_L=W_L, t=t, top_k=top_k, top_p=top_p)
+        try:
+            gu.compare_verify(res, ref, w)
+        except AssertionError as e:
+            raise AssertionError("sweep %d case %d (%s, t=%g, W_L=%d, top_k=%d, top_p=%g): %s"
+                                 % (sweep, case, spec, t, W_L, top_k, top_p, e))
+
+
 WARP_CASES = [
     # (config, overrides, top_k, top_p)
     ("c3", dict(V=5000, draft_top_k=4), 16, 1.0),

@@ -42,6 +42,7 @@ def test_bf16_round_trip_and_rounding():
 def test_tree_shapes():
     assert tree_parents("chain", 3, None) == [-1, 0, 1]
     assert tree_parents("fork_chain", 7, None) == [-1, 0, 0, 1, 2, 3, 4]
+    assert tree_parents("fork_chain", 2, None) == [-1, 0] and tree_parents("fork_chain", 1, None) == [-1]
     assert tree_parents("binary_bfs", 7, None) == [-1, 0, 0, 1, 1, 2, 2]
     assert tree_parents("binary_dfs", 7, None) == [-1, 0, 1, 1, 0, 4, 4]
 

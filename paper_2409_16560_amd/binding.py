@@ -178,7 +178,10 @@ class PrefixKV:
                  head_major=False):
         dev = k[0].device
         self.keep = (k, v, k_shared, v_shared)
-        ref = next((t for t in k if t.numel() > 0), k[0])
+        # the strides come from any cache that holds tokens (an empty tensor's strides say nothing); the shared
+        # segments have the layout of the beams' own
+        held = [t for t in list(k) + [t for t in (k_shared or []) if t is not None] if t.numel() > 0]
+        ref = held[0] if held else k[0]
         if head_major:
             self.token_stride, self.head_stride = ref.stride(1), ref.stride(0)
             lens = [t.shape[1] for t in k]

@@ -25,6 +25,7 @@ ATTN_CASES = [
     ("c5", dict(L=333)),                                          # GQA 32/8: 124 rows per (tree, KV head)
     ("c5", dict(L=96, Hq=16, Hkv=4, tree_nodes=63, tree="binary_bfs")),   # 63-node trees: 252 rows, two row blocks
     ("c3", dict(L=64, shared_len=0, Hq=8, Hkv=4, D=64)),          # D=64 with GQA
+    ("c3", dict(L=40, shared_len=40, Hq=8, Hkv=2)),               # the whole prefix shared: every beam's own part is empty
 ]
 
 
@@ -43,6 +44,40 @@ def test_forest_attention_matches_oracle(cfg, kw):
     ref_out, ref_lse = gu.oracle_attention(w)
     err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
     print("max abs err out/lse", err, flush=True)
+
+
+@pytest.mark.parametrize("sweep", [0, 1])
+def test_forest_attention_random_shapes(sweep):
+    """Randomized sweep: tree shapes up to 64 nodes, head groupings, both head sizes, prefix lengths from nothing to
+    several tiles (equal or ragged within the batch), shared leading segments up to the whole prefix, given to the
+    library as a segment of their own or duplicated into every beam's cache."""
+    from dsbd_synth.workloads import Spec
+    from oracle import forest as o_forest
+    gu = _gu()
+    rng = np.random.default_rng(2000 + sweep)
+    for case in range(30):
+        tree = str(rng.choice(["random", "binary_dfs", "binary_bfs", "chain", "fork_chain"]))
+        nodes = int(rng.choice([3, 7, 15, 31, 63])) if tree == "binary_dfs" else (1, int(rng.integers(1, 65)))
+        Hq, Hkv = [(1, 1), (4, 4), (8, 2), (4, 1), (32, 8), (16, 16)][int(rng.integers(0, 6))]
+        Lhi = int(rng.choice([0, 5, 40, 130, 300, 700]))
+        L = (0, Lhi) if rng.random() < 0.5 else Lhi
+        shared = int(rng.integers(0, (Lhi if isinstance(L, int) else 0) + 1)) if rng.random() < 0.4 else 0
+        if case % 10 == 0 and isinstance(L, int):
+            shared = L                                   # the whole prefix shared
+        spec = Spec("sweep", int(rng.integers(1, 4)), (1, int(rng.integers(1, 6))), tree, nodes, L, shared, Hq, Hkv,
+                    int(rng.choice([64, 128])), 64, 3.0, "noise", 0.5, int(rng.integers(0, 1 << 30)))
+        w = make_workload(spec)
+        d = gu.DeviceWorkload(w, share_prefix=bool(rng.integers(0, 2)))
+        anc = torch.zeros(w.n_nodes, dtype=torch.int64, device="cuda")
+        out, lse, fault = d.attention(anc_mask_out=anc)
+        torch.cuda.synchronize()
+        try:
+            assert int(fault.item()) == 0
+            assert np.array_equal(anc.cpu().numpy().view(np.uint64), o_forest.ancestor_masks(w.parent, w.tree_off))
+            ref_out, ref_lse = gu.oracle_attention(w)
+            gu.compare_attention(w, out, lse, ref_out, ref_lse)
+        except AssertionError as e:
+            raise AssertionError("sweep %d case %d (%s): %s" % (sweep, case, spec, e))
 
 
 def test_shared_prefix_equals_duplicated_prefix():

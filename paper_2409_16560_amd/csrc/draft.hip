@@ -221,7 +221,7 @@ __global__ __launch_bounds__(BF_BLOCK) void build_forest_kernel(BuildArgs a) {
       root = row - r0;
     }
     sh.root[tid] = root;
-    sh.key[tid] = l * a.W_S + j;
+    sh.key[tid] = tid < W ? 0 : l * a.W_S + j;          // a root comes first in its tree (its own index may exceed W_S)
     sh.par_local[tid] = par;
     atomicAdd(&sh.tree_n[root], 1);
   }

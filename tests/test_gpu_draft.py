@@ -115,7 +115,9 @@ def run_build(root_off, lp, lt, root_token=None):
 
 @pytest.mark.parametrize("seed,root_off,gamma,W_S", [(0, [0, 2], 3, 4), (1, [0, 1, 4, 6], 2, 5), (2, [0, 3], 1, 2),
                                                      (3, [0, 4, 5], 4, 3), (4, [0, 8], 4, 16), (5, [0, 64], 7, 64),
-                                                     (6, list(range(0, 17)), 5, 8), (7, [0, 5], 0, 0)])
+                                                     (6, list(range(0, 17)), 5, 8), (7, [0, 5], 0, 0),
+                                                     # more input beams than draws per step: a root's own index exceeds W_S
+                                                     (8, [0, 3], 1, 1), (9, [0, 6, 14], 3, 2), (10, [0, 8], 2, 3), (11, [0, 5, 10], 3, 3)])
 def test_build_forest_matches_oracle(seed, root_off, gamma, W_S):
     _, o_draft = _mods()
     rng = np.random.default_rng(seed)

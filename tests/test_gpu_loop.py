@@ -15,6 +15,8 @@ pytestmark = pytest.mark.gpu
     ("warped joints", [[(1, 2, 3), (1, 2, 4), (1, 5, 6)]], 5000, 8, 2, dict(W_L=3, t=-1.0, top_k=10, top_p=0.8)),
     ("one cache kept", [[(7,), (8,)]], 300, 4, 3, dict(W_L=2, t=-1.0, keep_one=True)),
     ("no draft layers", [[(3,), (4,)]], 300, 4, 0, dict(W_L=2, t=-1.0)),
+    ("more beams than draws per step", [[(269, 239, 253)]], 300, 1, 1, dict(W_L=3, t=-1.0, W_min=2, top_k=10, top_p=0.5)),
+    ("five beams, three draws", [[(4557, 8707)], [(6912, 130)]], 9000, 3, 3, dict(W_L=5, t=-1.0, W_min=2)),
 ])
 def test_loop_matches_the_oracle_loop(name, start, V, W_S, gamma, kw):
     import gpu_util as gu

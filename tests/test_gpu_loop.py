@@ -56,3 +56,56 @@ def test_loop_matches_the_oracle_loop(name, start, V, W_S, gamma, kw):
             n = ora.k_cache[j].shape[0]
             assert lib.kv_len[j] == n
             assert np.array_equal(bits(lib.k_buf[j][:n]), ora.k_cache[j]) and np.array_equal(bits(lib.v_buf[j][:n]), ora.v_cache[j])
+
+@pytest.mark.parametrize("sweep", [0, 1])
+def test_loop_random_parameters(sweep):
+    """Randomized sweep of the whole loop: prompts and input beams, draws per step above and below the number of
+    beams, draft depth 0..3, fixed and dynamic width, warping, one-cache mode, head groupings."""
+    import gpu_util as gu
+    from paper_2409_16560_amd.loop import DecodeLoop
+    from oracle.loop import OracleLoop
+    rng = np.random.default_rng(3000 + sweep)
+    g = lambda x: x.cpu().numpy()
+    bits = lambda t_: t_.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    for case in range(12):
+        V = int(rng.choice([50, 300, 2000, 9000]))
+        plen = int(rng.integers(1, 4))
+        start = [[tuple(int(x) for x in rng.integers(0, V, plen)) for _ in range(int(rng.integers(1, 4)))]
+                 for _ in range(int(rng.integers(1, 4)))]
+        W_S, gamma = int(rng.integers(1, 9)), int(rng.integers(0, 4))
+        kw = dict(W_L=int(rng.choice([0, 1, 2, 3, 5])), t=float(rng.choice([-1.0, -1.0, 0.4, 0.8])), W_min=int(rng.choice([1, 2])))
+        if rng.random() < 0.4:
+            kw.update(top_k=int(rng.choice([1, 4, 10, 32])), top_p=float(rng.choice([1.0, 0.8, 0.5])))
+        if rng.random() < 0.25:
+            kw.update(keep_one=True)
+        Hq, Hkv = [(4, 2), (2, 2), (8, 1)][int(rng.integers(0, 3))]
+        mseed, seed = int(rng.integers(0, 1000)), int(rng.integers(0, 1000))
+        what = "sweep %d case %d: V=%d start=%s W_S=%d gamma=%d %s heads %d/%d seeds %d %d" % (
+            sweep, case, V, start, W_S, gamma, kw, Hq, Hkv, mseed, seed)
+        print(what, flush=True)
+        m = SyntheticModels(V=V, seed=mseed, Hq=Hq, Hkv=Hkv, D=64)
+        lib = DecodeLoop(m, start, W_S, gamma, lambda n, stream: uniform01_f32(n, seed, stream), W_cap=8, kv_capacity=64, **kw)
+        ora = OracleLoop(m, start, W_S, gamma, W_cap=8, seed=seed, **kw)
+        for it in range(3):
+            a, b = lib.step(), ora.step()
+            torch.cuda.synchronize()
+            f = b["forest"]
+            for field in ("tree_prompt", "tree_off", "parent", "token", "draft_rank"):
+                assert np.array_equal(g(getattr(a["forest"], field)), f[field]), (what, it, field)
+            assert a["node_seq"] == b["node_seq"], (what, it)
+
+            class W:
+                tree_prompt, tree_off, n_nodes = f["tree_prompt"], f["tree_off"], len(f["parent"])
+            if gu.compare_verify(a["verify"], b["verify"], W):
+                break                                    # a near tie: the two loops may part ways from here on
+            for field in ("n_next", "src_tree", "src_out", "path_len", "path", "token"):
+                assert np.array_equal(g(getattr(a["next"], field)), b["next"][field]), (what, it, field)
+            assert int(a["attn_fault"].item()) == 0
+            assert np.max(np.abs(a["attn_out"].float().cpu().numpy() - b["attn_out"])) <= gu.ATOL, (what, it)
+            assert lib.beams == ora.beams, (what, it)
+            assert len(lib.k_buf) == len(ora.k_cache)
+            for j in range(len(ora.k_cache)):
+                n = ora.k_cache[j].shape[0]
+                assert lib.kv_len[j] == n, (what, it, j)
+                assert np.array_equal(bits(lib.k_buf[j][:n]), ora.k_cache[j]), (what, it, j)
+                assert np.array_equal(bits(lib.v_buf[j][:n]), ora.v_cache[j]), (what, it, j)

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
   // row 0 of the grid does the small jobs (dispatched first: done long before the streaming rows are)
   const int c = blockIdx.x, n = (int)blockIdx.y - 1, which = blockIdx.z;
   if (n < 0) {                // uniform over the workgroup
-    stats_service(a, which * gridDim.x + c, 2 * gridDim.x);
+    stats_service(a, which * gridDim.x + c, (int)(gridDim.z * gridDim.x));
     return;
   }
   const int lo = c * a.chunk;
@@ -240,6 +240,7 @@ struct LayersArgs {
   long long* trace;      // optional timeline (first workgroup of prompt 0): pairs (label, 100 MHz wall clock)
   int lds_elems;         // capacity (elements) of each of the two dynamic-LDS slice arrays; 0 = none
   int lds_slice;         // slices of up to this many elements are kept in the LDS (<= lds_elems)
+  int alias;             // one model in both roles (same logits, same beam likelihoods): q_beam IS p_beam, kept once
   long long sync_limit;  // bound of every wait, in ticks of the 100 MHz wall clock
   int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
                          // bounded waits give up and the error path can be exercised without a hang
@@ -628,7 +629,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     atomicMax(&sh.sgamma, d);
     // row statistics: the chunks of the statistics pass merged into the exact maximum and an fp32 log-sum-exp
     const float2* pp = a.part + (long long)n * a.nchunk;
-    const float2* pq = a.part + ((long long)a.n_nodes + n) * a.nchunk;
+    const float2* pq = a.alias ? pp : a.part + ((long long)a.n_nodes + n) * a.nchunk;
     // (the chunks' loads all leave before the first merge: one after the other they cost a memory latency each)
     float Mp, Sp, Mq, Sq;
     if (a.nchunk <= 4) {
@@ -774,9 +775,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     typedef __attribute__((address_space(3))) double lds_f64;
     typedef __attribute__((address_space(1))) double glb_f64;
     lds_f64* const pl = (lds_f64*)dyn_lds;
-    lds_f64* const ql = pl + a.lds_elems;
+    lds_f64* const ql = a.alias ? pl : pl + a.lds_elems;
     glb_f64* const pbg = (glb_f64*)pb;
-    glb_f64* const qbg = (glb_f64*)qb;
+    glb_f64* const qbg = a.alias ? pbg : (glb_f64*)qb;
     auto ldp = [&](long long j) -> double { double v; if (in_lds) v = pl[(int)j]; else v = pbg[j]; return v; };
     auto ldq = [&](long long j) -> double { double v; if (in_lds) v = ql[(int)j]; else v = qbg[j]; return v; };
     auto stp = [&](long long j, double v) { if (in_lds) pl[(int)j] = v; else pbg[j] = v; };
@@ -806,7 +807,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
             if (x + k * VL_BLOCK < x_hi) {
-              const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab), eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
+              const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab);
+              double eq = ep;
+              if (!a.alias) eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
               P[joff + x + k * VL_BLOCK] = ep; Q[joff + x + k * VL_BLOCK] = eq;
               s_p += ep; s_q += eq;
             }
@@ -1861,6 +1864,7 @@ namespace {
 
 struct VerifyPlan {
   int nchunk, chunk, I_cap, G, lds_elems;
+  size_t lds_bytes;        // dynamic LDS of the layer kernel
   SlotLayout sl;
   long long slice_cap;     // elements of the largest slice of I x V a workgroup can get
 };
@@ -1901,7 +1905,7 @@ int cached_cu_count() {
   return cus;
 }
 
-VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
+VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, bool alias = false) {
   VerifyPlan pl;
   // about four chunks per row, of 8k to 32k logits each: a few thousand workgroups at the large configurations,
   // and at most four chunk statistics per row for the layer kernel's prologue to merge (measured: a 32000-token
@@ -1930,7 +1934,7 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   }
   if (G < 1) G = 1;
   if (G > 256) G = 256;
-  const long long cap = VL_DYN_LDS_BYTES / 16;
+  const long long cap = VL_DYN_LDS_BYTES / (alias ? 8 : 16);   // one array instead of two when q_beam is p_beam
   pl.G = G;
   // exchange slots: every workgroup's slots of an exchange start a 128-byte line (no two writers per line)
   {
@@ -1966,6 +1970,9 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p) {
   pl.lds_elems = (int)(need < cap ? need : cap);
   // warping: the candidate lists of a merge (2 x WARP_CAND values and indices) sit in the dynamic LDS
   if (p->top_k > 0 && pl.lds_elems < (3 * WARP_CAND + 1) / 2) pl.lds_elems = (3 * WARP_CAND + 1) / 2;
+  pl.lds_bytes = (size_t)pl.lds_elems * (alias ? 8 : 16);
+  if (p->top_k > 0 && pl.lds_bytes < (size_t)((3 * WARP_CAND + 1) / 2) * 16) pl.lds_bytes = (size_t)((3 * WARP_CAND + 1) / 2) * 16;
+  pl.lds_bytes = (pl.lds_bytes + 15) & ~(size_t)15;
   return pl;
 }
 
@@ -2009,7 +2016,10 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   if (!workspace) return DSBD_ERR_INVALID;
   if (workspace_bytes < dsbd_verify_forest_workspace_bytes(f, in->V, p)) return DSBD_ERR_WORKSPACE;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const VerifyPlan pl = make_verify_plan(f, in->V, p);
+  // the same arrays given for both models (the draft stage does: its draws are the additional layer of a forest of
+  // single-node trees with the draft model in both roles): q_beam is p_beam and is kept, and computed, once
+  const bool alias = in->logits_target == in->logits_draft && in->beam_logp_target == in->beam_logp_draft;
+  const VerifyPlan pl = make_verify_plan(f, in->V, p, alias);
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
@@ -2045,7 +2055,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   sa.n_slot_words = (long long)f->n_prompts * pl.sl.prompt_stride * 2;
   // one extra row of workgroups (blockIdx.y == 0) for the small jobs
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, true, stream);
-  hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, 2), dim3(VS_BLOCK), 0, stream, sa);
+  hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, alias ? 1 : 2), dim3(VS_BLOCK), 0, stream, sa);
   dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, false, stream);
   DSBD_HIP_LAUNCH_CHECK();
 
@@ -2069,6 +2079,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   if (const char* e = getenv("DSBD_VERIFY_TEST_MUTE_WG")) la.mute_wg = atoi(e);   // error-path test hook
   la.G = pl.G; la.I_cap = pl.I_cap; la.sl = pl.sl; la.lds_elems = pl.lds_elems; la.fault = fault;
   la.lds_slice = pl.lds_elems;
+  la.alias = alias ? 1 : 0;
   if (const char* e = getenv("DSBD_VERIFY_LDS_SLICE")) {   // tuning / test knob: largest slice kept in the LDS
     const int v = atoi(e);
     if (v >= 0 && v < la.lds_slice) la.lds_slice = v;
@@ -2080,9 +2091,9 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   // exit on ROCm 7.2 and costs extra launch latency.)
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, true, stream);
   if (p->top_k > 0)
-    hipLaunchKernelGGL(verify_layers_kernel<true>, dim3((unsigned)grid3), dim3(VL_BLOCK), (size_t)pl.lds_elems * 16, stream, la);
+    hipLaunchKernelGGL(verify_layers_kernel<true>, dim3((unsigned)grid3), dim3(VL_BLOCK), pl.lds_bytes, stream, la);
   else
-    hipLaunchKernelGGL(verify_layers_kernel<false>, dim3((unsigned)grid3), dim3(VL_BLOCK), (size_t)pl.lds_elems * 16, stream, la);
+    hipLaunchKernelGGL(verify_layers_kernel<false>, dim3((unsigned)grid3), dim3(VL_BLOCK), pl.lds_bytes, stream, la);
   const hipError_t le = hipGetLastError();
   dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, false, stream);
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;

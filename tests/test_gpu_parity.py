@@ -294,6 +294,28 @@ def test_duplicate_beams_tie_exactly_as_in_a_row_by_row_evaluation():
             gu.compare_verify(res, ref, w)
 
 
+@pytest.mark.parametrize("cfg,kw,top_k,top_p", [("c3", dict(V=5000), 0, 1.0), ("c5", dict(V=40000), 0, 1.0),
+                                                 ("c3", dict(V=5000, draft_top_k=4), 8, 0.9),
+                                                 ("c4", dict(V=3000, n_prompts=5), 0, 1.0)])
+def test_one_model_in_both_roles(cfg, kw, top_k, top_p):
+    """The same arrays given as target and as draft (what the draft stage does): the library keeps and computes
+    the joint once; the result must be what the oracle gives for two equal models (every draft accepted: the
+    ratio is one; the additional layer's samples come from the joint itself)."""
+    import paper_2409_16560_amd as dsbd
+    from oracle import verify as o_verify
+    gu = _gu()
+    w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
+    d = gu.DeviceWorkload(w)
+    for t in (-1.0, 0.7):
+        res = dsbd.dsbd_verify_forest(d.forest, d.logits_p, d.logits_p, d.blp, d.blp, d.u_accept, d.u_resid, d.u_fill,
+                                      W_L=0, W_min=1, W_cap=w.W_cap, t=t, top_k=top_k, top_p=top_p)
+        torch.cuda.synchronize()
+        ref = o_verify.verify_forest(w.tree_prompt, w.tree_off, w.parent, w.token, w.logits_p, w.logits_p,
+                                     w.beam_logp_p, w.beam_logp_p, w.u_accept, w.u_resid, w.u_fill,
+                                     0, 1, w.W_cap, np.float32(t), top_k=top_k, top_p=float(np.float32(top_p)))
+        gu.compare_verify(res, ref, w)
+
+
 def test_warping_switched_off_is_the_plain_path():
     gu = _gu()
     w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=5000)

@@ -180,6 +180,9 @@ size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, 
  *     workgroups from starting; every wait is bounded (3 s by default) and ends in DSBD_FAULT_SYNC_TIMEOUT with
  *     unusable outputs, never in a hang.  Calls on one stream are safe.
  *   - The workspace must not be shared by calls that may overlap.
+ *   - logits_target == logits_draft together with beam_logp_target == beam_logp_draft (one model in both roles,
+ *     as dsbd_draft_layer passes them) is recognised: the joint is then formed once; the results are those of two
+ *     equal models.
  */
 int32_t dsbd_verify_forest(const dsbd_forest* forest, const dsbd_verify_in* in, const dsbd_params* params,
                            const dsbd_verify_out* out,

@@ -893,7 +893,7 @@ int32_t check_pointers(const dsbd_forest* f, const dsbd_kv* kv) {
 
 template <int D, int NRT, int RW, int TW>
 void launch_attn(const AttnArgs& a, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((forest_attention_kernel<D, NRT, RW, TW>), dim3(grid), dim3(256), 0, stream, a);
+  dsbd_launch(DSBD_KERNEL_ATTENTION, forest_attention_kernel<D, NRT, RW, TW>, dim3(grid), dim3(256), 0, stream, a);
 }
 
 template <int D>
@@ -901,11 +901,11 @@ void dispatch_attn(const AttnPlan& p, const AttnArgs& a, int grid, hipStream_t s
   if (p.shared) {
     if constexpr (D == 128) {
       if (p.nrt == 1) {
-        hipLaunchKernelGGL((forest_attention_shared_kernel<D, 8, 1>), dim3(grid), dim3(512), 0, stream, a);
+        dsbd_launch(DSBD_KERNEL_ATTENTION, forest_attention_shared_kernel<D, 8, 1>, dim3(grid), dim3(512), 0, stream, a);
         return;
       }
     }
-    hipLaunchKernelGGL((forest_attention_shared_kernel<D, 4, 2>), dim3(grid), dim3(256), 0, stream, a);
+    dsbd_launch(DSBD_KERNEL_ATTENTION, forest_attention_shared_kernel<D, 4, 2>, dim3(grid), dim3(256), 0, stream, a);
   } else if (p.nrt == 1) {
     launch_attn<D, 1, 1, 4>(a, grid, stream);
   } else {
@@ -966,10 +966,8 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
 
   const long long grid = (long long)f->n_trees * Hkv * p.n_rowblocks * p.nsplit;
   if (grid > 0x7fffffffLL) return DSBD_ERR_UNSUPPORTED;
-  dsbd_timing_mark(DSBD_KERNEL_ATTENTION, true, stream);
   if (D == 128) dispatch_attn<128>(p, a, (int)grid, stream);
   else dispatch_attn<64>(p, a, (int)grid, stream);
-  dsbd_timing_mark(DSBD_KERNEL_ATTENTION, false, stream);
   DSBD_HIP_LAUNCH_CHECK();
 
   const long long n_rows_total = (long long)f->n_nodes * Hq;

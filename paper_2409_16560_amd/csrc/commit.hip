@@ -117,9 +117,7 @@ extern "C" int32_t dsbd_commit_kv(const dsbd_forest* f, const dsbd_kv* src, cons
   const long long slots = (long long)f->n_prompts * W_cap;
   if (chunks > 0x7fffffffLL || slots > 65535) return DSBD_ERR_UNSUPPORTED;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  dsbd_timing_mark(DSBD_KERNEL_KV_COMMIT, true, stream);
-  hipLaunchKernelGGL(commit_kv_kernel, dim3((unsigned)chunks, (unsigned)slots, 2), dim3(CM_BLOCK), 0, stream, a);
-  dsbd_timing_mark(DSBD_KERNEL_KV_COMMIT, false, stream);
+  dsbd_launch(DSBD_KERNEL_KV_COMMIT, commit_kv_kernel, dim3((unsigned)chunks, (unsigned)slots, 2), dim3(CM_BLOCK), 0, stream, a);
   DSBD_HIP_LAUNCH_CHECK();
   return DSBD_OK;
 }

@@ -1,6 +1,6 @@
-// Measurement hook: HIP events recorded by the library itself around ONE chosen kernel, on the stream
-// that kernel is launched on, so a benchmark can read that kernel's duration per call without a
-// profiler attached.  Off by default; the only state the library keeps.
+// Measurement hook: HIP events stamped with the start and end of ONE chosen kernel, on the stream that kernel is
+// launched on (extended launch call, see dsbd_launch), so a benchmark can read that kernel's duration per call
+// without a profiler attached.  Off by default; the only state the library keeps.
 #include "common.h"
 #include <vector>
 
@@ -10,16 +10,11 @@ std::vector<hipEvent_t> g_start, g_stop;
 size_t g_used = 0;
 }  // namespace
 
-void dsbd_timing_mark(int kernel_id, bool begin, hipStream_t stream) {
-  if (kernel_id != g_kernel || g_kernel == 0) return;
-  if (begin) {
-    if (g_used >= g_start.size()) return;
-    (void)hipEventRecord(g_start[g_used], stream);
-  } else {
-    if (g_used >= g_stop.size()) return;
-    (void)hipEventRecord(g_stop[g_used], stream);
-    ++g_used;
-  }
+bool dsbd_timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop) {
+  if (kernel_id != g_kernel || g_kernel == 0 || g_used >= g_start.size()) return false;
+  *start = g_start[g_used]; *stop = g_stop[g_used];
+  ++g_used;
+  return true;
 }
 
 extern "C" int32_t dsbd_timing_enable(int32_t kernel_id, int32_t capacity) {

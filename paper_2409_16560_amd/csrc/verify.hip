@@ -2054,9 +2054,8 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   sa.slots = reinterpret_cast<unsigned long long*>(red);
   sa.n_slot_words = (long long)f->n_prompts * pl.sl.prompt_stride * 2;
   // one extra row of workgroups (blockIdx.y == 0) for the small jobs
-  dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, true, stream);
-  hipLaunchKernelGGL(vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, alias ? 1 : 2), dim3(VS_BLOCK), 0, stream, sa);
-  dsbd_timing_mark(DSBD_KERNEL_VOCAB_STATS, false, stream);
+  dsbd_launch(DSBD_KERNEL_VOCAB_STATS, vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, alias ? 1 : 2), dim3(VS_BLOCK), 0,
+              stream, sa);
   DSBD_HIP_LAUNCH_CHECK();
 
   LayersArgs la;
@@ -2089,12 +2088,12 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   // drained by the time this one starts, and every wait inside the kernel is bounded.  (A cooperative launch
   // would also guarantee co-residency against work on other streams, but it made rocprofv3 crash at process
   // exit on ROCm 7.2 and costs extra launch latency.)
-  dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, true, stream);
   if (p->top_k > 0)
-    hipLaunchKernelGGL(verify_layers_kernel<true>, dim3((unsigned)grid3), dim3(VL_BLOCK), pl.lds_bytes, stream, la);
+    dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<true>, dim3((unsigned)grid3), dim3(VL_BLOCK),
+                (unsigned int)pl.lds_bytes, stream, la);
   else
-    hipLaunchKernelGGL(verify_layers_kernel<false>, dim3((unsigned)grid3), dim3(VL_BLOCK), pl.lds_bytes, stream, la);
+    dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<false>, dim3((unsigned)grid3), dim3(VL_BLOCK),
+                (unsigned int)pl.lds_bytes, stream, la);
   const hipError_t le = hipGetLastError();
-  dsbd_timing_mark(DSBD_KERNEL_VERIFY_LAYERS, false, stream);
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
 }

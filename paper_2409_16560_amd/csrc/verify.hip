@@ -1288,7 +1288,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           if (lane == 0) sh.nU = __popcll(vm);
         }
         __syncthreads();
-        if (a.G > 1 && tid < WARP_RESULT_SLOTS) {          // (6) ... and down again: the count, then (index, p, q) each
+        if (a.G > 1 && tid < 1 + 6 * K) {          // (6) ... and down again: the count, then (index, p, q) of at most 2K entries
           const int u = (tid - 1) / 3, f = (tid - 1) % 3;
           double payload = 0.0;
           if (tid == 0) payload = (double)sh.nU;
@@ -1296,7 +1296,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           slot_post(slots + a.sl.d + tid, payload, tag_d);
         }
       } else {
-        if (tid < WARP_RESULT_SLOTS) {
+        if (tid < 1 + 6 * K) {
           double v = 0.0;
           if (!slot_wait(slots + a.sl.d + tid, tag_d, v, a.sync_limit)) give_up();
           const int u = (tid - 1) / 3, f = (tid - 1) % 3;

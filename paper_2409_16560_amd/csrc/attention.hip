@@ -786,6 +786,332 @@ void forest_attention_shared_kernel(AttnArgs a) {
 #endif
 }
 
+// ------------------------------------------------------------------------------------------------
+// The shared-tile kernel with the K/V tiles loaded straight into the LDS (global_load_lds_dwordx4: a wave's 64
+// lanes fill 1 KiB of consecutive LDS, no staging registers, no LDS stores).  Rows cannot be padded that way, so
+// bank conflicts are avoided by a swizzle instead: the 16-byte piece p of token t sits at position p ^ f(t) of the
+// token's 256-byte row, f(t) = 2 (t & 3) + ((t >> 2) & 1), which spreads both the K operand reads (16 consecutive
+// tokens, one piece) and the transposing V reads (4 consecutive tokens, two pieces) over all banks.  The two
+// tile buffers are four separate LDS arrays and the loop is written out for both, so that the compiler can tell
+// a read of one buffer from the load in flight into the other (it waits for every outstanding LDS-bound load
+// before an LDS read that may alias it).  D = 128, four waves of 32 rows.  Measured against the kernel above on the
+// benchmark shape: 60.5 us against 62.5 (fewer registers, no LDS stores, whole tiles addressed without per-lane
+// arithmetic); a variant with 32-token tiles and three waves per SIMD (168 registers, 11 of them spilled) took 68 us.
+#ifndef DSBD_DMA_AUX
+#define DSBD_DMA_AUX 2        // cache policy of the tile loads: non-temporal, as in the shared-tile kernel
+#endif
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_cvoid_t;
+template <int TILE, int WPE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void forest_attention_dma_kernel(AttnArgs a) {
+  constexpr int D = 128, RW = 4, NRT = 2;
+  constexpr int DS = D / 32, DT = D / 16;
+  constexpr int SLOTS = TILE * 16;          // 16-byte slots of a K or V tile
+  constexpr int ROWS_W = 16 * NRT, ROWS_B = ROWS_W * RW;
+  __shared__ __attribute__((aligned(16))) uint4 kA[SLOTS];
+  __shared__ __attribute__((aligned(16))) uint4 kB[SLOTS];
+  __shared__ __attribute__((aligned(16))) uint4 vA[SLOTS];
+  __shared__ __attribute__((aligned(16))) uint4 vB[SLOTS];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, qd = lane >> 4;
+
+  int bid = blockIdx.x;
+  const int split = bid % a.nsplit; bid /= a.nsplit;
+  const int rb = bid % a.n_rowblocks; bid /= a.n_rowblocks;
+  const int g = bid % a.Hkv;
+  const int b = bid / a.Hkv;
+
+  const dsbd_tree_range tr = dsbd_tree_range_of(b, a.n_nodes, a.tree_off, a.max_tree_nodes);
+  const bool reporter = split == 0 && rb == 0 && g == 0 && wave == 0;
+  if (!tr.valid) {
+    if (reporter && lane == 0) atomicOr(a.fault, tr.bad);
+    return;
+  }
+  const int base = tr.base;
+  const int n_b = min(tr.n_all, DSBD_MAX_TREE_NODES);
+  const int p_mine = dsbd_tree_parent_of(tr, lane, a.parent);
+  const int R = n_b * a.group;
+  if (rb * ROWS_B >= R) return;
+  const int row0 = rb * ROWS_B + wave * ROWS_W;
+  const int n_rows_total = a.n_nodes * a.Hq;
+
+  int Ls = (a.shared_len && a.k_shared_ptr) ? a.shared_len[b] : 0;
+  int Lo = a.len[b];
+  Ls = max(Ls, 0); Lo = max(Lo, 0);
+  int bad = 0;
+  if ((long long)Ls + Lo > a.max_len) { bad |= DSBD_FAULT_BOUNDS; Ls = min(Ls, a.max_len); Lo = min(Lo, a.max_len - Ls); }
+  const long long hoff = (long long)g * a.head_stride;
+  const __bf16* k0 = Ls ? (const __bf16*)a.k_shared_ptr[b] : nullptr;
+  const __bf16* v0 = Ls ? (const __bf16*)a.v_shared_ptr[b] : nullptr;
+  const __bf16* k1 = Lo ? (const __bf16*)a.k_ptr[b] : nullptr;
+  const __bf16* v1 = Lo ? (const __bf16*)a.v_ptr[b] : nullptr;
+  if (Ls && (!k0 || !v0 || (((uintptr_t)k0 | (uintptr_t)v0) & 15))) { bad |= DSBD_FAULT_BOUNDS; Ls = 0; }
+  if (Lo && (!k1 || !v1 || (((uintptr_t)k1 | (uintptr_t)v1) & 15))) { bad |= DSBD_FAULT_BOUNDS; Lo = 0; }
+  if (bad && tid == 0) atomicOr(a.fault, bad);
+  k0 += hoff; v0 += hoff; k1 += hoff; v1 += hoff;
+  const __bf16* k2 = a.k_tree + ((long long)base * a.Hkv + g) * D;
+  const __bf16* v2 = a.v_tree + ((long long)base * a.Hkv + g) * D;
+  const long long stride2 = (long long)a.Hkv * D;
+  const int n0 = (Ls + TILE - 1) / TILE, n1 = (Lo + TILE - 1) / TILE, n2 = (n_b + TILE - 1) / TILE;
+  const int total_tiles = n0 + n1 + n2;
+  const int t_begin = split * (total_tiles / a.nsplit) + min(split, total_tiles % a.nsplit);
+  const int t_end = t_begin + total_tiles / a.nsplit + (split < total_tiles % a.nsplit ? 1 : 0);
+
+  bf16x8 qf[NRT][DS];
+  uint64_t anc[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int r = row0 + rt * 16 + col;
+    const bool live = r < R;
+    const int node = live ? r / a.group : 0;
+    const int head = g * a.group + (live ? r % a.group : 0);
+    anc[rt] = 0ull;
+    const __bf16* qp = a.q + ((long long)(base + node) * a.Hq + head) * D + 8 * qd;
+#pragma unroll
+    for (int j = 0; j < DS; ++j) {
+      if (live) {
+        qf[rt][j] = load_global_bf16x8(qp + 32 * j);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[rt][j][e] = (__bf16)0.0f;
+      }
+    }
+  }
+  floatx4 o[NRT][DT];
+  float m_run[NRT], l_run[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    m_run[rt] = NEG_BIG; l_run[rt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[rt][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  auto locate = [&](int ti, const __bf16*& kp, const __bf16*& vp, long long& stride, int& tok0, int& len, bool& tree) {
+    if (ti < n0) { kp = k0; vp = v0; stride = a.token_stride; tok0 = ti * TILE; len = Ls; tree = false; }
+    else if (ti < n0 + n1) { kp = k1; vp = v1; stride = a.token_stride; tok0 = (ti - n0) * TILE; len = Lo; tree = false; }
+    else { kp = k2; vp = v2; stride = stride2; tok0 = (ti - n0 - n1) * TILE; len = n_b; tree = true; }
+  };
+  auto swz = [](int t) { return ((t & 3) << 1) | ((t >> 2) & 1); };
+  // tile ti -> the LDS arrays Kb / Vb: instruction r of wave w fills slots (4r + w) * 64 .. + 63, i.e. lane L fills
+  // position L % 16 of token 4 (4r + w) + L / 16 and therefore fetches piece (L % 16) ^ f(token)
+  const int ld_piece = (lane & 15) ^ swz((lane >> 4) + 4 * wave);          // (4 (4r + w)) & 7 = 4 (w & 1): f's last bit
+  // A whole tile (no ragged end) needs no per-lane arithmetic at all: the lane's byte offset inside the tile's
+  // first 16 tokens is a constant of the segment, the tile and the 16-token step are uniform.
+  const int ld_tok = 4 * wave + (lane >> 4);
+  auto issue = [&](int ti, auto& Kb, auto& Vb) {
+    const __bf16 *kp, *vp; long long stride; int tok0, len; bool tree;
+    locate(ti, kp, vp, stride, tok0, len, tree);
+    if (tok0 + TILE <= len) {
+      const char* const kb = reinterpret_cast<const char*>(kp + (long long)tok0 * stride);
+      const char* const vb = reinterpret_cast<const char*>(vp + (long long)tok0 * stride);
+      const unsigned int lo = (unsigned int)ld_tok * (unsigned int)(stride * 2) + (unsigned int)(ld_piece * 16);
+#pragma unroll
+      for (int r = 0; r < TILE / 16; ++r) {
+        const long long step = (long long)r * 16 * stride * 2;
+        __builtin_amdgcn_global_load_lds((glb_cvoid_t*)(kb + step + lo), (lds_void_t*)&Kb[(4 * r + wave) * 64], 16, 0, DSBD_DMA_AUX);
+        __builtin_amdgcn_global_load_lds((glb_cvoid_t*)(vb + step + lo), (lds_void_t*)&Vb[(4 * r + wave) * 64], 16, 0, DSBD_DMA_AUX);
+      }
+      return;
+    }
+#pragma unroll
+    for (int r = 0; r < TILE / 16; ++r) {
+      const int t = 4 * (4 * r + wave) + (lane >> 4);
+      const int tok = min(tok0 + t, len - 1);
+      const long long off = (long long)tok * stride + ld_piece * 8;
+      __builtin_amdgcn_global_load_lds((glb_cvoid_t*)(kp + off), (lds_void_t*)&Kb[(4 * r + wave) * 64], 16, 0, DSBD_DMA_AUX);
+      __builtin_amdgcn_global_load_lds((glb_cvoid_t*)(vp + off), (lds_void_t*)&Vb[(4 * r + wave) * 64], 16, 0, DSBD_DMA_AUX);
+    }
+  };
+  // byte offsets of this lane's operand reads inside a tile, without the token-block part (a multiple of 4 KiB)
+  int k_off[DS];                             // K: token col, piece (4 j + qd) ^ f(col)
+#pragma unroll
+  for (int j = 0; j < DS; ++j) k_off[j] = col * 256 + (((4 * j + qd) ^ swz(col)) << 4);
+  int v_off[DT];                             // V: token 4 qd + col / 4, piece (2 dt + (col & 3) / 2) ^ f, half col & 1
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const int t = 4 * qd + (col >> 2);
+    v_off[dt] = t * 256 + (((2 * dt + ((col & 3) >> 1)) ^ swz(t)) << 4) + ((col & 1) << 3);
+  }
+
+  auto compute = [&](int ti, auto& Kb, auto& Vb) {
+    const __bf16 *kp_, *vp_; long long stride_; int tok0, seglen; bool is_tree;
+    locate(ti, kp_, vp_, stride_, tok0, seglen, is_tree);
+    const int nvalid = min(TILE, seglen - tok0);
+    const char* const kl = reinterpret_cast<const char*>(&Kb[0]);
+    const char* const vl = reinterpret_cast<const char*>(&Vb[0]);
+    const bool need_mask = is_tree || nvalid < TILE;
+#pragma unroll
+    for (int ks = 0; ks < TILE / 32; ++ks) {
+      floatx4 s[NRT][2];
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) s[rt][t2] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < DS; ++j) {
+          const bf16x8 kfrag = *reinterpret_cast<const bf16x8*>(kl + (32 * ks + 16 * t2) * 256 + k_off[j]);
+#pragma unroll
+          for (int rt = 0; rt < NRT; ++rt)
+            s[rt][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfrag, qf[rt][j], s[rt][t2], 0, 0, 0);
+        }
+      }
+      bf16x8 pf[NRT];
+      bool raise = false;
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float mx = fmaxf(fmaxf(s[rt][0][0], s[rt][0][1]), fmaxf(s[rt][0][2], s[rt][0][3]));
+        mx = fmaxf(mx, fmaxf(fmaxf(s[rt][1][0], s[rt][1][1]), fmaxf(s[rt][1][2], s[rt][1][3])));
+        raise = raise || (mx * a.scale_log2 > m_run[rt] + REF_SLACK);
+      }
+      if (!need_mask && __builtin_amdgcn_ballot_w64(raise) == 0ull) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          const float nm = -m_run[rt];
+          float psum = 0.f;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float p = __builtin_amdgcn_exp2f(fmaf(s[rt][t2][i], a.scale_log2, nm));
+              psum += p;
+              pf[rt][4 * t2 + i] = (__bf16)p;
+            }
+          l_run[rt] += psum;
+        }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          float sv[8];
+          unsigned okbits = 0;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int t = 32 * ks + 16 * t2 + 4 * qd + i;
+              bool valid = t < nvalid;
+              if (is_tree) valid = valid && ((anc[rt] >> (tok0 + t)) & 1ull);
+              if (valid) okbits |= 1u << (4 * t2 + i);
+              sv[4 * t2 + i] = valid ? s[rt][t2][i] * a.scale_log2 : NEG_BIG;
+            }
+          float mx = sv[0];
+#pragma unroll
+          for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = (mx > m_run[rt] + REF_SLACK) ? mx : m_run[rt];
+          const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+          l_run[rt] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) o[rt][dt] *= alpha;
+          m_run[rt] = m_new;
+          float psum = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float p = ((okbits >> e) & 1u) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
+            psum += p;
+            pf[rt][e] = (__bf16)p;
+          }
+          l_run[rt] += psum;
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        union { v4i16 h[2]; bf16x8 v; } vf;
+        const char* rowp = vl + 32 * ks * 256 + v_off[dt];
+        vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(rowp));
+        vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(rowp + 16 * 256));
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+          o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[rt], o[rt][dt], 0, 0, 0);
+      }
+    }
+  };
+
+  int ti = t_begin;
+  if (ti < t_end) issue(ti, kA, vA);
+  {
+    uint64_t my_anc = 0;
+    const int tb = dsbd_tree_walk(tr, lane, p_mine, a.max_depth, nullptr, reporter ? a.anc_out : nullptr, &my_anc);
+    if (reporter && tb) atomicOr(a.fault, tb);
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      const int r = row0 + rt * 16 + col;
+      const int node = r < R ? r / a.group : 0;
+      const unsigned lo = __shfl((unsigned)my_anc, node), hi = __shfl((unsigned)(my_anc >> 32), node);
+      anc[rt] = r < R ? ((uint64_t)hi << 32) | lo : 0ull;
+    }
+  }
+  // One barrier per tile: it says that every wave's part of tile ti has landed (each wave waits for its own loads
+  // first) and that everybody is done reading the other buffer, into which the next tile is then requested.
+  while (ti < t_end) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+    lds_barrier();
+    if (ti + 1 < t_end) issue(ti + 1, kB, vB);
+    compute(ti, kA, vA);
+    if (++ti >= t_end) break;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    lds_barrier();
+    if (ti + 1 < t_end) issue(ti + 1, kA, vA);
+    compute(ti, kB, vB);
+    ++ti;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();                           // nobody reads a tile any more: the buffers become the output staging
+
+  // ---- partial results of this split: (m, l) per row, and O^T turned back into rows through the LDS (rows of
+  // 512 bytes, 32 rows per array, the 16-byte pieces of a row swizzled by the row number) so that every row leaves
+  // as one contiguous write
+  constexpr int RPA = SLOTS / 32;            // staged rows per array (512 bytes each): 32 or 16
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    l_run[rt] += __shfl_xor(l_run[rt], 16);
+    l_run[rt] += __shfl_xor(l_run[rt], 32);
+    const int rl = wave * ROWS_W + rt * 16 + col;
+    const int r = rb * ROWS_B + rl;
+    if (r < R && qd == 0) {
+      const int node = r / a.group;
+      const int head = g * a.group + r % a.group;
+      const long long prow = (long long)split * n_rows_total + (long long)(base + node) * a.Hq + head;
+      a.part_ml[prow * 2] = m_run[rt];
+      a.part_ml[prow * 2 + 1] = l_run[rt];
+    }
+  }
+  // a wave stages its rows in "its" array, RPA rows at a time (all 32 at once with 64-token tiles, else 16 and 16)
+  uint4* const st = wave == 0 ? kA : (wave == 1 ? kB : (wave == 2 ? vA : vB));
+#pragma unroll
+  for (int round = 0; round < ROWS_W / RPA; ++round) {
+    if (round > 0) __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      if (RPA == 16 && rt != round) continue;
+      const int lr = RPA == 16 ? col : rt * 16 + col;        // row within the array
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        union { floatx4 f; uint4 u; } cv;
+        cv.f = o[rt][dt];
+        st[lr * 32 + ((4 * dt + qd) ^ (col & 7))] = cv.u;
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < 4 * RPA * 32; c += 256) {
+      const int w = c / (RPA * 32), lr = (c / 32) % RPA, part = c & 31;
+      const int rl = w * ROWS_W + (RPA == 16 ? round * 16 + lr : lr);
+      const int r = rb * ROWS_B + rl;
+      if (r < R) {
+        const int node = r / a.group;
+        const int head = g * a.group + r % a.group;
+        const long long prow = (long long)split * n_rows_total + (long long)(base + node) * a.Hq + head;
+        const uint4* const sr = w == 0 ? kA : (w == 1 ? kB : (w == 2 ? vA : vB));
+        const uint4 u = sr[lr * 32 + (part ^ (lr & 7))];
+        *reinterpret_cast<uint4*>(&a.part_o[prow * D + 4 * part]) = u;
+      }
+    }
+  }
+}
+
 // Merge the KV splits of every (node, head) row: out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.
 template <int D>
 __global__ __launch_bounds__(256) void forest_attention_combine_kernel(int n_rows_total, int nsplit,
@@ -902,6 +1228,12 @@ void dispatch_attn(const AttnPlan& p, const AttnArgs& a, int grid, hipStream_t s
     if constexpr (D == 128) {
       if (p.nrt == 1) {
         dsbd_launch(DSBD_KERNEL_ATTENTION, forest_attention_shared_kernel<D, 8, 1>, dim3(grid), dim3(512), 0, stream, a);
+        return;
+      }
+    }
+    if constexpr (D == 128) {
+      if (!getenv("DSBD_ATTN_STAGED")) {     // (knob: the kernel that stages the tiles through registers, for comparison)
+        dsbd_launch(DSBD_KERNEL_ATTENTION, forest_attention_dma_kernel<64, 2>, dim3(grid), dim3(256), 0, stream, a);
         return;
       }
     }

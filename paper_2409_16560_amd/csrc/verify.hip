@@ -172,9 +172,20 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
                  x2 = make_float4(y2.x, y2.y, y2.z, y2.w), x3 = make_float4(y3.x, y3.y, y3.z, y3.w);
     online_add16(m, s, bad, x0, x1, x2, x3);
   }
-  for (; i < body4; i += VS_BLOCK) {
-    const float4 x = r4[i];
-    online_add4(m, s, bad, x.x, x.y, x.z, x.w);
+  if (i < body4) {
+    // the ragged last group, its loads in flight together as well (one after the other they cost a memory latency
+    // each at the end of every workgroup); the places beyond the end hold the most negative finite number, which
+    // changes neither the maximum nor the sum and is no fault
+    f32x4 y[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) y[k] = __builtin_nontemporal_load(&n4[min(i + k * VS_BLOCK, body4 - 1)]);
+    float4 x[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bool in = i + k * VS_BLOCK < body4;
+      x[k] = in ? make_float4(y[k].x, y[k].y, y[k].z, y[k].w) : make_float4(-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX);
+    }
+    online_add16(m, s, bad, x[0], x[1], x[2], x[3]);
   }
   if (tail0 + (int)threadIdx.x < hi) online_add1(m, s, bad, row[tail0 + threadIdx.x]);
 

@@ -80,6 +80,26 @@ def test_forest_attention_random_shapes(sweep):
             raise AssertionError("sweep %d case %d (%s): %s" % (sweep, case, spec, e))
 
 
+@pytest.mark.parametrize("cfg,kw", [("c5", dict(L=333)), ("c5", dict(L=96, Hq=16, Hkv=4, tree_nodes=63, tree="binary_bfs")),
+                                    ("c3", dict(L=300, shared_len=101, Hq=8, Hkv=1))])
+def test_register_staged_tile_kernel(cfg, kw, monkeypatch):
+    """Head size 128 with many rows per K/V stream normally runs the kernel that loads its tiles straight into the
+    LDS; the register-staged kernel (what head size 64 uses) is selected by a knob and must give the same."""
+    gu = _gu()
+    w = make_workload(cfg, V=64, **kw)
+    d = gu.DeviceWorkload(w)
+    ref_out, ref_lse = gu.oracle_attention(w)
+    out, lse, fault = d.attention()
+    torch.cuda.synchronize()
+    monkeypatch.setenv("DSBD_ATTN_STAGED", "1")
+    out2, lse2, fault2 = d.attention()
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0 and int(fault2.item()) == 0
+    gu.compare_attention(w, out, lse, ref_out, ref_lse)
+    gu.compare_attention(w, out2, lse2, ref_out, ref_lse)
+    assert float((out.float() - out2.float()).abs().max()) <= 2e-2
+
+
 def test_shared_prefix_equals_duplicated_prefix():
     gu = _gu()
     w = make_workload("c3", L=160, shared_len=70, V=64)

@@ -651,6 +651,14 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 #pragma unroll
       for (int c = 1; c < 4; ++c)
         if (c < a.nchunk) { online_merge(Mp, Sp, vp[c].x, vp[c].y); online_merge(Mq, Sq, vq[c].x, vq[c].y); }
+    } else if (a.nchunk <= 16) {             // small forests are cut finer (see the plan): the same, sixteen wide
+      float2 vp[16], vq[16];
+#pragma unroll
+      for (int c = 0; c < 16; ++c) { const int cc = min(c, a.nchunk - 1); vp[c] = pp[cc]; vq[c] = pq[cc]; }
+      Mp = vp[0].x; Sp = vp[0].y; Mq = vq[0].x; Sq = vq[0].y;
+#pragma unroll
+      for (int c = 1; c < 16; ++c)
+        if (c < a.nchunk) { online_merge(Mp, Sp, vp[c].x, vp[c].y); online_merge(Mq, Sq, vq[c].x, vq[c].y); }
     } else {
       Mp = pp[0].x; Sp = pp[0].y; Mq = pq[0].x; Sq = pq[0].y;
       for (int c = 1; c < a.nchunk; ++c) { online_merge(Mp, Sp, pp[c].x, pp[c].y); online_merge(Mq, Sq, pq[c].x, pq[c].y); }
@@ -1928,6 +1936,12 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
     const int v = atoi(e);
     if (v >= 1024) target = v;
   }
+  // few rows (a draft step's beams): finer chunks, down to 4k logits and up to 16 per row, until about a thousand
+  // workgroups stream (a workgroup of the pass is bound by memory latency x its number of load rounds)
+  if (!getenv("DSBD_STATS_CHUNK"))
+    while (target > 4096 && (V + target / 2 - 1) / (target / 2) <= 16 &&
+           2LL * f->n_nodes * ((V + target - 1) / target) < 1024)
+      target /= 2;
   pl.nchunk = (V + target - 1) / target;
   pl.chunk = ((V + pl.nchunk - 1) / pl.nchunk + 3) & ~3;
   pl.nchunk = (V + pl.chunk - 1) / pl.chunk;

@@ -253,6 +253,7 @@ struct LayersArgs {
   int lds_slice;         // slices of up to this many elements are kept in the LDS (<= lds_elems)
   int alias;             // one model in both roles (same logits, same beam likelihoods): q_beam IS p_beam, kept once
   long long sync_limit;  // bound of every wait, in ticks of the 100 MHz wall clock
+  unsigned long long nonce;   // base of this launch's exchange tags: no tag of an earlier launch on the same workspace can match
   int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
                          // bounded waits give up and the error path can be exercised without a hang
   int32_t* fault;
@@ -433,8 +434,8 @@ __device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh
 //    this one, which exists only after every reader of the earlier hops is done.
 struct Slot { unsigned long long w0, w1; };
 
-__device__ __forceinline__ unsigned long long exchange_tag(unsigned int epoch) {
-  return (unsigned long long)epoch * 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ unsigned long long exchange_tag(unsigned long long epoch) {
+  return epoch * 0x9E3779B97F4A7C15ull;
 }
 
 __device__ __forceinline__ void slot_post(Slot* s, double v, unsigned long long tag) {
@@ -851,7 +852,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // ===== all-reduce of the 2|I| row sums.  Only the workgroups that hold a piece of row i post its two
     // columns and only those are polled.
     epoch += 1;
-    const unsigned long long rs_tag = exchange_tag(epoch);
+    const unsigned long long rs_tag = exchange_tag(a.nonce + epoch);
     Slot* const rs_bank = slots + a.sl.r + (long long)(l - 1) * a.sl.r_stride;
     if (tid < 2 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
       const double* wp = &sh.u.wpart[(tid >> 1) * VL_WAVES * 2 + (tid & 1)];
@@ -1235,8 +1236,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const int first = g - g % WARP_GROUP;
         const int n_mem = min(WARP_GROUP, a.G - first);
         const int n_groups = (a.G + WARP_GROUP - 1) / WARP_GROUP;
-        const unsigned long long tag_b = exchange_tag(epoch + 1), tag_c = exchange_tag(epoch + 2);
-        tag_d = exchange_tag(epoch + 3);
+        const unsigned long long tag_b = exchange_tag(a.nonce + epoch + 1), tag_c = exchange_tag(a.nonce + epoch + 2);
+        tag_d = exchange_tag(a.nonce + epoch + 3);
         epoch += 3;
         post_list(slots + a.sl.b + (long long)g * a.sl.b_w, tag_b);
         if (g == first) {                    // the group's first workgroup merges the group's lists
@@ -1369,7 +1370,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const double tot = wg_total(f1);      // barrier inside: also publishes the scaled slices
       stamp(27);
       epoch += 1;
-      spec_tag = exchange_tag(epoch);
+      spec_tag = exchange_tag(a.nonce + epoch);
       spec_bank = slots + a.sl.s + (long long)(l - 1) * a.sl.s_stride;
       spec_gbank = slots + a.sl.sc + (long long)(l - 1) * a.sl.sc_stride;
       if (tid == 0) dense_post(spec_bank, a.G, g, tot, spec_tag);
@@ -1464,7 +1465,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       __syncthreads();
       // ... and over the workgroups (same order everywhere), gathered and scanned by one wave
       epoch += 1;
-      const unsigned long long tag = exchange_tag(epoch);
+      const unsigned long long tag = exchange_tag(a.nonce + epoch);
       Slot* bank = slots + a.sl.x[xchg++ & 1];
       if (wave == 0) {
         const double mine = sh.tsum[VL_BLOCK - 1];
@@ -1688,7 +1689,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           return true;
         }
         epoch += 1;
-        const unsigned long long tag = exchange_tag(epoch);
+        const unsigned long long tag = exchange_tag(a.nonce + epoch);
         Slot* bank = slots + a.sl.x[xchg & 1];
         Slot* gbank = slots + a.sl.xc[xchg++ & 1];
         if (wave == 0) {
@@ -1790,7 +1791,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         }
         if (!posted) {
           epoch += 1;
-          x_tag = exchange_tag(epoch);
+          x_tag = exchange_tag(a.nonce + epoch);
           x_bank = slots + a.sl.x[xchg & 1];
           x_gbank = slots + a.sl.xc[xchg++ & 1];
           if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
@@ -2096,6 +2097,8 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
   la.sync_limit = SYNC_LIMIT_TICKS;
   la.mute_wg = -1;
+  static unsigned long long launch_counter = 0;
+  la.nonce = (++launch_counter) << 20;
   if (const char* e = getenv("DSBD_VERIFY_SYNC_LIMIT_US")) {   // bound of the kernel's waits (default 3 s)
     const long long us = atoll(e);
     if (us >= 1 && us <= 10000000LL) la.sync_limit = us * 100;

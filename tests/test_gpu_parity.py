@@ -46,6 +46,133 @@ def test_forest_attention_matches_oracle(cfg, kw):
     print("max abs err out/lse", err, flush=True)
 
 
+# The three main kernels: wave-private K/V streams (at most 32 rows per stream, 16 or 32 of them), the register-staged
+# shared tile (head size 64), the tile loaded straight into the LDS (head size 128); each with a ragged last tile and
+# a shared leading segment whose end falls inside a split.
+SPLIT_KERNELS = [
+    ("wave-private, 15 rows", "c3", dict(L=777, shared_len=301, Hq=8, Hkv=8)),
+    ("wave-private, 30 rows", "c3", dict(L=777, shared_len=301, Hq=8, Hkv=4)),
+    ("shared tile, D=64", "c5", dict(L=1100, shared_len=413, Hq=16, Hkv=4, D=64)),
+    ("tile into LDS, D=128", "c5", dict(L=1100, shared_len=413, Hq=16, Hkv=4)),
+    ("tile into LDS, 63-node trees", "c5", dict(L=600, shared_len=0, Hq=8, Hkv=2, tree_nodes=63, tree="binary_bfs", W=3)),
+]
+
+
+@pytest.mark.parametrize("nsplit", [2, 4, 8])
+@pytest.mark.parametrize("name,cfg,kw", SPLIT_KERNELS)
+def test_forest_attention_with_pinned_kv_splits(name, cfg, kw, nsplit, monkeypatch):
+    """Every main kernel with 2, 4 and 8 KV splits per (tree, KV head, row block) and the merge kernel behind them
+    (the plan of the scaled-down cases would otherwise settle on one or two splits)."""
+    gu = _gu()
+    monkeypatch.setenv("DSBD_ATTN_NSPLIT", str(nsplit))
+    _reload_knobs()
+    try:
+        w = make_workload(cfg, V=64, **kw)
+        print("case", name, kw, "nsplit", nsplit, "N", w.n_nodes, flush=True)
+        d = gu.DeviceWorkload(w)
+        out, lse, fault = d.attention()
+        torch.cuda.synchronize()
+        assert int(fault.item()) == 0
+        ref_out, ref_lse = gu.oracle_attention(w)
+        err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
+        print("max abs err out/lse", err, flush=True)
+    finally:
+        monkeypatch.delenv("DSBD_ATTN_NSPLIT")
+        _reload_knobs()
+
+
+def _reload_knobs():
+    import paper_2409_16560_amd as dsbd
+    if hasattr(dsbd, "dsbd_reload_knobs"):
+        dsbd.dsbd_reload_knobs()
+
+
+def _plant_outlier_keys(w, beta=8.0, seed=7):
+    """Overwrites a few keys so that one query row each scores far above everything it has seen: key = beta x that
+    row's query (exact in bf16 for a power of two), i.e. beta |q|^2 / sqrt(D) ~ 90 (64 at head size 64) against N(0,1) scores.  Places:
+    late in the own prefix segment, at the end of the shared segment, in the first tile, and among the tree rows (an
+    ancestor's key).  Returns the (node, head) rows that now have such a key."""
+    from dsbd_synth import bf16_bits_to_f32, f32_to_bf16_bits
+    rng = np.random.default_rng(seed)
+    group = w.Hq // w.Hkv
+    hit = []
+    qf = bf16_bits_to_f32(w.q)
+    for b in range(w.n_trees):
+        a0, a1 = int(w.tree_off[b]), int(w.tree_off[b + 1])
+        p = int(w.tree_prompt[b])
+        own, sh = int(w.own_len[b]), int(w.shared_len[b])
+        places = []
+        if own > 0:
+            places += [("own", own - 1 - int(rng.integers(0, min(own, 40)))), ("own", int(rng.integers(0, own)))]
+        if sh > 0 and b == int(np.argmax(w.tree_prompt == p)):
+            places += [("shared", sh - 1)]
+        if own > 3:
+            places += [("own", 2)]
+        for kind, pos in places:
+            n = int(rng.integers(a0, a1)); h = int(rng.integers(0, w.Hq)); g = h // group
+            key = f32_to_bf16_bits(np.float32(beta) * qf[n, h])
+            if kind == "own":
+                w.k_own[b][pos, g, :] = key
+            else:
+                w.k_shared[p][pos, g, :] = key
+            hit.append((n, h))
+        if a1 - a0 >= 2:
+            # a tree row: the key of node n's parent, tuned to n's query
+            n = int(rng.integers(a0 + 1, a1)); h = int(rng.integers(0, w.Hq)); g = h // group
+            w.k_tree[int(w.parent[n]), g, :] = f32_to_bf16_bits(np.float32(beta) * qf[n, h])
+            hit.append((n, h))
+    return hit
+
+
+@pytest.mark.parametrize("name,cfg,kw", SPLIT_KERNELS)
+@pytest.mark.parametrize("nsplit", [1, 4])
+def test_forest_attention_outlier_scores_raise_the_reference(name, cfg, kw, nsplit, monkeypatch):
+    """The kernels keep a per-row softmax reference that is only raised when a score exceeds it by 2^40, and then
+    rescale what they have accumulated.  Random N(0,1) caches never get there after a row's first step, so keys tuned
+    to single query rows are planted late in the prefix, at the end of the shared segment and among the tree rows:
+    the reference rises in mid-stream, with non-zero accumulators, inside and across KV splits."""
+    gu = _gu()
+    monkeypatch.setenv("DSBD_ATTN_NSPLIT", str(nsplit))
+    _reload_knobs()
+    try:
+        w = make_workload(cfg, V=64, **kw)
+        hit = _plant_outlier_keys(w)
+        d = gu.DeviceWorkload(w)
+        out, lse, fault = d.attention()
+        torch.cuda.synchronize()
+        assert int(fault.item()) == 0
+        ref_out, ref_lse = gu.oracle_attention(w)
+        # the planted keys do dominate their rows (the case tests what it says): 2^40 is 27.7 in natural units
+        assert min(ref_lse[n, h] for n, h in hit) > 35.0
+        err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
+        print("case", name, "nsplit", nsplit, "rows with a planted key", len(hit), "max abs err out/lse", err, flush=True)
+    finally:
+        monkeypatch.delenv("DSBD_ATTN_NSPLIT")
+        _reload_knobs()
+
+
+@pytest.mark.parametrize("name,cfg,kw", SPLIT_KERNELS)
+@pytest.mark.parametrize("scale", [0.03, 0.25, 2.0])
+def test_forest_attention_explicit_scale(name, cfg, kw, scale):
+    """A caller-supplied softmax scale instead of 1/sqrt(D): flatter than the default, sharper, and so sharp
+    (score deviations of tens of units) that new maxima more than 2^40 above the reference keep turning up along the
+    prefix and the softmax is close to one-hot."""
+    gu = _gu()
+    from oracle import attention as o_attn
+    w = make_workload(cfg, V=64, **kw)
+    d = gu.DeviceWorkload(w)
+    out, lse, fault = d.attention(scale=scale)
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0
+    pk, pv = zip(*[gu.logical_prefix(w, t) for t in range(w.n_trees)])
+    ref_out, ref_lse = o_attn.forest_attention(w.parent, w.tree_off, gu.f64(w.q), gu.f64(w.k_tree), gu.f64(w.v_tree),
+                                               list(pk), list(pv), scale=scale)
+    # the lse tolerance is absolute on a quantity that now reaches hundreds: bf16 keys and queries are exact inputs on
+    # both sides and the scores are fp32 sums of exact products, so the absolute bound still holds up to scale 2
+    err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
+    print("case", name, "scale", scale, "max abs err out/lse", err, "largest lse", float(np.max(ref_lse)), flush=True)
+
+
 @pytest.mark.parametrize("sweep", [0, 1])
 def test_forest_attention_random_shapes(sweep):
     """Randomized sweep: tree shapes up to 64 nodes, head groupings, both head sizes, prefix lengths from nothing to

@@ -74,6 +74,11 @@ def test_forest_equals_masked_library_attention(cfg, kw):
         ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=torch.from_numpy(mask))[0].permute(1, 0, 2).numpy()
         assert np.max(np.abs(ref - out[a:b])) < 1e-12
         assert (tree[a:b] == t).all()
+        # the log-sum-exp of every row against the library's, over the scores that the brute-force mask leaves
+        scores = torch.einsum("hnd,hmd->hnm", tq[0], tk[0]) / 8.0                         # [Hq,n,L+n], D = 64
+        scores = scores.masked_fill(~torch.from_numpy(mask)[None], float("-inf"))
+        ref_lse = torch.logsumexp(scores, dim=-1).permute(1, 0).numpy()                   # [n,Hq]
+        assert np.max(np.abs(ref_lse - lse[a:b])) < 1e-12
 
 
 def test_gqa_with_all_heads_equals_mha_and_sibling_permutation():

@@ -198,3 +198,28 @@ def test_accept_count_table_is_the_exact_accept_count_distribution(W_in, M, V):
     alpha = verify.acceptance_chain(p_ref, q_ref, M)
     P = verify.accept_count_table(alpha, M)
     assert np.max(np.abs(P[M] - hist)) < 1e-12
+
+    # Eq. 6: W~(t) = the largest K such that at least K of the M drafts are accepted with probability >= t, read off
+    # the ENUMERATED accept-count histogram (not the oracle's table), for thresholds just below and just above every
+    # tail probability.  Summing from k = 1 as Eq. 4 prints it (instead of from k = 0) adds P(no draft accepted) to
+    # every tail and must come out wrong for at least one of these thresholds.
+    tails = [float(hist[K:].sum()) for K in range(M + 1)]          # P(at least K accepted), K = 0..M (enumerated)
+    assert abs(tails[0] - 1.0) < 1e-12 and all(a >= b for a, b in zip(tails, tails[1:]))
+    assert hist[0] > 1e-3                                           # the two readings do differ on this case
+    planted_differs = False
+    for K in range(1, M + 1):
+        for t in (tails[K] - 1e-7, tails[K] + 1e-7):
+            if not 0.0 < t < 1.0:
+                continue
+            want = max(k for k in range(M + 1) if tails[k] >= t)
+            got = verify.dynamic_width(p_ref, q_ref, M, t, 1, 16)[1]
+            assert got == want, (K, t, got, want)
+            # the variant that starts the sum at k = 1
+            planted = max(k for k in range(M + 1) if 1.0 - float(hist[1:k].sum()) >= t)
+            planted_differs |= planted != want
+    assert planted_differs
+    # and the floor / the cap around it: W_L = min(W_cap, max(W_min, W~))
+    t_mid = 0.5 * (tails[1] + tails[2]) if M >= 2 else 0.5 * tails[1]
+    wt = verify.dynamic_width(p_ref, q_ref, M, t_mid, 1, 16)[1]
+    assert verify.dynamic_width(p_ref, q_ref, M, t_mid, wt + 1, 16)[0] == wt + 1
+    assert verify.dynamic_width(p_ref, q_ref, M, 0.0, 1, M - 1 if M > 1 else 1)[0] == (M - 1 if M > 1 else 1)

@@ -308,6 +308,13 @@ int32_t dsbd_build_forest(int32_t n_prompts, int32_t n_roots, int32_t gamma, int
                           const dsbd_forest_out* out, int32_t* fault, void* stream);
 
 /*
+ * Tuning overrides (no counterpart in the paper).  The library reads its DSBD_* environment variables (numbers of
+ * KV splits and of workgroups per prompt, chunk sizes, the bound of the layer kernel's waits, test hooks) ONCE per
+ * process, at the first call that needs them; dsbd_reload_knobs() reads them again.  Host call, no GPU work.
+ */
+void dsbd_reload_knobs(void);
+
+/*
  * Measurement hook (no counterpart in the paper).  dsbd_timing_enable(kernel, capacity) makes the
  * library record a pair of HIP events around every launch of ONE of its kernels, on the stream the
  * kernel is launched on, for up to `capacity` launches; dsbd_timing_collect() waits for the recorded

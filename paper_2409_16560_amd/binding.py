@@ -121,6 +121,8 @@ def load_library():
     lib.dsbd_build_forest.restype = C.c_int32
     lib.dsbd_build_forest.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(_ForestOut), C.c_void_p, C.c_void_p]
+    lib.dsbd_reload_knobs.restype = None
+    lib.dsbd_reload_knobs.argtypes = []
     lib.dsbd_timing_enable.restype = C.c_int32
     lib.dsbd_timing_enable.argtypes = [C.c_int32, C.c_int32]
     lib.dsbd_timing_collect.restype = C.c_int32
@@ -456,6 +458,11 @@ def dsbd_build_forest(root_off, layer_parent, layer_token, root_token=None, *, n
     f = Forest(tree_prompt[:n_roots], tree_off[:n_roots + 1], parent[:N], token[:N], rank[:N], n_prompts=P,
                max_tree_nodes=64, max_depth=gamma, max_prompt_trees=int(max_prompt_trees), device=dev)
     return f, node_of_root[:n_roots], node_of[:gamma * P * W_S].view(gamma, P * W_S) if gamma else node_of[:0], mx, fault
+
+
+def dsbd_reload_knobs():
+    """Read the tuning overrides (DSBD_* environment variables) again; the library reads them once per process."""
+    load_library().dsbd_reload_knobs()
 
 
 def dsbd_timing_enable(kernel: int, capacity: int = 0):

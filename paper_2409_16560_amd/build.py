@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsbd.so")
-SOURCES = ["attention.hip", "verify.hip", "select.hip", "commit.hip", "draft.hip", "timing.hip"]
+SOURCES = ["attention.hip", "verify.hip", "select.hip", "commit.hip", "draft.hip", "timing.hip", "knobs.hip"]
 # Per-file flags.  attention.hip: scores come out of the matrix units and go through max / exp2 only; without
 # -fno-honor-nans every fmaxf operand is first canonicalised (v_max x, x), which triples the instructions of the
 # row-maximum checks.  (verify.hip must keep NaN semantics: it detects non-finite logits.)

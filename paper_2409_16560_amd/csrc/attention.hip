@@ -1176,7 +1176,7 @@ AttnPlan make_plan(const dsbd_forest* f, const dsbd_kv* kv, int Hq, int Hkv) {
   if (rmax <= 16) { p.nrt = 1; p.rw = 1; p.tw = 4; }
   else if (rmax <= 32) { p.nrt = 2; p.rw = 1; p.tw = 4; }
   else { p.nrt = 2; p.rw = 4; p.tw = 1; p.shared = true; p.step = 64; }   // 128 rows per workgroup
-  if (p.shared && getenv("DSBD_ATTN_WAVES8")) { p.nrt = 1; p.rw = 8; }   // tuning knob: 8 waves x 16 rows
+  if (p.shared && dsbd_knobs().attn_waves8) { p.nrt = 1; p.rw = 8; }   // tuning knob: 8 waves x 16 rows
   p.rows_block = 16 * p.nrt * p.rw;
   p.n_rowblocks = (rmax + p.rows_block - 1) / p.rows_block;
   // enough workgroups to cover the chip several times, but at least two steps per wave and split
@@ -1192,8 +1192,8 @@ AttnPlan make_plan(const dsbd_forest* f, const dsbd_kv* kv, int Hq, int Hkv) {
   p.nsplit = want < by_steps ? want : by_steps;
   if (p.nsplit > by_traffic) p.nsplit = by_traffic;
   if (p.nsplit > 64) p.nsplit = 64;
-  if (const char* e = getenv("DSBD_ATTN_NSPLIT")) {      // tuning knob: KV splits per (tree, KV head, row block)
-    const int v = atoi(e);
+  {      // tuning knob: KV splits per (tree, KV head, row block)
+    const int v = dsbd_knobs().attn_nsplit;
     if (v >= 1 && v <= 64) p.nsplit = v;
   }
   return p;
@@ -1232,7 +1232,7 @@ void dispatch_attn(const AttnPlan& p, const AttnArgs& a, int grid, hipStream_t s
       }
     }
     if constexpr (D == 128) {
-      if (!getenv("DSBD_ATTN_STAGED")) {     // (knob: the kernel that stages the tiles through registers, for comparison)
+      if (!dsbd_knobs().attn_staged) {     // (knob: the kernel that stages the tiles through registers, for comparison)
         dsbd_launch(DSBD_KERNEL_ATTENTION, forest_attention_dma_kernel<64, 2>, dim3(grid), dim3(256), 0, stream, a);
         return;
       }
@@ -1294,7 +1294,7 @@ extern "C" int32_t dsbd_forest_attention(const dsbd_forest* f, const dsbd_kv* kv
   a.scale_log2 = sc * 1.4426950408889634f;
   a.nsplit = p.nsplit; a.n_rowblocks = p.n_rowblocks; a.max_len = kv->max_len;
   a.part_o = part_o; a.part_ml = part_ml; a.fault = fault;
-  a.trace = getenv("DSBD_ATTN_TRACE") ? trace : nullptr;
+  a.trace = dsbd_knobs().attn_trace ? trace : nullptr;
 
   const long long grid = (long long)f->n_trees * Hkv * p.n_rowblocks * p.nsplit;
   if (grid > 0x7fffffffLL) return DSBD_ERR_UNSUPPORTED;

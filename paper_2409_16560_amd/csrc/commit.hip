@@ -18,7 +18,7 @@ struct CommitArgs {
   const __bf16 *k_tree, *v_tree;            // [n_nodes, Hkv, D]
   const int32_t *n_next, *src_tree, *path_len, *path;
   void* const* dst_k; void* const* dst_v; int32_t* dst_len;
-  int capacity;
+  int capacity, max_len;
   int32_t* fault;
 };
 
@@ -38,14 +38,24 @@ __global__ __launch_bounds__(CM_BLOCK) void commit_kv_kernel(CommitArgs a) {
     if (speaker) { a.dst_len[j] = 0; atomicOr(a.fault, DSBD_FAULT_TOPOLOGY); }
     return;
   }
-  const int L = max(a.src_len[b], 0);
+  // the source length is the caller's: the grid covers max_len + path tokens, so a longer source cannot be copied
+  const int L_raw = a.src_len[b];
+  const int L = max(0, min(L_raw, a.max_len));
   const int pl = max(0, min(a.path_len[j], a.plen));
   const int total = L + pl;
-  const char* src = static_cast<const char*>(is_v ? a.src_v[b] : a.src_k[b]);
-  char* dst = static_cast<char*>(is_v ? a.dst_v[j] : a.dst_k[j]);
-  const bool bad = total > a.capacity || !dst || (L > 0 && !src) ||
-                   ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15);
-  if (bad) {      // uniform over the workgroup: the destination is left untouched
+  // Both planes are checked by every workgroup (the K and the V workgroups of a destination must take the same
+  // decision: a destination with a usable K buffer and a null or misaligned V buffer is left untouched as a whole).
+  const char* src_kp = static_cast<const char*>(a.src_k[b]);
+  const char* src_vp = static_cast<const char*>(a.src_v[b]);
+  char* dst_kp = static_cast<char*>(a.dst_k[j]);
+  char* dst_vp = static_cast<char*>(a.dst_v[j]);
+  const bool bad = L_raw < 0 || L_raw > a.max_len || total > a.capacity || !dst_kp || !dst_vp ||
+                   (L > 0 && (!src_kp || !src_vp)) ||
+                   ((reinterpret_cast<uintptr_t>(dst_kp) | reinterpret_cast<uintptr_t>(src_kp) |
+                     reinterpret_cast<uintptr_t>(dst_vp) | reinterpret_cast<uintptr_t>(src_vp)) & 15);
+  const char* src = is_v ? src_vp : src_kp;
+  char* dst = is_v ? dst_vp : dst_kp;
+  if (bad) {      // uniform over the destination's workgroups: the destination is left untouched
     if (speaker) { a.dst_len[j] = 0; atomicOr(a.fault, DSBD_FAULT_BOUNDS); }
     return;
   }
@@ -110,7 +120,7 @@ extern "C" int32_t dsbd_commit_kv(const dsbd_forest* f, const dsbd_kv* src, cons
   a.token_stride = src->token_stride; a.head_stride = src->head_stride;
   a.k_tree = static_cast<const __bf16*>(k_tree); a.v_tree = static_cast<const __bf16*>(v_tree);
   a.n_next = next->n_next; a.src_tree = next->src_tree; a.path_len = next->path_len; a.path = next->path;
-  a.dst_k = dst->k_ptr; a.dst_v = dst->v_ptr; a.dst_len = dst->len; a.capacity = dst->capacity;
+  a.dst_k = dst->k_ptr; a.dst_v = dst->v_ptr; a.dst_len = dst->len; a.capacity = dst->capacity; a.max_len = src->max_len;
   a.fault = fault;
   const long long max_tokens = (long long)src->max_len + a.plen;
   const long long chunks = (max_tokens + CM_TOKENS - 1) / CM_TOKENS;

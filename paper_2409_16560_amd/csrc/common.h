@@ -30,6 +30,22 @@ struct WorkspaceCarver {
   size_t total() const { return dsbd_align_up(used, 256); }
 };
 
+// Tuning overrides and test hooks from the environment, read once per process (knobs.hip).
+struct DsbdKnobs {
+  int attn_nsplit;             // DSBD_ATTN_NSPLIT: KV splits per (tree, KV head, row block); 0 = the plan's choice
+  bool attn_waves8;            // DSBD_ATTN_WAVES8: 8 waves x 16 rows in the shared-tile kernel
+  bool attn_staged;            // DSBD_ATTN_STAGED: the register-staged tile kernel also for head size 128
+  bool attn_trace;             // DSBD_ATTN_TRACE: timeline of the attention kernel (instrumented builds)
+  int stats_chunk;             // DSBD_STATS_CHUNK: logits per workgroup of the statistics pass; 0 = the plan's choice
+  int verify_g;                // DSBD_VERIFY_G: workgroups per prompt of the layer kernel; 0 = the plan's choice
+  bool verify_trace;           // DSBD_VERIFY_TRACE: timeline of the layer kernel into the workspace
+  long long verify_sync_limit_us;   // DSBD_VERIFY_SYNC_LIMIT_US: bound of every wait of the layer kernel; 0 = default
+  int verify_mute_wg;          // DSBD_VERIFY_TEST_MUTE_WG: test hook, this workgroup withholds its first post; -1 = none
+  int verify_lds_slice;        // DSBD_VERIFY_LDS_SLICE: largest joint slice kept in the LDS; -1 = the plan's choice
+  int verify_overlap;          // DSBD_VERIFY_OVERLAP: 0 = statistics pass and layer kernel one after the other
+};
+const DsbdKnobs& dsbd_knobs();
+
 // Measurement hook (timing.hip).  When timing is enabled for `kernel_id`, the launch goes through HIP's extended
 // launch call, which stamps a pair of events with the kernel's own start and end on the device (what a profiler's
 // kernel trace reports); a pair of hipEventRecord calls around an ordinary launch would also count the dispatch

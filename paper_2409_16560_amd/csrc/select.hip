@@ -7,8 +7,11 @@
 // lowest perplexity is the highest cumulative target log-likelihood (ties: lowest output index).
 #include "common.h"
 
+#define SELECT_LDS_TREES 8192
+
 struct SelectArgs {
   int n_prompts, n_trees, n_nodes, W_cap, Lmax, keep_one;
+  int toff_in_lds;       // tree_off staged in the dynamic LDS (forests of up to SELECT_LDS_TREES trees), else read in place
   const int32_t *tree_off, *parent;
   const int32_t *n_out, *out_parent, *out_token;
   const double *out_lp, *out_lq;
@@ -26,7 +29,9 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
   __shared__ int best;
   __shared__ int path_lds[64][DSBD_MAX_TREE_NODES + 1];   // one row per output beam (padded against bank conflicts)
   extern __shared__ int toff_lds[];                       // tree_off[0 .. n_trees], staged once for the searches
-  for (int t = j; t <= a.n_trees; t += 64) toff_lds[t] = a.tree_off[t];
+  if (a.toff_in_lds)
+    for (int t = j; t <= a.n_trees; t += 64) toff_lds[t] = a.tree_off[t];
+  const int* const toff = a.toff_in_lds ? toff_lds : a.tree_off;
   if (j == 0) {
     best = 0;
     if (a.keep_one)
@@ -69,7 +74,7 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
   int tree = -1;
   if (root >= 0) {
     int lo = 0, hi = a.n_trees;
-    while (lo < hi) { const int mid = (lo + hi) >> 1; if (toff_lds[mid + 1] <= root) lo = mid + 1; else hi = mid; }
+    while (lo < hi) { const int mid = (lo + hi) >> 1; if (toff[mid + 1] <= root) lo = mid + 1; else hi = mid; }
     tree = lo < a.n_trees ? lo : -1;
   }
   a.nx.src_tree[o] = tree;
@@ -100,8 +105,11 @@ extern "C" int32_t dsbd_select_beams(const dsbd_forest* f, const dsbd_verify_out
   a.n_out = v->n_out; a.out_parent = v->out_parent; a.out_token = v->out_token;
   a.out_lp = v->out_logp_target; a.out_lq = v->out_logp_draft;
   a.nx = *nx; a.fault = fault;
-  const size_t toff_bytes = ((size_t)f->n_trees + 1) * sizeof(int32_t);
-  if (toff_bytes > 64 * 1024) return DSBD_ERR_UNSUPPORTED;
+  // static (16.6 KB) + dynamic LDS must stay within the 64 KB a launch gets without asking for more: larger forests
+  // search tree_off where it lies
+  size_t toff_bytes = ((size_t)f->n_trees + 1) * sizeof(int32_t);
+  a.toff_in_lds = toff_bytes <= SELECT_LDS_TREES * sizeof(int32_t) ? 1 : 0;
+  if (!a.toff_in_lds) toff_bytes = 0;
   hipLaunchKernelGGL(select_beams_kernel, dim3(f->n_prompts), dim3(64), toff_bytes, static_cast<hipStream_t>(stream_), a);
   DSBD_HIP_LAUNCH_CHECK();
   return DSBD_OK;

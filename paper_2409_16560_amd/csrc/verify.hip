@@ -28,12 +28,17 @@
 #include <float.h>
 #include <limits.h>
 #include <stdlib.h>
+#include <atomic>
+#include <mutex>
 
 #define VS_BLOCK 256
 #define VL_BLOCK 512
 #define NODE_CAP 512           // nodes of one prompt (all its trees)
 #define NEAR_TIE 1.0e-6
 #define SYNC_LIMIT_TICKS 300000000LL   // default bound of every wait: 3 s of the 100 MHz wall clock
+#define XU 4                   // logits per thread and model in flight in the exponential pass.  Eight (a 4008-entry piece of the
+                               // benchmark's joint in one round) cost 256 vector registers; with four the kernel needs 186,
+                               // which leaves room on every SIMD for waves of the statistics pass running beside it
 #define VL_DYN_LDS_BYTES (80 * 1024)   // dynamic LDS of the layer kernel (its static LDS takes most of the rest)
 
 // ------------------------------------------------------------------------------------------------ kernel 1
@@ -42,13 +47,6 @@ struct StatsArgs {
   int n_nodes, V, nchunk, chunk;
   float2* part;      // [2][n_nodes][nchunk] (max, sum of exp(x - max))
   int32_t* fault;
-  // service workgroups (blockIdx.y == 0)
-  int n_trees, n_prompts, max_tree_nodes, max_depth;
-  const int32_t *tree_prompt, *tree_off, *parent;
-  int32_t* depth;              // [n_nodes]
-  int4* prompt_rec;            // [n_prompts] (first tree, end tree, first node, end node) of every prompt
-  unsigned long long* slots;   // exchange slots of the layer kernel, cleared here
-  long long n_slot_words;
 };
 
 // 2^x by the hardware instruction alone: results below 2^-126 come out as zero instead of denormal, which a sum
@@ -109,44 +107,8 @@ __device__ __forceinline__ void online_merge(float& m, float& s, float m2, float
   m = mn;
 }
 
-// The small jobs done by the extra row of workgroups (blockIdx.y == 0) while the others stream.
-__device__ void stats_service(const StatsArgs& a, int sidx, int n_service) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // exchange slots of the layer kernel: a slot is valid only with the tag of its exchange, so zeros never are
-  ulonglong2* const s2 = reinterpret_cast<ulonglong2*>(a.slots);     // the slot array is 256-byte aligned
-  for (long long k = (long long)sidx * VS_BLOCK + tid; k < a.n_slot_words / 2; k += (long long)n_service * VS_BLOCK)
-    s2[k] = make_ulonglong2(0ull, 0ull);
-  // forest topology, one wave per tree
-  for (int b = sidx * (VS_BLOCK / 64) + wave; b < a.n_trees; b += n_service * (VS_BLOCK / 64)) {
-    const int bad = dsbd_tree_topology(b, lane, a.n_nodes, a.tree_off, a.parent, a.max_tree_nodes, a.max_depth,
-                                       a.depth, nullptr, nullptr);
-    if (bad) atomicOr(a.fault, bad);
-  }
-  // trees of each prompt (tree_prompt is non-decreasing): counted by one wave, so that the layer kernel starts
-  // from this record instead of searching with dependent loads of its own
-  for (int p = sidx * (VS_BLOCK / 64) + wave; p < a.n_prompts; p += n_service * (VS_BLOCK / 64)) {
-    int lt = 0, le = 0;
-    for (int t = lane; t < a.n_trees; t += 64) {
-      const int tp = a.tree_prompt[t];
-      lt += tp < p; le += tp <= p;
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) { lt += __shfl_xor(lt, off); le += __shfl_xor(le, off); }
-    if (lane == 0) {
-      int4 rec = make_int4(lt, le, 0, 0);
-      if (le > lt) { rec.z = a.tree_off[lt]; rec.w = a.tree_off[le]; }
-      a.prompt_rec[p] = rec;
-    }
-  }
-}
-
 __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
-  // row 0 of the grid does the small jobs (dispatched first: done long before the streaming rows are)
-  const int c = blockIdx.x, n = (int)blockIdx.y - 1, which = blockIdx.z;
-  if (n < 0) {                // uniform over the workgroup
-    stats_service(a, which * gridDim.x + c, (int)(gridDim.z * gridDim.x));
-    return;
-  }
+  const int c = blockIdx.x, n = (int)blockIdx.y, which = blockIdx.z;
   const int lo = c * a.chunk;
   const int hi = min(a.V, lo + a.chunk);
   const float* row = a.z[which] + (long long)n * a.V;
@@ -211,6 +173,41 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_stats_kernel(StatsArgs a) {
   }
 }
 
+// Per-node outputs of the statistics pass: the chunks of a row merged into its fp32 log-sum-exp, and the
+// log-probability of each node's own token under its parent's row (Section 2.1: the likelihood a beam stores grows by
+// this term).  One thread per node; the parent's chunks are merged again by the child (a handful of values).
+struct FinishArgs {
+  const float* z[2];
+  int n_nodes, V, nchunk, alias;
+  const float2* part;
+  const int32_t *parent, *token;
+  float *lse[2], *logp[2];     // outputs (any may be null)
+};
+
+__device__ __forceinline__ float merged_lse(const float2* pp, int nchunk) {
+  float M = pp[0].x, S = pp[0].y;
+  for (int c = 1; c < nchunk; ++c) online_merge(M, S, pp[c].x, pp[c].y);
+  return M + logf(S);
+}
+
+__global__ __launch_bounds__(VS_BLOCK) void vocab_finish_kernel(FinishArgs a) {
+  const int n = blockIdx.x * VS_BLOCK + threadIdx.x;
+  if (n >= a.n_nodes) return;
+  const int par = a.parent[n];
+  const int tok = a.token[n];
+  const bool has_parent = par >= 0 && par < n && tok >= 0 && tok < a.V;
+#pragma unroll
+  for (int m = 0; m < 2; ++m) {
+    const float2* base = a.part + (a.alias ? 0 : (long long)m * a.n_nodes * a.nchunk);
+    if (a.lse[m]) a.lse[m][n] = merged_lse(base + (long long)n * a.nchunk, a.nchunk);
+    if (a.logp[m]) {
+      float lp = 0.f;
+      if (has_parent) lp = a.z[m][(long long)par * a.V + tok] - merged_lse(base + (long long)par * a.nchunk, a.nchunk);
+      a.logp[m][n] = lp;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ kernel 2
 // Where the exchanges of one prompt keep their 16-byte slots (offsets in slots from the prompt's first one).
 struct SlotLayout {
@@ -239,10 +236,8 @@ struct LayersArgs {
   int top_k;             // warping T (Section 2.1): keep the top_k largest entries of each joint (0: T is the identity) ...
   float top_p;           // ... then the smallest leading part of those whose share of the kept mass exceeds top_p
   dsbd_verify_out out;
-  const int32_t* depth;
-  const int4* prompt_rec; // [n_prompts] (first tree, end tree, first node, end node)
-  const float2* part;    // [2][n_nodes][nchunk] row statistics per chunk (max, sum of exp(x - max))
-  int nchunk;
+  int prompt0;           // first prompt of this launch (forests of more prompts than fit the device run in groups)
+  int max_tree_nodes;
   double* pb;            // [n_prompts][G][slice_cap]  p_beam slice storage, a private region per workgroup
   double* qb;            // the same for q_beam
   long long slice_cap;   // elements of a workgroup's region
@@ -270,6 +265,10 @@ struct LayerShared {
   double cum_p[64], cum_q[64];       // cumulative log-likelihoods of the input beams
   double lse_p[64], lse_q[64];       // fp64 log-sum-exp of their logit rows
   double max_p[64], max_q[64];       // exact row maxima
+  double lm_p[64], lm_q[64];         // maxima of this workgroup's pieces of its rows (row i_lo first)
+  float wmax[2][2 * VL_WAVES];       // per-wave maxima of a piece, two rows in flight
+  double tmax[VL_BLOCK];             // partial row maxima of the gathering threads
+  double colmax[128];                // maxima of the (row, model) columns
   double sp[64], sq[64];             // beam weight / row sum: p_beam(i,x) = exp(z - max) * sp[i]
   double bw_p[64], bw_q[64];         // beam weights
   // accepted beams of the layer (next layer's inputs): node and its position among the candidates
@@ -279,8 +278,6 @@ struct LayerShared {
   int n_parent[NODE_CAP], n_token[NODE_CAP], n_rank[NODE_CAP];
   short n_depth[NODE_CAP];
   float n_u[NODE_CAP];               // accept uniform of each node
-  float n_maxp[NODE_CAP], n_maxq[NODE_CAP];   // exact maxima of each node's logit rows
-  float n_lsep[NODE_CAP], n_lseq[NODE_CAP];   // fp32 log-sum-exp of each node's logit rows
   // candidates
   short slot_of[NODE_CAP];           // slot in I of a prompt node, -1 if not an input beam
   int S_node[NODE_CAP], S_tmp[NODE_CAP];
@@ -426,6 +423,23 @@ __device__ __forceinline__ bool slot_wait(Slot* s, unsigned long long tag, doubl
   }
 }
 
+// The same for two slots at once (their loads in flight together).
+__device__ __forceinline__ bool slot_wait2(Slot* s0, Slot* s1, unsigned long long tag, double& v0, double& v1, long long limit) {
+  long long t0 = 0;
+  bool h0 = false, h1 = false;
+  for (int spin = 0;; ++spin) {
+    unsigned long long a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+    if (!h0) { a0 = __hip_atomic_load(&s0->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); a1 = __hip_atomic_load(&s0->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    if (!h1) { b0 = __hip_atomic_load(&s1->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); b1 = __hip_atomic_load(&s1->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    if (!h0 && (a0 ^ a1) == tag) { v0 = __longlong_as_double((long long)a0); h0 = true; }
+    if (!h1 && (b0 ^ b1) == tag) { v1 = __longlong_as_double((long long)b0); h1 = true; }
+    if (h0 && h1) return true;
+    if (spin == 0) t0 = wall_clock64();
+    else if ((spin & 15) == 0 && wall_clock64() - t0 > limit) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
 // Single-value exchanges: workgroup w owns the slot at the start of its own 128-byte line of the bank (slot index
 // w * LINE_SLOTS), so that no two workgroups ever write the same cache line.  Measured with a microbenchmark
 // on this chip, all-to-all among 256 workgroups: 2.3 us with a line per workgroup, 3.1 us with the words packed
@@ -554,7 +568,7 @@ template <bool WARP>
 __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   __shared__ LayerShared sh;
   extern __shared__ __attribute__((aligned(16))) double dyn_lds[];
-  const int prompt = blockIdx.x / a.G;
+  const int prompt = a.prompt0 + blockIdx.x / a.G;
   const int g = blockIdx.x % a.G;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -562,6 +576,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   unsigned int epoch = 0;      // exchanges so far (sets the tag); identical in every workgroup of the prompt
   unsigned int xchg = 0;       // of those, the ones on the two alternating banks
   Slot* const slots = prompt_slots(a, prompt);
+  // (selected, not indexed: a run-time index into the kernel's argument block would move the whole block into scratch memory)
+  const int slx0 = a.sl.x[0], slx1 = a.sl.x[1], slxc0 = a.sl.xc[0], slxc1 = a.sl.xc[1];
+  auto bank_x = [&](unsigned int n) { return (n & 1) ? slx1 : slx0; };
+  auto bank_xc = [&](unsigned int n) { return (n & 1) ? slxc1 : slxc0; };
   unsigned int wsum_round = 0; // alternates the two wsum buffers
   unsigned int decide_round = 0;
   int trace_n = 0;
@@ -572,17 +590,32 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   };
   stamp(0);
 
-  if (tid == 0) { sh.abort = 0; sh.sbad = 0; sh.sgamma = 0; }
+  if (tid == 0) { sh.abort = 0; sh.sbad = 0; sh.sgamma = 0; sh.counter = 0; sh.found = 0; }
   if (tid < 64) sh.exp_tab[tid] = c_exp2_tab[tid];
 
-  // ---- trees and nodes of this prompt (found by the statistics kernels' epilogue)
-  const int4 rec = a.prompt_rec[prompt];
-  const int t_first = rec.x;
-  int n_roots = rec.y - rec.x;
-  const int n_begin = rec.z, n_end = rec.w;
+  // ---- trees and nodes of this prompt.  tree_prompt is non-decreasing: the prompt's trees are those behind the
+  // trees of earlier prompts.  (Everything the kernel needs it derives from the call's inputs: it does not wait for
+  // the statistics pass, which runs beside it.)
+  int t_first = 0, t_end = a.n_trees;
+  if (a.n_prompts > 1) {
+    __syncthreads();
+    int lt = 0, le = 0;
+    for (int t = tid; t < a.n_trees; t += VL_BLOCK) {
+      const int tp = a.tree_prompt[t];
+      lt += tp < prompt; le += tp <= prompt;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { lt += __shfl_xor(lt, off); le += __shfl_xor(le, off); }
+    if (lane == 0) { atomicAdd(&sh.counter, lt); atomicAdd(&sh.found, le); }
+    __syncthreads();
+    t_first = sh.counter; t_end = sh.found;
+  }
+  int n_roots = t_end - t_first;
   int bad = 0;
-  if (n_roots < 0 || t_first < 0 || rec.y > a.n_trees) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
+  if (n_roots < 0) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
   if (n_roots > a.max_prompt_trees || n_roots > a.I_cap || n_roots > 64) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
+  int n_begin = 0, n_end = 0;
+  if (n_roots > 0) { n_begin = a.tree_off[t_first]; n_end = a.tree_off[t_end]; }
   if (n_begin < 0 || n_end > a.n_nodes || n_end < n_begin) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
   if (n_end - n_begin > NODE_CAP) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
   int n_pn = n_roots > 0 ? n_end - n_begin : 0;          // nodes of the prompt
@@ -598,68 +631,41 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   }
   if (tid < n_pn) {
     const int n = n_begin + tid;
-    const int d = a.depth[n];
     int tok = a.token[n];
     if (tok < 0 || tok >= V) { atomicOr(&sh.sbad, DSBD_FAULT_TOKEN); tok = 0; }
-    sh.n_depth[tid] = (short)d;
     sh.n_parent[tid] = a.parent[n];
     sh.n_token[tid] = tok;
     sh.n_rank[tid] = a.rank ? a.rank[n] : 0;
     sh.n_u[tid] = a.u_acc[n];
     sh.slot_of[tid] = -1;
+    sh.S_tmp[tid] = 0;
+  }
+  __syncthreads();
+  if (sh.sbad & DSBD_FAULT_TOPOLOGY) { n_roots = 0; n_pn = 0; }
+  // node depths (and the validation of the parent pointers): one wave per tree walks the parent chains with lane
+  // shuffles over the entries already in the LDS; depths land in S_tmp (prompt-local index)
+  for (int b = wave; b < n_roots; b += VL_WAVES) {
+    dsbd_tree_range t;
+    t.base = sh.I_node[b];
+    t.n_all = (b + 1 < n_roots ? sh.I_node[b + 1] : n_end) - t.base;
+    t.n = min(t.n_all, min(a.max_tree_nodes, DSBD_MAX_TREE_NODES));
+    t.bad = t.n_all > t.n ? DSBD_FAULT_BOUNDS : 0;
+    t.valid = true;
+    const int p_mine = lane < t.n ? sh.n_parent[t.base - n_begin + lane] : -1;
+    const int fb = dsbd_tree_walk(t, lane, p_mine, a.max_depth, reinterpret_cast<int32_t*>(sh.S_tmp) - n_begin, nullptr, nullptr);
+    if (fb) atomicOr(&sh.sbad, fb);
+  }
+  __syncthreads();
+  if (tid < n_pn) {
+    const int d = sh.S_tmp[tid];
+    sh.n_depth[tid] = (short)d;
     atomicMax(&sh.sgamma, d);
-    // row statistics: the chunks of the statistics pass merged into the exact maximum and an fp32 log-sum-exp
-    const float2* pp = a.part + (long long)n * a.nchunk;
-    const float2* pq = a.alias ? pp : a.part + ((long long)a.n_nodes + n) * a.nchunk;
-    // (the chunks' loads all leave before the first merge: one after the other they cost a memory latency each)
-    float Mp, Sp, Mq, Sq;
-    if (a.nchunk <= 4) {
-      float2 vp[4], vq[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) { const int cc = min(c, a.nchunk - 1); vp[c] = pp[cc]; vq[c] = pq[cc]; }
-      Mp = vp[0].x; Sp = vp[0].y; Mq = vq[0].x; Sq = vq[0].y;
-#pragma unroll
-      for (int c = 1; c < 4; ++c)
-        if (c < a.nchunk) { online_merge(Mp, Sp, vp[c].x, vp[c].y); online_merge(Mq, Sq, vq[c].x, vq[c].y); }
-    } else if (a.nchunk <= 16) {             // small forests are cut finer (see the plan): the same, sixteen wide
-      float2 vp[16], vq[16];
-#pragma unroll
-      for (int c = 0; c < 16; ++c) { const int cc = min(c, a.nchunk - 1); vp[c] = pp[cc]; vq[c] = pq[cc]; }
-      Mp = vp[0].x; Sp = vp[0].y; Mq = vq[0].x; Sq = vq[0].y;
-#pragma unroll
-      for (int c = 1; c < 16; ++c)
-        if (c < a.nchunk) { online_merge(Mp, Sp, vp[c].x, vp[c].y); online_merge(Mq, Sq, vq[c].x, vq[c].y); }
-    } else {
-      Mp = pp[0].x; Sp = pp[0].y; Mq = pq[0].x; Sq = pq[0].y;
-      for (int c = 1; c < a.nchunk; ++c) { online_merge(Mp, Sp, pp[c].x, pp[c].y); online_merge(Mq, Sq, pq[c].x, pq[c].y); }
-    }
-    const float lp = Mp + logf(Sp), lq = Mq + logf(Sq);
-    sh.n_maxp[tid] = Mp; sh.n_maxq[tid] = Mq;
-    sh.n_lsep[tid] = lp; sh.n_lseq[tid] = lq;
-    if (g == 0) {
-      if (a.out.lse_target) a.out.lse_target[n] = lp;
-      if (a.out.lse_draft) a.out.lse_draft[n] = lq;
-    }
   }
   __syncthreads();
   bad |= sh.sbad;
-  if (sh.sbad & DSBD_FAULT_TOPOLOGY) { n_roots = 0; n_pn = 0; }
   const int gamma = min(sh.sgamma, a.max_depth);
   if (bad && g == 0 && tid == 0) atomicOr(a.fault, bad);
 
-  // ---- per-node log-probabilities: node g, g + G, ... of the prompt belong to this workgroup.  The loads are
-  // issued here and the values stored after the first exponential pass, so nobody waits for them.
-  float node_lp = 0.f, node_lq = 0.f;
-  const int my_node = g + tid * a.G;                     // prompt-local
-  if (my_node < n_pn) {
-    const int n = n_begin + my_node;
-    const int par = sh.n_parent[my_node];
-    if (sh.n_depth[my_node] != 0 && par >= n_begin && par < n) {
-      const int tok = sh.n_token[my_node];
-      node_lp = a.zp[(long long)par * V + tok] - sh.n_lsep[par - n_begin];
-      node_lq = a.zq[(long long)par * V + tok] - sh.n_lseq[par - n_begin];
-    }
-  }
   // ---- initial statuses (first workgroup of the prompt)
   if (g == 0) {
     if (tid < n_pn) a.out.node_status[n_begin + tid] = sh.n_depth[tid] == 0 ? DSBD_ROOT : DSBD_NOT_REACHED;
@@ -690,18 +696,13 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   // Slices that do not fit the LDS live in the workspace, each workgroup's in a region of its own: the layers
   // cut I x V differently, and an address written by workgroups of two XCDs in turn (whose L2 caches write back
   // in no particular order) could later be read back stale.
-  double* pb = a.pb + ((long long)prompt * a.G + g) * a.slice_cap;
-  double* qb = a.qb + ((long long)prompt * a.G + g) * a.slice_cap;
+  double* pb = a.pb + (long long)blockIdx.x * a.slice_cap;
+  double* qb = a.qb + (long long)blockIdx.x * a.slice_cap;
   const float* u_res = a.u_res + (long long)prompt * Lw;
   const float* u_fill = a.u_fill + (long long)prompt * Lw * a.W_cap;
 
   // ---- layer 1 inputs: the roots
-  if (tid < n_roots) {
-    const int i = sh.I_node[tid] - n_begin;
-    sh.max_p[tid] = (double)sh.n_maxp[i];
-    sh.max_q[tid] = (double)sh.n_maxq[i];
-    sh.slot_of[i] = (short)tid;
-  }
+  if (tid < n_roots) sh.slot_of[sh.I_node[tid] - n_begin] = (short)tid;
   int nI = n_roots;
   int near_tie = 0;          // meaningful in thread 0
   int l_last = gamma + 1;
@@ -773,28 +774,77 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     auto stq = [&](long long j, double v) { if (in_lds) ql[(int)j] = v; else qbg[j] = v; };
     // The hot loops are written once and instantiated for both homes of the slices, with the choice taken outside
     // the loop (left per access, it becomes a pair of branches around every load and store).
-    auto with_slices = [&](auto&& body) { if (in_lds) body(pl, ql); else body(pbg, qbg); };
+    auto with_slices = [&](auto&& body) __attribute__((always_inline)) { if (in_lds) body(pl, ql); else body(pbg, qbg); };
 
-    // ===== p_beam / q_beam over I x V: exponentials and this workgroup's share of the row sums
+    // ===== p_beam / q_beam over I x V: exponentials and this workgroup's share of the row sums.  The exponentials
+    // are taken against the maximum of the workgroup's own piece of the row (found here, in the same pass over the
+    // logits); the pieces' maxima travel with their sums and are folded into the row's maximum and total below.
     for (int i = i_lo; i <= i_hi; ++i) {
       const int node = sh.I_node[i];
       const long long x_lo = max(e_lo, (long long)i * V) - (long long)i * V;
       const long long x_hi = min(e_hi, (long long)(i + 1) * V) - (long long)i * V;
       const float* zp = a.zp + (long long)node * V;
       const float* zq = a.zq + (long long)node * V;
-      const double mp = sh.max_p[i], mq = sh.max_q[i];
       double s_p = 0.0, s_q = 0.0;
       const long long joff = (long long)i * V - e_lo;
-      with_slices([&](auto P, auto Q) {
-        for (long long x = x_lo + tid; x < x_hi; x += 8 * VL_BLOCK) {   // eight logits of each model in flight, ragged end predicated
-          float fp[8], fq[8];
+      with_slices([&](auto P, auto Q) __attribute__((always_inline)) {
+      // the first XU logits of each model stay in registers; longer pieces are read a second time (from the caches)
+      float fp0[XU], fq0[XU];
+      float lmp = -INFINITY, lmq = -INFINITY;
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < XU; ++k) {
+        const long long xx = min(x_lo + tid + k * VL_BLOCK, x_hi - 1);     // clamped repeats do not change a maximum
+        fp0[k] = zp[xx]; fq0[k] = zq[xx];
+      }
+      bool nonfinite = false;        // (the statistics pass reports these for every row; this kernel for the rows it uses)
+#pragma unroll
+      for (int k = 0; k < XU; ++k) {
+        lmp = fmaxf(lmp, fp0[k]); lmq = fmaxf(lmq, fq0[k]);
+        nonfinite |= !(fabsf(fp0[k]) <= FLT_MAX) | !(fabsf(fq0[k]) <= FLT_MAX);
+      }
+      for (long long x = x_lo + tid + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {
+        float fp[XU], fq[XU];
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+          const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
+          fp[k] = zp[xx]; fq[k] = zq[xx];
+        }
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+          lmp = fmaxf(lmp, fp[k]); lmq = fmaxf(lmq, fq[k]);
+          nonfinite |= !(fabsf(fp[k]) <= FLT_MAX) | !(fabsf(fq[k]) <= FLT_MAX);
+        }
+      }
+      if (nonfinite) atomicOr(a.fault, DSBD_FAULT_NONFINITE);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) { lmp = fmaxf(lmp, __shfl_xor(lmp, off)); lmq = fmaxf(lmq, __shfl_xor(lmq, off)); }
+      float* const wm = sh.wmax[(i - i_lo) & 1];       // two buffers: a wave is at most one row ahead of the slowest
+      if (lane == 0) { wm[2 * wave] = lmp; wm[2 * wave + 1] = lmq; }
+      __syncthreads();
+#pragma unroll
+      for (int w = 0; w < VL_WAVES; ++w) { lmp = fmaxf(lmp, wm[2 * w]); lmq = fmaxf(lmq, wm[2 * w + 1]); }
+      const double mp = (double)lmp, mq = (double)lmq;
+      if (tid == 0) { sh.lm_p[i - i_lo] = mp; sh.lm_q[i - i_lo] = mq; }
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+          const long long x = x_lo + tid + k * VL_BLOCK;
+          if (x < x_hi) {
+            const double ep = exp_nonpos((double)fp0[k] - mp, sh.exp_tab);
+            double eq = ep;
+            if (!a.alias) eq = exp_nonpos((double)fq0[k] - mq, sh.exp_tab);
+            P[joff + x] = ep; Q[joff + x] = eq;
+            s_p += ep; s_q += eq;
+          }
+        }
+        for (long long x = x_lo + tid + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {   // XU logits of each model in flight, ragged end predicated
+          float fp[XU], fq[XU];
+#pragma unroll
+          for (int k = 0; k < XU; ++k) {
             const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
             fp[k] = zp[xx]; fq[k] = zq[xx];
           }
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
+          for (int k = 0; k < XU; ++k) {
             if (x + k * VL_BLOCK < x_hi) {
               const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab);
               double eq = ep;
@@ -812,21 +862,23 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         sh.u.wpart[((i - i_lo) * VL_WAVES + wave) * 2 + 1] = s_q;
       }
     }
-    if (l == 1 && my_node < n_pn) {
-      if (a.out.node_logp_target) a.out.node_logp_target[n_begin + my_node] = node_lp;
-      if (a.out.node_logp_draft) a.out.node_logp_draft[n_begin + my_node] = node_lq;
-    }
     stamp(100);
     __syncthreads();
-    // ===== all-reduce of the 2|I| row sums.  Only the workgroups that hold a piece of row i post its two
-    // columns and only those are polled.
+    // ===== all-reduce of the rows' maxima and sums.  Only the workgroups that hold a piece of row i post its four
+    // values (sum and maximum of the piece, both models) and only those are polled.
     epoch += 1;
     const unsigned long long rs_tag = exchange_tag(a.nonce + epoch);
     Slot* const rs_bank = slots + a.sl.r + (long long)(l - 1) * a.sl.r_stride;
-    if (tid < 2 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
-      const double* wp = &sh.u.wpart[(tid >> 1) * VL_WAVES * 2 + (tid & 1)];
-      const double s = ((wp[0] + wp[2]) + (wp[4] + wp[6])) + ((wp[8] + wp[10]) + (wp[12] + wp[14]));
-      slot_post(rs_bank + (long long)g * a.sl.r_w + 2 * i_lo + tid, s, rs_tag);
+    if (tid < 4 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
+      const int r = tid >> 2, which = tid & 3;
+      double v;
+      if (which < 2) {
+        const double* wp = &sh.u.wpart[r * VL_WAVES * 2 + which];
+        v = ((wp[0] + wp[2]) + (wp[4] + wp[6])) + ((wp[8] + wp[10]) + (wp[12] + wp[14]));
+      } else {
+        v = which == 2 ? sh.lm_p[r] : sh.lm_q[r];
+      }
+      slot_post(rs_bank + (long long)g * a.sl.r_w + 4 * i_lo + tid, v, rs_tag);
     }
     stamp(102);
 
@@ -877,7 +929,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
     }
 
-    // ===== row sums: thread (r, c) gathers column c from every R-th workgroup that holds part of it
+    // ===== rows' maxima and totals: thread (r, c) gathers column c = (row, model) from every R-th workgroup that holds
+    // part of it and folds the pieces (sum relative to the piece's maximum) as it goes; the R partial results of a
+    // column are then put on the column's maximum and added up in a fixed order.  Every workgroup of the prompt
+    // does the same arithmetic on the same numbers.
     {
       const int ncols = 2 * nI;
       int cshift = 0;
@@ -885,43 +940,42 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       const int cpow = 1 << cshift;
       const int R = min(32, VL_BLOCK / cpow);
       const int c = tid & (cpow - 1), r = tid >> cshift;
-      double acc = 0.0;
+      double accM = -INFINITY, accS = 0.0;
       bool mine = true;
       if (c < ncols && r < R) {
         const int i = c >> 1;
         const int w_lo = cut.rows_per_wg > 0 ? i / cut.rows_per_wg : i * cut.wg_per_row;
         const int w_hi = cut.rows_per_wg > 0 ? w_lo : w_lo + geo_pieces - 1;
         for (int w = w_lo + r; w <= w_hi; w += R) {
-          double v = 0.0;
-          mine = mine && slot_wait(rs_bank + (long long)w * a.sl.r_w + c, rs_tag, v, a.sync_limit);
-          acc += v;
+          double vs = 0.0, vm = 0.0;
+          Slot* const sl0 = rs_bank + (long long)w * a.sl.r_w + 4 * i + (c & 1);
+          mine = mine && slot_wait2(sl0, sl0 + 2, rs_tag, vs, vm, a.sync_limit);
+          const double Mn = fmax(accM, vm);
+          accS = accS * exp_nonpos(accM - Mn, sh.exp_tab) + vs * exp_nonpos(vm - Mn, sh.exp_tab);
+          accM = Mn;
         }
       }
-      // fold the parts held by this wave (lanes c, c + cpow, ...), the waves' results through LDS
-      for (int off = cpow; off < 64; off <<= 1) acc += __shfl_xor(acc, off);
-      sh.tsum[tid] = acc;
+      sh.tmax[tid] = accM;
+      sh.tsum[tid] = accS;
       stamp(20);
       if (!mine) give_up();
       __syncthreads();
       if (sh.abort) return;
       stamp(21);
-      // row totals; one wave turns them into the scale factors, another keeps them for the fp64 log-sum-exp
-      if (wave < 2 && lane < nI) {
-        double totp = 0.0, totq = 0.0;
-#pragma unroll
-        for (int w = 0; w < VL_WAVES; ++w) {     // with 128 columns a column lives in every other wave
-          const int ip = w * 64 + ((2 * lane) & 63), iq = w * 64 + ((2 * lane + 1) & 63);
-          const double vp = sh.tsum[ip], vq = sh.tsum[iq];
-          if ((ip & (cpow - 1)) == 2 * lane) totp += vp;
-          if ((iq & (cpow - 1)) == 2 * lane + 1) totq += vq;
-        }
-        if (wave == 0) {
-          sh.sp[lane] = sh.bw_p[lane] / totp;
-          sh.sq[lane] = sh.bw_q[lane] / totq;
-        } else {             // the logarithms wait until the other waves have nothing to do (below)
-          sh.lse_p[lane] = totp;
-          sh.lse_q[lane] = totq;
-        }
+      if (c < ncols && r < R) {
+        double cm = -INFINITY;
+        for (int rr = 0; rr < R; ++rr) cm = fmax(cm, sh.tmax[c + (rr << cshift)]);
+        sh.tsum[tid] = accS * exp_nonpos(accM - cm, sh.exp_tab);      // partial results without a piece: 0 x exp(-inf) = 0
+        if (r == 0) sh.colmax[c] = cm;
+      }
+      __syncthreads();
+      // column totals; the scale factors of the rows, and what the fp64 log-sum-exp needs (taken later)
+      if (tid < ncols) {
+        double tot = 0.0;
+        for (int rr = 0; rr < R; ++rr) tot += sh.tsum[tid + (rr << cshift)];
+        const int i = tid >> 1;
+        if (tid & 1) { sh.max_q[i] = sh.colmax[tid]; sh.sq[i] = sh.bw_q[i] / tot; sh.lse_q[i] = tot; }
+        else { sh.max_p[i] = sh.colmax[tid]; sh.sp[i] = sh.bw_p[i] / tot; sh.lse_p[i] = tot; }
       }
       __syncthreads();
     }
@@ -932,7 +986,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     for (int i = i_lo; i <= i_hi; ++i) {
       const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
       const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
-      const double fp = sh.sp[i], fq = sh.sq[i];
+      // (the slice holds exponentials against the piece's own maximum: put them on the row's)
+      const double fp = sh.sp[i] * exp_nonpos(sh.lm_p[i - i_lo] - sh.max_p[i], sh.exp_tab);
+      const double fq = sh.sq[i] * exp_nonpos(sh.lm_q[i - i_lo] - sh.max_q[i], sh.exp_tab);
       with_slices([&](auto P, auto Q) {
         long long j = j_lo + tid;
         for (; j + 3 * VL_BLOCK < j_hi; j += 4 * VL_BLOCK) {      // four elements of each array in flight
@@ -1435,7 +1491,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       // ... and over the workgroups (same order everywhere), gathered and scanned by one wave
       epoch += 1;
       const unsigned long long tag = exchange_tag(a.nonce + epoch);
-      Slot* bank = slots + a.sl.x[xchg++ & 1];
+      Slot* bank = slots + bank_x(xchg++);
       if (wave == 0) {
         const double mine = sh.tsum[VL_BLOCK - 1];
         if (lane == 0) dense_post(bank, a.G, g, mine, tag);
@@ -1659,8 +1715,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         }
         epoch += 1;
         const unsigned long long tag = exchange_tag(a.nonce + epoch);
-        Slot* bank = slots + a.sl.x[xchg & 1];
-        Slot* gbank = slots + a.sl.xc[xchg++ & 1];
+        Slot* bank = slots + bank_x(xchg);
+        Slot* gbank = slots + bank_xc(xchg++);
         if (wave == 0) {
           if (lane == 0) dense_post(bank, a.G, g, tot, tag);
           double F;
@@ -1761,8 +1817,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (!posted) {
           epoch += 1;
           x_tag = exchange_tag(a.nonce + epoch);
-          x_bank = slots + a.sl.x[xchg & 1];
-          x_gbank = slots + a.sl.xc[xchg++ & 1];
+          x_bank = slots + bank_x(xchg);
+          x_gbank = slots + bank_xc(xchg++);
           if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
           x_own = tot;
         }
@@ -1831,8 +1887,6 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       sh.I_node[tid] = sh.A_node[tid];
       sh.cum_p[tid] = sh.A_cum_p[tid];
       sh.cum_q[tid] = sh.A_cum_q[tid];
-      sh.max_p[tid] = (double)sh.n_maxp[i];
-      sh.max_q[tid] = (double)sh.n_maxq[i];
       sh.slot_of[i] = (short)tid;
     }
     nI = nacc;
@@ -1853,6 +1907,7 @@ namespace {
 
 struct VerifyPlan {
   int nchunk, chunk, I_cap, G, lds_elems;
+  int group;               // prompts per launch of the layer kernel (all of them, unless they do not fit the device at once)
   size_t lds_bytes;        // dynamic LDS of the layer kernel
   SlotLayout sl;
   long long slice_cap;     // elements of the largest slice of I x V a workgroup can get
@@ -1864,7 +1919,7 @@ int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
   if (V < 1) return DSBD_ERR_UNSUPPORTED;
   if (p->W_cap < 1 || p->W_cap > 64) return DSBD_ERR_UNSUPPORTED;
   if (p->W_min < 1 || p->W_min > p->W_cap || p->W_L > p->W_cap) return DSBD_ERR_INVALID;
-  if (p->t > 1.0f) return DSBD_ERR_INVALID;
+  if (!(p->t <= 1.0f)) return DSBD_ERR_INVALID;      // also rejects NaN (which would otherwise read as dynamic width 0)
   if (f->max_tree_nodes < 1 || f->max_tree_nodes > DSBD_MAX_TREE_NODES) return DSBD_ERR_UNSUPPORTED;
   if (f->max_prompt_trees < 1 || f->max_prompt_trees > 64) return DSBD_ERR_UNSUPPORTED;
   if (p->W_L <= 0 && f->max_prompt_trees > p->W_cap) return DSBD_ERR_INVALID;
@@ -1881,34 +1936,45 @@ int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
   return DSBD_OK;
 }
 
-int cached_cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
+// What the layer kernel may occupy: all its workgroups must be resident at once.
+struct DeviceLimits { int cus, blocks_per_cu; };
+const DeviceLimits& device_limits() {
+  static DeviceLimits lim = {0, 0};
+  static std::once_flag once;
+  std::call_once(once, [] {
     int dev = 0, v = 0;
+    lim.cus = 256;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cus = v;
-    else
-      cus = 256;
-  }
-  return cus;
+      lim.cus = v;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
+    int nb = 0, nb2 = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel<false>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
+      nb = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb2, verify_layers_kernel<true>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb2 < 1)
+      nb2 = 1;
+    lim.blocks_per_cu = nb < nb2 ? nb : nb2;
+    (void)hipGetLastError();
+  });
+  return lim;
 }
 
 VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, bool alias = false) {
   VerifyPlan pl;
-  // about four chunks per row, of 8k to 32k logits each: a few thousand workgroups at the large configurations,
-  // and at most four chunk statistics per row for the layer kernel's prologue to merge (measured: a 32000-token
-  // vocabulary in one chunk per row ran the 16-prompt batch at 45 % of the HBM peak, in four at 57 %)
+  const DsbdKnobs& knobs = dsbd_knobs();
+  // about four chunks per row, of 8k to 32k logits each: a few thousand workgroups at the large configurations
+  // (measured: a 32000-token vocabulary in one chunk per row ran the 16-prompt batch at 45 % of the HBM peak, in
+  // four at 57 %)
   int target = V / 4;
   if (target < 8192) target = 8192;
   if (target > 32768) target = 32768;
-  if (const char* e = getenv("DSBD_STATS_CHUNK")) {   // tuning knob: logits per workgroup of the statistics pass
-    const int v = atoi(e);
-    if (v >= 1024) target = v;
-  }
+  if (knobs.stats_chunk >= 1024) target = knobs.stats_chunk;   // tuning knob: logits per workgroup of the statistics pass
   // few rows (a draft step's beams): finer chunks, down to 4k logits and up to 16 per row, until about a thousand
   // workgroups stream (a workgroup of the pass is bound by memory latency x its number of load rounds)
-  if (!getenv("DSBD_STATS_CHUNK"))
+  else
     while (target > 4096 && (V + target / 2 - 1) / (target / 2) <= 16 &&
            2LL * f->n_nodes * ((V + target - 1) / target) < 1024)
       target /= 2;
@@ -1916,21 +1982,23 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
   pl.chunk = ((V + pl.nchunk - 1) / pl.nchunk + 3) & ~3;
   pl.nchunk = (V + pl.chunk - 1) / pl.chunk;
   pl.I_cap = p->W_cap > f->max_prompt_trees ? p->W_cap : f->max_prompt_trees;
-  // one workgroup per compute unit in total, shared evenly by the prompts, at least 4096 joint
-  // elements per workgroup
-  const int cus = cached_cu_count();
-  int G = f->n_prompts > 0 ? cus / f->n_prompts : 1;
+  // one workgroup per compute unit in total, shared evenly by the prompts, at least 4096 joint elements per
+  // workgroup.  More prompts than workgroups fit the device at once: groups of prompts, one launch after the other
+  // (Algorithm 1 runs per prompt), one workgroup per prompt.
+  const DeviceLimits& lim = device_limits();
+  const int resident = lim.cus * lim.blocks_per_cu;
+  int G = f->n_prompts > 0 ? lim.cus / f->n_prompts : 1;
   const long long joint = (long long)pl.I_cap * V;
   const int by_work = (int)((joint + 4095) / 4096);
   if (G > by_work) G = by_work;
-  if (const char* e = getenv("DSBD_VERIFY_G")) {   // tuning knob: workgroups per prompt
-    const int v = atoi(e);
-    if (v >= 1 && (long long)v * f->n_prompts <= cus) G = v;
-  }
+  if (knobs.verify_g >= 1 && (long long)knobs.verify_g * f->n_prompts <= resident) G = knobs.verify_g;   // tuning knob
   if (G < 1) G = 1;
   if (G > 256) G = 256;
-  const long long cap = VL_DYN_LDS_BYTES / (alias ? 8 : 16);   // one array instead of two when q_beam is p_beam
   pl.G = G;
+  pl.group = f->n_prompts;
+  if ((long long)pl.group * G > resident) pl.group = resident / G;     // G is 1 here
+  if (pl.group < 1) pl.group = 1;
+  const long long cap = VL_DYN_LDS_BYTES / (alias ? 8 : 16);   // one array instead of two when q_beam is p_beam
   // exchange slots: every workgroup's slots of an exchange start a 128-byte line (no two writers per line)
   {
     auto up8 = [](int v) { return (v + LINE_SLOTS - 1) / LINE_SLOTS * LINE_SLOTS; };
@@ -1941,7 +2009,7 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
     sl.x[1] = off; off += G * LINE_SLOTS;
     sl.xc[0] = off; off += SUM_GROUPS * LINE_SLOTS;
     sl.xc[1] = off; off += SUM_GROUPS * LINE_SLOTS;
-    sl.r_w = up8(2 * pl.I_cap);
+    sl.r_w = up8(4 * pl.I_cap);
     sl.r = off; sl.r_stride = G * sl.r_w; off += layers * sl.r_stride;
     sl.s = off; sl.s_stride = G * LINE_SLOTS; off += layers * sl.s_stride;
     sl.sc = off; sl.sc_stride = SUM_GROUPS * LINE_SLOTS; off += layers * sl.sc_stride;
@@ -1971,18 +2039,46 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
   return pl;
 }
 
-size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const VerifyPlan& pl, int32_t** depth,
-                    float2** part, double** pb, double** qb, double** red, int4** prompt_rec) {
+size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const VerifyPlan& pl, float2** part, double** pb,
+                    double** qb, double** red) {
   const size_t N = (size_t)f->n_nodes, P = (size_t)f->n_prompts;
+  (void)V;
   ws.take<long long>(512);                 // timeline of the layer kernel (diagnostics), first in the workspace
-  *depth = ws.take<int32_t>(N);
   *part = ws.take<float2>(2 * N * pl.nchunk);
-  *pb = ws.take<double>(P * pl.G * (size_t)pl.slice_cap);
-  *qb = ws.take<double>(P * pl.G * (size_t)pl.slice_cap);
+  // slices that do not fit the LDS: a region per workgroup of a launch (the launches of a forest that runs in groups
+  // of prompts follow each other and share the regions); exchange slots: a region per prompt
+  *pb = ws.take<double>((size_t)pl.group * pl.G * (size_t)pl.slice_cap);
+  *qb = ws.take<double>((size_t)pl.group * pl.G * (size_t)pl.slice_cap);
   *red = ws.take<double>(P * (size_t)pl.sl.prompt_stride * 2);
-  *prompt_rec = ws.take<int4>(P);
   return ws.total();
 }
+
+// The second stream the statistics pass runs on, next to the layer kernel on the caller's stream; one per device,
+// created on first use and kept until the process ends (with the two events that order it after the caller's
+// earlier work and order the caller's later work after it).
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool tried = false, ok = false;
+};
+SideStream* side_stream_of_current_device() {
+  static SideStream table[64];
+  static std::mutex mutex;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mutex);
+  SideStream& s = table[dev];
+  if (!s.tried) {
+    s.tried = true;
+    s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+    if (!s.ok) (void)hipGetLastError();
+  }
+  return s.ok ? &s : nullptr;
+}
+
+std::atomic<unsigned long long> g_launch_counter{0};
 
 }  // namespace
 
@@ -1990,8 +2086,8 @@ extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32
   if (check_verify(f, V, p) != DSBD_OK) return 0;
   const VerifyPlan pl = make_verify_plan(f, V, p);
   WorkspaceCarver ws(nullptr);
-  int32_t* d; float2* pt; double *pb, *qb, *red; int4* pr;
-  return carve_verify(ws, f, V, pl, &d, &pt, &pb, &qb, &red, &pr) + 256;
+  float2* pt; double *pb, *qb, *red;
+  return carve_verify(ws, f, V, pl, &pt, &pb, &qb, &red) + 256;
 }
 
 extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
@@ -2011,6 +2107,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   if (!workspace) return DSBD_ERR_INVALID;
   if (workspace_bytes < dsbd_verify_forest_workspace_bytes(f, in->V, p)) return DSBD_ERR_WORKSPACE;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const DsbdKnobs& knobs = dsbd_knobs();
   // the same arrays given for both models (the draft stage does: its draws are the additional layer of a forest of
   // single-node trees with the draft model in both roles): q_beam is p_beam and is kept, and computed, once
   const bool alias = in->logits_target == in->logits_draft && in->beam_logp_target == in->beam_logp_draft;
@@ -2018,79 +2115,83 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
 
   char* wbase = reinterpret_cast<char*>(dsbd_align_up(reinterpret_cast<uintptr_t>(workspace), 256));
   WorkspaceCarver ws(wbase);
-  int32_t* depth; float2* part; double *pb, *qb, *red; int4* prompt_rec;
-  carve_verify(ws, f, in->V, pl, &depth, &part, &pb, &qb, &red, &prompt_rec);
+  float2* part; double *pb, *qb, *red;
+  carve_verify(ws, f, in->V, pl, &part, &pb, &qb, &red);
 
-  // the persistent kernel needs all its workgroups resident at once
-  static int max_blocks_per_cu = -1;
-  if (max_blocks_per_cu < 0) {
-    int nb = 0;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
-    int nb2 = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel<false>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
-      nb = 1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb2, verify_layers_kernel<true>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb2 < 1)
-      nb2 = 1;
-    max_blocks_per_cu = nb < nb2 ? nb : nb2;
-  }
-  const long long grid3 = (long long)f->n_prompts * pl.G;
-  if (grid3 > (long long)max_blocks_per_cu * cached_cu_count()) return DSBD_ERR_UNSUPPORTED;
-
+  // ---- the statistics pass (per-node outputs; the layer kernel does not depend on it) runs on a second stream next
+  // to the layer kernel: ordered after everything the caller's stream holds so far, and the caller's stream continues
+  // only when both are done.  DSBD_VERIFY_OVERLAP=0 (or a stream that cannot be created) puts it in front instead.
+  const bool want_stats = out->lse_target || out->lse_draft || out->node_logp_target || out->node_logp_draft;
+  SideStream* side = (want_stats && knobs.verify_overlap) ? side_stream_of_current_device() : nullptr;
   StatsArgs sa;
   sa.z[0] = in->logits_target; sa.z[1] = in->logits_draft;
   sa.n_nodes = f->n_nodes; sa.V = in->V; sa.nchunk = pl.nchunk; sa.chunk = pl.chunk;
   sa.part = part; sa.fault = fault;
-  sa.n_trees = f->n_trees; sa.n_prompts = f->n_prompts; sa.max_tree_nodes = f->max_tree_nodes; sa.max_depth = f->max_depth;
-  sa.tree_prompt = f->tree_prompt; sa.tree_off = f->tree_off; sa.parent = f->parent;
-  sa.depth = depth; sa.prompt_rec = prompt_rec;
-  sa.slots = reinterpret_cast<unsigned long long*>(red);
-  sa.n_slot_words = (long long)f->n_prompts * pl.sl.prompt_stride * 2;
-  // one extra row of workgroups (blockIdx.y == 0) for the small jobs
-  dsbd_launch(DSBD_KERNEL_VOCAB_STATS, vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes + 1, alias ? 1 : 2), dim3(VS_BLOCK), 0,
-              stream, sa);
-  DSBD_HIP_LAUNCH_CHECK();
+  FinishArgs fa;
+  fa.z[0] = in->logits_target; fa.z[1] = in->logits_draft;
+  fa.n_nodes = f->n_nodes; fa.V = in->V; fa.nchunk = pl.nchunk; fa.alias = alias ? 1 : 0; fa.part = part;
+  fa.parent = f->parent; fa.token = f->token;
+  fa.lse[0] = out->lse_target; fa.lse[1] = out->lse_draft;
+  fa.logp[0] = out->node_logp_target; fa.logp[1] = out->node_logp_draft;
+  auto launch_stats = [&](hipStream_t st) {
+    dsbd_launch(DSBD_KERNEL_VOCAB_STATS, vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes, alias ? 1 : 2), dim3(VS_BLOCK), 0,
+                st, sa);
+    hipLaunchKernelGGL(vocab_finish_kernel, dim3((f->n_nodes + VS_BLOCK - 1) / VS_BLOCK), dim3(VS_BLOCK), 0, st, fa);
+  };
+  if (want_stats && !side) {
+    launch_stats(stream);
+    DSBD_HIP_LAUNCH_CHECK();
+  }
+  if (side) {
+    if (hipEventRecord(side->fork, stream) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+      return DSBD_ERR_HIP;
+  }
 
   LayersArgs la;
   la.n_prompts = f->n_prompts; la.n_trees = f->n_trees; la.n_nodes = f->n_nodes;
   la.tree_prompt = f->tree_prompt; la.tree_off = f->tree_off; la.parent = f->parent; la.token = f->token;
   la.rank = f->draft_rank; la.max_depth = f->max_depth; la.max_prompt_trees = f->max_prompt_trees;
+  la.max_tree_nodes = f->max_tree_nodes;
   la.V = in->V; la.zp = in->logits_target; la.zq = in->logits_draft;
   la.blp = in->beam_logp_target; la.blq = in->beam_logp_draft;
   la.u_acc = in->u_accept; la.u_res = in->u_resid; la.u_fill = in->u_fill;
   la.W_L = p->W_L; la.W_min = p->W_min; la.W_cap = p->W_cap; la.t = p->t;
-  la.out = *out; la.depth = depth; la.prompt_rec = prompt_rec; la.part = part; la.nchunk = pl.nchunk;
+  la.out = *out;
   la.pb = pb; la.qb = qb; la.red = red; la.slice_cap = pl.slice_cap;
-  la.trace = getenv("DSBD_VERIFY_TRACE") ? reinterpret_cast<long long*>(wbase) : nullptr;
+  la.trace = knobs.verify_trace ? reinterpret_cast<long long*>(wbase) : nullptr;
   la.sync_limit = SYNC_LIMIT_TICKS;
-  la.mute_wg = -1;
-  static unsigned long long launch_counter = 0;
-  la.nonce = (++launch_counter) << 20;
-  if (const char* e = getenv("DSBD_VERIFY_SYNC_LIMIT_US")) {   // bound of the kernel's waits (default 3 s)
-    const long long us = atoll(e);
-    if (us >= 1 && us <= 10000000LL) la.sync_limit = us * 100;
-  }
-  if (const char* e = getenv("DSBD_VERIFY_TEST_MUTE_WG")) la.mute_wg = atoi(e);   // error-path test hook
+  if (knobs.verify_sync_limit_us >= 1 && knobs.verify_sync_limit_us <= 10000000LL)   // bound of the kernel's waits (default 3 s)
+    la.sync_limit = knobs.verify_sync_limit_us * 100;
+  la.mute_wg = knobs.verify_mute_wg;   // error-path test hook
+  // Exchange slots carry a tag made of this number and the exchange's index: nothing an earlier launch left in the
+  // workspace can pass for a value of this one, so the slots need no clearing.
+  la.nonce = (g_launch_counter.fetch_add(1, std::memory_order_relaxed) + 1) << 24;
   la.G = pl.G; la.I_cap = pl.I_cap; la.sl = pl.sl; la.lds_elems = pl.lds_elems; la.fault = fault;
   la.lds_slice = pl.lds_elems;
   la.alias = alias ? 1 : 0;
-  if (const char* e = getenv("DSBD_VERIFY_LDS_SLICE")) {   // tuning / test knob: largest slice kept in the LDS
-    const int v = atoi(e);
-    if (v >= 0 && v < la.lds_slice) la.lds_slice = v;
-  }
+  if (knobs.verify_lds_slice >= 0 && knobs.verify_lds_slice < la.lds_slice) la.lds_slice = knobs.verify_lds_slice;   // tuning / test knob
   la.top_k = p->top_k; la.top_p = (p->top_p > 0.0f && p->top_p < 1.0f) ? p->top_p : 1.0f;
-  // Ordinary launch: the grid was checked above to fit the device at once, the stream's earlier kernels have
-  // drained by the time this one starts, and every wait inside the kernel is bounded.  (A cooperative launch
-  // would also guarantee co-residency against work on other streams, but it made rocprofv3 crash at process
-  // exit on ROCm 7.2 and costs extra launch latency.)
-  if (p->top_k > 0)
-    dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<true>, dim3((unsigned)grid3), dim3(VL_BLOCK),
-                (unsigned int)pl.lds_bytes, stream, la);
-  else
-    dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<false>, dim3((unsigned)grid3), dim3(VL_BLOCK),
-                (unsigned int)pl.lds_bytes, stream, la);
-  const hipError_t le = hipGetLastError();
+  // Ordinary launches: a launch was sized to fit the device at once, and every wait inside the kernel is bounded.
+  // (A cooperative launch would also guarantee co-residency against work on other streams, but it made rocprofv3
+  // crash at process exit on ROCm 7.2 and costs extra launch latency.)
+  for (int p0 = 0; p0 < f->n_prompts; p0 += pl.group) {
+    la.prompt0 = p0;
+    const int np = f->n_prompts - p0 < pl.group ? f->n_prompts - p0 : pl.group;
+    const unsigned grid3 = (unsigned)np * (unsigned)pl.G;
+    if (p->top_k > 0)
+      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<true>, dim3(grid3), dim3(VL_BLOCK),
+                  (unsigned int)pl.lds_bytes, stream, la);
+    else
+      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<false>, dim3(grid3), dim3(VL_BLOCK),
+                  (unsigned int)pl.lds_bytes, stream, la);
+  }
+  hipError_t le = hipGetLastError();
+  if (side) {
+    launch_stats(side->stream);
+    if (hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
+      le = hipErrorUnknown;
+    const hipError_t le2 = hipGetLastError();
+    if (le == hipSuccess) le = le2;
+  }
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
 }

@@ -27,3 +27,38 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+class _Knobs:
+    """Sets the library's tuning overrides (DSBD_* environment variables) for one test: the library reads them once
+    per process, so every change is followed by a reload; on teardown the variables are removed and read again."""
+
+    def __init__(self):
+        self.names = []
+
+    @staticmethod
+    def _reload():
+        import paper_2409_16560_amd as dsbd
+        dsbd.dsbd_reload_knobs()
+
+    def set(self, name, value):
+        import os
+        os.environ[name] = str(value)
+        self.names.append(name)
+        self._reload()
+
+    def clear(self):
+        import os
+        for n in self.names:
+            os.environ.pop(n, None)
+        self.names = []
+        self._reload()
+
+
+@pytest.fixture
+def knobs():
+    k = _Knobs()
+    try:
+        yield k
+    finally:
+        k.clear()

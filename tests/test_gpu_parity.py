@@ -60,31 +60,20 @@ SPLIT_KERNELS = [
 
 @pytest.mark.parametrize("nsplit", [2, 4, 8])
 @pytest.mark.parametrize("name,cfg,kw", SPLIT_KERNELS)
-def test_forest_attention_with_pinned_kv_splits(name, cfg, kw, nsplit, monkeypatch):
+def test_forest_attention_with_pinned_kv_splits(name, cfg, kw, nsplit, knobs):
     """Every main kernel with 2, 4 and 8 KV splits per (tree, KV head, row block) and the merge kernel behind them
     (the plan of the scaled-down cases would otherwise settle on one or two splits)."""
     gu = _gu()
-    monkeypatch.setenv("DSBD_ATTN_NSPLIT", str(nsplit))
-    _reload_knobs()
-    try:
-        w = make_workload(cfg, V=64, **kw)
-        print("case", name, kw, "nsplit", nsplit, "N", w.n_nodes, flush=True)
-        d = gu.DeviceWorkload(w)
-        out, lse, fault = d.attention()
-        torch.cuda.synchronize()
-        assert int(fault.item()) == 0
-        ref_out, ref_lse = gu.oracle_attention(w)
-        err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
-        print("max abs err out/lse", err, flush=True)
-    finally:
-        monkeypatch.delenv("DSBD_ATTN_NSPLIT")
-        _reload_knobs()
-
-
-def _reload_knobs():
-    import paper_2409_16560_amd as dsbd
-    if hasattr(dsbd, "dsbd_reload_knobs"):
-        dsbd.dsbd_reload_knobs()
+    knobs.set("DSBD_ATTN_NSPLIT", nsplit)
+    w = make_workload(cfg, V=64, **kw)
+    print("case", name, kw, "nsplit", nsplit, "N", w.n_nodes, flush=True)
+    d = gu.DeviceWorkload(w)
+    out, lse, fault = d.attention()
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0
+    ref_out, ref_lse = gu.oracle_attention(w)
+    err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
+    print("max abs err out/lse", err, flush=True)
 
 
 def _plant_outlier_keys(w, beta=8.0, seed=7):
@@ -126,29 +115,24 @@ def _plant_outlier_keys(w, beta=8.0, seed=7):
 
 @pytest.mark.parametrize("name,cfg,kw", SPLIT_KERNELS)
 @pytest.mark.parametrize("nsplit", [1, 4])
-def test_forest_attention_outlier_scores_raise_the_reference(name, cfg, kw, nsplit, monkeypatch):
+def test_forest_attention_outlier_scores_raise_the_reference(name, cfg, kw, nsplit, knobs):
     """The kernels keep a per-row softmax reference that is only raised when a score exceeds it by 2^40, and then
     rescale what they have accumulated.  Random N(0,1) caches never get there after a row's first step, so keys tuned
     to single query rows are planted late in the prefix, at the end of the shared segment and among the tree rows:
     the reference rises in mid-stream, with non-zero accumulators, inside and across KV splits."""
     gu = _gu()
-    monkeypatch.setenv("DSBD_ATTN_NSPLIT", str(nsplit))
-    _reload_knobs()
-    try:
-        w = make_workload(cfg, V=64, **kw)
-        hit = _plant_outlier_keys(w)
-        d = gu.DeviceWorkload(w)
-        out, lse, fault = d.attention()
-        torch.cuda.synchronize()
-        assert int(fault.item()) == 0
-        ref_out, ref_lse = gu.oracle_attention(w)
-        # the planted keys do dominate their rows (the case tests what it says): 2^40 is 27.7 in natural units
-        assert min(ref_lse[n, h] for n, h in hit) > 35.0
-        err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
-        print("case", name, "nsplit", nsplit, "rows with a planted key", len(hit), "max abs err out/lse", err, flush=True)
-    finally:
-        monkeypatch.delenv("DSBD_ATTN_NSPLIT")
-        _reload_knobs()
+    knobs.set("DSBD_ATTN_NSPLIT", nsplit)
+    w = make_workload(cfg, V=64, **kw)
+    hit = _plant_outlier_keys(w)
+    d = gu.DeviceWorkload(w)
+    out, lse, fault = d.attention()
+    torch.cuda.synchronize()
+    assert int(fault.item()) == 0
+    ref_out, ref_lse = gu.oracle_attention(w)
+    # the planted keys do dominate their rows (the case tests what it says): 2^40 is 27.7 in natural units
+    assert min(ref_lse[n, h] for n, h in hit) > 35.0
+    err = gu.compare_attention(w, out, lse, ref_out, ref_lse)
+    print("case", name, "nsplit", nsplit, "rows with a planted key", len(hit), "max abs err out/lse", err, flush=True)
 
 
 @pytest.mark.parametrize("name,cfg,kw", SPLIT_KERNELS)
@@ -209,7 +193,7 @@ def test_forest_attention_random_shapes(sweep):
 
 @pytest.mark.parametrize("cfg,kw", [("c5", dict(L=333)), ("c5", dict(L=96, Hq=16, Hkv=4, tree_nodes=63, tree="binary_bfs")),
                                     ("c3", dict(L=300, shared_len=101, Hq=8, Hkv=1))])
-def test_register_staged_tile_kernel(cfg, kw, monkeypatch):
+def test_register_staged_tile_kernel(cfg, kw, knobs):
     """Head size 128 with many rows per K/V stream normally runs the kernel that loads its tiles straight into the
     LDS; the register-staged kernel (what head size 64 uses) is selected by a knob and must give the same."""
     gu = _gu()
@@ -218,7 +202,7 @@ def test_register_staged_tile_kernel(cfg, kw, monkeypatch):
     ref_out, ref_lse = gu.oracle_attention(w)
     out, lse, fault = d.attention()
     torch.cuda.synchronize()
-    monkeypatch.setenv("DSBD_ATTN_STAGED", "1")
+    knobs.set("DSBD_ATTN_STAGED", "1")
     out2, lse2, fault2 = d.attention()
     torch.cuda.synchronize()
     assert int(fault.item()) == 0 and int(fault2.item()) == 0
@@ -404,11 +388,11 @@ def test_warping_with_many_equal_entries(cfg, kw):
 
 @pytest.mark.parametrize("cfg,kw,top_k", [("c3", dict(V=5000), 0), ("c4", dict(V=3000, n_prompts=6), 0),
                                           ("c5", dict(V=20000, draft_top_k=4), 16), ("c5", dict(V=20000), 0)])
-def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, monkeypatch):
+def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, knobs):
     """The same results when the joint slices live in the workspace instead of the LDS (as they do at large
     I x V per workgroup): each workgroup's region is private, whatever way the layers cut I x V."""
     gu = _gu()
-    monkeypatch.setenv("DSBD_VERIFY_LDS_SLICE", "0")
+    knobs.set("DSBD_VERIFY_LDS_SLICE", "0")
     w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
     d = gu.DeviceWorkload(w)
     for t in (-1.0, 0.6):
@@ -564,7 +548,7 @@ def test_device_side_faults_are_reported_not_fatal():
     assert f & dsbd.DSBD_FAULT_NONFINITE and f & dsbd.DSBD_FAULT_TOKEN
 
 
-def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang():
+def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang(knobs):
     """Error path of the layer kernel's exchanges, forced from the host: one workgroup withholds its first post
     (test hook), every wait for it is bounded (2 ms here instead of 3 s), so all workgroups give up, the kernel ends
     normally and the call reports DSBD_FAULT_SYNC_TIMEOUT.  The next call on the same workspace works."""
@@ -575,14 +559,11 @@ def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang():
     d = gu.DeviceWorkload(w)
     nbytes = dsbd.dsbd_verify_forest_workspace_bytes(d.forest, w.V, 0, 1, w.W_cap, -1.0)
     ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
-    os.environ["DSBD_VERIFY_SYNC_LIMIT_US"] = "2000"
-    os.environ["DSBD_VERIFY_TEST_MUTE_WG"] = "5"
-    try:
-        res = d.verify(workspace=ws)
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["DSBD_VERIFY_SYNC_LIMIT_US"]
-        del os.environ["DSBD_VERIFY_TEST_MUTE_WG"]
+    knobs.set("DSBD_VERIFY_SYNC_LIMIT_US", "2000")
+    knobs.set("DSBD_VERIFY_TEST_MUTE_WG", "5")
+    res = d.verify(workspace=ws)
+    torch.cuda.synchronize()
+    knobs.clear()
     assert int(res.fault.item()) & dsbd.DSBD_FAULT_SYNC_TIMEOUT
     res = d.verify(workspace=ws)
     torch.cuda.synchronize()
@@ -684,3 +665,103 @@ def test_commit_kv_reports_what_does_not_fit():
     assert (int(fault.item()) & dsbd.DSBD_FAULT_BOUNDS != 0) == bool(too_long)
     for p, s_ in too_long:
         assert int(dlen[p, s_]) == 0 and bool((small[p * w.W_cap + s_] == -1.0).all())
+
+
+@pytest.mark.parametrize("broken", ["null V", "misaligned V", "null K", "source longer than max_len"])
+def test_commit_kv_rejects_a_destination_with_one_unusable_plane(broken):
+    """A destination whose K buffer is fine and whose V buffer is missing or misaligned (or the other way round) is
+    left untouched as a whole: both planes' workgroups take the same decision, the length reads 0 and the bounds
+    fault is raised.  The other destinations are copied as usual."""
+    gu = _gu()
+    import paper_2409_16560_amd as dsbd
+    from oracle import commit as o_commit, select as o_select
+    w = make_workload("c2", L=50, V=500, Hq=4, Hkv=4)
+    d = gu.DeviceWorkload(w)
+    res = d.verify()
+    nx = dsbd.dsbd_select_beams(d.forest, res)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w)
+    if gu.compare_verify(res, ref, w):
+        pytest.skip("near tie in the verification")
+    sref = o_select.select_beams(w.tree_off, w.parent, ref["n_out"], ref["out_parent"], ref["out_token"],
+                                 ref["out_logp_p"], ref["out_logp_q"], w.max_depth + 1)
+    rk, rv, rlen = o_commit.commit_kv(w.k_own, w.v_own, w.k_tree, w.v_tree, sref["n_next"], sref["src_tree"],
+                                      sref["path_len"], sref["path"])
+    n = w.n_prompts * w.W_cap
+    cap = 50 + w.max_depth + 1
+    mk = lambda: torch.full((cap + 1, w.Hkv, w.D), -1.0, dtype=torch.bfloat16, device="cuda")
+    dst_k, dst_v = [mk() for _ in range(n)], [mk() for _ in range(n)]
+    used = int(sref["n_next"][0])
+    assert used >= 2
+    victim = 1
+    dst = dsbd.KVDst([t[:cap] for t in dst_k], [t[:cap] for t in dst_v], d.kv)
+    kv = d.kv
+    if broken == "null V":
+        dst.v_ptr[victim] = 0
+    elif broken == "misaligned V":
+        dst.v_ptr[victim] += 8
+    elif broken == "null K":
+        dst.k_ptr[victim] = 0
+    else:
+        # the lengths array claims more tokens than the max_len the grid was sized for
+        victim = None
+        kv = dsbd.PrefixKV(d.kv.keep[0], d.kv.keep[1])
+        kv.len[int(sref["src_tree"][0, 1])] += 7
+    dlen, fault = dsbd.dsbd_commit_kv(d.forest, kv, d.k_tree, d.v_tree, nx, w.W_cap, dst)
+    torch.cuda.synchronize()
+    assert int(fault.item()) & dsbd.DSBD_FAULT_BOUNDS
+    bits = lambda t_: t_.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    hit = 0
+    for (p, s_), want in rk.items():
+        j = p * w.W_cap + s_
+        affected = (j == victim) if victim is not None else int(sref["src_tree"][p, s_]) == int(sref["src_tree"][0, 1])
+        if affected:
+            hit += 1
+            assert int(dlen[p, s_]) == 0
+            assert bool((dst_k[j] == -1.0).all()) and bool((dst_v[j] == -1.0).all())     # neither plane was written
+        else:
+            assert int(dlen[p, s_]) == rlen[p, s_]
+            assert np.array_equal(bits(dst_k[j][:want.shape[0]]), want) and np.array_equal(bits(dst_v[j][:want.shape[0]]), rv[(p, s_)])
+    assert hit >= 1
+
+
+def test_select_beams_with_more_trees_than_the_lds_staging_holds():
+    """Selection stages tree_off in the LDS for its binary searches; a forest of more than 8192 trees is searched where
+    it lies instead.  9000 single-node trees in 9000 prompts (no draft layers: every prompt draws from its root)."""
+    import paper_2409_16560_amd as dsbd
+    from oracle import select as o_select
+    T = 9000
+    rng = np.random.default_rng(5)
+    tree_off = np.arange(T + 1, dtype=np.int32)
+    parent = np.full(T, -1, dtype=np.int32)
+    forest = dsbd.Forest(np.arange(T, dtype=np.int32), tree_off, parent, np.zeros(T, dtype=np.int32), None, n_prompts=T,
+                         max_tree_nodes=1, max_depth=0, max_prompt_trees=1, device="cuda")
+    W_cap = 2
+    res = dsbd.VerifyResult.allocate(forest, W_cap)
+    n_out = rng.integers(0, 3, T).astype(np.int32)
+    out_parent = np.where(np.arange(W_cap)[None, :] < n_out[:, None], np.arange(T, dtype=np.int32)[:, None], -1).astype(np.int32)
+    out_token = rng.integers(0, 100, (T, W_cap)).astype(np.int32)
+    lp = rng.normal(0, 1, (T, W_cap)); lq = rng.normal(0, 1, (T, W_cap))
+    res.n_out.copy_(torch.from_numpy(n_out)); res.out_parent.copy_(torch.from_numpy(out_parent))
+    res.out_token.copy_(torch.from_numpy(out_token))
+    res.out_logp_target.copy_(torch.from_numpy(lp)); res.out_logp_draft.copy_(torch.from_numpy(lq))
+    for keep_one in (False, True):
+        nx = dsbd.dsbd_select_beams(forest, res, keep_one=keep_one)
+        torch.cuda.synchronize()
+        sref = o_select.select_beams(tree_off, parent, n_out, out_parent, out_token, lp, lq, 1, keep_one=keep_one)
+        _gu().compare_select(nx, sref)
+
+
+@pytest.mark.parametrize("n_prompts,t", [(300, -1.0), (300, 0.7), (700, -1.0)])
+def test_verify_more_prompts_than_workgroups_fit_the_device(n_prompts, t):
+    """Algorithm 1 runs per prompt.  A forest with more prompts than the layer kernel can keep resident at once (one
+    workgroup per prompt and compute unit) is verified in groups of prompts, one launch after the other, on the same
+    workspace."""
+    gu = _gu()
+    w = make_workload("c4", n_prompts=n_prompts, W=(1, 2), tree_nodes=(2, 6), L=1, Hq=1, Hkv=1, D=64, V=300, seed=11)
+    d = gu.DeviceWorkload(w)
+    res = d.verify(t=t)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t)
+    near = gu.compare_verify(res, ref, w)
+    print("prompts", n_prompts, "trees", w.n_trees, "nodes", w.n_nodes, "near ties", near, flush=True)

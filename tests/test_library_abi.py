@@ -71,6 +71,10 @@ def test_host_side_argument_checks_need_no_gpu():
         assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(pw)) == 0
     pw = b._Params(2, 1, 4, -1.0, 32, 0.9)
     assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(pw)) > 0
+    # a threshold that is not a number must not slip through as "dynamic width" (NaN compares false with everything)
+    pn = b._Params(2, 1, 4, float("nan"))
+    assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(pn)) == 0
+    assert lib.dsbd_verify_forest_workspace_bytes(C.byref(f), 100, C.byref(b._Params(2, 1, 4, 1.5))) == 0
     vin = b._VerifyIn(100, None, None, None, None, None, None, None)
     vout = b._VerifyOut(*([None] * 14))
     assert lib.dsbd_verify_forest(C.byref(f), C.byref(vin), C.byref(p), C.byref(vout), None, 0, None, None) == -1

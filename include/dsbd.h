@@ -329,6 +329,14 @@ void dsbd_reload_knobs(void);
 int32_t dsbd_timing_enable(int32_t kernel, int32_t capacity);
 int32_t dsbd_timing_collect(float* ms, int32_t max_n);
 
+/*
+ * Measurement aid (no counterpart in the paper): a plain streaming read of `bytes` (>= 1 MiB, 16-byte aligned DEVICE
+ * buffer, left unchanged) with the access pattern of the library's bandwidth-bound kernels, `reps` times between HIP
+ * events on `stream`; the shortest time in milliseconds goes to the HOST word best_ms.  It says what fraction of the
+ * datasheet bandwidth a pure read reaches on the box at hand.  Blocks until the runs are done.
+ */
+int32_t dsbd_stream_read_probe(const void* buf, size_t bytes, int32_t reps, float* best_ms, void* stream);
+
 /* Library version and the offload architecture it was built for. */
 const char* dsbd_version(void);
 

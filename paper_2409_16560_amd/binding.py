@@ -121,6 +121,8 @@ def load_library():
     lib.dsbd_build_forest.restype = C.c_int32
     lib.dsbd_build_forest.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(_ForestOut), C.c_void_p, C.c_void_p]
+    lib.dsbd_stream_read_probe.restype = C.c_int32
+    lib.dsbd_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_float), C.c_void_p]
     lib.dsbd_reload_knobs.restype = None
     lib.dsbd_reload_knobs.argtypes = []
     lib.dsbd_timing_enable.restype = C.c_int32
@@ -458,6 +460,15 @@ def dsbd_build_forest(root_off, layer_parent, layer_token, root_token=None, *, n
     f = Forest(tree_prompt[:n_roots], tree_off[:n_roots + 1], parent[:N], token[:N], rank[:N], n_prompts=P,
                max_tree_nodes=64, max_depth=gamma, max_prompt_trees=int(max_prompt_trees), device=dev)
     return f, node_of_root[:n_roots], node_of[:gamma * P * W_S].view(gamma, P * W_S) if gamma else node_of[:0], mx, fault
+
+
+def dsbd_stream_read_probe(buf: torch.Tensor, reps: int = 10, stream=None) -> float:
+    """GB/s of a plain streaming read over `buf` (a device tensor of at least 1 MiB), best of `reps`."""
+    ms = C.c_float(0.0)
+    nbytes = buf.numel() * buf.element_size()
+    _check(load_library().dsbd_stream_read_probe(_ptr(buf), nbytes, int(reps), C.byref(ms), _stream(stream)),
+           "dsbd_stream_read_probe")
+    return nbytes / (ms.value * 1e-3) / 1e9
 
 
 def dsbd_reload_knobs():

@@ -36,6 +36,8 @@
 #define NODE_CAP 512           // nodes of one prompt (all its trees)
 #define NEAR_TIE 1.0e-6
 #define SYNC_LIMIT_TICKS 300000000LL   // default bound of every wait: 3 s of the 100 MHz wall clock
+#define CU_LDS_BYTES (160 * 1024)  // LDS of a compute unit (gfx950)
+#define STATS_SIDE_WGS 3        // workgroups of the statistics pass per compute unit beside the layer kernel
 #define XU 4                   // logits per thread and model in flight in the exponential pass.  Eight (a 4008-entry piece of the
                                // benchmark's joint in one round) cost 256 vector registers; with four the kernel needs 186,
                                // which leaves room on every SIMD for waves of the statistics pass running beside it
@@ -268,7 +270,6 @@ struct LayerShared {
   double lm_p[64], lm_q[64];         // maxima of this workgroup's pieces of its rows (row i_lo first)
   float wmax[2][2 * VL_WAVES];       // per-wave maxima of a piece, two rows in flight
   double tmax[VL_BLOCK];             // partial row maxima of the gathering threads
-  double colmax[128];                // maxima of the (row, model) columns
   double sp[64], sq[64];             // beam weight / row sum: p_beam(i,x) = exp(z - max) * sp[i]
   double bw_p[64], bw_q[64];         // beam weights
   // accepted beams of the layer (next layer's inputs): node and its position among the candidates
@@ -788,21 +789,29 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       double s_p = 0.0, s_q = 0.0;
       const long long joff = (long long)i * V - e_lo;
       with_slices([&](auto P, auto Q) __attribute__((always_inline)) {
-      // the first XU logits of each model stay in registers; longer pieces are read a second time (from the caches)
-      float fp0[XU], fq0[XU];
+      // the first two rounds of XU logits per model stay in registers (a 4008-entry piece of the benchmark's joint is
+      // two rounds); longer pieces are read a second time (from the caches)
+      float fpA[XU], fqA[XU], fpB[XU], fqB[XU];
       float lmp = -INFINITY, lmq = -INFINITY;
+      const long long xA = x_lo + tid, xB = xA + XU * VL_BLOCK;
+      const bool haveB = x_lo + XU * VL_BLOCK < x_hi;                      // uniform over the workgroup
 #pragma unroll
       for (int k = 0; k < XU; ++k) {
-        const long long xx = min(x_lo + tid + k * VL_BLOCK, x_hi - 1);     // clamped repeats do not change a maximum
-        fp0[k] = zp[xx]; fq0[k] = zq[xx];
+        const long long xx = min(xA + k * VL_BLOCK, x_hi - 1);              // clamped repeats do not change a maximum
+        fpA[k] = zp[xx]; fqA[k] = zq[xx];
+      }
+#pragma unroll
+      for (int k = 0; k < XU; ++k) {
+        const long long xx = min(xB + k * VL_BLOCK, x_hi - 1);
+        fpB[k] = zp[xx]; fqB[k] = zq[xx];
       }
       bool nonfinite = false;        // (the statistics pass reports these for every row; this kernel for the rows it uses)
 #pragma unroll
       for (int k = 0; k < XU; ++k) {
-        lmp = fmaxf(lmp, fp0[k]); lmq = fmaxf(lmq, fq0[k]);
-        nonfinite |= !(fabsf(fp0[k]) <= FLT_MAX) | !(fabsf(fq0[k]) <= FLT_MAX);
+        lmp = fmaxf(fmaxf(lmp, fpA[k]), fpB[k]); lmq = fmaxf(fmaxf(lmq, fqA[k]), fqB[k]);
+        nonfinite |= !(fabsf(fpA[k]) <= FLT_MAX) | !(fabsf(fqA[k]) <= FLT_MAX) | !(fabsf(fpB[k]) <= FLT_MAX) | !(fabsf(fqB[k]) <= FLT_MAX);
       }
-      for (long long x = x_lo + tid + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {
+      for (long long x = xB + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {
         float fp[XU], fq[XU];
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
@@ -825,35 +834,50 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       for (int w = 0; w < VL_WAVES; ++w) { lmp = fmaxf(lmp, wm[2 * w]); lmq = fmaxf(lmq, wm[2 * w + 1]); }
       const double mp = (double)lmp, mq = (double)lmq;
       if (tid == 0) { sh.lm_p[i - i_lo] = mp; sh.lm_q[i - i_lo] = mq; }
+      // XU exponentials per model at a time (all of a round's at once would cost more registers than there are to spare)
+#pragma unroll
+      for (int k = 0; k < XU; ++k) {
+        const long long x = xA + k * VL_BLOCK;
+        if (x < x_hi) {
+          const double ep = exp_nonpos((double)fpA[k] - mp, sh.exp_tab);
+          double eq = ep;
+          if (!a.alias) eq = exp_nonpos((double)fqA[k] - mq, sh.exp_tab);
+          P[joff + x] = ep; Q[joff + x] = eq;
+          s_p += ep; s_q += eq;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (haveB) {
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
-          const long long x = x_lo + tid + k * VL_BLOCK;
+          const long long x = xB + k * VL_BLOCK;
           if (x < x_hi) {
-            const double ep = exp_nonpos((double)fp0[k] - mp, sh.exp_tab);
+            const double ep = exp_nonpos((double)fpB[k] - mp, sh.exp_tab);
             double eq = ep;
-            if (!a.alias) eq = exp_nonpos((double)fq0[k] - mq, sh.exp_tab);
+            if (!a.alias) eq = exp_nonpos((double)fqB[k] - mq, sh.exp_tab);
             P[joff + x] = ep; Q[joff + x] = eq;
             s_p += ep; s_q += eq;
           }
         }
-        for (long long x = x_lo + tid + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {   // XU logits of each model in flight, ragged end predicated
-          float fp[XU], fq[XU];
+      }
+      for (long long x = xB + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {   // XU logits of each model in flight, ragged end predicated
+        float fp[XU], fq[XU];
 #pragma unroll
-          for (int k = 0; k < XU; ++k) {
-            const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
-            fp[k] = zp[xx]; fq[k] = zq[xx];
-          }
+        for (int k = 0; k < XU; ++k) {
+          const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
+          fp[k] = zp[xx]; fq[k] = zq[xx];
+        }
 #pragma unroll
-          for (int k = 0; k < XU; ++k) {
-            if (x + k * VL_BLOCK < x_hi) {
-              const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab);
-              double eq = ep;
-              if (!a.alias) eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
-              P[joff + x + k * VL_BLOCK] = ep; Q[joff + x + k * VL_BLOCK] = eq;
-              s_p += ep; s_q += eq;
-            }
+        for (int k = 0; k < XU; ++k) {
+          if (x + k * VL_BLOCK < x_hi) {
+            const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab);
+            double eq = ep;
+            if (!a.alias) eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
+            P[joff + x + k * VL_BLOCK] = ep; Q[joff + x + k * VL_BLOCK] = eq;
+            s_p += ep; s_q += eq;
           }
         }
+      }
       });
       s_p = wave_sum(s_p);
       s_q = wave_sum(s_q);
@@ -955,27 +979,34 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           accM = Mn;
         }
       }
-      sh.tmax[tid] = accM;
-      sh.tsum[tid] = accS;
       stamp(20);
       if (!mine) give_up();
+      // Fold the R partial results of every column: first the maxima (lanes of a wave that share a column by lane
+      // exchanges, the waves' results through the LDS), then the sums put on the column's maximum, the same way.  The
+      // exchanges pair lanes symmetrically and the table is added up in index order, so every lane of a column, in
+      // every workgroup, gets the same bits.
+      const int gshift = cshift < 6 ? cshift : 6;                   // lanes (lane >> gshift) > 0 repeat a column of lane & (cpow - 1)
+      const int q = cshift < 6 ? wave : r;                          // this thread's row of the table
+      const int nq = cshift < 6 ? VL_WAVES : R;
+      double Mw = accM;
+      for (int off = cpow; off < 64; off <<= 1) Mw = fmax(Mw, __shfl_xor(Mw, off));
+      if ((lane >> gshift) == 0) sh.tmax[q * cpow + c] = Mw;
       __syncthreads();
       if (sh.abort) return;
       stamp(21);
-      if (c < ncols && r < R) {
-        double cm = -INFINITY;
-        for (int rr = 0; rr < R; ++rr) cm = fmax(cm, sh.tmax[c + (rr << cshift)]);
-        sh.tsum[tid] = accS * exp_nonpos(accM - cm, sh.exp_tab);      // partial results without a piece: 0 x exp(-inf) = 0
-        if (r == 0) sh.colmax[c] = cm;
-      }
+      double cm = -INFINITY;
+      for (int k = 0; k < nq; ++k) cm = fmax(cm, sh.tmax[k * cpow + c]);
+      double Sw = accS * exp_nonpos(accM - cm, sh.exp_tab);        // partial results without a piece: 0 x exp(-inf) = 0
+      for (int off = cpow; off < 64; off <<= 1) Sw += __shfl_xor(Sw, off);
+      if ((lane >> gshift) == 0) sh.tsum[q * cpow + c] = Sw;
       __syncthreads();
       // column totals; the scale factors of the rows, and what the fp64 log-sum-exp needs (taken later)
       if (tid < ncols) {
         double tot = 0.0;
-        for (int rr = 0; rr < R; ++rr) tot += sh.tsum[tid + (rr << cshift)];
+        for (int k = 0; k < nq; ++k) tot += sh.tsum[k * cpow + tid];
         const int i = tid >> 1;
-        if (tid & 1) { sh.max_q[i] = sh.colmax[tid]; sh.sq[i] = sh.bw_q[i] / tot; sh.lse_q[i] = tot; }
-        else { sh.max_p[i] = sh.colmax[tid]; sh.sp[i] = sh.bw_p[i] / tot; sh.lse_p[i] = tot; }
+        if (tid & 1) { sh.max_q[i] = cm; sh.sq[i] = sh.bw_q[i] / tot; sh.lse_q[i] = tot; }
+        else { sh.max_p[i] = cm; sh.sp[i] = sh.bw_p[i] / tot; sh.lse_p[i] = tot; }
       }
       __syncthreads();
     }
@@ -2134,8 +2165,20 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   fa.lse[0] = out->lse_target; fa.lse[1] = out->lse_draft;
   fa.logp[0] = out->node_logp_target; fa.logp[1] = out->node_logp_draft;
   auto launch_stats = [&](hipStream_t st) {
-    dsbd_launch(DSBD_KERNEL_VOCAB_STATS, vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes, alias ? 1 : 2), dim3(VS_BLOCK), 0,
-                st, sa);
+    // Beside the layer kernel the pass is held to STATS_SIDE_WGS workgroups per compute unit by the LDS it claims
+    // (it uses none of it): measured on the benchmark shape, four per unit (all that the registers left over admit)
+    // stream at full rate for 45 us and slow the layer kernel's first layers by 18 us, three stream for 88 us inside
+    // the layer kernel's 120 us and cost it 8 us, two take longer than the layer kernel itself.
+    unsigned int side_lds = 0;
+    if (st != stream) {
+      const long long layer_lds = (long long)(sizeof(LayerShared) + pl.lds_bytes + 511) / 512 * 512;
+      long long per = (CU_LDS_BYTES - layer_lds) / STATS_SIDE_WGS / 512 * 512 - 64;
+      if (per > 60000) per = 60000;
+      if (per > 0) side_lds = (unsigned int)per;
+      if (knobs.stats_side_lds >= 0) side_lds = (unsigned int)knobs.stats_side_lds;
+    }
+    dsbd_launch(DSBD_KERNEL_VOCAB_STATS, vocab_stats_kernel, dim3(pl.nchunk, f->n_nodes, alias ? 1 : 2), dim3(VS_BLOCK),
+                side_lds, st, sa);
     hipLaunchKernelGGL(vocab_finish_kernel, dim3((f->n_nodes + VS_BLOCK - 1) / VS_BLOCK), dim3(VS_BLOCK), 0, st, fa);
   };
   if (want_stats && !side) {

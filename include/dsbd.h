@@ -188,6 +188,26 @@ int32_t dsbd_verify_forest(const dsbd_forest* forest, const dsbd_verify_in* in, 
                            const dsbd_verify_out* out,
                            void* workspace, size_t workspace_bytes, int32_t* fault, void* stream);
 
+/*
+ * dsbd_verify_forest for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and error behaviour as dsbd_verify_forest, minus
+ * the workspace: it lives in a device array of dsbd_verify_forest_static_capacity() bytes (32 MiB) that is part of
+ * the library's image (every GPU the library runs on holds its own copy until the process ends).  A problem whose
+ * dsbd_verify_forest_workspace_bytes() exceeds the capacity is refused with DSBD_ERR_WORKSPACE and nothing is
+ * enqueued.  The call allocates nothing: no device memory, no stream, no event; the statistics pass runs beside the
+ * layer kernel only if an earlier ordinary call or dsbd_init() has already created the library's second stream on
+ * this device, otherwise in front of it on the caller's stream.  Nothing in the array has to be cleared between
+ * calls (exchange slots are told apart by a per-launch tag).  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (different streams, or host threads) race and give undefined results.
+ *
+ * dsbd_init() (optional): resolves the array's address and creates the second stream for the CURRENT device, so
+ * that the first call after it allocates nothing either.  Returns DSBD_OK or DSBD_ERR_HIP.
+ */
+int32_t dsbd_init(void);
+size_t dsbd_verify_forest_static_capacity(void);
+int32_t dsbd_verify_forest_static(const dsbd_forest* forest, const dsbd_verify_in* in, const dsbd_params* params,
+                                  const dsbd_verify_out* out, int32_t* fault, void* stream);
+
 /* Next beam set. */
 typedef struct dsbd_next_beams {
   int32_t* n_next;      /* [n_prompts]                                                               */

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     dsbd_forest_attention, dsbd_verify_forest, dsbd_select_beams, dsbd_commit_kv, dsbd_draft_layer, dsbd_build_forest,
     dsbd_version,
     dsbd_forest_attention_workspace_bytes, dsbd_verify_forest_workspace_bytes,
-    dsbd_timing_enable, dsbd_timing_collect, dsbd_reload_knobs, dsbd_stream_read_probe, DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS, DSBD_KERNEL_KV_COMMIT,
+    dsbd_timing_enable, dsbd_timing_collect, dsbd_reload_knobs, dsbd_stream_read_probe, dsbd_init, dsbd_verify_forest_static, dsbd_verify_forest_static_capacity, DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS, DSBD_KERNEL_KV_COMMIT,
     DSBD_NOT_REACHED, DSBD_ACCEPTED, DSBD_REJECTED, DSBD_PRUNED, DSBD_ROOT,
     DSBD_FAULT_TOPOLOGY, DSBD_FAULT_TOKEN, DSBD_FAULT_NONFINITE, DSBD_FAULT_ZERO_RESIDUAL,
     DSBD_FAULT_BOUNDS, DSBD_FAULT_SYNC_TIMEOUT,

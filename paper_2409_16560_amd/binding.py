@@ -121,6 +121,13 @@ def load_library():
     lib.dsbd_build_forest.restype = C.c_int32
     lib.dsbd_build_forest.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(_ForestOut), C.c_void_p, C.c_void_p]
+    lib.dsbd_init.restype = C.c_int32
+    lib.dsbd_init.argtypes = []
+    lib.dsbd_verify_forest_static_capacity.restype = C.c_size_t
+    lib.dsbd_verify_forest_static_capacity.argtypes = []
+    lib.dsbd_verify_forest_static.restype = C.c_int32
+    lib.dsbd_verify_forest_static.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyIn), C.POINTER(_Params),
+                                              C.POINTER(_VerifyOut), C.c_void_p, C.c_void_p]
     lib.dsbd_stream_read_probe.restype = C.c_int32
     lib.dsbd_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_float), C.c_void_p]
     lib.dsbd_reload_knobs.restype = None
@@ -318,6 +325,32 @@ def dsbd_verify_forest(forest: Forest, logits_target, logits_draft, beam_logp_ta
     rc = lib.dsbd_verify_forest(C.byref(f), C.byref(vin), C.byref(p), C.byref(vout), _ptr(workspace),
                                 workspace.numel(), _ptr(result.fault), _stream(stream))
     _check(rc, "dsbd_verify_forest")
+    return result
+
+
+def dsbd_init():
+    """Optional set-up for the current device (second stream, address of the static scratch array)."""
+    _check(load_library().dsbd_init(), "dsbd_init")
+
+
+def dsbd_verify_forest_static_capacity() -> int:
+    return int(load_library().dsbd_verify_forest_static_capacity())
+
+
+def dsbd_verify_forest_static(forest: Forest, logits_target, logits_draft, beam_logp_target, beam_logp_draft,
+                              u_accept, u_resid, u_fill, result: VerifyResult, W_L=0, W_min=1, W_cap=16, t=-1.0,
+                              stream=None, top_k=0, top_p=1.0):
+    """dsbd_verify_forest without a workspace argument (the library's static device array serves as one).  The
+    caller passes the result arrays: this wrapper allocates nothing either."""
+    lib = load_library()
+    N, V = logits_target.shape
+    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t, top_k, top_p)
+    vin = _VerifyIn(int(V), _ptr(logits_target), _ptr(logits_draft), _ptr(beam_logp_target), _ptr(beam_logp_draft),
+                    _ptr(u_accept), _ptr(u_resid), _ptr(u_fill))
+    vout = result.c_struct()
+    rc = lib.dsbd_verify_forest_static(C.byref(f), C.byref(vin), C.byref(p), C.byref(vout), _ptr(result.fault),
+                                       _stream(stream))
+    _check(rc, "dsbd_verify_forest_static")
     return result
 
 

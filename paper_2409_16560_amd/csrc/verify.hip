@@ -36,6 +36,7 @@
 #define NODE_CAP 512           // nodes of one prompt (all its trees)
 #define NEAR_TIE 1.0e-6
 #define SYNC_LIMIT_TICKS 300000000LL   // default bound of every wait: 3 s of the 100 MHz wall clock
+#define DSBD_STATIC_SCRATCH_BYTES (32u << 20)   // the device array behind dsbd_verify_forest_static
 #define CU_LDS_BYTES (160 * 1024)  // LDS of a compute unit (gfx950)
 #define STATS_SIDE_WGS 3        // workgroups of the statistics pass per compute unit beside the layer kernel
 #define XU 4                   // logits per thread and model in flight in the exponential pass.  Eight (a 4008-entry piece of the
@@ -2092,14 +2093,14 @@ struct SideStream {
   hipEvent_t fork = nullptr, join = nullptr;
   bool tried = false, ok = false;
 };
-SideStream* side_stream_of_current_device() {
+SideStream* side_stream_of_current_device(bool may_create) {
   static SideStream table[64];
   static std::mutex mutex;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
   std::lock_guard<std::mutex> lock(mutex);
   SideStream& s = table[dev];
-  if (!s.tried) {
+  if (!s.tried && may_create) {
     s.tried = true;
     s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
            hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
@@ -2121,9 +2122,11 @@ extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32
   return carve_verify(ws, f, V, pl, &pt, &pb, &qb, &red) + 256;
 }
 
-extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
-                                      const dsbd_verify_out* out, void* workspace, size_t workspace_bytes,
-                                      int32_t* fault, void* stream_) {
+namespace {
+// may_create_side: the second stream may be created by this call (an ordinary call); false for the entry point that
+// must not allocate, which uses the second stream only if an earlier call or dsbd_init() has made it.
+int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p, const dsbd_verify_out* out,
+                    void* workspace, size_t workspace_bytes, int32_t* fault, void* stream_, bool may_create_side) {
   if (!in || !out || !fault) return DSBD_ERR_INVALID;
   int32_t rc = check_verify(f, in->V, p);
   if (rc != DSBD_OK) return rc;
@@ -2153,7 +2156,7 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
   // to the layer kernel: ordered after everything the caller's stream holds so far, and the caller's stream continues
   // only when both are done.  DSBD_VERIFY_OVERLAP=0 (or a stream that cannot be created) puts it in front instead.
   const bool want_stats = out->lse_target || out->lse_draft || out->node_logp_target || out->node_logp_draft;
-  SideStream* side = (want_stats && knobs.verify_overlap) ? side_stream_of_current_device() : nullptr;
+  SideStream* side = (want_stats && knobs.verify_overlap) ? side_stream_of_current_device(may_create_side) : nullptr;
   StatsArgs sa;
   sa.z[0] = in->logits_target; sa.z[1] = in->logits_draft;
   sa.n_nodes = f->n_nodes; sa.V = in->V; sa.nchunk = pl.nchunk; sa.chunk = pl.chunk;
@@ -2237,4 +2240,57 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
     if (le == hipSuccess) le = le2;
   }
   return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
+}
+}  // namespace
+
+extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
+                                      const dsbd_verify_out* out, void* workspace, size_t workspace_bytes,
+                                      int32_t* fault, void* stream_) {
+  return verify_impl(f, in, p, out, workspace, workspace_bytes, fault, stream_, true);
+}
+
+// ---- the same call for callers that cannot allocate device memory (code under HIP graph capture, serving loops,
+// harnesses that forbid hipMalloc): the workspace is a device array that is part of the library's image.
+static __device__ __align__(256) unsigned char scratch[DSBD_STATIC_SCRATCH_BYTES];
+
+namespace {
+// Address of `scratch` on the current device (every GPU holds its own copy of the array at its own address; the
+// array's name is only a host-side stand-in and must never reach a kernel or a memory call).
+void* static_scratch_of_current_device() {
+  static void* table[64] = {nullptr};
+  static std::mutex mutex;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mutex);
+  if (!table[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    table[dev] = ptr;
+  }
+  return table[dev];
+}
+}  // namespace
+
+extern "C" int32_t dsbd_init(void) {
+  if (!static_scratch_of_current_device()) return DSBD_ERR_HIP;
+  (void)device_limits();
+  (void)dsbd_knobs();
+  return side_stream_of_current_device(true) ? DSBD_OK : DSBD_ERR_HIP;
+}
+
+extern "C" size_t dsbd_verify_forest_static_capacity(void) { return DSBD_STATIC_SCRATCH_BYTES; }
+
+extern "C" int32_t dsbd_verify_forest_static(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
+                                             const dsbd_verify_out* out, int32_t* fault, void* stream_) {
+  if (!in) return DSBD_ERR_INVALID;
+  const int32_t rc = check_verify(f, in->V, p);
+  if (rc != DSBD_OK) return rc;
+  // the same plan as the ordinary call; a problem whose workspace exceeds the array is turned away, nothing is enqueued
+  if (dsbd_verify_forest_workspace_bytes(f, in->V, p) > (size_t)DSBD_STATIC_SCRATCH_BYTES) return DSBD_ERR_WORKSPACE;
+  void* ptr = static_scratch_of_current_device();
+  if (!ptr) return DSBD_ERR_HIP;
+  return verify_impl(f, in, p, out, ptr, DSBD_STATIC_SCRATCH_BYTES, fault, stream_, false);
 }

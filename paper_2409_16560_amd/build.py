@@ -13,8 +13,13 @@ SOURCES = ["attention.hip", "verify.hip", "select.hip", "commit.hip", "draft.hip
 # row-maximum checks.  (verify.hip must keep NaN semantics: it detects non-finite logits.)
 # verify.hip: the layer kernel sits at the 256-register limit; hoisting loop-invariant address arithmetic out of its
 # layer loop (machine LICM) made it spill 84-120 bytes per lane, with reloads in front of stores on the critical path.
+# (-Rpass-analysis: the compiler's per-kernel register report, checked below)
 FILE_FLAGS = {"attention.hip": os.environ.get("DSBD_ATTN_FLAGS", "-fno-honor-nans").split(),
-              "verify.hip": os.environ.get("DSBD_VERIFY_FLAGS", "-mllvm -disable-machine-licm").split()}
+              "verify.hip": os.environ.get("DSBD_VERIFY_FLAGS", "-mllvm -disable-machine-licm").split()
+              + ["-Rpass-analysis=kernel-resource-usage"]}
+# The statistics pass runs beside the layer kernel, one workgroup (a wave of 32 registers per SIMD) per compute unit:
+# that needs the layer kernel's two waves per SIMD to leave registers free; 208 leaves room for three such waves.
+LAYER_KERNEL_VGPR_BUDGET = 208
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fgpu-rdc-", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
@@ -24,6 +29,32 @@ def hipcc():
         if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
             return c
     return "hipcc"
+
+
+def check_registers(report, verbose):
+    """Reads the compiler's resource report: warns when a layer kernel outgrows the register budget that lets the
+    statistics pass share its compute units, or spills.  Returns what is left of the compiler's output."""
+    import re
+    rest, name = [], None
+    for line in report.splitlines():
+        if "-Rpass-analysis=kernel-resource-usage" not in line:
+            if "remark:" not in line and not (name and (line.strip().startswith(("|", "^")) or re.match(r"\s*\d+ \|", line))):
+                rest.append(line)
+            continue
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"\bVGPRs: (\d+)", line)
+        if m and name and "verify_layers_kernel" in name:
+            if verbose:
+                print("%s: %s vector registers" % (name, m.group(1)))
+            if int(m.group(1)) > LAYER_KERNEL_VGPR_BUDGET:
+                print("WARNING: %s uses %s vector registers (budget %d): the statistics pass will no longer fit beside it"
+                      % (name, m.group(1), LAYER_KERNEL_VGPR_BUDGET))
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name and "verify_layers_kernel" in name and int(m.group(1)) > 0:
+            print("WARNING: %s spills %s bytes per lane" % (name, m.group(1)))
+    return "\n".join(rest)
 
 
 def build(verbose=True):
@@ -41,6 +72,8 @@ def build(verbose=True):
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if p.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, out))
+        if "-Rpass-analysis=kernel-resource-usage" in FILE_FLAGS.get(src, []):
+            out = check_registers(out, verbose)
         if verbose and out.strip():
             print(out)
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs

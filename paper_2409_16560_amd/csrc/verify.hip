@@ -38,7 +38,7 @@
 #define SYNC_LIMIT_TICKS 300000000LL   // default bound of every wait: 3 s of the 100 MHz wall clock
 #define DSBD_STATIC_SCRATCH_BYTES (32u << 20)   // the device array behind dsbd_verify_forest_static
 #define CU_LDS_BYTES (160 * 1024)  // LDS of a compute unit (gfx950)
-#define STATS_SIDE_WGS 3        // workgroups of the statistics pass per compute unit beside the layer kernel
+#define STATS_SIDE_WGS 1        // workgroups of the statistics pass per compute unit beside the layer kernel
 #define XU 4                   // logits per thread and model in flight in the exponential pass.  Eight (a 4008-entry piece of the
                                // benchmark's joint in one round) cost 256 vector registers; with four the kernel needs 186,
                                // which leaves room on every SIMD for waves of the statistics pass running beside it
@@ -1454,14 +1454,19 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         return c2 < sh.nU ? fmax(sh.U_p[c2] - c * sh.U_q[c2], 0.0) : 0.0;
       }
       with_slices([&](auto P, auto Q) {
-        long long j = tid - t0;
-        for (; j + 3 * nt < len; j += 4 * nt) {
-          const double p0 = P[j], p1 = P[j + nt], p2 = P[j + 2 * nt], p3 = P[j + 3 * nt];
-          const double q0 = Q[j], q1 = Q[j + nt], q2 = Q[j + 2 * nt], q3 = Q[j + 3 * nt];
-          s0 += fmax(p0 - c * q0, 0.0); s1 += fmax(p1 - c * q1, 0.0);
-          s2 += fmax(p2 - c * q2, 0.0); s3 += fmax(p3 - c * q3, 0.0);
+        // four elements of each array in flight per thread, the ragged end predicated (one element after the other,
+        // the tail of a 4008-entry slice cost four dependent LDS round trips per chain entry; eight in flight cost
+        // more registers than the kernel can spare beside the statistics pass)
+        const int n = (int)len;            // a slice has fewer than 2^31 entries
+        for (int j = tid - t0; j < n; j += 4 * nt) {
+          const int j1 = min(j + nt, n - 1), j2 = min(j + 2 * nt, n - 1), j3 = min(j + 3 * nt, n - 1);
+          const double p0 = P[j], p1 = P[j1], p2 = P[j2], p3 = P[j3];
+          const double q0 = Q[j], q1 = Q[j1], q2 = Q[j2], q3 = Q[j3];
+          s0 += fmax(p0 - c * q0, 0.0);
+          s1 += (j + nt < n) ? fmax(p1 - c * q1, 0.0) : 0.0;
+          s2 += (j + 2 * nt < n) ? fmax(p2 - c * q2, 0.0) : 0.0;
+          s3 += (j + 3 * nt < n) ? fmax(p3 - c * q3, 0.0) : 0.0;
         }
-        for (; j < len; j += nt) s0 += fmax(P[j] - c * Q[j], 0.0);
       });
       return (s0 + s1) + (s2 + s3);
     };
@@ -1773,45 +1778,89 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
       const int kdone = sh.kmax;     // entries 1..kdone valid
       __syncthreads();
-      // alpha_i (Eq. 3), first[i] = alpha_i prod_{j<i} (1 - alpha_j) (Eq. 2), Pa[m] = P(m,0)
-      for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
-        double alpha = 1.0;            // no residual mass left: accepted with certainty
-        if (i + 1 <= kdone && sh.FF[i] > 0.0) alpha = 1.0 - sh.FF[i + 1] / sh.FF[i];
-        sh.u.w.alpha[i] = alpha;
-      }
-      __syncthreads();
-      for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
-        double f = sh.u.w.alpha[i];
-        for (int j = 1; j < i; ++j) f *= (1.0 - sh.u.w.alpha[j]);
-        sh.u.w.first[i] = f;
-      }
-      if (tid == 0) {
-        double none = 1.0;
-        sh.Pa[0] = 1.0;
-        for (int m = 1; m <= M; ++m) { none *= (1.0 - sh.u.w.alpha[m]); sh.Pa[m] = none; }
-      }
-      __syncthreads();
-      // W~ = max{K : 1 - sum_{k<K} P(M,k) >= t}; K = 0 always qualifies
       int Wt = 0;
-      double below = 0.0;              // sum_{k<K} P(M,k)
-      const int Kmax = min(M, a.W_cap);
-      for (int K = 1; K <= Kmax; ++K) {
-        below += sh.Pa[M];             // column K-1 is in Pa
-        if (!(1.0 - below >= thr)) break;
-        Wt = K;
-        if (K == Kmax) break;
-        // column K from column K-1:  P(m,K) = sum_{i=1..m} first[i] P(m-i,K-1), zero for m < K
-        for (int m = tid; m <= M; m += VL_BLOCK) {
-          double tot = 0.0;
-          if (m >= K)
-            for (int i = 1; i <= m; ++i) tot += sh.u.w.first[i] * ((m - i >= K - 1) ? sh.Pa[m - i] : 0.0);
-          sh.Pb[m] = tot;
+      if (M < 64) {
+        // up to 63 drafts (every forest of the paper's shapes): the table fits one wave, lane m = row m, and the
+        // steps are ordered by wavefront fences instead of workgroup barriers.  Same sums in the same order as the
+        // general form below.
+        if (wave == 0) {
+          const int m = lane;
+          if (m >= 1 && m <= M) {
+            double alpha = 1.0;            // no residual mass left: accepted with certainty
+            if (m + 1 <= kdone && sh.FF[m] > 0.0) alpha = 1.0 - sh.FF[m + 1] / sh.FF[m];
+            sh.u.w.alpha[m] = alpha;
+          }
+          wave_lds_fence();
+          if (m >= 1 && m <= M) {
+            double f = sh.u.w.alpha[m];
+            for (int j = 1; j < m; ++j) f *= (1.0 - sh.u.w.alpha[j]);
+            sh.u.w.first[m] = f;
+          }
+          if (m <= M) {
+            double none = 1.0;
+            for (int j = 1; j <= m; ++j) none *= (1.0 - sh.u.w.alpha[j]);
+            sh.Pa[m] = none;
+          }
+          wave_lds_fence();
+          double below = 0.0;              // sum_{k<K} P(M,k)
+          const int Kmax = min(M, a.W_cap);
+          for (int K = 1; K <= Kmax; ++K) {
+            below += sh.Pa[M];             // column K-1 is in Pa (uniform over the wave)
+            if (!(1.0 - below >= thr)) break;
+            Wt = K;
+            if (K == Kmax) break;
+            double tot = 0.0;
+            if (m <= M && m >= K)
+              for (int i = 1; i <= m; ++i) tot += sh.u.w.first[i] * ((m - i >= K - 1) ? sh.Pa[m - i] : 0.0);
+            wave_lds_fence();              // everybody has read column K-1
+            if (m <= M) sh.Pa[m] = tot;
+            wave_lds_fence();
+          }
+          if (lane == 0) sh.found = Wt;
         }
         __syncthreads();
-        for (int m = tid; m <= M; m += VL_BLOCK) sh.Pa[m] = sh.Pb[m];
+        Wt = sh.found;
+        __syncthreads();
+      } else {
+        // alpha_i (Eq. 3), first[i] = alpha_i prod_{j<i} (1 - alpha_j) (Eq. 2), Pa[m] = P(m,0)
+        for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
+          double alpha = 1.0;            // no residual mass left: accepted with certainty
+          if (i + 1 <= kdone && sh.FF[i] > 0.0) alpha = 1.0 - sh.FF[i + 1] / sh.FF[i];
+          sh.u.w.alpha[i] = alpha;
+        }
+        __syncthreads();
+        for (int i = 1 + tid; i <= M; i += VL_BLOCK) {
+          double f = sh.u.w.alpha[i];
+          for (int j = 1; j < i; ++j) f *= (1.0 - sh.u.w.alpha[j]);
+          sh.u.w.first[i] = f;
+        }
+        if (tid == 0) {
+          double none = 1.0;
+          sh.Pa[0] = 1.0;
+          for (int m = 1; m <= M; ++m) { none *= (1.0 - sh.u.w.alpha[m]); sh.Pa[m] = none; }
+        }
+        __syncthreads();
+        // W~ = max{K : 1 - sum_{k<K} P(M,k) >= t}; K = 0 always qualifies
+        double below = 0.0;              // sum_{k<K} P(M,k)
+        const int Kmax = min(M, a.W_cap);
+        for (int K = 1; K <= Kmax; ++K) {
+          below += sh.Pa[M];             // column K-1 is in Pa
+          if (!(1.0 - below >= thr)) break;
+          Wt = K;
+          if (K == Kmax) break;
+          // column K from column K-1:  P(m,K) = sum_{i=1..m} first[i] P(m-i,K-1), zero for m < K
+          for (int m = tid; m <= M; m += VL_BLOCK) {
+            double tot = 0.0;
+            if (m >= K)
+              for (int i = 1; i <= m; ++i) tot += sh.u.w.first[i] * ((m - i >= K - 1) ? sh.Pa[m - i] : 0.0);
+            sh.Pb[m] = tot;
+          }
+          __syncthreads();
+          for (int m = tid; m <= M; m += VL_BLOCK) sh.Pa[m] = sh.Pb[m];
+          __syncthreads();
+        }
         __syncthreads();
       }
-      __syncthreads();
       WL = min(a.W_cap, max(a.W_min, Wt));
     }
     WL = min(WL, a.W_cap);
@@ -2169,9 +2218,10 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   fa.logp[0] = out->node_logp_target; fa.logp[1] = out->node_logp_draft;
   auto launch_stats = [&](hipStream_t st) {
     // Beside the layer kernel the pass is held to STATS_SIDE_WGS workgroups per compute unit by the LDS it claims
-    // (it uses none of it): measured on the benchmark shape, four per unit (all that the registers left over admit)
-    // stream at full rate for 45 us and slow the layer kernel's first layers by 18 us, three stream for 88 us inside
-    // the layer kernel's 120 us and cost it 8 us, two take longer than the layer kernel itself.
+    // (it uses none of it).  Measured on the benchmark shape (layer kernel alone: 120 us, the call with the pass in
+    // front of it: 167 us): four per unit (all that the registers left over admit) stream at full rate for 49 us,
+    // slow the layer kernel's first layers down and give a call of 149 us; three: 55 us and 146 us; one: 88 us, inside
+    // the layer kernel's run, 142 us; none: the pass runs behind the layer kernel, 184 us.
     unsigned int side_lds = 0;
     if (st != stream) {
       const long long layer_lds = (long long)(sizeof(LayerShared) + pl.lds_bytes + 511) / 512 * 512;

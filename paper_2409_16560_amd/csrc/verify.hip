@@ -222,6 +222,8 @@ struct SlotLayout {
   int b, b_w;            // warping: every workgroup's candidate list, b_w slots each
   int c;                 // warping: the groups' merged lists (b_w slots each)
   int d;                 // warping: the final entries, posted by the prompt's first workgroup
+  int acc;               // accumulator words of the one-hop sums: 2 banks x NACC lines
+  int acc0;              // their values at launch, posted by the prompt's first workgroup: 2 x NACC slots
   int prompt_stride;
 };
 #define WARP_RESULT_SLOTS 193     // count + 64 x (index, p, q)
@@ -259,6 +261,8 @@ struct LayersArgs {
 };
 
 #define VL_WAVES (VL_BLOCK / 64)
+#define NACC 8                 // accumulator words of a one-hop sum (see wave_sum_accumulators)
+#define ACC_FIELD_BITS 54
 static_assert(NODE_CAP <= VL_BLOCK, "one thread per node of a prompt");
 static_assert(VL_WAVES == 8, "the fixed reduction trees below are written for eight waves");
 
@@ -295,6 +299,7 @@ struct LayerShared {
   } u;
   double Pa[NODE_CAP + 2], Pb[NODE_CAP + 2];
   double wsum[2][VL_WAVES];
+  unsigned long long acc_prev[2][NACC];   // the accumulator words' values before their next exchange
   double scan_w[VL_WAVES];
   double tsum[VL_BLOCK];
   double gpart[256];                 // one partial per workgroup of the prompt (G <= 256)
@@ -522,6 +527,48 @@ __device__ __forceinline__ bool wave_sum_groups(Slot* bank, Slot* gbank, int G, 
   return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
 }
 
+// Sum over the prompt's G workgroups of one value in [0, 4) each, in one hop: every workgroup adds its value, as a
+// 2^-52 fixed-point number with a 1 in the count field above it, to one of NACC accumulator words (an agent-scope
+// integer atomic: the order of the additions does not matter, so the sum is the same in every run), and one wave
+// polls the NACC words until each has counted all its members.  The accumulators are never cleared: a word only ever
+// grows (modulo 2^64), and what an exchange added to it is the difference to the value it had before the exchange,
+// which every workgroup knows (the value it read at the end of the word's previous exchange; the values at launch are
+// read by the prompt's first workgroup before anybody adds and handed round with the first layer's row sums).  The
+// difference decodes as (members << 54) + sum as long as the sum stays below 2^54 units and there are fewer than 1024
+// members per word.  Two banks alternate as for the slot exchanges.  Measured among 256 workgroups: 1.8 us against
+// 2.45 us for the two-hop slot exchange (a microbenchmark of both on the same box).
+__device__ __forceinline__ bool wave_sum_accumulators(unsigned long long* accs, unsigned long long* prev, int G, int g,
+                                                      double own, long long limit, double& total) {
+  const int lane = threadIdx.x & 63;
+  if (G == 1) { total = own; return true; }
+  if (lane == 0) {
+    const unsigned long long q = (unsigned long long)__double2ull_rn(fmin(fmax(own, 0.0), 3.999) * 4503599627370496.0);
+    __hip_atomic_fetch_add(&accs[(g % NACC) * 16], (1ull << ACC_FIELD_BITS) + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  bool ok = true;
+  unsigned long long field = 0;
+  if (lane < NACC) {
+    const unsigned long long members = lane < G ? (unsigned long long)((G - lane + NACC - 1) / NACC) : 0ull;
+    if (members) {
+      const unsigned long long before = prev[lane];
+      long long t0 = 0;
+      for (int spin = 0;; ++spin) {
+        const unsigned long long w = __hip_atomic_load(&accs[lane * 16], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long diff = w - before;
+        if ((diff >> ACC_FIELD_BITS) == members) { field = diff & ((1ull << ACC_FIELD_BITS) - 1); prev[lane] = w; break; }
+        if (spin == 0) t0 = wall_clock64();
+        else if ((spin & 15) == 0 && wall_clock64() - t0 > limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 1; off < NACC; off <<= 1) field += __shfl_xor(field, off);     // lanes 0..NACC-1 hold the total
+  field = __shfl(field, 0);
+  total = (double)field * (1.0 / 4503599627370496.0);
+  return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
+}
+
 __device__ __forceinline__ Slot* prompt_slots(const LayersArgs& a, int prompt) {
   return reinterpret_cast<Slot*>(a.red) + (long long)prompt * a.sl.prompt_stride;
 }
@@ -591,6 +638,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
   };
   stamp(0);
+
+  // the accumulator words of the one-hop sums as the launch finds them: read by the prompt's first workgroup before
+  // anybody adds to them (nobody does before the first layer's row sums, which wait for this workgroup's), and handed
+  // to the others in tagged slots, collected during the first layer
+  unsigned long long* const accs = reinterpret_cast<unsigned long long*>(slots + a.sl.acc);
+  const unsigned long long acc0_tag = exchange_tag(a.nonce + 0xFFFFFFull);
+  unsigned int achg = 0;       // accumulator exchanges so far (alternates their two banks)
+  if (g == 0 && tid < 2 * NACC) {
+    const unsigned long long w = __hip_atomic_load(&accs[tid * 16], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    (&sh.acc_prev[0][0])[tid] = w;
+    slot_post(slots + a.sl.acc0 + tid, __longlong_as_double((long long)w), acc0_tag);
+  }
 
   if (tid == 0) { sh.abort = 0; sh.sbad = 0; sh.sgamma = 0; sh.counter = 0; sh.found = 0; }
   if (tid < 64) sh.exp_tab[tid] = c_exp2_tab[tid];
@@ -907,6 +966,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     }
     stamp(102);
 
+    if (l == 1 && g != 0 && wave == 2 && lane < 2 * NACC) {      // the accumulator words' values at launch
+      double v = 0.0;
+      if (!slot_wait(slots + a.sl.acc0 + lane, acc0_tag, v, a.sync_limit)) give_up();
+      (&sh.acc_prev[0][0])[lane] = (unsigned long long)__double_as_longlong(v);
+    }
     // ===== meanwhile: beam weights = softmax of the cumulative likelihoods over I (Section 2.1), by one wave
     if (wave == 1) {
       const bool valid = lane < nI;
@@ -1750,14 +1814,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           __syncthreads();
           return true;
         }
-        epoch += 1;
-        const unsigned long long tag = exchange_tag(a.nonce + epoch);
-        Slot* bank = slots + bank_x(xchg);
-        Slot* gbank = slots + bank_xc(xchg++);
+        unsigned long long* const x_acc = accs + (size_t)(achg & 1) * NACC * 16;
+        unsigned long long* const x_prev = sh.acc_prev[achg & 1];
+        achg += 1;
         if (wave == 0) {
-          if (lane == 0) dense_post(bank, a.G, g, tot, tag);
           double F;
-          if (!wave_sum_groups(bank, gbank, a.G, g, tot, tag, a.sync_limit, F)) give_up();
+          if (!wave_sum_accumulators(x_acc, x_prev, a.G, g, tot, a.sync_limit, F)) give_up();
           stamp(45);
           if (lane == 0) { sh.cc[k + 1] = c; sh.FF[k + 1] = F; sh.kmax = k + 1; }
           if (then_decide) decide(decide_round, k + 1);
@@ -1895,17 +1957,16 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           __syncthreads();
           continue;
         }
-        if (!posted) {
-          epoch += 1;
-          x_tag = exchange_tag(a.nonce + epoch);
-          x_bank = slots + bank_x(xchg);
-          x_gbank = slots + bank_xc(xchg++);
-          if (tid == 0) dense_post(x_bank, a.G, g, tot, x_tag);
-          x_own = tot;
-        }
+        // the entry posted ahead of time (c = 1) comes through its slots; every later one through the accumulators
+        const bool via_acc = !posted;
+        unsigned long long* const x_acc = accs + (size_t)(achg & 1) * NACC * 16;
+        unsigned long long* const x_prev = sh.acc_prev[achg & 1];
+        if (via_acc) achg += 1;
         if (wave == 0) {
           double F;
-          if (!wave_sum_groups(x_bank, x_gbank, a.G, g, x_own, x_tag, a.sync_limit, F)) give_up();
+          const bool ok_x = via_acc ? wave_sum_accumulators(x_acc, x_prev, a.G, g, tot, a.sync_limit, F)
+                                    : wave_sum_groups(x_bank, x_gbank, a.G, g, x_own, x_tag, a.sync_limit, F);
+          if (!ok_x) give_up();
           if (lane == 0) { sh.cc[k + 1] = c_next; sh.FF[k + 1] = F; sh.kmax = k + 1; }
         }
         posted = false;
@@ -2069,8 +2130,12 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
   const DeviceLimits& lim = device_limits();
   const int resident = lim.cus * lim.blocks_per_cu;
   int G = f->n_prompts > 0 ? lim.cus / f->n_prompts : 1;
-  const long long joint = (long long)pl.I_cap * V;
-  const int by_work = (int)((joint + 4095) / 4096);
+  // (sized by the joint of the input beams, which is what a fixed width keeps every layer at: an exchange among 64
+  // workgroups costs 1.7 us against 2.5 us among 256, and below about 4000 entries per workgroup the passes over a
+  // slice are shorter than that difference.  Measured: 8 beams x 32000 tokens 83 us with 64 workgroups, 88 us with
+  // 256; with the dynamic width, which runs many more exchanges, 147 us against 165 us.)
+  const long long joint = (long long)f->max_prompt_trees * V;
+  const int by_work = (int)((joint + 3999) / 4000);
   if (G > by_work) G = by_work;
   if (knobs.verify_g >= 1 && (long long)knobs.verify_g * f->n_prompts <= resident) G = knobs.verify_g;   // tuning knob
   if (G < 1) G = 1;
@@ -2101,6 +2166,8 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
       sl.c = off; off += (G + WARP_GROUP - 1) / WARP_GROUP * sl.b_w;
       sl.d = off; off += up8(WARP_RESULT_SLOTS);
     }
+    sl.acc = off; off += 2 * NACC * LINE_SLOTS;
+    sl.acc0 = off; off += up8(2 * NACC);
     sl.prompt_stride = off;
   }
   // dynamic LDS for the p_beam / q_beam slices: what one slice needs, at most VL_DYN_LDS_BYTES for the two arrays
@@ -2225,7 +2292,11 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
     unsigned int side_lds = 0;
     if (st != stream) {
       const long long layer_lds = (long long)(sizeof(LayerShared) + pl.lds_bytes + 511) / 512 * 512;
-      long long per = (CU_LDS_BYTES - layer_lds) / STATS_SIDE_WGS / 512 * 512 - 64;
+      // a claim that STATS_SIDE_WGS workgroups fit in beside the layer kernel's LDS and one more does not, with
+      // half a claim of slack on either side (the allocation granule and the pass's own few bytes are not known here)
+      const long long free_lds = CU_LDS_BYTES - layer_lds;
+      long long per = free_lds / (STATS_SIDE_WGS + 1) + free_lds / (2 * STATS_SIDE_WGS * (STATS_SIDE_WGS + 1));
+      per = per / 256 * 256;
       if (per > 60000) per = 60000;
       if (per > 0) side_lds = (unsigned int)per;
       if (knobs.stats_side_lds >= 0) side_lds = (unsigned int)knobs.stats_side_lds;

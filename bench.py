@@ -218,6 +218,8 @@ def main():
     ap.add_argument("--no-commit", action="store_true", help="skip the (separately reported) cache-commit measurement")
     ap.add_argument("--no-warp", action="store_true", help="skip the (separately reported) warped verification")
     ap.add_argument("--no-draft", action="store_true", help="skip the (separately reported) draft-side sampling step")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first copy 256 MiB device to device (a kernel of known traffic, for scaling a profiler's byte counters)")
     ap.add_argument("--warp-top-k", type=int, default=10, help="warping of the separately reported runs (the paper's setting)")
     ap.add_argument("--warp-top-p", type=float, default=0.8)
     args = ap.parse_args()
@@ -230,6 +232,12 @@ def main():
     import paper_2409_16560_amd as dsbd
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibration_copy:
+        x = torch.ones(1 << 28, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        y.copy_(x)
+        torch.cuda.synchronize()
+        del x, y
     kw = {} if args.shared_len is None else {"shared_len": args.shared_len}
     case = Case(dsbd, torch, args.config, args.copies, args.t, **kw)
     w = case.w

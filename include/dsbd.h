@@ -16,15 +16,16 @@
  * Conventions
  *   - Every array argument is a DEVICE pointer owned by the caller unless marked "host".
  *     The structs themselves are host memory, read during the call only.
- *   - The library allocates nothing and keeps no state between calls (the measurement hook at the
- *     end of this header aside).  Scratch memory comes
+ *   - The library allocates no device memory and keeps no state between calls (apart from the measurement
+ *     hook at the end of this header, the tuning knobs it reads once, and one extra stream with two events per
+ *     device that dsbd_verify_forest creates at its first call or dsbd_init() creates).  Scratch memory comes
  *     from the caller's `workspace` (device, 256-byte aligned), at least as large as the
  *     matching dsbd_*_workspace_bytes() says.  Its contents need not be initialised.
  *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work; outputs are valid
  *     once the stream has been synchronised.  No call synchronises the device.
  *   - Return value: DSBD_OK or a negative DSBD_ERR_* for problems visible on the host
  *     (null pointers, sizes, unsupported shapes, workspace too small, HIP launch errors).
- *     Nothing is enqueued when an error is returned.
+ *     Nothing is enqueued when an error is returned (one exception: see dsbd_verify_forest).
  *   - Problems only visible in device data are OR-ed into the device word `*fault`
  *     (DSBD_FAULT_* bits) and never cause out-of-bounds accesses; the caller clears the word.
  */
@@ -173,12 +174,20 @@ size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, 
  * p' <- norm(max(0, p' - q_beam)) on rejection and p' <- p_beam on acceptance, early stop at
  * W_L^(l) accepted beams, residual + p_beam sampling when a layer falls short, and the bonus
  * layer when every layer passes.  Decisions are taken in fp64.
- *   - Limits: at most 64 input beams, 512 forest nodes and W_cap <= 64 per prompt; n_prompts times the workgroups
- *     per prompt must fit the device at once (at most one workgroup per compute unit and prompt: UNSUPPORTED beyond).
- *   - The layer kernel's workgroups wait for each other, so it needs the device to itself while it runs: work that
- *     another stream keeps resident at the same time (a second verification in particular) can keep some of its
- *     workgroups from starting; every wait is bounded (3 s by default) and ends in DSBD_FAULT_SYNC_TIMEOUT with
- *     unusable outputs, never in a hang.  Calls on one stream are safe.
+ *   - Limits: at most 64 input beams, 512 forest nodes and W_cap <= 64 per prompt.  Any number of prompts: when
+ *     they need more workgroups than the device holds at once, the layer kernel is launched for one group of
+ *     prompts after the other (Algorithm 1 runs per prompt).
+ *   - Two kernels run side by side: the layer kernel on `stream`, and the pass over all logits that produces the
+ *     per-node outputs (lse_*, node_logp_*) on a second stream that the library creates once per device; the second
+ *     stream starts after everything `stream` holds at the time of the call and `stream` continues only when both
+ *     kernels are done, so the caller sees ordinary stream semantics.  If all four per-node outputs are NULL the
+ *     pass is left out; non-finite logits are then reported only for the rows of beams that enter a layer.
+ *   - The layer kernel's workgroups wait for each other, so it needs its share of the device while it runs: work
+ *     that ANOTHER stream of the caller keeps resident at the same time (a second verification in particular) can
+ *     keep some of its workgroups from starting; every wait is bounded (3 s by default) and ends in
+ *     DSBD_FAULT_SYNC_TIMEOUT with unusable outputs, never in a hang.  Calls on one stream are safe.
+ *   - If a launch fails after the first kernel has been enqueued the call returns DSBD_ERR_HIP with that kernel
+ *     already on the stream (every other error is reported before anything is enqueued).
  *   - The workspace must not be shared by calls that may overlap.
  *   - logits_target == logits_draft together with beam_logp_target == beam_logp_draft (one model in both roles,
  *     as dsbd_draft_layer passes them) is recognised: the joint is then formed once; the results are those of two

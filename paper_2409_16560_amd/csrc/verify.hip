@@ -1,17 +1,18 @@
 // Layer-wise verification of a draft forest on gfx950 (paper Section 3.1 "Details", Algorithm 1,
 // and the dynamic layer width of Section 3.2, Eq. 1-6).
 //
-// Two kernels on the caller's stream:
+// Two kernels that do not depend on each other and run side by side (the layer kernel on the caller's stream, the
+// statistics pass on a second stream of the library's own, forked from and joined to the caller's):
 //
-// 1. vocab_stats_kernel (bandwidth-bound, all nodes, both models): one pass over the fp32 logits with
-//    a per-thread online max / sum-of-exponentials, reduced per row chunk.  This is the O(W |V|)
-//    softmax work of the beam-sampling joint (Section 2.1) done once for every forest node.  A few extra
-//    workgroups of the same launch do the small jobs the next kernel depends on: forest topology (node
-//    depths, validation), the tree range of every prompt, clearing the exchange slots.
-// 2. verify_layers_kernel (latency-bound, persistent; all its workgroups must be resident at once): G workgroups per prompt walk
-//    the layers in order.  Every decision is taken in fp64.  For the layer's input beams I the
-//    workgroups materialise p_beam and q_beam over I x V (their slice each), and every dependent
-//    reduction over I x V is one pass over the slices plus one barrier among the G workgroups.
+// 1. vocab_stats_kernel + vocab_finish_kernel (bandwidth-bound, all nodes, both models): one pass over the fp32 logits
+//    with a per-thread online max / sum-of-exponentials, reduced per row chunk, then per node the fp32 log-sum-exp and
+//    the log-probability of the node's own token under its parent.  This is the O(W |V|) softmax work of the
+//    beam-sampling joint (Section 2.1) done once for every forest node; it feeds the per-node outputs only.
+// 2. verify_layers_kernel (latency-bound, persistent; all its workgroups must be resident at once): G workgroups per
+//    prompt walk the layers in order.  Every decision is taken in fp64.  The kernel derives everything from the call's
+//    inputs (tree and node range of its prompt, node depths, the maxima and sums of the rows it uses).  For the
+//    layer's input beams I the workgroups materialise p_beam and q_beam over I x V (their slice each), and every
+//    dependent reduction over I x V is one pass over the slices plus one exchange among the G workgroups.
 //
 // The running residual p' is never stored.  After k consecutive rejections since the last reset
 //     p'_k = max(p_beam - c_k q_beam, 0) / F(c_k),   F(c) = sum max(p_beam - c q_beam, 0),

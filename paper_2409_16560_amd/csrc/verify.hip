@@ -1803,6 +1803,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       } else {
         const int k = sh.kmax;
         const double c = sh.cc[k] + sh.FF[k];
+        stamp(46);
         const double sl = slice_sum(c, 0, VL_BLOCK);
         stamp(43);
         const double tot = wg_total(sl);

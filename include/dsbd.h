@@ -182,10 +182,15 @@ size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, 
  *     stream starts after everything `stream` holds at the time of the call and `stream` continues only when both
  *     kernels are done, so the caller sees ordinary stream semantics.  If all four per-node outputs are NULL the
  *     pass is left out; non-finite logits are then reported only for the rows of beams that enter a layer.
- *   - The layer kernel's workgroups wait for each other, so it needs its share of the device while it runs: work
- *     that ANOTHER stream of the caller keeps resident at the same time (a second verification in particular) can
- *     keep some of its workgroups from starting; every wait is bounded (3 s by default) and ends in
- *     DSBD_FAULT_SYNC_TIMEOUT with unusable outputs, never in a hang.  Calls on one stream are safe.
+ *   - The layer kernel's workgroups wait for each other, so it needs its share of the device while it runs.
+ *     Verifications on DIFFERENT streams are kept apart by the library: the first call that arrives on another
+ *     stream than the one before waits for the device to drain (once per device and process), and from then on
+ *     every layer kernel is ordered behind the previous one by an event (6 us per call, which callers that stay on
+ *     one stream never pay).  Not covered: a stream under graph capture (the call records nothing outside the
+ *     capture; keep replays apart from other verifications yourself), dsbd_verify_forest_static() before the
+ *     library's second stream exists, and other processes on the device.  Foreign kernels that occupy compute
+ *     units only delay the layer kernel; every wait in it is bounded (3 s by default) and ends in
+ *     DSBD_FAULT_SYNC_TIMEOUT with unusable outputs, never in a hang.
  *   - If a launch fails after the first kernel has been enqueued the call returns DSBD_ERR_HIP with that kernel
  *     already on the stream (every other error is reported before anything is enqueued).
  *   - The workspace must not be shared by calls that may overlap.

@@ -2210,6 +2210,16 @@ struct SideStream {
   hipStream_t stream = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
   bool tried = false, ok = false;
+  // Two layer kernels on different streams must not share the compute units: each waits for workgroups of its own
+  // that the other one's keep out.  The library therefore orders its layer launches itself once it has seen calls on
+  // more than one stream: the first change of stream waits for the device to drain, and from then on layers_done is
+  // recorded behind every layer launch and a launch on another stream than the last one waits for it.  (Recording
+  // from the start would cost every single-stream caller 6 us per call, measured.)  enqueue makes one call's records
+  // and waits a unit among host threads.
+  hipEvent_t layers_done = nullptr;
+  hipStream_t last_stream = nullptr;
+  bool have_last = false, several_streams = false;
+  std::mutex enqueue;
 };
 SideStream* side_stream_of_current_device(bool may_create) {
   static SideStream table[64];
@@ -2220,9 +2230,10 @@ SideStream* side_stream_of_current_device(bool may_create) {
   SideStream& s = table[dev];
   if (!s.tried && may_create) {
     s.tried = true;
+    const unsigned ev = hipEventDisableTiming;
     s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
-           hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-           hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+           hipEventCreateWithFlags(&s.fork, ev) == hipSuccess && hipEventCreateWithFlags(&s.join, ev) == hipSuccess &&
+           hipEventCreateWithFlags(&s.layers_done, ev) == hipSuccess;
     if (!s.ok) (void)hipGetLastError();
   }
   return s.ok ? &s : nullptr;
@@ -2274,7 +2285,18 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   // to the layer kernel: ordered after everything the caller's stream holds so far, and the caller's stream continues
   // only when both are done.  DSBD_VERIFY_OVERLAP=0 (or a stream that cannot be created) puts it in front instead.
   const bool want_stats = out->lse_target || out->lse_draft || out->node_logp_target || out->node_logp_draft;
-  SideStream* side = (want_stats && knobs.verify_overlap) ? side_stream_of_current_device(may_create_side) : nullptr;
+  SideStream* state = side_stream_of_current_device(may_create_side);
+  SideStream* side = (want_stats && knobs.verify_overlap) ? state : nullptr;
+  std::unique_lock<std::mutex> enqueue_lock;
+  if (state) enqueue_lock = std::unique_lock<std::mutex>(state->enqueue);
+  // a stream under capture takes no part in the ordering of layer launches (an event recorded into a capture cannot
+  // be waited for from outside it): replays of such a graph are the caller's to keep apart from other verifications
+  bool capturing = false;
+  {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cs) == hipSuccess) capturing = cs != hipStreamCaptureStatusNone;
+    else { (void)hipGetLastError(); capturing = true; }
+  }
   StatsArgs sa;
   sa.z[0] = in->logits_target; sa.z[1] = in->logits_draft;
   sa.n_nodes = f->n_nodes; sa.V = in->V; sa.nchunk = pl.nchunk; sa.chunk = pl.chunk;
@@ -2343,6 +2365,14 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   // Ordinary launches: a launch was sized to fit the device at once, and every wait inside the kernel is bounded.
   // (A cooperative launch would also guarantee co-residency against work on other streams, but it made rocprofv3
   // crash at process exit on ROCm 7.2 and costs extra launch latency.)
+  if (state && !capturing && state->have_last && state->last_stream != stream) {
+    if (!state->several_streams) {
+      if (hipDeviceSynchronize() != hipSuccess) return DSBD_ERR_HIP;
+      state->several_streams = true;
+    } else if (hipStreamWaitEvent(stream, state->layers_done, 0) != hipSuccess) {
+      return DSBD_ERR_HIP;
+    }
+  }
   for (int p0 = 0; p0 < f->n_prompts; p0 += pl.group) {
     la.prompt0 = p0;
     const int np = f->n_prompts - p0 < pl.group ? f->n_prompts - p0 : pl.group;
@@ -2355,6 +2385,11 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
                   (unsigned int)pl.lds_bytes, stream, la);
   }
   hipError_t le = hipGetLastError();
+  if (state && !capturing) {
+    if (state->several_streams && hipEventRecord(state->layers_done, stream) != hipSuccess) le = hipErrorUnknown;
+    state->last_stream = stream;
+    state->have_last = true;
+  }
   if (side) {
     launch_stats(side->stream);
     if (hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)

@@ -41,7 +41,7 @@ extern "C" {
 
 #define DSBD_OK               0
 #define DSBD_ERR_INVALID     (-1)   /* null pointer, negative size, Hq % Hkv != 0, ...              */
-#define DSBD_ERR_UNSUPPORTED (-2)   /* D not 128 or 64, tree bound above 64 nodes, V < 1, ...       */
+#define DSBD_ERR_UNSUPPORTED (-2)   /* D not 128 or 64, tree bound above 64 nodes, V < 1 or > 2^30, ... */
 #define DSBD_ERR_WORKSPACE   (-3)   /* workspace smaller than dsbd_*_workspace_bytes()              */
 #define DSBD_ERR_HIP         (-4)   /* HIP runtime reported an error at launch                      */
 

@@ -38,7 +38,8 @@ struct DsbdKnobs {
   bool attn_trace;             // DSBD_ATTN_TRACE: timeline of the attention kernel (instrumented builds)
   int stats_chunk;             // DSBD_STATS_CHUNK: logits per workgroup of the statistics pass; 0 = the plan's choice
   int verify_g;                // DSBD_VERIFY_G: workgroups per prompt of the layer kernel; 0 = the plan's choice
-  bool verify_trace;           // DSBD_VERIFY_TRACE: timeline of the layer kernel into the workspace
+  bool verify_trace;           // DSBD_VERIFY_TRACE: timeline of the layer kernel into the workspace ...
+  int verify_trace_wg;         // ... of workgroup N - 1 when the variable holds N > 1 (else of the first)
   long long verify_sync_limit_us;   // DSBD_VERIFY_SYNC_LIMIT_US: bound of every wait of the layer kernel; 0 = default
   int verify_mute_wg;          // DSBD_VERIFY_TEST_MUTE_WG: test hook, this workgroup withholds its first post; -1 = none
   int verify_lds_slice;        // DSBD_VERIFY_LDS_SLICE: largest joint slice kept in the LDS; -1 = the plan's choice

@@ -23,6 +23,8 @@ void load(DsbdKnobs& k) {
   k.stats_chunk = env_int("DSBD_STATS_CHUNK", 0);
   k.verify_g = env_int("DSBD_VERIFY_G", 0);
   k.verify_trace = getenv("DSBD_VERIFY_TRACE") != nullptr;
+  k.verify_trace_wg = 0;
+  if (const char* e = getenv("DSBD_VERIFY_TRACE")) { const int v = atoi(e); if (v > 1) k.verify_trace_wg = v - 1; }
   const char* e = getenv("DSBD_VERIFY_SYNC_LIMIT_US");
   k.verify_sync_limit_us = e ? atoll(e) : 0;
   k.verify_mute_wg = env_int("DSBD_VERIFY_TEST_MUTE_WG", -1);

@@ -26,6 +26,7 @@
 #include "common.h"
 #include "topology_device.h"
 #include "exp_nonpos.h"
+#include <type_traits>
 #include <float.h>
 #include <limits.h>
 #include <stdlib.h>
@@ -43,7 +44,9 @@
 #define XU 4                   // logits per thread and model in flight in the exponential pass.  Eight (a 4008-entry piece of the
                                // benchmark's joint in one round) cost 256 vector registers; with four the kernel needs 186,
                                // which leaves room on every SIMD for waves of the statistics pass running beside it
-#define VL_DYN_LDS_BYTES (80 * 1024)   // dynamic LDS of the layer kernel (its static LDS takes most of the rest)
+#define VL_DYN_LDS_BYTES (80 * 1024)   // dynamic LDS of the layer kernel (its static LDS takes most of the rest) ...
+#define VL_DYN_LDS_BYTES_SMALL (112 * 1024)   // ... and of its variant for prompts of at most NODE_CAP_SMALL nodes
+#define NODE_CAP_SMALL 128
 
 // ------------------------------------------------------------------------------------------------ kernel 1
 struct StatsArgs {
@@ -250,7 +253,8 @@ struct LayersArgs {
   double* red;           // exchange slots of 16 bytes each, n_prompts regions laid out as in `sl`
   SlotLayout sl;
   int G, I_cap;
-  long long* trace;      // optional timeline (first workgroup of prompt 0): pairs (label, 100 MHz wall clock)
+  long long* trace;      // optional timeline of workgroup trace_wg: pairs (label, 100 MHz wall clock)
+  int trace_wg;
   int lds_elems;         // capacity (elements) of each of the two dynamic-LDS slice arrays; 0 = none
   int lds_slice;         // slices of up to this many elements are kept in the LDS (<= lds_elems)
   int alias;             // one model in both roles (same logits, same beam likelihoods): q_beam IS p_beam, kept once
@@ -267,6 +271,9 @@ struct LayersArgs {
 static_assert(NODE_CAP <= VL_BLOCK, "one thread per node of a prompt");
 static_assert(VL_WAVES == 8, "the fixed reduction trees below are written for eight waves");
 
+// NC: the most nodes a prompt may have (all its trees).  Two sizes are built: what the arrays below do not take of a
+// compute unit's LDS is room for the joint slices.
+template <int NC>
 struct LayerShared {
   // input beams of the layer
   int I_node[64];
@@ -282,23 +289,23 @@ struct LayerShared {
   int A_node[64], A_idx[64];
   double A_cum_p[64], A_cum_q[64];
   // the prompt's nodes (loaded once: the sequential parts must not wait for global memory)
-  int n_parent[NODE_CAP], n_token[NODE_CAP], n_rank[NODE_CAP];
-  short n_depth[NODE_CAP];
-  float n_u[NODE_CAP];               // accept uniform of each node
+  int n_parent[NC], n_token[NC], n_rank[NC];
+  short n_depth[NC];
+  float n_u[NC];               // accept uniform of each node
   // candidates
-  short slot_of[NODE_CAP];           // slot in I of a prompt node, -1 if not an input beam
-  int S_node[NODE_CAP], S_tmp[NODE_CAP];
-  float S_zp[NODE_CAP], S_zq[NODE_CAP];   // logits at the candidates' (parent, token)
-  double S_pb[NODE_CAP], S_qb[NODE_CAP];
-  float S_u[NODE_CAP];               // accept uniform of each candidate
-  unsigned char S_flag[NODE_CAP];    // test against p_beam itself: bit 0 = accepted, bit 1 = near tie
+  short slot_of[NC];           // slot in I of a prompt node, -1 if not an input beam
+  int S_node[NC], S_tmp[NC];
+  float S_zp[NC], S_zq[NC];   // logits at the candidates' (parent, token)
+  double S_pb[NC], S_qb[NC];
+  float S_u[NC];               // accept uniform of each candidate
+  unsigned char S_flag[NC];    // test against p_beam itself: bit 0 = accepted, bit 1 = near tie
   // residual chain and accept-count table
-  double cc[NODE_CAP + 2], FF[NODE_CAP + 2];
+  double cc[NC + 2], FF[NC + 2];
   union {
-    struct { double alpha[NODE_CAP + 2], first[NODE_CAP + 2]; } w;   // dynamic width only
+    struct { double alpha[NC + 2], first[NC + 2]; } w;   // dynamic width only
     double wpart[64 * VL_WAVES * 2];                                   // per-wave row sums of the exponential pass
   } u;
-  double Pa[NODE_CAP + 2], Pb[NODE_CAP + 2];
+  double Pa[NC + 2], Pb[NC + 2];
   double wsum[2][VL_WAVES];
   unsigned long long acc_prev[2][NACC];   // the accumulator words' values before their next exchange
   double scan_w[VL_WAVES];
@@ -315,8 +322,12 @@ struct LayerShared {
   int state[2];                      // outcome of the decision rounds, alternating entries
   int kmax, counter, abort, found, sbad, sgamma;
   int acc_n, pos, kidx;        // accept loop: accepted so far, next candidate, chain index of p'
+  int pick_th;                 // sampling from workspace slices: the thread whose chunk holds the draw
 };
-static_assert(sizeof(((LayerShared*)0)->u.w) >= sizeof(((LayerShared*)0)->u.wpart), "union sizes");
+
+
+static_assert(sizeof(LayerShared<NODE_CAP>) + VL_DYN_LDS_BYTES + 2048 <= CU_LDS_BYTES, "the layer kernel's LDS must fit a compute unit");
+static_assert(sizeof(LayerShared<NODE_CAP_SMALL>) + VL_DYN_LDS_BYTES_SMALL + 2048 <= CU_LDS_BYTES, "the layer kernel's LDS must fit a compute unit");
 
 // 2^(j/64), j = 0..63 (exp_nonpos.h)
 __constant__ double c_exp2_tab[64] = {DSBD_EXP2_TABLE_64};
@@ -375,7 +386,8 @@ __device__ __forceinline__ void lds_barrier() {
 
 // Inclusive prefix sum over the block's threads in thread order (fixed tree: identical in every workgroup
 // that scans the same values).
-__device__ __forceinline__ double block_inclusive_scan(double v, LayerShared& sh) {
+template <class Shared>
+__device__ __forceinline__ double block_inclusive_scan(double v, Shared& sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -614,9 +626,9 @@ __host__ __device__ inline SliceCut slice_cut(int nI, int V, int G) {
   return c;
 }
 
-template <bool WARP>
+template <bool WARP, int NC>
 __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
-  __shared__ LayerShared sh;
+  __shared__ LayerShared<NC> sh;
   extern __shared__ __attribute__((aligned(16))) double dyn_lds[];
   const int prompt = a.prompt0 + blockIdx.x / a.G;
   const int g = blockIdx.x % a.G;
@@ -634,7 +646,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   unsigned int decide_round = 0;
   int trace_n = 0;
   auto stamp = [&](int label) {
-    if (a.trace && blockIdx.x == 0 && tid == 0 && trace_n < 255) {
+    if (a.trace && (int)blockIdx.x == a.trace_wg && tid == 0 && trace_n < 255) {
       a.trace[2 * trace_n + 2] = label; a.trace[2 * trace_n + 3] = wall_clock64(); ++trace_n; a.trace[0] = trace_n;
     }
   };
@@ -679,7 +691,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   int n_begin = 0, n_end = 0;
   if (n_roots > 0) { n_begin = a.tree_off[t_first]; n_end = a.tree_off[t_end]; }
   if (n_begin < 0 || n_end > a.n_nodes || n_end < n_begin) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
-  if (n_end - n_begin > NODE_CAP) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
+  if (n_end - n_begin > NC) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
   int n_pn = n_roots > 0 ? n_end - n_begin : 0;          // nodes of the prompt
   const int Lw = a.max_depth + 2;                        // row length of the per-layer arrays
   __syncthreads();
@@ -820,8 +832,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const long long e_lo = geo_lo, e_hi = geo_hi;
     const long long len = e_hi - e_lo;
     const int i_lo = geo_ilo, i_hi = geo_ihi;
-    // slice storage: LDS when the slice fits (no memory latency in the dependent passes), else the workspace
-    const bool in_lds = ch <= (long long)a.lds_slice;
+    // slice storage: the leading n_lds entries of the slice in the LDS (no memory latency in the dependent passes, and
+    // no traffic: a batch of prompts whose slices all lived in the workspace re-read them through the memory system
+    // a dozen times per layer), what does not fit behind them in the workspace
+    const long long n_lds = min(len, (long long)a.lds_slice);
+    const bool in_lds = n_lds == len;
     // Accessors with explicit address spaces (LDS or global): through generic pointers the compiler merges the two
     // cases into one FLAT access with a selected address, which is slower than either.
     typedef __attribute__((address_space(3))) double lds_f64;
@@ -830,40 +845,42 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     lds_f64* const ql = a.alias ? pl : pl + a.lds_elems;
     glb_f64* const pbg = (glb_f64*)pb;
     glb_f64* const qbg = a.alias ? pbg : (glb_f64*)qb;
-    auto ldp = [&](long long j) -> double { double v; if (in_lds) v = pl[(int)j]; else v = pbg[j]; return v; };
-    auto ldq = [&](long long j) -> double { double v; if (in_lds) v = ql[(int)j]; else v = qbg[j]; return v; };
-    auto stp = [&](long long j, double v) { if (in_lds) pl[(int)j] = v; else pbg[j] = v; };
-    auto stq = [&](long long j, double v) { if (in_lds) ql[(int)j] = v; else qbg[j] = v; };
-    // The hot loops are written once and instantiated for both homes of the slices, with the choice taken outside
-    // the loop (left per access, it becomes a pair of branches around every load and store).
-    auto with_slices = [&](auto&& body) __attribute__((always_inline)) { if (in_lds) body(pl, ql); else body(pbg, qbg); };
+    auto ldp = [&](long long j) -> double { double v; if (j < n_lds) v = pl[(int)j]; else v = pbg[j]; return v; };
+    auto ldq = [&](long long j) -> double { double v; if (j < n_lds) v = ql[(int)j]; else v = qbg[j]; return v; };
+    // The hot loops are written once, over a range [r0, r1) of the slice, and instantiated for both homes, with the
+    // choice taken outside the loop (left per access, it becomes a pair of branches around every load and store).
+    auto with_slices = [&](auto&& body) __attribute__((always_inline)) {
+      if (in_lds) { body(pl, ql, 0LL, len); return; }
+      if (n_lds > 0) body(pl, ql, 0LL, n_lds);
+      body(pbg, qbg, n_lds, len);
+    };
 
     // ===== p_beam / q_beam over I x V: exponentials and this workgroup's share of the row sums.  The exponentials
     // are taken against the maximum of the workgroup's own piece of the row (found here, in the same pass over the
     // logits); the pieces' maxima travel with their sums and are folded into the row's maximum and total below.
     for (int i = i_lo; i <= i_hi; ++i) {
       const int node = sh.I_node[i];
-      const long long x_lo = max(e_lo, (long long)i * V) - (long long)i * V;
-      const long long x_hi = min(e_hi, (long long)(i + 1) * V) - (long long)i * V;
+      const int x_lo = (int)(max(e_lo, (long long)i * V) - (long long)i * V);      // positions in the row: below V < 2^30
+      const int x_hi = (int)(min(e_hi, (long long)(i + 1) * V) - (long long)i * V);
       const float* zp = a.zp + (long long)node * V;
       const float* zq = a.zq + (long long)node * V;
       double s_p = 0.0, s_q = 0.0;
       const long long joff = (long long)i * V - e_lo;
-      with_slices([&](auto P, auto Q) __attribute__((always_inline)) {
+      auto exp_pass = [&](auto store) __attribute__((always_inline)) {
       // the first two rounds of XU logits per model stay in registers (a 4008-entry piece of the benchmark's joint is
       // two rounds); longer pieces are read a second time (from the caches)
       float fpA[XU], fqA[XU], fpB[XU], fqB[XU];
       float lmp = -INFINITY, lmq = -INFINITY;
-      const long long xA = x_lo + tid, xB = xA + XU * VL_BLOCK;
+      const int xA = x_lo + tid, xB = xA + XU * VL_BLOCK;
       const bool haveB = x_lo + XU * VL_BLOCK < x_hi;                      // uniform over the workgroup
 #pragma unroll
       for (int k = 0; k < XU; ++k) {
-        const long long xx = min(xA + k * VL_BLOCK, x_hi - 1);              // clamped repeats do not change a maximum
+        const int xx = min(xA + k * VL_BLOCK, x_hi - 1);              // clamped repeats do not change a maximum
         fpA[k] = zp[xx]; fqA[k] = zq[xx];
       }
 #pragma unroll
       for (int k = 0; k < XU; ++k) {
-        const long long xx = min(xB + k * VL_BLOCK, x_hi - 1);
+        const int xx = min(xB + k * VL_BLOCK, x_hi - 1);
         fpB[k] = zp[xx]; fqB[k] = zq[xx];
       }
       bool nonfinite = false;        // (the statistics pass reports these for every row; this kernel for the rows it uses)
@@ -872,20 +889,22 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         lmp = fmaxf(fmaxf(lmp, fpA[k]), fpB[k]); lmq = fmaxf(fmaxf(lmq, fqA[k]), fqB[k]);
         nonfinite |= !(fabsf(fpA[k]) <= FLT_MAX) | !(fabsf(fqA[k]) <= FLT_MAX) | !(fabsf(fpB[k]) <= FLT_MAX) | !(fabsf(fqB[k]) <= FLT_MAX);
       }
-      for (long long x = xB + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {
-        float fp[XU], fq[XU];
+      // (the rest of a long piece: maxima only, so four times as many logits in flight as in the rounds above)
+      for (int x = xB + XU * VL_BLOCK; x < x_hi; x += 4 * XU * VL_BLOCK) {
+        float fp[4 * XU], fq[4 * XU];
 #pragma unroll
-        for (int k = 0; k < XU; ++k) {
-          const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
+        for (int k = 0; k < 4 * XU; ++k) {
+          const int xx = min(x + k * VL_BLOCK, x_hi - 1);
           fp[k] = zp[xx]; fq[k] = zq[xx];
         }
 #pragma unroll
-        for (int k = 0; k < XU; ++k) {
+        for (int k = 0; k < 4 * XU; ++k) {
           lmp = fmaxf(lmp, fp[k]); lmq = fmaxf(lmq, fq[k]);
           nonfinite |= !(fabsf(fp[k]) <= FLT_MAX) | !(fabsf(fq[k]) <= FLT_MAX);
         }
       }
       if (nonfinite) atomicOr(a.fault, DSBD_FAULT_NONFINITE);
+      stamp(73);
 #pragma unroll
       for (int off = 32; off >= 1; off >>= 1) { lmp = fmaxf(lmp, __shfl_xor(lmp, off)); lmq = fmaxf(lmq, __shfl_xor(lmq, off)); }
       float* const wm = sh.wmax[(i - i_lo) & 1];       // two buffers: a wave is at most one row ahead of the slowest
@@ -898,12 +917,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       // XU exponentials per model at a time (all of a round's at once would cost more registers than there are to spare)
 #pragma unroll
       for (int k = 0; k < XU; ++k) {
-        const long long x = xA + k * VL_BLOCK;
+        const int x = xA + k * VL_BLOCK;
         if (x < x_hi) {
           const double ep = exp_nonpos((double)fpA[k] - mp, sh.exp_tab);
           double eq = ep;
           if (!a.alias) eq = exp_nonpos((double)fqA[k] - mq, sh.exp_tab);
-          P[joff + x] = ep; Q[joff + x] = eq;
+          store(joff + x, ep, eq);
           s_p += ep; s_q += eq;
         }
       }
@@ -911,34 +930,59 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       if (haveB) {
 #pragma unroll
         for (int k = 0; k < XU; ++k) {
-          const long long x = xB + k * VL_BLOCK;
+          const int x = xB + k * VL_BLOCK;
           if (x < x_hi) {
             const double ep = exp_nonpos((double)fpB[k] - mp, sh.exp_tab);
             double eq = ep;
             if (!a.alias) eq = exp_nonpos((double)fqB[k] - mq, sh.exp_tab);
-            P[joff + x] = ep; Q[joff + x] = eq;
+            store(joff + x, ep, eq);
             s_p += ep; s_q += eq;
           }
         }
       }
-      for (long long x = xB + XU * VL_BLOCK; x < x_hi; x += XU * VL_BLOCK) {   // XU logits of each model in flight, ragged end predicated
-        float fp[XU], fq[XU];
+      // the rest of a long piece, read a second time (from the caches): XU logits of each model at a time, the next
+      // round's requested before this round's exponentials are taken; ragged end predicated
+      {
+        int x = xB + XU * VL_BLOCK;
+        float np[XU], nq[XU];
+        if (x < x_hi) {
 #pragma unroll
-        for (int k = 0; k < XU; ++k) {
-          const long long xx = min(x + k * VL_BLOCK, x_hi - 1);
-          fp[k] = zp[xx]; fq[k] = zq[xx];
-        }
-#pragma unroll
-        for (int k = 0; k < XU; ++k) {
-          if (x + k * VL_BLOCK < x_hi) {
-            const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab);
-            double eq = ep;
-            if (!a.alias) eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
-            P[joff + x + k * VL_BLOCK] = ep; Q[joff + x + k * VL_BLOCK] = eq;
-            s_p += ep; s_q += eq;
+          for (int k = 0; k < XU; ++k) {
+            const int xx = min(x + k * VL_BLOCK, x_hi - 1);
+            np[k] = zp[xx]; nq[k] = zq[xx];
           }
         }
+        while (x < x_hi) {
+          float fp[XU], fq[XU];
+#pragma unroll
+          for (int k = 0; k < XU; ++k) { fp[k] = np[k]; fq[k] = nq[k]; }
+          const int xn = x + XU * VL_BLOCK;
+          if (xn < x_hi) {
+#pragma unroll
+            for (int k = 0; k < XU; ++k) {
+              const int xx = min(xn + k * VL_BLOCK, x_hi - 1);
+              np[k] = zp[xx]; nq[k] = zq[xx];
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < XU; ++k) {
+            if (x + k * VL_BLOCK < x_hi) {
+              const double ep = exp_nonpos((double)fp[k] - mp, sh.exp_tab);
+              double eq = ep;
+              if (!a.alias) eq = exp_nonpos((double)fq[k] - mq, sh.exp_tab);
+              store(joff + x + k * VL_BLOCK, ep, eq);
+              s_p += ep; s_q += eq;
+            }
+          }
+          x = xn;
+        }
       }
+      };
+      // (an aliased q_beam is p_beam: both stores then go to one place)
+      if (in_lds) exp_pass([&](long long jj, double ep, double eq) { pl[(int)jj] = ep; ql[(int)jj] = eq; });
+      else if (n_lds == 0) exp_pass([&](long long jj, double ep, double eq) { pbg[jj] = ep; qbg[jj] = eq; });
+      else exp_pass([&](long long jj, double ep, double eq) {
+        if (jj < n_lds) { pl[(int)jj] = ep; ql[(int)jj] = eq; } else { pbg[jj] = ep; qbg[jj] = eq; }
       });
       s_p = wave_sum(s_p);
       s_q = wave_sum(s_q);
@@ -1086,9 +1130,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       // (the slice holds exponentials against the piece's own maximum: put them on the row's)
       const double fp = sh.sp[i] * exp_nonpos(sh.lm_p[i - i_lo] - sh.max_p[i], sh.exp_tab);
       const double fq = sh.sq[i] * exp_nonpos(sh.lm_q[i - i_lo] - sh.max_q[i], sh.exp_tab);
-      with_slices([&](auto P, auto Q) {
-        long long j = j_lo + tid;
-        for (; j + 3 * VL_BLOCK < j_hi; j += 4 * VL_BLOCK) {      // four elements of each array in flight
+      with_slices([&](auto P, auto Q, long long r0, long long r1) {
+        const long long j_end = min(j_hi, r1);
+        long long j = max(j_lo, r0) + tid;
+        for (; j + 3 * VL_BLOCK < j_end; j += 4 * VL_BLOCK) {      // four elements of each array in flight
           double pv[4], qv[4];
 #pragma unroll
           for (int k = 0; k < 4; ++k) { pv[k] = P[j + k * VL_BLOCK]; qv[k] = Q[j + k * VL_BLOCK]; }
@@ -1100,7 +1145,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
             else f1 += fmax(pv[k] - qv[k], 0.0);
           }
         }
-        for (; j < j_hi; j += VL_BLOCK) {
+        for (; j < j_end; j += VL_BLOCK) {
           const double pv = P[j] * fp, qv = Q[j] * fq;
           P[j] = pv; Q[j] = qv;
           if constexpr (WARP) { tmax_p = fmax(tmax_p, pv); tmax_q = fmax(tmax_q, qv); }
@@ -1199,16 +1244,16 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
             if (c < WARP_CAND) { cvq[c] = vq; ciq[c] = (int)(e_lo + j); }
           }
         };
-        with_slices([&](auto P, auto Q) {
-          long long j = tid;
-          for (; j + 3 * VL_BLOCK < len; j += 4 * VL_BLOCK) {
+        with_slices([&](auto P, auto Q, long long r0, long long r1) {
+          long long j = r0 + tid;
+          for (; j + 3 * VL_BLOCK < r1; j += 4 * VL_BLOCK) {
             double pv[4], qv[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) { pv[k] = P[j + k * VL_BLOCK]; qv[k] = Q[j + k * VL_BLOCK]; }
 #pragma unroll
             for (int k = 0; k < 4; ++k) offer(j + k * VL_BLOCK, pv[k], qv[k]);
           }
-          for (; j < len; j += VL_BLOCK) offer(j, P[j], Q[j]);
+          for (; j < r1; j += VL_BLOCK) offer(j, P[j], Q[j]);
         });
       }
       __syncthreads();
@@ -1518,19 +1563,36 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         const int c2 = tid - t0;
         return c2 < sh.nU ? fmax(sh.U_p[c2] - c * sh.U_q[c2], 0.0) : 0.0;
       }
-      with_slices([&](auto P, auto Q) {
+      with_slices([&](auto P, auto Q, long long r0, long long r1) {
         // four elements of each array in flight per thread, the ragged end predicated (one element after the other,
         // the tail of a 4008-entry slice cost four dependent LDS round trips per chain entry; eight in flight cost
         // more registers than the kernel can spare beside the statistics pass)
-        const int n = (int)len;            // a slice has fewer than 2^31 entries
-        for (int j = tid - t0; j < n; j += 4 * nt) {
-          const int j1 = min(j + nt, n - 1), j2 = min(j + 2 * nt, n - 1), j3 = min(j + 3 * nt, n - 1);
-          const double p0 = P[j], p1 = P[j1], p2 = P[j2], p3 = P[j3];
-          const double q0 = Q[j], q1 = Q[j1], q2 = Q[j2], q3 = Q[j3];
-          s0 += fmax(p0 - c * q0, 0.0);
-          s1 += (j + nt < n) ? fmax(p1 - c * q1, 0.0) : 0.0;
-          s2 += (j + 2 * nt < n) ? fmax(p2 - c * q2, 0.0) : 0.0;
-          s3 += (j + 3 * nt < n) ? fmax(p3 - c * q3, 0.0) : 0.0;
+        const int n = (int)r1;             // a slice has fewer than 2^31 entries
+        const int j_first = (int)r0 + tid - t0;
+        if constexpr (std::is_same<decltype(P), glb_f64*>::value) {
+          // the part in the workspace (read through the caches): eight of each array in flight
+          for (int j = j_first; j < n; j += 8 * nt) {
+            double pv[8], qv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { const int jk = min(j + k * nt, n - 1); pv[k] = P[jk]; qv[k] = Q[jk]; }
+#pragma unroll
+            for (int k = 0; k < 8; k += 4) {
+              s0 += (j + k * nt < n) ? fmax(pv[k] - c * qv[k], 0.0) : 0.0;
+              s1 += (j + (k + 1) * nt < n) ? fmax(pv[k + 1] - c * qv[k + 1], 0.0) : 0.0;
+              s2 += (j + (k + 2) * nt < n) ? fmax(pv[k + 2] - c * qv[k + 2], 0.0) : 0.0;
+              s3 += (j + (k + 3) * nt < n) ? fmax(pv[k + 3] - c * qv[k + 3], 0.0) : 0.0;
+            }
+          }
+        } else {
+          for (int j = j_first; j < n; j += 4 * nt) {
+            const int j1 = min(j + nt, n - 1), j2 = min(j + 2 * nt, n - 1), j3 = min(j + 3 * nt, n - 1);
+            const double p0 = P[j], p1 = P[j1], p2 = P[j2], p3 = P[j3];
+            const double q0 = Q[j], q1 = Q[j1], q2 = Q[j2], q3 = Q[j3];
+            s0 += fmax(p0 - c * q0, 0.0);
+            s1 += (j + nt < n) ? fmax(p1 - c * q1, 0.0) : 0.0;
+            s2 += (j + 2 * nt < n) ? fmax(p2 - c * q2, 0.0) : 0.0;
+            s3 += (j + 3 * nt < n) ? fmax(p3 - c * q3, 0.0) : 0.0;
+          }
         }
       });
       return (s0 + s1) + (s2 + s3);
@@ -1579,13 +1641,61 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       float uj = 0.f;
       if (tid < cnt) uj = u[tid];
       // inclusive prefixes over this workgroup's threads (contiguous chunks) ...
-      const long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
+      long long per = (len + VL_BLOCK - 1) / VL_BLOCK;
+      if (!in_lds) {                      // slices in the workspace: chunks of a power of two (at least one) entries
+        long long p2 = 1;
+        while (p2 < per) p2 <<= 1;
+        per = p2;
+      }
       const long long t_lo = min(len, per * tid), t_hi = min(len, t_lo + per);   // slice-local
       double ts = 0.0;
-      with_slices([&](auto P, auto Q) {
-        if (use_q) for (long long j = t_lo; j < t_hi; ++j) ts += fmax(P[j] - c * Q[j], 0.0);
-        else for (long long j = t_lo; j < t_hi; ++j) ts += P[j];
-      });
+      if (in_lds) {
+        if (use_q) for (int j = (int)t_lo; j < (int)t_hi; ++j) ts += fmax((double)pl[j] - c * (double)ql[j], 0.0);
+        else for (int j = (int)t_lo; j < (int)t_hi; ++j) ts += (double)pl[j];
+      } else {
+        // A thread walking its own chunk would make every load of a wave touch 64 cache lines (measured: 14 us for a
+        // 16000-entry slice).  Instead a wave reads the 64 chunks of its threads 64 consecutive entries at a time and
+        // adds them up across the lanes: `per` rounds, each holding 64 / per whole chunks or a 64th of one.
+        const long long w_lo = per * 64 * wave;
+        auto weight = [&](long long jj) -> double {
+          if (jj >= len) return 0.0;
+          if (jj < n_lds) return use_q ? fmax((double)pl[(int)jj] - c * (double)ql[(int)jj], 0.0) : (double)pl[(int)jj];
+          return use_q ? fmax((double)pbg[jj] - c * (double)qbg[jj], 0.0) : (double)pbg[jj];
+        };
+        if (per < 64) {
+          const int S = 64 / (int)per;                  // chunks per round
+          for (long long r0 = 0; r0 < per; r0 += 8) {
+            double w[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w[k] = r0 + k < per ? weight(w_lo + (r0 + k) * 64 + lane) : 0.0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              double v = w[k];
+              for (int off = 1; off < (int)per; off <<= 1) v += __shfl_xor(v, off);
+              const double mine = __shfl(v, (lane % S) * (int)per);       // chunk (r0 + k) * S + lane % S
+              if (r0 + k < per && lane / S == (int)(r0 + k)) ts = mine;
+            }
+          }
+        } else {
+          const long long rpc = per / 64;                // rounds per chunk (a power of two); chunk after chunk
+          double acc = 0.0;
+          for (long long r0 = 0; r0 < per; r0 += 8) {
+            double w[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w[k] = weight(w_lo + (r0 + k) * 64 + lane);     // per >= 64 is a multiple of 8
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              acc += w[k];
+              if (((r0 + k + 1) & (rpc - 1)) == 0) {
+                const double tot = wave_sum(acc);
+                if (lane == (int)((r0 + k) / rpc)) ts = tot;
+                acc = 0.0;
+              }
+            }
+          }
+        }
+      }
+      stamp(70);
       const double tincl = block_inclusive_scan(ts, sh);
       sh.tsum[tid] = tincl;
       if (tid == 0) sh.counter = 0;
@@ -1623,6 +1733,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (lane == 0) sh.found = nz;
       }
       __syncthreads();
+      stamp(71);
       if (sh.abort) return false;
       const double Z = sh.gpart[a.G - 1];
       const double before = g > 0 ? sh.gpart[g - 1] : 0.0;
@@ -1636,6 +1747,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (owner == g) sh.S_tmp[atomicAdd(&sh.counter, 1)] = tid;
       }
       __syncthreads();
+      stamp(72);
       const int n_mine = sh.counter;
       for (int k = 0; k < n_mine; ++k) {
         const int j = sh.S_tmp[k];
@@ -1644,20 +1756,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         // found by the last thread)
         const bool above = before + sh.tsum[tid] > target;
         const bool prev_above = tid > 0 && (before + sh.tsum[tid - 1] > target);
-        if ((above && !prev_above) || (tid == VL_BLOCK - 1 && !above)) {
-          int th = tid;
-          if (!above)
-            while (th > 0 && !(sh.tsum[th] > sh.tsum[th - 1])) --th;
-          const long long c_lo = min(len, per * th), c_hi = min(len, c_lo + per);
-          double accl = before + (th > 0 ? sh.tsum[th - 1] : 0.0);
-          long long pick = -1, last = -1;
-          for (long long jj = c_lo; jj < c_hi; ++jj) {
-            const double v = use_q ? fmax(ldp(jj) - c * ldq(jj), 0.0) : ldp(jj);
-            if (v > 0.0) last = jj;
-            accl += v;
-            if (accl > target) { pick = jj; break; }
-          }
-          if (pick < 0) pick = last >= 0 ? last : c_lo;
+        const bool holder = (above && !prev_above) || (tid == VL_BLOCK - 1 && !above);
+        auto emit = [&](long long pick) {
           pick = min(pick + e_lo, total - 1);   // back to the flat index over I x V
           const int i = (int)div_floor(pick, V);
           const int x = (int)(pick - (long long)i * V);
@@ -1668,6 +1768,59 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           a.out.out_node[o] = -1;
           a.out.out_logp_target[o] = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
           a.out.out_logp_draft[o] = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+        };
+        if (in_lds) {
+          if (holder) {
+            int th = tid;
+            if (!above)
+              while (th > 0 && !(sh.tsum[th] > sh.tsum[th - 1])) --th;
+            const long long c_lo = min(len, per * th), c_hi = min(len, c_lo + per);
+            double accl = before + (th > 0 ? sh.tsum[th - 1] : 0.0);
+            long long pick = -1, last = -1;
+            for (long long jj = c_lo; jj < c_hi; ++jj) {
+              const double v = use_q ? fmax((double)pl[(int)jj] - c * (double)ql[(int)jj], 0.0) : (double)pl[(int)jj];
+              if (v > 0.0) last = jj;
+              accl += v;
+              if (accl > target) { pick = jj; break; }
+            }
+            if (pick < 0) pick = last >= 0 ? last : c_lo;
+            emit(pick);
+          }
+        } else {
+          // slices in the workspace: one thread walking its chunk would wait for a load per element, so the first wave
+          // takes the chunk 64 entries at a time (coalesced loads, a scan across the lanes)
+          if (holder) {
+            int th = tid;
+            if (!above)
+              while (th > 0 && !(sh.tsum[th] > sh.tsum[th - 1])) --th;
+            sh.pick_th = th;
+          }
+          __syncthreads();
+          if (wave == 0) {
+            const int th = sh.pick_th;
+            const long long c_lo = min(len, per * th), c_hi = min(len, c_lo + per);
+            double start = before + (th > 0 ? sh.tsum[th - 1] : 0.0);
+            long long pick = -1, last = -1;
+            for (long long b0 = c_lo; b0 < c_hi && pick < 0; b0 += 64) {
+              const long long jj = b0 + lane;
+              double v = 0.0;
+              if (jj < c_hi) v = use_q ? fmax(ldp(jj) - c * ldq(jj), 0.0) : ldp(jj);
+              double incl = v;
+#pragma unroll
+              for (int off = 1; off < 64; off <<= 1) {
+                const double up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+              }
+              const unsigned long long mass = __ballot(v > 0.0);
+              if (mass) last = b0 + 63 - __clzll((long long)mass);
+              const unsigned long long over = __ballot(start + incl > target);
+              if (over) pick = b0 + __ffsll((long long)over) - 1;
+              start += __shfl(incl, 63);
+            }
+            if (pick < 0) pick = last >= 0 ? last : c_lo;
+            if (lane == 0) emit(pick);
+          }
+          __syncthreads();                   // sh.pick_th is free again
         }
       }
       __syncthreads();
@@ -2051,6 +2204,7 @@ namespace {
 
 struct VerifyPlan {
   int nchunk, chunk, I_cap, G, lds_elems;
+  bool small_nodes;        // the layer kernel built for prompts of at most NODE_CAP_SMALL nodes serves (more LDS for slices)
   int group;               // prompts per launch of the layer kernel (all of them, unless they do not fit the device at once)
   size_t lds_bytes;        // dynamic LDS of the layer kernel
   SlotLayout sl;
@@ -2060,7 +2214,7 @@ struct VerifyPlan {
 int32_t check_verify(const dsbd_forest* f, int V, const dsbd_params* p) {
   if (!f || !p) return DSBD_ERR_INVALID;
   if (f->n_prompts < 0 || f->n_trees < 0 || f->n_nodes < 0) return DSBD_ERR_INVALID;
-  if (V < 1) return DSBD_ERR_UNSUPPORTED;
+  if (V < 1 || V > (1 << 30)) return DSBD_ERR_UNSUPPORTED;     // positions in a row are 32-bit integers with room to step past the end
   if (p->W_cap < 1 || p->W_cap > 64) return DSBD_ERR_UNSUPPORTED;
   if (p->W_min < 1 || p->W_min > p->W_cap || p->W_L > p->W_cap) return DSBD_ERR_INVALID;
   if (!(p->t <= 1.0f)) return DSBD_ERR_INVALID;      // also rejects NaN (which would otherwise read as dynamic width 0)
@@ -2091,15 +2245,20 @@ const DeviceLimits& device_limits() {
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
       lim.cus = v;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<false>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<false, NODE_CAP>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<true>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<true, NODE_CAP>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES);
-    int nb = 0, nb2 = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel<false>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(verify_layers_kernel<false, NODE_CAP_SMALL>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, VL_DYN_LDS_BYTES_SMALL);
+    int nb = 0, nb2 = 0, nb3 = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, verify_layers_kernel<false, NODE_CAP>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb < 1)
       nb = 1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb2, verify_layers_kernel<true>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb2 < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb2, verify_layers_kernel<true, NODE_CAP>, VL_BLOCK, VL_DYN_LDS_BYTES) != hipSuccess || nb2 < 1)
       nb2 = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb3, verify_layers_kernel<false, NODE_CAP_SMALL>, VL_BLOCK, VL_DYN_LDS_BYTES_SMALL) != hipSuccess || nb3 < 1)
+      nb3 = 1;
+    if (nb3 < nb2) nb2 = nb3;
     lim.blocks_per_cu = nb < nb2 ? nb : nb2;
     (void)hipGetLastError();
   });
@@ -2146,7 +2305,10 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
   pl.group = f->n_prompts;
   if ((long long)pl.group * G > resident) pl.group = resident / G;     // G is 1 here
   if (pl.group < 1) pl.group = 1;
-  const long long cap = VL_DYN_LDS_BYTES / (alias ? 8 : 16);   // one array instead of two when q_beam is p_beam
+  // prompts of few nodes and no warping (whose scratch lists use the per-node arrays at full size): the kernel
+  // variant with the short per-node arrays, which leaves more of the LDS to the slices
+  pl.small_nodes = p->top_k == 0 && (long long)f->max_prompt_trees * f->max_tree_nodes <= NODE_CAP_SMALL;
+  const long long cap = (pl.small_nodes ? VL_DYN_LDS_BYTES_SMALL : VL_DYN_LDS_BYTES) / (alias ? 8 : 16);   // one array instead of two when q_beam is p_beam
   // exchange slots: every workgroup's slots of an exchange start a 128-byte line (no two writers per line)
   {
     auto up8 = [](int v) { return (v + LINE_SLOTS - 1) / LINE_SLOTS * LINE_SLOTS; };
@@ -2315,7 +2477,8 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
     // the layer kernel's run, 142 us; none: the pass runs behind the layer kernel, 184 us.
     unsigned int side_lds = 0;
     if (st != stream) {
-      const long long layer_lds = (long long)(sizeof(LayerShared) + pl.lds_bytes + 511) / 512 * 512;
+      const size_t layer_static = pl.small_nodes ? sizeof(LayerShared<NODE_CAP_SMALL>) : sizeof(LayerShared<NODE_CAP>);
+      const long long layer_lds = (long long)(layer_static + pl.lds_bytes + 511) / 512 * 512;
       // a claim that STATS_SIDE_WGS workgroups fit in beside the layer kernel's LDS and one more does not, with
       // half a claim of slack on either side (the allocation granule and the pass's own few bytes are not known here)
       const long long free_lds = CU_LDS_BYTES - layer_lds;
@@ -2350,6 +2513,7 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   la.out = *out;
   la.pb = pb; la.qb = qb; la.red = red; la.slice_cap = pl.slice_cap;
   la.trace = knobs.verify_trace ? reinterpret_cast<long long*>(wbase) : nullptr;
+  la.trace_wg = knobs.verify_trace_wg;
   la.sync_limit = SYNC_LIMIT_TICKS;
   if (knobs.verify_sync_limit_us >= 1 && knobs.verify_sync_limit_us <= 10000000LL)   // bound of the kernel's waits (default 3 s)
     la.sync_limit = knobs.verify_sync_limit_us * 100;
@@ -2378,10 +2542,13 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
     const int np = f->n_prompts - p0 < pl.group ? f->n_prompts - p0 : pl.group;
     const unsigned grid3 = (unsigned)np * (unsigned)pl.G;
     if (p->top_k > 0)
-      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<true>, dim3(grid3), dim3(VL_BLOCK),
+      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<true, NODE_CAP>, dim3(grid3), dim3(VL_BLOCK),
+                  (unsigned int)pl.lds_bytes, stream, la);
+    else if (pl.small_nodes)
+      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<false, NODE_CAP_SMALL>, dim3(grid3), dim3(VL_BLOCK),
                   (unsigned int)pl.lds_bytes, stream, la);
     else
-      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<false>, dim3(grid3), dim3(VL_BLOCK),
+      dsbd_launch(DSBD_KERNEL_VERIFY_LAYERS, verify_layers_kernel<false, NODE_CAP>, dim3(grid3), dim3(VL_BLOCK),
                   (unsigned int)pl.lds_bytes, stream, la);
   }
   hipError_t le = hipGetLastError();

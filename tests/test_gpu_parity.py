@@ -386,13 +386,18 @@ def test_warping_with_many_equal_entries(cfg, kw):
         gu.compare_verify(res, ref, w)
 
 
-@pytest.mark.parametrize("cfg,kw,top_k", [("c3", dict(V=5000), 0), ("c4", dict(V=3000, n_prompts=6), 0),
-                                          ("c5", dict(V=20000, draft_top_k=4), 16), ("c5", dict(V=20000), 0)])
-def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, knobs):
+@pytest.mark.parametrize("cfg,kw,top_k,G", [("c3", dict(V=5000), 0, 0), ("c4", dict(V=3000, n_prompts=6), 0, 0),
+                                            ("c5", dict(V=20000, draft_top_k=4), 16, 0), ("c5", dict(V=20000), 0, 0),
+                                            # few workgroups: long slices (sampling walks chunks of 64 entries and more)
+                                            ("c3", dict(V=5000), 0, 1), ("c3", dict(V=5000), 0, 2),
+                                            ("c5", dict(V=20000), 0, 3), ("c3", dict(V=5000, draft="indep"), 0, 2)])
+def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, G, knobs):
     """The same results when the joint slices live in the workspace instead of the LDS (as they do at large
     I x V per workgroup): each workgroup's region is private, whatever way the layers cut I x V."""
     gu = _gu()
     knobs.set("DSBD_VERIFY_LDS_SLICE", "0")
+    if G:
+        knobs.set("DSBD_VERIFY_G", G)
     w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
     d = gu.DeviceWorkload(w)
     for t in (-1.0, 0.6):

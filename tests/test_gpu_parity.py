@@ -391,11 +391,13 @@ def test_warping_with_many_equal_entries(cfg, kw):
                                             # few workgroups: long slices (sampling walks chunks of 64 entries and more)
                                             ("c3", dict(V=5000), 0, 1), ("c3", dict(V=5000), 0, 2),
                                             ("c5", dict(V=20000), 0, 3), ("c3", dict(V=5000, draft="indep"), 0, 2)])
-def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, G, knobs):
-    """The same results when the joint slices live in the workspace instead of the LDS (as they do at large
-    I x V per workgroup): each workgroup's region is private, whatever way the layers cut I x V."""
+@pytest.mark.parametrize("lds_slice", [0, 1000, 2502])
+def test_verify_with_slices_in_the_workspace(cfg, kw, top_k, G, lds_slice, knobs):
+    """The same results when the joint slices live in the workspace instead of the LDS, wholly or from entry 1000 or
+    2502 on (as they do at large I x V per workgroup): each workgroup's region is private, whatever way the layers
+    cut I x V."""
     gu = _gu()
-    knobs.set("DSBD_VERIFY_LDS_SLICE", "0")
+    knobs.set("DSBD_VERIFY_LDS_SLICE", lds_slice)
     if G:
         knobs.set("DSBD_VERIFY_G", G)
     w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)

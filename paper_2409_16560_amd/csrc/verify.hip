@@ -1662,27 +1662,58 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           if (jj < n_lds) return use_q ? fmax((double)pl[(int)jj] - c * (double)ql[(int)jj], 0.0) : (double)pl[(int)jj];
           return use_q ? fmax((double)pbg[jj] - c * (double)qbg[jj], 0.0) : (double)pbg[jj];
         };
+        // eight rounds from r0 on (rounds beyond `lim` count nothing): one home for all eight in all but one group of
+        // a wave, and then loads without branches between them, which the compiler keeps in flight together
+        auto weights8 = [&](long long r0, long long lim, double (&w)[8]) {
+          const long long b0 = w_lo + r0 * 64, b1 = w_lo + min(r0 + 8, lim) * 64;     // the group's range (uniform)
+          if (b0 >= n_lds && b0 < len) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const long long jj = b0 + k * 64 + lane, jc = min(jj, len - 1);
+              const double pv = pbg[jc], qv = use_q ? (double)qbg[jc] : 0.0;
+              const double v = use_q ? fmax(pv - c * qv, 0.0) : pv;
+              w[k] = (r0 + k < lim && jj < len) ? v : 0.0;
+            }
+          } else if (b1 <= n_lds) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const int jc = (int)min(b0 + k * 64 + lane, n_lds - 1);
+              const double pv = pl[jc], qv = use_q ? (double)ql[jc] : 0.0;
+              const double v = use_q ? fmax(pv - c * qv, 0.0) : pv;
+              w[k] = (r0 + k < lim) ? v : 0.0;
+            }
+          } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w[k] = r0 + k < lim ? weight(b0 + k * 64 + lane) : 0.0;
+          }
+        };
         if (per < 64) {
+          // sums over aligned groups of `per` lanes by lane moves inside the SIMD (one LDS exchange for groups of 32);
+          // a group's first lane leaves the chunk's total in the table, where its thread picks it up
           const int S = 64 / (int)per;                  // chunks per round
           for (long long r0 = 0; r0 < per; r0 += 8) {
             double w[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) w[k] = r0 + k < per ? weight(w_lo + (r0 + k) * 64 + lane) : 0.0;
+            weights8(r0, per, w);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
               double v = w[k];
-              for (int off = 1; off < (int)per; off <<= 1) v += __shfl_xor(v, off);
-              const double mine = __shfl(v, (lane % S) * (int)per);       // chunk (r0 + k) * S + lane % S
-              if (r0 + k < per && lane / S == (int)(r0 + k)) ts = mine;
+              if (per >= 2) v += dpp_move_f64<0xB1, 0xf>(v);      // quad_perm [1,0,3,2]
+              if (per >= 4) v += dpp_move_f64<0x4E, 0xf>(v);      // quad_perm [2,3,0,1]
+              if (per >= 8) v += dpp_move_f64<0x141, 0xf>(v);     // row_half_mirror: the other quad of the eight
+              if (per >= 16) v += dpp_move_f64<0x140, 0xf>(v);    // row_mirror: the other half of the sixteen
+              if (per >= 32) v += __shfl_xor(v, 16);
+              if (r0 + k < per && (lane & ((int)per - 1)) == 0)
+                sh.tsum[wave * 64 + (int)(r0 + k) * S + lane / (int)per] = v;
             }
           }
+          wave_lds_fence();
+          ts = sh.tsum[tid];
         } else {
           const long long rpc = per / 64;                // rounds per chunk (a power of two); chunk after chunk
           double acc = 0.0;
           for (long long r0 = 0; r0 < per; r0 += 8) {
             double w[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) w[k] = weight(w_lo + (r0 + k) * 64 + lane);     // per >= 64 is a multiple of 8
+            weights8(r0, per, w);                                                       // per >= 64 is a multiple of 8
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
               acc += w[k];

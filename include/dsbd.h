@@ -85,7 +85,10 @@ typedef struct dsbd_forest {
  * The prefix of tree b is an optional segment shared with other beams (k_shared_ptr[b], first
  * shared_len[b] tokens) followed by the beam's own segment (k_ptr[b], len[b] tokens).
  * Element (token t, kv-head g, channel d) of a segment lives at ptr[t*token_stride + g*head_stride + d]
- * (strides in elements; covers [L,Hkv,D] and [Hkv,L,D]).  The root token's K/V is NOT part of
+ * (strides in elements; covers [L,Hkv,D] and [Hkv,L,D]).  The two strides are common to ALL segments of all
+ * trees (head-major caches therefore share one capacity: head_stride = capacity * D), and the library cannot
+ * check them against the allocations: the caller guarantees that t*token_stride + g*head_stride + d stays inside
+ * every segment for t < its length and g < Hkv.  The root token's K/V is NOT part of
  * the prefix: it is row tree_off[b] of k_tree / v_tree.
  */
 typedef struct dsbd_kv {

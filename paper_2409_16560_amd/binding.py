@@ -201,6 +201,15 @@ class PrefixKV:
             lens = [t.shape[0] for t in k]
         for t in list(k) + list(v):
             assert t.dtype == torch.bfloat16 and (t.numel() == 0 or t.stride(-1) == 1)
+        # the library takes ONE token stride and ONE head stride for all caches and cannot check them against the
+        # allocations: caches whose strides differ (head-major tensors of different lengths, say) would be read out
+        # of bounds, so they are refused here
+        ts_ax, hs_ax = (1, 0) if head_major else (0, 1)
+        for t in held + [t for t in list(v) + [t for t in (v_shared or []) if t is not None] if t.numel() > 0]:
+            if t.dim() != 3 or (t.stride(ts_ax), t.stride(hs_ax)) != (self.token_stride, self.head_stride):
+                raise ValueError("PrefixKV: every cache must have the same token and head strides (got %s against %s); "
+                                 "allocate head-major caches with one common capacity and pass views of them"
+                                 % ((t.stride(ts_ax), t.stride(hs_ax)), (self.token_stride, self.head_stride)))
         self.k_ptr = torch.tensor([t.data_ptr() for t in k], dtype=torch.int64, device=dev)
         self.v_ptr = torch.tensor([t.data_ptr() for t in v], dtype=torch.int64, device=dev)
         self.len = torch.tensor(lens, dtype=torch.int32, device=dev)

@@ -110,3 +110,22 @@ def test_workspace_sizes_scale_with_the_problem():
     p = b._Params(0, 1, 16, 0.9)
     assert 0 < lib.dsbd_verify_forest_workspace_bytes(C.byref(small), 256, C.byref(p)) < \
         lib.dsbd_verify_forest_workspace_bytes(C.byref(big), 128256, C.byref(p))
+
+
+def test_prefix_kv_refuses_caches_of_different_strides():
+    """One token stride and one head stride serve all caches (include/dsbd.h, dsbd_kv): head-major tensors of
+    different lengths would be read out of bounds, so the binding refuses them; views of equally sized buffers pass."""
+    import torch
+    import paper_2409_16560_amd as dsbd
+    k = [torch.zeros(4, 10, 64, dtype=torch.bfloat16), torch.zeros(4, 20, 64, dtype=torch.bfloat16)]
+    with pytest.raises(ValueError):
+        dsbd.PrefixKV(k, k, head_major=True)
+    buf = [torch.zeros(4, 32, 64, dtype=torch.bfloat16) for _ in range(2)]
+    views = [buf[0][:, :10], buf[1][:, :20]]
+    kv = dsbd.PrefixKV(views, views, head_major=True)
+    assert (kv.token_stride, kv.head_stride, kv.max_len) == (64, 32 * 64, 20)
+    k = [torch.zeros(10, 4, 64, dtype=torch.bfloat16), torch.zeros(20, 4, 64, dtype=torch.bfloat16)]
+    kv = dsbd.PrefixKV(k, k)
+    assert (kv.token_stride, kv.head_stride) == (256, 64)
+    with pytest.raises(ValueError):
+        dsbd.PrefixKV(k, [k[0], torch.zeros(20, 8, 64, dtype=torch.bfloat16)])

@@ -311,6 +311,8 @@ struct LayerShared {
   double scan_w[VL_WAVES];
   double tsum[VL_BLOCK];
   double gpart[256];                 // one partial per workgroup of the prompt (G <= 256)
+  double ptot[256];                  // p_beam total of every workgroup's slice, worked out from the layer's row sums
+  int ptot_ok;                       // ... when every gathering thread saw a single piece (else 0: totals are exchanged)
   double exp_tab[64];                // 2^(j/64)
   double d_target[64];               // sampling: u * total of each draw
   // warped joints (top-k / top-p): union of the two supports, ascending flat index over I x V
@@ -1118,7 +1120,18 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         if (tid & 1) { sh.max_q[i] = cm; sh.sq[i] = sh.bw_q[i] / tot; sh.lse_q[i] = tot; }
         else { sh.max_p[i] = cm; sh.sp[i] = sh.bw_p[i] / tot; sh.lse_p[i] = tot; }
       }
+      // every workgroup's share of p_beam follows from its piece's sum: sampling from p_beam (the additional layer,
+      // the draws that fill a layer up) then needs no exchange of the workgroups' totals.  Only where a gathering
+      // thread holds exactly one piece (its sum and maximum are still in its registers).
+      // (entries of workgroups without a piece are never written: the reader knows which those are; the table is
+      // read after later barriers only)
+      const bool single_piece = !WARP && cut.rows_per_wg == 0 && geo_pieces <= R;
       __syncthreads();
+      if (tid == 0) sh.ptot_ok = single_piece ? 1 : 0;
+      if (single_piece && c < ncols && (c & 1) == 0 && r < geo_pieces) {
+        const int i = c >> 1;
+        sh.ptot[i * cut.wg_per_row + r] = sh.sp[i] * (accS * exp_nonpos(accM - sh.max_p[i], sh.exp_tab));
+      }
     }
     stamp(24);
     // scaling, fused with this thread's part of F(1) = sum max(p_beam - q_beam, 0) (second entry of the chain)
@@ -1732,19 +1745,33 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       if (tid == 0) sh.counter = 0;
       __syncthreads();
       // ... and over the workgroups (same order everywhere), gathered and scanned by one wave
-      epoch += 1;
-      const unsigned long long tag = exchange_tag(a.nonce + epoch);
-      Slot* bank = slots + bank_x(xchg++);
+      // (p_beam itself: the totals are known from the row sums, see above; the same in every workgroup of the prompt)
+      const bool known_totals = !use_q && sh.ptot_ok != 0;
+      unsigned long long tag = 0;
+      Slot* bank = nullptr;
+      if (!known_totals) {
+        epoch += 1;
+        tag = exchange_tag(a.nonce + epoch);
+        bank = slots + bank_x(xchg++);
+      }
       if (wave == 0) {
-        const double mine = sh.tsum[VL_BLOCK - 1];
-        if (lane == 0) dense_post(bank, a.G, g, mine, tag);
         double v[4];
-        if (!wave_collect4(bank, a.G, g, mine, tag, v, a.sync_limit)) give_up();
+        if (!known_totals) {
+          const double mine = sh.tsum[VL_BLOCK - 1];
+          if (lane == 0) dense_post(bank, a.G, g, mine, tag);
+          if (!wave_collect4(bank, a.G, g, mine, tag, v, a.sync_limit)) give_up();
 #pragma unroll
-        for (int k = 0; k < 4; ++k) if (lane + 64 * k < a.G) sh.gpart[lane + 64 * k] = v[k];
-        wave_lds_fence();          // now four consecutive workgroups per lane
+          for (int k = 0; k < 4; ++k) if (lane + 64 * k < a.G) sh.gpart[lane + 64 * k] = v[k];
+          wave_lds_fence();          // now four consecutive workgroups per lane
+        }
+        lds_f64* const totals = known_totals ? (lds_f64*)sh.ptot : (lds_f64*)sh.gpart;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = 4 * lane + k < a.G ? sh.gpart[4 * lane + k] : 0.0;
+        for (int k = 0; k < 4; ++k) {
+          const int w = 4 * lane + k;
+          bool holds = w < a.G;
+          if (known_totals) holds = holds && w / cut.wg_per_row < nI && w % cut.wg_per_row < geo_pieces;
+          v[k] = holds ? (double)totals[w] : 0.0;
+        }
         int nz = -1;
 #pragma unroll
         for (int k = 0; k < 4; ++k) if (v[k] > 0.0) nz = 4 * lane + k;

@@ -660,14 +660,14 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   unsigned long long* const accs = reinterpret_cast<unsigned long long*>(slots + a.sl.acc);
   const unsigned long long acc0_tag = exchange_tag(a.nonce + 0xFFFFFFull);
   unsigned int achg = 0;       // accumulator exchanges so far (alternates their two banks)
-  if (g == 0 && tid < 2 * NACC) {
-    const unsigned long long w = __hip_atomic_load(&accs[tid * 16], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    (&sh.acc_prev[0][0])[tid] = w;
-    slot_post(slots + a.sl.acc0 + tid, __longlong_as_double((long long)w), acc0_tag);
-  }
+  // (requested here, used at the end of the prologue: the round trip through the memory system runs beside it)
+  unsigned long long acc0_w = 0;
+  if (g == 0 && tid < 2 * NACC)
+    acc0_w = __hip_atomic_load(&accs[tid * 16], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
   if (tid == 0) { sh.abort = 0; sh.sbad = 0; sh.sgamma = 0; sh.counter = 0; sh.found = 0; }
-  if (tid < 64) sh.exp_tab[tid] = c_exp2_tab[tid];
+  double exp_tab_mine = 0.0;     // (the table entry travels while the prompt's trees are looked up; stored below)
+  if (tid < 64) exp_tab_mine = c_exp2_tab[tid];
 
   // ---- trees and nodes of this prompt.  tree_prompt is non-decreasing: the prompt's trees are those behind the
   // trees of earlier prompts.  (Everything the kernel needs it derives from the call's inputs: it does not wait for
@@ -686,6 +686,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     __syncthreads();
     t_first = sh.counter; t_end = sh.found;
   }
+  stamp(2);
   int n_roots = t_end - t_first;
   int bad = 0;
   if (n_roots < 0) { bad |= DSBD_FAULT_TOPOLOGY; n_roots = 0; }
@@ -696,6 +697,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   if (n_end - n_begin > NC) { bad |= DSBD_FAULT_BOUNDS; n_roots = 0; }
   int n_pn = n_roots > 0 ? n_end - n_begin : 0;          // nodes of the prompt
   const int Lw = a.max_depth + 2;                        // row length of the per-layer arrays
+  stamp(3);
   __syncthreads();
   if (tid < n_roots) {                                   // every tree inside the prompt's node range
     const int b = t_first + tid;
@@ -716,7 +718,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     sh.slot_of[tid] = -1;
     sh.S_tmp[tid] = 0;
   }
+  if (tid < 64) sh.exp_tab[tid] = exp_tab_mine;
   __syncthreads();
+  stamp(4);
   if (sh.sbad & DSBD_FAULT_TOPOLOGY) { n_roots = 0; n_pn = 0; }
   // node depths (and the validation of the parent pointers): one wave per tree walks the parent chains with lane
   // shuffles over the entries already in the LDS; depths land in S_tmp (prompt-local index)
@@ -730,14 +734,17 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     const int p_mine = lane < t.n ? sh.n_parent[t.base - n_begin + lane] : -1;
     const int fb = dsbd_tree_walk(t, lane, p_mine, a.max_depth, reinterpret_cast<int32_t*>(sh.S_tmp) - n_begin, nullptr, nullptr);
     if (fb) atomicOr(&sh.sbad, fb);
+    // the tree's deepest node: the wave's maximum by lane exchanges, one LDS atomic per tree (an atomic per node, all
+    // on one word, took 2 us on a prompt of 248 nodes)
+    wave_lds_fence();
+    int d = lane < t.n ? sh.S_tmp[t.base - n_begin + lane] : 0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) d = max(d, __shfl_xor(d, off));
+    if (lane == 0 && d > 0) atomicMax(&sh.sgamma, d);
   }
   __syncthreads();
-  if (tid < n_pn) {
-    const int d = sh.S_tmp[tid];
-    sh.n_depth[tid] = (short)d;
-    atomicMax(&sh.sgamma, d);
-  }
-  __syncthreads();
+  if (tid < n_pn) sh.n_depth[tid] = (short)sh.S_tmp[tid];      // (read after later barriers only)
+  stamp(5);
   bad |= sh.sbad;
   const int gamma = min(sh.sgamma, a.max_depth);
   if (bad && g == 0 && tid == 0) atomicOr(a.fault, bad);
@@ -783,7 +790,12 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   int near_tie = 0;          // meaningful in thread 0
   int l_last = gamma + 1;
   int n_out = 0;
+  if (g == 0 && tid < 2 * NACC) {
+    (&sh.acc_prev[0][0])[tid] = acc0_w;
+    slot_post(slots + a.sl.acc0 + tid, __longlong_as_double((long long)acc0_w), acc0_tag);
+  }
   __syncthreads();
+  stamp(6);
 
   // total over the workgroup of one value per thread: valid in every thread after the barrier inside
   auto wg_total = [&](double s, bool lds_only = false) -> double {

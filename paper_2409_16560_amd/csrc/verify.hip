@@ -1079,18 +1079,21 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 
     // ===== rows' maxima and totals: thread (r, c) gathers column c = (row, model) from every R-th workgroup that holds
     // part of it and folds the pieces (sum relative to the piece's maximum) as it goes; the R partial results of a
-    // column are then put on the column's maximum and added up in a fixed order.  Every workgroup of the prompt
-    // does the same arithmetic on the same numbers.
+    // column sit in R neighbouring lanes of one wave and are put on the column's maximum and added up by lane
+    // exchanges that pair the lanes symmetrically (no table in the LDS, no barrier in between): every lane of a
+    // column, in every workgroup of the prompt, gets the same bits.
     {
       const int ncols = 2 * nI;
       int cshift = 0;
       while ((1 << cshift) < ncols) ++cshift;
       const int cpow = 1 << cshift;
-      const int R = min(32, VL_BLOCK / cpow);
-      const int c = tid & (cpow - 1), r = tid >> cshift;
+      const int R = min(32, VL_BLOCK / cpow);                        // a power of two, 4 .. 32
+      int rshift = 2;
+      while ((1 << rshift) < R) ++rshift;
+      const int r = tid & (R - 1), c = tid >> rshift;                // c < VL_BLOCK / R, which is at least cpow
       double accM = -INFINITY, accS = 0.0;
       bool mine = true;
-      if (c < ncols && r < R) {
+      if (c < ncols) {
         const int i = c >> 1;
         const int w_lo = cut.rows_per_wg > 0 ? i / cut.rows_per_wg : i * cut.wg_per_row;
         const int w_hi = cut.rows_per_wg > 0 ? w_lo : w_lo + geo_pieces - 1;
@@ -1105,45 +1108,40 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
       stamp(20);
       if (!mine) give_up();
-      // Fold the R partial results of every column: first the maxima (lanes of a wave that share a column by lane
-      // exchanges, the waves' results through the LDS), then the sums put on the column's maximum, the same way.  The
-      // exchanges pair lanes symmetrically and the table is added up in index order, so every lane of a column, in
-      // every workgroup, gets the same bits.
-      const int gshift = cshift < 6 ? cshift : 6;                   // lanes (lane >> gshift) > 0 repeat a column of lane & (cpow - 1)
-      const int q = cshift < 6 ? wave : r;                          // this thread's row of the table
-      const int nq = cshift < 6 ? VL_WAVES : R;
-      double Mw = accM;
-      for (int off = cpow; off < 64; off <<= 1) Mw = fmax(Mw, __shfl_xor(Mw, off));
-      if ((lane >> gshift) == 0) sh.tmax[q * cpow + c] = Mw;
-      __syncthreads();
+      // over aligned groups of R lanes: quads, the other quad of an eight, the other half of a sixteen (lane moves
+      // inside the SIMD), then the other sixteen (one LDS exchange)
+      double cm = accM;
+      cm = fmax(cm, dpp_move_f64<0xB1, 0xf>(cm));                    // quad_perm [1,0,3,2]
+      cm = fmax(cm, dpp_move_f64<0x4E, 0xf>(cm));                    // quad_perm [2,3,0,1]
+      if (R >= 8) cm = fmax(cm, dpp_move_f64<0x141, 0xf>(cm));       // row_half_mirror
+      if (R >= 16) cm = fmax(cm, dpp_move_f64<0x140, 0xf>(cm));      // row_mirror
+      if (R >= 32) cm = fmax(cm, __shfl_xor(cm, 16));
+      double tot = accS * exp_nonpos(accM - cm, sh.exp_tab);         // partial results without a piece: 0 x exp(-inf) = 0
+      tot += dpp_move_f64<0xB1, 0xf>(tot);
+      tot += dpp_move_f64<0x4E, 0xf>(tot);
+      if (R >= 8) tot += dpp_move_f64<0x141, 0xf>(tot);
+      if (R >= 16) tot += dpp_move_f64<0x140, 0xf>(tot);
+      if (R >= 32) tot += __shfl_xor(tot, 16);
+      __syncthreads();                       // the beam weights (another wave's) are there; so is a give-up
       if (sh.abort) return;
       stamp(21);
-      double cm = -INFINITY;
-      for (int k = 0; k < nq; ++k) cm = fmax(cm, sh.tmax[k * cpow + c]);
-      double Sw = accS * exp_nonpos(accM - cm, sh.exp_tab);        // partial results without a piece: 0 x exp(-inf) = 0
-      for (int off = cpow; off < 64; off <<= 1) Sw += __shfl_xor(Sw, off);
-      if ((lane >> gshift) == 0) sh.tsum[q * cpow + c] = Sw;
-      __syncthreads();
       // column totals; the scale factors of the rows, and what the fp64 log-sum-exp needs (taken later)
-      if (tid < ncols) {
-        double tot = 0.0;
-        for (int k = 0; k < nq; ++k) tot += sh.tsum[k * cpow + tid];
-        const int i = tid >> 1;
-        if (tid & 1) { sh.max_q[i] = cm; sh.sq[i] = sh.bw_q[i] / tot; sh.lse_q[i] = tot; }
+      if (c < ncols && r == 0) {
+        const int i = c >> 1;
+        if (c & 1) { sh.max_q[i] = cm; sh.sq[i] = sh.bw_q[i] / tot; sh.lse_q[i] = tot; }
         else { sh.max_p[i] = cm; sh.sp[i] = sh.bw_p[i] / tot; sh.lse_p[i] = tot; }
       }
       // every workgroup's share of p_beam follows from its piece's sum: sampling from p_beam (the additional layer,
       // the draws that fill a layer up) then needs no exchange of the workgroups' totals.  Only where a gathering
       // thread holds exactly one piece (its sum and maximum are still in its registers).
-      // (entries of workgroups without a piece are never written: the reader knows which those are; the table is
-      // read after later barriers only)
+      // (entries of workgroups without a piece are never written: the reader knows which those are)
       const bool single_piece = !WARP && cut.rows_per_wg == 0 && geo_pieces <= R;
-      __syncthreads();
       if (tid == 0) sh.ptot_ok = single_piece ? 1 : 0;
       if (single_piece && c < ncols && (c & 1) == 0 && r < geo_pieces) {
         const int i = c >> 1;
-        sh.ptot[i * cut.wg_per_row + r] = sh.sp[i] * (accS * exp_nonpos(accM - sh.max_p[i], sh.exp_tab));
+        sh.ptot[i * cut.wg_per_row + r] = (sh.bw_p[i] / tot) * (accS * exp_nonpos(accM - cm, sh.exp_tab));
       }
+      __syncthreads();
     }
     stamp(24);
     // scaling, fused with this thread's part of F(1) = sum max(p_beam - q_beam, 0) (second entry of the chain)

@@ -2244,9 +2244,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       break;
     }
 
-    // ===== the layer passed: its accepted beams are the next layer's inputs
+    // ===== the layer passed: its accepted beams are the next layer's inputs.  (No barrier between the two steps:
+    // the old inputs and the new ones are nodes of different depths, so their slot_of entries are different words,
+    // and thread t reads I_node[t] before it alone overwrites it.)
     if (tid < nI) sh.slot_of[sh.I_node[tid] - n_begin] = -1;
-    __syncthreads();
     if (tid < nacc) {
       const int i = sh.A_node[tid] - n_begin;
       sh.I_node[tid] = sh.A_node[tid];

@@ -364,6 +364,18 @@ __device__ __forceinline__ double wave_sum(double v) {
   const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
   return __hiloint2double(hi, lo);
 }
+
+// Inclusive prefix sums over the lanes of a wave by the same kind of lane moves: inside every row of 16 (sources
+// outside the row count 0), then the row totals handed on to the rows behind.  Fixed order, equal bits everywhere.
+__device__ __forceinline__ double wave_inclusive_scan(double v) {
+  v += dpp_move_f64<0x111, 0xf>(v);   // row_shr:1
+  v += dpp_move_f64<0x112, 0xf>(v);   // row_shr:2
+  v += dpp_move_f64<0x114, 0xf>(v);   // row_shr:4
+  v += dpp_move_f64<0x118, 0xf>(v);   // row_shr:8
+  v += dpp_move_f64<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_move_f64<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
 __device__ __forceinline__ double wave_max_all(double v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
@@ -391,11 +403,7 @@ __device__ __forceinline__ void lds_barrier() {
 template <class Shared>
 __device__ __forceinline__ double block_inclusive_scan(double v, Shared& sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const double up = __shfl_up(v, off);
-    if (lane >= off) v += up;
-  }
+  v = wave_inclusive_scan(v);
   __syncthreads();
   if (lane == 63) sh.scan_w[wave] = v;
   __syncthreads();
@@ -1627,16 +1635,13 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       if constexpr (WARP) {
         // the weights live on the short list (ascending flat index) that every workgroup holds: one wave scans
         // it, the first workgroup writes the samples
+        __syncthreads();           // the rows' log-sum-exps (another wave's work since the fold) are in place
         if (wave == 0) {
           const int nU = sh.nU;
           double w = 0.0;
           if (lane < nU) w = use_q ? fmax(sh.U_p[lane] - c * sh.U_q[lane], 0.0) : sh.U_p[lane];
           double incl = w;
-#pragma unroll
-          for (int off = 1; off < 64; off <<= 1) {
-            const double up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-          }
+          incl = wave_inclusive_scan(incl);
           const double Z = __shfl(incl, 63);
           const unsigned long long mass = __ballot(w > 0.0);
           for (int j = 0; j < cnt; ++j) {
@@ -1782,22 +1787,19 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           if (known_totals) holds = holds && w / cut.wg_per_row < nI && w % cut.wg_per_row < geo_pieces;
           v[k] = holds ? (double)totals[w] : 0.0;
         }
-        int nz = -1;
+        int nz = -1;                 // the last workgroup that holds any mass (uniform: from ballots)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) if (v[k] > 0.0) nz = 4 * lane + k;
+        for (int k = 0; k < 4; ++k) {
+          const unsigned long long has = __ballot(v[k] > 0.0);
+          if (has) nz = max(nz, 4 * (63 - __clzll((long long)has)) + k);
+        }
         v[1] += v[0]; v[2] += v[1]; v[3] += v[2];
         double incl = v[3];
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const double up = __shfl_up(incl, off);
-          if (lane >= off) incl += up;
-        }
+        incl = wave_inclusive_scan(incl);
         double excl = __shfl_up(incl, 1);
         if (lane == 0) excl = 0.0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) if (4 * lane + k < a.G) sh.gpart[4 * lane + k] = excl + v[k];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) nz = max(nz, __shfl_xor(nz, off));
         if (lane == 0) sh.found = nz;
       }
       __syncthreads();
@@ -1874,11 +1876,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
               double v = 0.0;
               if (jj < c_hi) v = use_q ? fmax(ldp(jj) - c * ldq(jj), 0.0) : ldp(jj);
               double incl = v;
-#pragma unroll
-              for (int off = 1; off < 64; off <<= 1) {
-                const double up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-              }
+              incl = wave_inclusive_scan(incl);
               const unsigned long long mass = __ballot(v > 0.0);
               if (mass) last = b0 + 63 - __clzll((long long)mass);
               const unsigned long long over = __ballot(start + incl > target);

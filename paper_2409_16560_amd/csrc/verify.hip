@@ -365,6 +365,22 @@ __device__ __forceinline__ double wave_sum(double v) {
   return __hiloint2double(hi, lo);
 }
 
+// The largest of a value over the lanes of a wave, in every lane: rows of 16 by lane moves that pair the lanes
+// symmetrically, the rows' results handed on to the rows behind, the last lane's read back as a uniform value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_other_f32(float v) {          // lanes without a source lane read their own value
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+  v = fmaxf(v, dpp_other_f32<0xB1, 0xf>(v));    // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_other_f32<0x4E, 0xf>(v));    // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_other_f32<0x141, 0xf>(v));   // row_half_mirror
+  v = fmaxf(v, dpp_other_f32<0x140, 0xf>(v));   // row_mirror
+  v = fmaxf(v, dpp_other_f32<0x142, 0xa>(v));   // row_bcast:15 into rows 1 and 3
+  v = fmaxf(v, dpp_other_f32<0x143, 0xc>(v));   // row_bcast:31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 // Inclusive prefix sums over the lanes of a wave by the same kind of lane moves: inside every row of 16 (sources
 // outside the row count 0), then the row totals handed on to the rows behind.  Fixed order, equal bits everywhere.
 __device__ __forceinline__ double wave_inclusive_scan(double v) {
@@ -927,8 +943,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       }
       if (nonfinite) atomicOr(a.fault, DSBD_FAULT_NONFINITE);
       stamp(73);
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) { lmp = fmaxf(lmp, __shfl_xor(lmp, off)); lmq = fmaxf(lmq, __shfl_xor(lmq, off)); }
+      lmp = wave_max_f32(lmp); lmq = wave_max_f32(lmq);
       float* const wm = sh.wmax[(i - i_lo) & 1];       // two buffers: a wave is at most one row ahead of the slowest
       if (lane == 0) { wm[2 * wave] = lmp; wm[2 * wave + 1] = lmq; }
       __syncthreads();

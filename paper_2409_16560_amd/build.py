@@ -18,9 +18,9 @@ FILE_FLAGS = {"attention.hip": os.environ.get("DSBD_ATTN_FLAGS", "-fno-honor-nan
               "verify.hip": os.environ.get("DSBD_VERIFY_FLAGS", "-mllvm -disable-machine-licm").split()
               + ["-Rpass-analysis=kernel-resource-usage"]}
 # The statistics pass runs beside the layer kernel, one workgroup (a wave of 32 registers per SIMD) per compute unit:
-# that needs the layer kernel's two waves per SIMD to leave registers free; 224 leaves room for two such waves
-# (512 registers per SIMD lane, handed out in eights).
-LAYER_KERNEL_VGPR_BUDGET = 224
+# that needs the layer kernel's two waves per SIMD to leave 32 of the 512 registers of a SIMD lane free (handed out in
+# eights): at most 240 each.
+LAYER_KERNEL_VGPR_BUDGET = 240
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fgpu-rdc-", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

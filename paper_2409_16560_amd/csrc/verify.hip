@@ -837,9 +837,84 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
   SliceCut geo_cut = {0, 1, 0};
   long long geo_lo = 0, geo_hi = 0;
 
+  // (worked out when the number of rows changes: a handful of 64-bit divisions, on every workgroup's critical
+  // path, that a fixed layer width repeats unchanged layer after layer)
+  auto set_geometry = [&](int rows) {
+    if (rows == geo_nI) return;
+    const long long all = (long long)rows * V;
+    geo_nI = rows;
+    geo_cut = slice_cut(rows, V, a.G);
+    geo_lo = all; geo_hi = all;
+    if (geo_cut.rows_per_wg > 0) {
+      geo_lo = min(all, (long long)g * geo_cut.rows_per_wg * V);
+      geo_hi = min(all, geo_lo + (long long)geo_cut.rows_per_wg * V);
+    } else if (g / geo_cut.wg_per_row < rows) {
+      const long long r0 = (long long)(g / geo_cut.wg_per_row) * V, k = g % geo_cut.wg_per_row;
+      geo_lo = r0 + min((long long)V, k * geo_cut.len);
+      geo_hi = r0 + min((long long)V, (k + 1) * geo_cut.len);
+    }
+    geo_ilo = (int)div_floor(geo_lo, V);
+    geo_ihi = geo_hi > geo_lo ? (int)div_floor(geo_hi - 1, V) : geo_ilo - 1;
+    geo_pieces = (int)((V + geo_cut.len - 1) / geo_cut.len);
+  };
+  int passed_nacc = -1;      // >= 0: the layer before passed with this many accepted beams, not yet handed over
+
   stamp(1);
   for (int l = 1; l <= gamma + 1; ++l) {
     stamp(10 + l);
+    // The layer before passed: its accepted beams are this layer's inputs.  The first two rounds of logits of this
+    // workgroup's first row are requested BEFORE the hand-over's book-keeping, which then runs while they travel
+    // (its barriers order the LDS only).
+    float eA_p[XU], eA_q[XU], eB_p[XU], eB_q[XU];
+    bool early = false;
+#pragma unroll
+    for (int k = 0; k < XU; ++k) { eA_p[k] = 0.f; eA_q[k] = 0.f; eB_p[k] = 0.f; eB_q[k] = 0.f; }
+    if (passed_nacc >= 0) {
+      const int nacc = passed_nacc;
+      passed_nacc = -1;
+      set_geometry(nacc);
+      if (geo_ihi >= geo_ilo) {
+        const int i = geo_ilo;
+        const int node = sh.A_node[i];
+        const int x_lo = (int)(max(geo_lo, (long long)i * V) - (long long)i * V);
+        const int x_hi = (int)(min(geo_hi, (long long)(i + 1) * V) - (long long)i * V);
+        const float* zp = a.zp + (long long)node * V;
+        const float* zq = a.zq + (long long)node * V;
+        const int xA = x_lo + tid, xB = xA + XU * VL_BLOCK;
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+          const int xx = min(xA + k * VL_BLOCK, x_hi - 1);
+          eA_p[k] = zp[xx]; eA_q[k] = zq[xx];
+        }
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+          const int xx = min(xB + k * VL_BLOCK, x_hi - 1);
+          eB_p[k] = zp[xx]; eB_q[k] = zq[xx];
+        }
+        early = true;
+      }
+      // cumulative likelihoods of the accepted beams (fp64)
+      if (tid < nacc) {
+        const int n = sh.A_node[tid];
+        const int ci = sh.A_idx[tid];
+        const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
+        sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)sh.S_zp[ci] - sh.lse_p[slot]);
+        sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)sh.S_zq[ci] - sh.lse_q[slot]);
+      }
+      lds_barrier();
+      // (no barrier between the next two steps: the old inputs and the new ones are nodes of different depths, so
+      // their slot_of entries are different words, and thread t reads I_node[t] before it alone overwrites it)
+      if (tid < nI) sh.slot_of[sh.I_node[tid] - n_begin] = -1;
+      if (tid < nacc) {
+        const int i = sh.A_node[tid] - n_begin;
+        sh.I_node[tid] = sh.A_node[tid];
+        sh.cum_p[tid] = sh.A_cum_p[tid];
+        sh.cum_q[tid] = sh.A_cum_q[tid];
+        sh.slot_of[i] = (short)tid;
+      }
+      nI = nacc;
+      lds_barrier();
+    }
     const bool bonus = (l == gamma + 1);
     const long long total = (long long)nI * V;           // elements of I x V
     // I x V is cut along the rows: with fewer rows than workgroups every row is cut into the same pieces (the
@@ -847,24 +922,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // sum is formed in an order that depends on the row's length only, so beams with equal logits and equal
     // likelihoods (duplicates are common in beam sampling) get bitwise equal joint entries, and the order of
     // equal entries (by index) is the same as in a plain row-by-row evaluation.
-    // (worked out when the number of rows changes: a handful of 64-bit divisions, on every workgroup's critical
-    // path, that a fixed layer width repeats unchanged layer after layer)
-    if (nI != geo_nI) {
-      geo_nI = nI;
-      geo_cut = slice_cut(nI, V, a.G);
-      geo_lo = total; geo_hi = total;
-      if (geo_cut.rows_per_wg > 0) {
-        geo_lo = min(total, (long long)g * geo_cut.rows_per_wg * V);
-        geo_hi = min(total, geo_lo + (long long)geo_cut.rows_per_wg * V);
-      } else if (g / geo_cut.wg_per_row < nI) {
-        const long long r0 = (long long)(g / geo_cut.wg_per_row) * V, k = g % geo_cut.wg_per_row;
-        geo_lo = r0 + min((long long)V, k * geo_cut.len);
-        geo_hi = r0 + min((long long)V, (k + 1) * geo_cut.len);
-      }
-      geo_ilo = (int)div_floor(geo_lo, V);
-      geo_ihi = geo_hi > geo_lo ? (int)div_floor(geo_hi - 1, V) : geo_ilo - 1;
-      geo_pieces = (int)((V + geo_cut.len - 1) / geo_cut.len);
-    }
+    set_geometry(nI);
     const SliceCut cut = geo_cut;
     const long long ch = cut.len;            // the longest slice of the layer
     const long long e_lo = geo_lo, e_hi = geo_hi;
@@ -911,15 +969,20 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       float lmp = -INFINITY, lmq = -INFINITY;
       const int xA = x_lo + tid, xB = xA + XU * VL_BLOCK;
       const bool haveB = x_lo + XU * VL_BLOCK < x_hi;                      // uniform over the workgroup
+      if (early && i == i_lo) {            // requested at the top of the layer
 #pragma unroll
-      for (int k = 0; k < XU; ++k) {
-        const int xx = min(xA + k * VL_BLOCK, x_hi - 1);              // clamped repeats do not change a maximum
-        fpA[k] = zp[xx]; fqA[k] = zq[xx];
-      }
+        for (int k = 0; k < XU; ++k) { fpA[k] = eA_p[k]; fqA[k] = eA_q[k]; fpB[k] = eB_p[k]; fqB[k] = eB_q[k]; }
+      } else {
 #pragma unroll
-      for (int k = 0; k < XU; ++k) {
-        const int xx = min(xB + k * VL_BLOCK, x_hi - 1);
-        fpB[k] = zp[xx]; fqB[k] = zq[xx];
+        for (int k = 0; k < XU; ++k) {
+          const int xx = min(xA + k * VL_BLOCK, x_hi - 1);              // clamped repeats do not change a maximum
+          fpA[k] = zp[xx]; fqA[k] = zq[xx];
+        }
+#pragma unroll
+        for (int k = 0; k < XU; ++k) {
+          const int xx = min(xB + k * VL_BLOCK, x_hi - 1);
+          fpB[k] = zp[xx]; fqB[k] = zq[xx];
+        }
       }
       bool nonfinite = false;        // (the statistics pass reports these for every row; this kernel for the rows it uses)
 #pragma unroll
@@ -2216,18 +2279,17 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     if (g == 0)
       for (int i = pos_end + tid; i < M; i += VL_BLOCK) a.out.node_status[sh.S_node[i]] = DSBD_REJECTED;
 
-    // cumulative likelihoods of the accepted beams (fp64)
-    if (tid < nacc) {
-      const int n = sh.A_node[tid];
-      const int ci = sh.A_idx[tid];
-      const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
-      sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)sh.S_zp[ci] - sh.lse_p[slot]);
-      sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)sh.S_zq[ci] - sh.lse_q[slot]);
-    }
-    __syncthreads();
-
     stamp(50);
     if (nacc < WL) {
+      // cumulative likelihoods of the accepted beams (fp64)
+      if (tid < nacc) {
+        const int n = sh.A_node[tid];
+        const int ci = sh.A_idx[tid];
+        const int slot = sh.slot_of[sh.n_parent[n - n_begin] - n_begin];
+        sh.A_cum_p[tid] = sh.cum_p[slot] + ((double)sh.S_zp[ci] - sh.lse_p[slot]);
+        sh.A_cum_q[tid] = sh.cum_q[slot] + ((double)sh.S_zq[ci] - sh.lse_q[slot]);
+      }
+      __syncthreads();
       // ===== the layer falls short: accepted beams, one residual sample, then p_beam samples
       if (g == 0 && tid < nacc) {
         const int n = sh.A_node[tid];
@@ -2257,19 +2319,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       break;
     }
 
-    // ===== the layer passed: its accepted beams are the next layer's inputs.  (No barrier between the two steps:
-    // the old inputs and the new ones are nodes of different depths, so their slot_of entries are different words,
-    // and thread t reads I_node[t] before it alone overwrites it.)
-    if (tid < nI) sh.slot_of[sh.I_node[tid] - n_begin] = -1;
-    if (tid < nacc) {
-      const int i = sh.A_node[tid] - n_begin;
-      sh.I_node[tid] = sh.A_node[tid];
-      sh.cum_p[tid] = sh.A_cum_p[tid];
-      sh.cum_q[tid] = sh.A_cum_q[tid];
-      sh.slot_of[i] = (short)tid;
-    }
-    nI = nacc;
-    __syncthreads();
+    // ===== the layer passed: handed over at the top of the next layer
+    passed_nacc = nacc;
   }
 
   stamp(99);

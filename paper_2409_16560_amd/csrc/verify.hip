@@ -353,6 +353,12 @@ __device__ __forceinline__ double dpp_move_f64(double v) {       // lanes withou
   const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
   return __hiloint2double(hi, lo);
 }
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_move_u64(unsigned long long v) {
+  const unsigned int lo = (unsigned int)__builtin_amdgcn_update_dpp(0, (int)(unsigned int)v, CTRL, 0xf, 0xf, false);
+  const unsigned int hi = (unsigned int)__builtin_amdgcn_update_dpp(0, (int)(unsigned int)(v >> 32), CTRL, 0xf, 0xf, false);
+  return ((unsigned long long)hi << 32) | lo;
+}
 __device__ __forceinline__ double wave_sum(double v) {
   v += dpp_move_f64<0xB1, 0xf>(v);    // quad_perm [1,0,3,2]
   v += dpp_move_f64<0x4E, 0xf>(v);    // quad_perm [2,3,0,1]
@@ -601,9 +607,17 @@ __device__ __forceinline__ bool wave_sum_accumulators(unsigned long long* accs, 
       }
     }
   }
-#pragma unroll
-  for (int off = 1; off < NACC; off <<= 1) field += __shfl_xor(field, off);     // lanes 0..NACC-1 hold the total
-  field = __shfl(field, 0);
+  // the eight words' fields added up by lane moves inside the SIMD (quads, then the other quad of the eight) and the
+  // first lane's total read back as a uniform value: no LDS round trips on the chain's critical path
+  static_assert(NACC == 8, "the reduction below is written for eight words");
+  field += dpp_move_u64<0xB1>(field);       // quad_perm [1,0,3,2]
+  field += dpp_move_u64<0x4E>(field);       // quad_perm [2,3,0,1]
+  field += dpp_move_u64<0x141>(field);      // row_half_mirror
+  {
+    const unsigned int lo = (unsigned int)__builtin_amdgcn_readfirstlane((int)(unsigned int)field);
+    const unsigned int hi = (unsigned int)__builtin_amdgcn_readfirstlane((int)(unsigned int)(field >> 32));
+    field = ((unsigned long long)hi << 32) | lo;
+  }
   total = (double)field * (1.0 / 4503599627370496.0);
   return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
 }

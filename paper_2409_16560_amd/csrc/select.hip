@@ -8,13 +8,10 @@
 #include "common.h"
 
 #define SELECT_LDS_TREES 8192
-#define SELECT_LDS_NODES 4096
 
 struct SelectArgs {
   int n_prompts, n_trees, n_nodes, W_cap, Lmax, keep_one;
   int toff_in_lds;       // tree_off staged in the dynamic LDS (forests of up to SELECT_LDS_TREES trees), else read in place
-  int par_in_lds;        // the parent array staged behind it (forests of up to SELECT_LDS_NODES nodes): the walk from a
-                         // beam's node to its root is a chain of dependent reads, 0.7 us each from global memory
   const int32_t *tree_off, *parent;
   const int32_t *n_out, *out_parent, *out_token;
   const double *out_lp, *out_lq;
@@ -35,10 +32,6 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
   if (a.toff_in_lds)
     for (int t = j; t <= a.n_trees; t += 64) toff_lds[t] = a.tree_off[t];
   const int* const toff = a.toff_in_lds ? toff_lds : a.tree_off;
-  int* const par_lds = toff_lds + (a.toff_in_lds ? a.n_trees + 1 : 0);
-  if (a.par_in_lds)
-    for (int t = j; t < a.n_nodes; t += 64) par_lds[t] = a.parent[t];
-  const int* const parent = a.par_in_lds ? par_lds : a.parent;
   if (j == 0) {
     best = 0;
     if (a.keep_one)
@@ -68,7 +61,7 @@ __global__ __launch_bounds__(64) void select_beams_kernel(SelectArgs a) {
     int cur = node;
     for (int it = 0; it < DSBD_MAX_TREE_NODES; ++it) {
       tmp[len++] = cur;
-      const int par = parent[cur];
+      const int par = a.parent[cur];
       if (par < 0) { root = cur; break; }
       if (par >= cur) { bad = DSBD_FAULT_TOPOLOGY; break; }
       cur = par;
@@ -117,12 +110,9 @@ extern "C" int32_t dsbd_select_beams(const dsbd_forest* f, const dsbd_verify_out
   size_t toff_bytes = ((size_t)f->n_trees + 1) * sizeof(int32_t);
   a.toff_in_lds = toff_bytes <= SELECT_LDS_TREES * sizeof(int32_t) ? 1 : 0;
   if (!a.toff_in_lds) toff_bytes = 0;
-  size_t par_bytes = (size_t)f->n_nodes * sizeof(int32_t);
-  a.par_in_lds = (f->n_nodes <= SELECT_LDS_NODES && toff_bytes + par_bytes <= 40 * 1024) ? 1 : 0;
-  if (!a.par_in_lds) par_bytes = 0;
-  hipLaunchKernelGGL(select_beams_kernel, dim3(f->n_prompts), dim3(64), toff_bytes + par_bytes, static_cast<hipStream_t>(stream_), a);
+  hipLaunchKernelGGL(select_beams_kernel, dim3(f->n_prompts), dim3(64), toff_bytes, static_cast<hipStream_t>(stream_), a);
   DSBD_HIP_LAUNCH_CHECK();
   return DSBD_OK;
 }
 
-extern "C" const char* dsbd_version(void) { return "dsbd 0.4 (gfx950)"; }
+extern "C" const char* dsbd_version(void) { return "dsbd 0.5 (gfx950)"; }

@@ -2,7 +2,8 @@
 """Benchmark of the forest-verification hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic input: dsbd_forest_attention (one transformer
-layer's attention over the draft forest), dsbd_verify_forest and dsbd_select_beams, on the largest configuration
+layer's attention over the draft forest) and dsbd_verify_forest_select (dsbd_verify_forest and dsbd_select_beams in
+one call: the layer kernel writes the next-beam plan along with the output beams), on the largest configuration
 (c5: W=8 beams, 31-node trees, prefix 8192, GQA 32/8, head_dim 128, vocabulary 128256).  Inputs are resident in HBM
 before the timed region; steps rotate over several copies of the inputs so that the 256 MB Infinity Cache cannot
 serve the K/V and logit streams.
@@ -87,8 +88,13 @@ class Case:
         d, o = self.sets[i % len(self.sets)], self.outs[i % len(self.sets)]
         self.dsbd.dsbd_select_beams(d.forest, o["vres"], result=o["nx"])
 
+    def verify_select(self, i, t=None):
+        d, o = self.sets[i % len(self.sets)], self.outs[i % len(self.sets)]
+        d.verify_select(t=self.t if t is None else t, result=o["vres"], next_beams=o["nx"], workspace=o["vws"])
+
     def step(self, i, t=None):
-        self.attention(i); self.verify(i, t); self.select(i)
+        # verification and selection through the one-call form (the layer kernel writes the next-beam plan itself)
+        self.attention(i); self.verify_select(i, t)
 
     def check_faults(self):
         for o in self.outs:
@@ -261,7 +267,8 @@ def main():
     ts = case.event_times(case.step, ev_steps)
     # ---- per call (events around each library call)
     br = {name + "_ms": (lambda v: v[len(v) // 2])(case.event_times(fn, 30))
-          for name, fn in (("attention", case.attention), ("verify", case.verify), ("select", case.select))}
+          for name, fn in (("attention", case.attention), ("verify", case.verify), ("verify_select", case.verify_select),
+                           ("select", case.select))}
     # ---- per kernel: the library's timing hook stamps the kernel's own start and end (one kernel at a time)
     kernels = []
     step_bytes = case.attn_bytes + case.verify_bytes
@@ -302,7 +309,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": case.describe(), "input_copies_rotated": len(case.sets),
                    **({} if args.shared_len is None else {"control_shared_prefix_tokens": args.shared_len})},
-        "roofline": {"bound": "hbm", "kernel": "whole step: forest attention + merge, vocabulary statistics beside the layer kernel, selection",
+        "roofline": {"bound": "hbm", "kernel": "whole step: forest attention + merge, vocabulary statistics beside the layer kernel (which also writes the next-beam plan)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (sum(traffic.values()) if traffic else None),
                      "algorithmic_bytes_per_step": step_bytes, "target_frac": 0.60,

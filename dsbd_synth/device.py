@@ -50,3 +50,9 @@ class DeviceWorkload:
     def verify(self, W_L=0, W_min=1, t=-1.0, **kw):
         return dsbd.dsbd_verify_forest(self.forest, self.logits_p, self.logits_q, self.blp, self.blq, self.u_accept,
                                        self.u_resid, self.u_fill, W_L=W_L, W_min=W_min, W_cap=self.w.W_cap, t=t, **kw)
+
+    def verify_select(self, W_L=0, W_min=1, t=-1.0, **kw):
+        """Verification with the next-beam plan written in the same call; returns (VerifyResult, NextBeams)."""
+        return dsbd.dsbd_verify_forest_select(self.forest, self.logits_p, self.logits_q, self.blp, self.blq,
+                                              self.u_accept, self.u_resid, self.u_fill, W_L=W_L, W_min=W_min,
+                                              W_cap=self.w.W_cap, t=t, **kw)

@@ -249,6 +249,19 @@ int32_t dsbd_select_beams(const dsbd_forest* forest, const dsbd_verify_out* veri
                           int32_t keep_one, const dsbd_next_beams* next, int32_t* fault, void* stream);
 
 /*
+ * Verification and selection in one call (Algorithm 1 with its return statement; Section 3.3, last paragraph;
+ * Section 3.4 for keep_one): dsbd_verify_forest followed by dsbd_select_beams with W_cap = params->W_cap, same
+ * arguments, same results in `out` and `next`, same error behaviour, one `fault` word for both.  With keep_one == 0
+ * no selection kernel is launched: the workgroup of the layer kernel that writes an output beam also writes the
+ * beam's entry of the plan (the tree whose cache it continues, the path of forest nodes from the root).  With
+ * keep_one != 0 the single surviving beam is chosen among all output beams of a prompt, so the selection kernel
+ * runs behind the verification on `stream`.  An empty forest writes nothing, as in dsbd_verify_forest.
+ */
+int32_t dsbd_verify_forest_select(const dsbd_forest* forest, const dsbd_verify_in* in, const dsbd_params* params,
+                                  const dsbd_verify_out* out, int32_t keep_one, const dsbd_next_beams* next,
+                                  void* workspace, size_t workspace_bytes, int32_t* fault, void* stream);
+
+/*
  * Destination caches of the next iteration's beams, one per slot (p, j) of the next-beam plan, in the layout
  * (strides) of the source caches.  Only the own segment is written; a segment shared by the beams of a prompt
  * stays where it is.

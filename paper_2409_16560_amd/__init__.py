@@ -6,7 +6,7 @@ this package fails loudly if the library has not been built (python -m paper_240
 """
 from .binding import (  # noqa: F401
     DsbdError, Forest, PrefixKV, VerifyResult, NextBeams, KVDst, lib_path, load_library,
-    dsbd_forest_attention, dsbd_verify_forest, dsbd_select_beams, dsbd_commit_kv, dsbd_draft_layer, dsbd_build_forest,
+    dsbd_forest_attention, dsbd_verify_forest, dsbd_verify_forest_select, dsbd_select_beams, dsbd_commit_kv, dsbd_draft_layer, dsbd_build_forest,
     dsbd_version,
     dsbd_forest_attention_workspace_bytes, dsbd_verify_forest_workspace_bytes,
     dsbd_timing_enable, dsbd_timing_collect, dsbd_reload_knobs, dsbd_stream_read_probe, dsbd_init, dsbd_verify_forest_static, dsbd_verify_forest_static_capacity, DSBD_KERNEL_ATTENTION, DSBD_KERNEL_VOCAB_STATS, DSBD_KERNEL_VERIFY_LAYERS, DSBD_KERNEL_KV_COMMIT,

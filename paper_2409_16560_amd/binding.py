@@ -110,6 +110,10 @@ def load_library():
     lib.dsbd_select_beams.restype = C.c_int32
     lib.dsbd_select_beams.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyOut), C.c_int32, C.c_int32,
                                       C.POINTER(_NextBeams), C.c_void_p, C.c_void_p]
+    lib.dsbd_verify_forest_select.restype = C.c_int32
+    lib.dsbd_verify_forest_select.argtypes = [C.POINTER(_Forest), C.POINTER(_VerifyIn), C.POINTER(_Params),
+                                              C.POINTER(_VerifyOut), C.c_int32, C.POINTER(_NextBeams), C.c_void_p,
+                                              C.c_size_t, C.c_void_p, C.c_void_p]
     lib.dsbd_commit_kv.restype = C.c_int32
     lib.dsbd_commit_kv.argtypes = [C.POINTER(_Forest), C.POINTER(_KV), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                    C.POINTER(_NextBeams), C.c_int32, C.POINTER(_KVDst), C.c_void_p, C.c_void_p]
@@ -335,6 +339,40 @@ def dsbd_verify_forest(forest: Forest, logits_target, logits_draft, beam_logp_ta
                                 workspace.numel(), _ptr(result.fault), _stream(stream))
     _check(rc, "dsbd_verify_forest")
     return result
+
+
+def dsbd_verify_forest_select(forest: Forest, logits_target, logits_draft, beam_logp_target, beam_logp_draft,
+                              u_accept, u_resid, u_fill, W_L=0, W_min=1, W_cap=16, t=-1.0, keep_one=False,
+                              result: VerifyResult = None, next_beams: "NextBeams" = None, workspace=None, stream=None,
+                              top_k=0, top_p=1.0):
+    """dsbd_verify_forest and dsbd_select_beams in one call.  Returns (VerifyResult, NextBeams); faults of both are
+    reported in VerifyResult.fault."""
+    lib = load_library()
+    N, V = logits_target.shape
+    f, p = forest.c_struct(), _params(W_L, W_min, W_cap, t, top_k, top_p)
+    for t_, dt in ((logits_target, torch.float32), (logits_draft, torch.float32), (beam_logp_target, torch.float64),
+                   (beam_logp_draft, torch.float64), (u_accept, torch.float32), (u_resid, torch.float32),
+                   (u_fill, torch.float32)):
+        assert t_.dtype == dt and t_.is_contiguous()
+    assert u_resid.numel() == forest.n_prompts * (forest.max_depth + 2)
+    assert u_fill.numel() == forest.n_prompts * (forest.max_depth + 2) * W_cap
+    vin = _VerifyIn(int(V), _ptr(logits_target), _ptr(logits_draft), _ptr(beam_logp_target), _ptr(beam_logp_draft),
+                    _ptr(u_accept), _ptr(u_resid), _ptr(u_fill))
+    if result is None:
+        result = VerifyResult.allocate(forest, W_cap)
+    if next_beams is None:
+        next_beams = NextBeams.allocate(forest, W_cap)
+    if workspace is None:
+        nbytes = int(lib.dsbd_verify_forest_workspace_bytes(C.byref(f), int(V), C.byref(p)))
+        if nbytes == 0 and N > 0:
+            raise DsbdError(-2, "dsbd_verify_forest_workspace_bytes")
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=logits_target.device)
+    vout, nx = result.c_struct(), next_beams.c_struct()
+    rc = lib.dsbd_verify_forest_select(C.byref(f), C.byref(vin), C.byref(p), C.byref(vout), int(bool(keep_one)),
+                                       C.byref(nx), _ptr(workspace), workspace.numel(), _ptr(result.fault),
+                                       _stream(stream))
+    _check(rc, "dsbd_verify_forest_select")
+    return result, next_beams
 
 
 def dsbd_init():

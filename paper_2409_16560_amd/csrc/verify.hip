@@ -263,9 +263,13 @@ struct LayersArgs {
   int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
                          // bounded waits give up and the error path can be exercised without a hang
   int32_t* fault;
+  dsbd_next_beams nx;    // next-beam plan written along with the output beams (fused selection) ...
+  int nx_on;             // ... when this is set
 };
 
 #define VL_WAVES (VL_BLOCK / 64)
+#define NODE_DEPTH_MASK 0xff   // LayerShared::n_depth: depth of the node (below 64) ...
+#define NODE_TREE_SHIFT 8      // ... and, above it, the index of its tree among the prompt's trees (below 64)
 #define NACC 8                 // accumulator words of a one-hop sum (see wave_sum_accumulators)
 #define ACC_FIELD_BITS 54
 static_assert(NODE_CAP <= VL_BLOCK, "one thread per node of a prompt");
@@ -775,10 +779,13 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // the tree's deepest node: the wave's maximum by lane exchanges, one LDS atomic per tree (an atomic per node, all
     // on one word, took 2 us on a prompt of 248 nodes)
     wave_lds_fence();
-    int d = lane < t.n ? sh.S_tmp[t.base - n_begin + lane] : 0;
+    const int d_mine = lane < t.n ? sh.S_tmp[t.base - n_begin + lane] : 0;
+    int d = d_mine;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) d = max(d, __shfl_xor(d, off));
     if (lane == 0 && d > 0) atomicMax(&sh.sgamma, d);
+    // (the node's tree within the prompt rides in the bits above its depth: the next-beam plan names it)
+    if (lane < t.n) sh.S_tmp[t.base - n_begin + lane] = (d_mine & NODE_DEPTH_MASK) | (b << NODE_TREE_SHIFT);
   }
   __syncthreads();
   if (tid < n_pn) sh.n_depth[tid] = (short)sh.S_tmp[tid];      // (read after later barriers only)
@@ -789,24 +796,53 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
 
   // ---- initial statuses (first workgroup of the prompt)
   if (g == 0) {
-    if (tid < n_pn) a.out.node_status[n_begin + tid] = sh.n_depth[tid] == 0 ? DSBD_ROOT : DSBD_NOT_REACHED;
+    if (tid < n_pn) a.out.node_status[n_begin + tid] = (sh.n_depth[tid] & NODE_DEPTH_MASK) == 0 ? DSBD_ROOT : DSBD_NOT_REACHED;
     for (int i = tid; i < Lw; i += VL_BLOCK) a.out.layer_width[(long long)prompt * Lw + i] = i == 0 ? n_roots : 0;
   }
   // Output words are written by exactly one workgroup each (sampled beams by the workgroup that owns the
   // sample, per-node log-probabilities by the node's workgroup, everything else by the prompt's first
   // workgroup): the XCDs' L2 caches are not coherent with each other, so two workgroups must never write
   // the same word.
+  const int plan_len = a.max_depth + 1;                   // row length of the plan's paths
   auto clear_out_slots = [&](int from) {
     for (int i = from + tid; i < a.W_cap; i += VL_BLOCK) {
       const long long o = (long long)prompt * a.W_cap + i;
       a.out.out_parent[o] = -1; a.out.out_token[o] = -1; a.out.out_node[o] = -1;
       a.out.out_logp_target[o] = 0.0; a.out.out_logp_draft[o] = 0.0;
+      if (a.nx_on) {
+        a.nx.src_tree[o] = -1; a.nx.src_out[o] = -1; a.nx.path_len[o] = 0; a.nx.token[o] = -1;
+        a.nx.logp_target[o] = 0.0; a.nx.logp_draft[o] = 0.0;
+        for (int k = 0; k < plan_len; ++k) a.nx.path[o * plan_len + k] = -1;
+      }
     }
+  };
+  // Fused selection (Algorithm 1's return; Section 3.3, last paragraph): whoever writes output beam j of the prompt
+  // also writes its entry of the next-beam plan: the tree whose cache it continues and the nodes root .. `node`
+  // (the beam's last forest node), root first, read off the parent entries in the LDS.  One thread per beam.
+  auto emit_next = [&](int j, int node, int x, double lp, double lq) {
+    if (!a.nx_on) return;
+    const long long o = (long long)prompt * a.W_cap + j;
+    const int dt = sh.n_depth[node - n_begin];
+    const int d = min(dt & NODE_DEPTH_MASK, a.max_depth);
+    int32_t* const path = a.nx.path + o * plan_len;
+    int cur = node;
+    for (int k = d; k >= 0; --k) {
+      path[k] = cur;
+      cur = k > 0 ? sh.n_parent[cur - n_begin] : cur;
+    }
+    for (int k = d + 1; k < plan_len; ++k) path[k] = -1;
+    a.nx.src_tree[o] = t_first + (dt >> NODE_TREE_SHIFT);
+    a.nx.src_out[o] = j;
+    a.nx.path_len[o] = d + 1;
+    a.nx.token[o] = x;
+    a.nx.logp_target[o] = lp;
+    a.nx.logp_draft[o] = lq;
   };
   if (n_roots == 0) {
     if (g == 0) clear_out_slots(0);
     if (g == 0 && tid == 0) {
       a.out.l_last[prompt] = 0; a.out.n_out[prompt] = 0; a.out.near_tie_count[prompt] = 0;
+      if (a.nx_on) a.nx.n_next[prompt] = 0;
     }
     return;   // uniform over the prompt's workgroups: nobody waits for a missing partner
   }
@@ -1147,7 +1183,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     if (!bonus) {
       if (tid == 0) sh.counter = 0;
       __syncthreads();
-      if (tid < n_pn && sh.n_depth[tid] == l) {
+      if (tid < n_pn && (sh.n_depth[tid] & NODE_DEPTH_MASK) == l) {
         const int n = n_begin + tid;
         const int par = sh.n_parent[tid];
         const bool cand = par >= n_begin && par < n && sh.slot_of[par - n_begin] >= 0;
@@ -1750,8 +1786,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
               a.out.out_parent[o] = node;
               a.out.out_token[o] = x;
               a.out.out_node[o] = -1;
-              a.out.out_logp_target[o] = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
-              a.out.out_logp_draft[o] = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+              const double lp_o = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
+              const double lq_o = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+              a.out.out_logp_target[o] = lp_o;
+              a.out.out_logp_draft[o] = lq_o;
+              emit_next(out_base + j, node, x, lp_o, lq_o);
             }
           }
         }
@@ -1928,8 +1967,11 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           a.out.out_parent[o] = node;
           a.out.out_token[o] = x;
           a.out.out_node[o] = -1;
-          a.out.out_logp_target[o] = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
-          a.out.out_logp_draft[o] = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+          const double lp_o = sh.cum_p[i] + ((double)a.zp[(long long)node * V + x] - sh.lse_p[i]);
+          const double lq_o = sh.cum_q[i] + ((double)a.zq[(long long)node * V + x] - sh.lse_q[i]);
+          a.out.out_logp_target[o] = lp_o;
+          a.out.out_logp_draft[o] = lq_o;
+          emit_next(out_base + j, node, x, lp_o, lq_o);
         };
         if (in_lds) {
           if (holder) {
@@ -2313,6 +2355,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         a.out.out_node[o] = n;
         a.out.out_logp_target[o] = sh.A_cum_p[tid];
         a.out.out_logp_draft[o] = sh.A_cum_q[tid];
+        emit_next(tid, sh.n_parent[n - n_begin], sh.n_token[n - n_begin], sh.A_cum_p[tid], sh.A_cum_q[tid]);
       }
       // p' = p'_kcur; its chain entry may still be missing if the last candidate was rejected
       int k = kcur;
@@ -2343,6 +2386,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     a.out.l_last[prompt] = l_last;
     a.out.n_out[prompt] = n_out;
     a.out.near_tie_count[prompt] = near_tie;
+    if (a.nx_on) a.nx.n_next[prompt] = n_out;
   }
 }
 
@@ -2539,7 +2583,7 @@ SideStream* side_stream_of_current_device(bool may_create) {
   SideStream& s = table[dev];
   if (!s.tried && may_create) {
     s.tried = true;
-    const unsigned ev = hipEventDisableTiming;
+    const unsigned ev = hipEventDisableTiming | (dsbd_knobs().event_fence ? 0u : (unsigned)hipEventDisableSystemFence);
     s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
            hipEventCreateWithFlags(&s.fork, ev) == hipSuccess && hipEventCreateWithFlags(&s.join, ev) == hipSuccess &&
            hipEventCreateWithFlags(&s.layers_done, ev) == hipSuccess;
@@ -2563,11 +2607,18 @@ extern "C" size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* f, int32
 namespace {
 // may_create_side: the second stream may be created by this call (an ordinary call); false for the entry point that
 // must not allocate, which uses the second stream only if an earlier call or dsbd_init() has made it.
+// next: the next-beam plan to be written along with the output beams (nullptr: none).  With keep_one == 0 the layer
+// kernel writes it itself; the single surviving beam of keep_one != 0 needs all of a prompt's output beams side by
+// side, which sit in several workgroups' hands: there the selection kernel is launched behind the verification.
 int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p, const dsbd_verify_out* out,
-                    void* workspace, size_t workspace_bytes, int32_t* fault, void* stream_, bool may_create_side) {
+                    void* workspace, size_t workspace_bytes, int32_t* fault, void* stream_, bool may_create_side,
+                    const dsbd_next_beams* next = nullptr, int keep_one = 0) {
   if (!in || !out || !fault) return DSBD_ERR_INVALID;
   int32_t rc = check_verify(f, in->V, p);
   if (rc != DSBD_OK) return rc;
+  if (next && (!next->n_next || !next->src_tree || !next->src_out || !next->path_len || !next->path || !next->token ||
+               !next->logp_target || !next->logp_draft))
+    return DSBD_ERR_INVALID;
   if (f->n_nodes == 0 || f->n_trees == 0 || f->n_prompts == 0) return DSBD_OK;
   if (!f->tree_prompt || !f->tree_off || !f->parent || !f->token) return DSBD_ERR_INVALID;
   if (!in->logits_target || !in->logits_draft || !in->beam_logp_target || !in->beam_logp_draft || !in->u_accept ||
@@ -2671,6 +2722,8 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   la.G = pl.G; la.I_cap = pl.I_cap; la.sl = pl.sl; la.lds_elems = pl.lds_elems; la.fault = fault;
   la.lds_slice = pl.lds_elems;
   la.alias = alias ? 1 : 0;
+  la.nx_on = (next && !keep_one) ? 1 : 0;
+  if (la.nx_on) la.nx = *next; else la.nx = dsbd_next_beams{};
   if (knobs.verify_lds_slice >= 0 && knobs.verify_lds_slice < la.lds_slice) la.lds_slice = knobs.verify_lds_slice;   // tuning / test knob
   la.top_k = p->top_k; la.top_p = (p->top_p > 0.0f && p->top_p < 1.0f) ? p->top_p : 1.0f;
   // Ordinary launches: a launch was sized to fit the device at once, and every wait inside the kernel is bounded.
@@ -2711,7 +2764,9 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
     const hipError_t le2 = hipGetLastError();
     if (le == hipSuccess) le = le2;
   }
-  return le == hipSuccess ? DSBD_OK : DSBD_ERR_HIP;
+  if (le != hipSuccess) return DSBD_ERR_HIP;
+  if (next && keep_one) return dsbd_select_beams(f, out, p->W_cap, keep_one, next, fault, stream_);
+  return DSBD_OK;
 }
 }  // namespace
 
@@ -2719,6 +2774,13 @@ extern "C" int32_t dsbd_verify_forest(const dsbd_forest* f, const dsbd_verify_in
                                       const dsbd_verify_out* out, void* workspace, size_t workspace_bytes,
                                       int32_t* fault, void* stream_) {
   return verify_impl(f, in, p, out, workspace, workspace_bytes, fault, stream_, true);
+}
+
+extern "C" int32_t dsbd_verify_forest_select(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_params* p,
+                                             const dsbd_verify_out* out, int32_t keep_one, const dsbd_next_beams* next,
+                                             void* workspace, size_t workspace_bytes, int32_t* fault, void* stream_) {
+  if (!next) return DSBD_ERR_INVALID;
+  return verify_impl(f, in, p, out, workspace, workspace_bytes, fault, stream_, true, next, keep_one != 0);
 }
 
 // ---- the same call for callers that cannot allocate device memory (code under HIP graph capture, serving loops,

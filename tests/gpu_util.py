@@ -90,3 +90,22 @@ def compare_select(nx, ref):
                       ("path", "path"), ("token", "token")):
         assert np.array_equal(g(getattr(nx, name)), ref[key]), name
     assert np.array_equal(g(nx.logp_target), ref["logp_p"]) and np.array_equal(g(nx.logp_draft), ref["logp_q"])
+
+
+def check_verify_select(d, w, ref, **verify_args):
+    """The one-call form (dsbd_verify_forest_select) against the oracle: the verification outputs as compare_verify
+    holds them, and the next-beam plan against the oracle's selection from the oracle's own verification, for both
+    values of keep_one.  The plan is compared for prompts without a near tie (a near tie may change the output beams)."""
+    g = lambda x: x.cpu().numpy()
+    for keep_one in (False, True):
+        res, nx = d.verify_select(keep_one=keep_one, **verify_args)
+        torch.cuda.synchronize()
+        compare_verify(res, ref, w)
+        sref = o_select.select_beams(w.tree_off, w.parent, ref["n_out"], ref["out_parent"], ref["out_token"],
+                                     ref["out_logp_p"], ref["out_logp_q"], w.max_depth + 1, keep_one=keep_one)
+        clean = ref["near_tie"] == 0
+        for name in ("n_next", "src_tree", "src_out", "path_len", "path", "token"):
+            got, want = g(getattr(nx, name))[clean], sref[name][clean]
+            assert np.array_equal(got, want), (name, "keep_one", keep_one, got[got != want][:8], want[got != want][:8])
+        assert np.max(np.abs(g(nx.logp_target)[clean] - sref["logp_p"][clean]), initial=0.0) <= 1e-9
+        assert np.max(np.abs(g(nx.logp_draft)[clean] - sref["logp_q"][clean]), initial=0.0) <= 1e-9

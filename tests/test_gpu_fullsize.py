@@ -102,6 +102,7 @@ def test_c5_verify_and_select_whole_forest(c5, t):
         g = lambda x: x.cpu().numpy()
         for name in ("n_next", "src_tree", "src_out", "path_len", "path", "token"):
             assert np.array_equal(g(getattr(nx, name)), sref[name]), name
+    gu.check_verify_select(d, w, ref, t=t)     # the one-call form, which the benchmark's step uses
 
 
 @pytest.mark.parametrize("top_k,top_p,t", [(32, 0.9, -1.0), (32, 0.9, 0.6), (8, 1.0, -1.0)])
@@ -120,6 +121,7 @@ def test_c5_verify_with_warping_whole_forest(c5, top_k, top_p, t):
     torch.cuda.synchronize()
     ref = gu.oracle_verify(w2, t=t, top_k=top_k, top_p=top_p)
     near = gu.compare_verify(res, ref, w2)
+    gu.check_verify_select(d2, w2, ref, t=t, top_k=top_k, top_p=top_p)
     st = ref["node_status"]
     print("c5 warped top_k=%d top_p=%g t=%g: l_last %s accepted %d rejected %d near ties %d"
           % (top_k, top_p, t, ref["l_last"].tolist(), int((st == 1).sum()), int((st == 2).sum()), near), flush=True)
@@ -136,6 +138,7 @@ def test_c4_verify_whole_batch(t):
     ref = gu.oracle_verify(w, t=t)
     near = gu.compare_verify(res, ref, w)
     print("c4 verify t=%g: %d prompts, %d nodes, l_last %s near ties %d" % (t, w.n_prompts, w.n_nodes, ref["l_last"].tolist(), near), flush=True)
+    gu.check_verify_select(d, w, ref, t=t)
 
 
 def test_c5_commit_kv_whole_caches(c5):

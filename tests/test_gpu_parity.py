@@ -260,6 +260,7 @@ def test_verify_forest_matches_oracle(cfg, kw, W_L, t):
     ref = gu.oracle_verify(w, W_L=W_L, t=t)
     near = gu.compare_verify(res, ref, w)
     print("l_last", ref["l_last"].tolist(), "widths", ref["layer_width"].tolist(), "near ties", near, flush=True)
+    gu.check_verify_select(d, w, ref, W_L=W_L, t=t)        # the same through the one-call form
     import paper_2409_16560_amd as dsbd
     from oracle import select as o_select
     for keep_one in (False, True):
@@ -288,6 +289,7 @@ def test_verify_accept_patterns_over_seeds(seed, noise):
         torch.cuda.synchronize()
         ref = gu.oracle_verify(w, t=t)
         gu.compare_verify(res, ref, w)
+        gu.check_verify_select(d, w, ref, t=t)
 
 
 @pytest.mark.parametrize("sweep", [0, 1, 2])
@@ -316,6 +318,7 @@ def test_verify_random_forests_and_parameters(sweep):
         ref = gu.oracle_verify(w, W_L=W_L, t=t, top_k=top_k, top_p=top_p)
         try:
             gu.compare_verify(res, ref, w)
+            gu.check_verify_select(d, w, ref, W_L=W_L, t=t, top_k=top_k, top_p=top_p)
         except AssertionError as e:
             raise AssertionError("sweep %d case %d (%s, t=%g, W_L=%d, top_k=%d, top_p=%g): %s"
                                  % (sweep, case, spec, t, W_L, top_k, top_p, e))
@@ -772,3 +775,4 @@ def test_verify_more_prompts_than_workgroups_fit_the_device(n_prompts, t):
     ref = gu.oracle_verify(w, t=t)
     near = gu.compare_verify(res, ref, w)
     print("prompts", n_prompts, "trees", w.n_trees, "nodes", w.n_nodes, "near ties", near, flush=True)
+    gu.check_verify_select(d, w, ref, t=t)

@@ -13,7 +13,8 @@ against the HBM peak (algorithmic bytes of the step / step time), because no sin
 attention kernel and the vocabulary statistics stream from HBM, the layer kernel is bound by the latency of its
 dependent reductions and moves next to nothing.  `roofline_kernels` lists every kernel of the step with its own
 HIP-event duration (the library's timing hook on the stream the kernel is launched on) and, where it streams, its own
-fraction.  `other_configs` holds the step on c4 (fixed and dynamic width), c3 and c2; `stream_read_ceiling` a plain
+fraction.  `other_configs` holds the step on c5 with the dynamic width (t = 0.9, 0.7) and with an independent draft
+model, on c4 (fixed and dynamic width), c3 and c2; `stream_read_ceiling` a plain
 streaming read on the same box; `cpu_baseline` the CPU oracle on the same workload.
 """
 import argparse
@@ -370,13 +371,20 @@ def main():
         res.setdefault("next_rows", {})["draft_layer"] = dr
     if not args.no_other_configs and args.config == "c5" and args.shared_len is None:
         # the other configurations (parity-test cases; here only their step times, apart from the headline)
+        # first the benchmark's own configuration with the dynamic width (Section 3.2; t = 0.9 and 0.7) ...
+        other = [case.step_summary(60, t=t_) for t_ in (0.9, 0.7)]
+        case.check_faults()
         del case
         torch.cuda.empty_cache()
-        other = []
-        for cfg, copies, ts_ in (("c4", 2, (-1.0, 0.9)), ("c3", 3, (-1.0,)), ("c2", 3, (-1.0,))):
-            c = Case(dsbd, torch, cfg, copies, ts_[0])
+        # ... and with a draft model independent of the target (near-total rejection: the residual path), fixed width
+        for cfg, copies, ts_, kw_ in (("c5", 3, (-1.0,), {"draft": "indep"}), ("c4", 2, (-1.0, 0.9), {}),
+                                      ("c3", 3, (-1.0,), {}), ("c2", 3, (-1.0,), {})):
+            c = Case(dsbd, torch, cfg, copies, ts_[0], **kw_)
             for t_ in ts_:
-                other.append(c.step_summary(60, t=t_))
+                e = c.step_summary(60, t=t_)
+                if kw_:
+                    e["workload"] += ", draft logits independent of the target"
+                other.append(e)
             c.check_faults()
             del c
             torch.cuda.empty_cache()

@@ -2,7 +2,8 @@
 
 One iteration: gamma calls of dsbd_draft_layer (the small model's beam sampling), dsbd_build_forest, one pass of
 both models over the forest's nodes (a callback: `models.logits(seqs)`, `models.qkv(seqs)` for token sequences;
-this package holds no model), dsbd_forest_attention, dsbd_verify_forest, dsbd_select_beams, dsbd_commit_kv.
+this package holds no model), dsbd_forest_attention, dsbd_verify_forest_select (verification and selection in one
+call), dsbd_commit_kv.
 The loop itself only moves data between the calls and keeps the token sequences on the host for the callback.
 
 Uniforms come from `uniforms(n, stream) -> float32[n]`; the streams of iteration `it` are 4*it (accept tests),
@@ -95,10 +96,9 @@ class DecodeLoop:
         u_acc = self._dev(self.uniforms(N, 4 * it))
         u_res = self._dev(self.uniforms(P * (gamma + 2), 4 * it + 1))
         u_fill = self._dev(self.uniforms(P * (gamma + 2) * self.W_cap, 4 * it + 2))
-        ver = B.dsbd_verify_forest(forest, self._dev(zp), self._dev(zq), self.cum_p, self.cum_q, u_acc, u_res, u_fill,
-                                   W_L=self.W_L, W_min=self.W_min, W_cap=self.W_cap, t=self.t, top_k=self.top_k,
-                                   top_p=self.top_p)
-        nxt = B.dsbd_select_beams(forest, ver, keep_one=self.keep_one)
+        ver, nxt = B.dsbd_verify_forest_select(forest, self._dev(zp), self._dev(zq), self.cum_p, self.cum_q, u_acc,
+                                               u_res, u_fill, W_L=self.W_L, W_min=self.W_min, W_cap=self.W_cap,
+                                               t=self.t, keep_one=self.keep_one, top_k=self.top_k, top_p=self.top_p)
         rec.update(verify=ver, next=nxt)
         # ---- the next input beams
         n_next = nxt.n_next.cpu().numpy()

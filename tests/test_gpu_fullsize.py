@@ -84,7 +84,7 @@ def test_c4_attention_whole_batch():
     print("c4 attention, all rows (%d nodes, %d trees): max abs err (out, lse):" % (w.n_nodes, w.n_trees), err, flush=True)
 
 
-@pytest.mark.parametrize("t", [-1.0, 0.9])
+@pytest.mark.parametrize("t", [-1.0, 0.9, 0.7])
 def test_c5_verify_and_select_whole_forest(c5, t):
     import gpu_util as gu
     import paper_2409_16560_amd as dsbd
@@ -103,6 +103,23 @@ def test_c5_verify_and_select_whole_forest(c5, t):
         for name in ("n_next", "src_tree", "src_out", "path_len", "path", "token"):
             assert np.array_equal(g(getattr(nx, name)), sref[name]), name
     gu.check_verify_select(d, w, ref, t=t)     # the one-call form, which the benchmark's step uses
+
+
+@pytest.mark.parametrize("t", [-1.0, 0.9])
+def test_c5_verify_with_an_independent_draft_model(t):
+    """The benchmark's forest at the full vocabulary with draft logits drawn independently of the target's: nearly
+    every draft is rejected, the layers fall short early and the residual chain and its draw carry the result."""
+    import gpu_util as gu
+    w = make_workload("c5", L=1, Hq=1, Hkv=1, D=64, draft="indep")
+    d = gu.DeviceWorkload(w)
+    res = d.verify(t=t)
+    torch.cuda.synchronize()
+    ref = gu.oracle_verify(w, t=t)
+    near = gu.compare_verify(res, ref, w)
+    st = ref["node_status"]
+    print("c5 independent draft t=%g: l_last %s widths %s accepted %d rejected %d near ties %d"
+          % (t, ref["l_last"].tolist(), ref["layer_width"].tolist(), int((st == 1).sum()), int((st == 2).sum()), near), flush=True)
+    gu.check_verify_select(d, w, ref, t=t)
 
 
 @pytest.mark.parametrize("top_k,top_p,t", [(32, 0.9, -1.0), (32, 0.9, 0.6), (8, 1.0, -1.0)])

@@ -44,6 +44,7 @@ struct DsbdKnobs {
   int verify_mute_wg;          // DSBD_VERIFY_TEST_MUTE_WG: test hook, this workgroup withholds its first post; -1 = none
   int verify_lds_slice;        // DSBD_VERIFY_LDS_SLICE: largest joint slice kept in the LDS; -1 = the plan's choice
   int verify_overlap;          // DSBD_VERIFY_OVERLAP: 0 = statistics pass and layer kernel one after the other
+  int warp_fast;               // DSBD_WARP_FAST: 0 = the warping selection always takes its tree form
   int event_fence;             // DSBD_EVENT_FENCE: 1 = the library's cross-stream events keep HIP's system-scope fence; 0 = they order
                                // device work only (no cache write-back for the host's sake at every fork and join)
   int stats_side_lds;          // DSBD_STATS_SIDE_LDS: LDS bytes claimed by a workgroup of the statistics pass when it runs beside

@@ -30,6 +30,7 @@ void load(DsbdKnobs& k) {
   k.verify_mute_wg = env_int("DSBD_VERIFY_TEST_MUTE_WG", -1);
   k.verify_lds_slice = env_int("DSBD_VERIFY_LDS_SLICE", -1);
   k.verify_overlap = env_int("DSBD_VERIFY_OVERLAP", 1);
+  k.warp_fast = env_int("DSBD_WARP_FAST", 1);
   k.event_fence = env_int("DSBD_EVENT_FENCE", 0);
   k.stats_side_lds = env_int("DSBD_STATS_SIDE_LDS", -1);
   if (k.stats_side_lds > 65536) k.stats_side_lds = -1;

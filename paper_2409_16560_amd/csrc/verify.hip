@@ -226,6 +226,8 @@ struct SlotLayout {
   int b, b_w;            // warping: every workgroup's candidate list, b_w slots each
   int c;                 // warping: the groups' merged lists (b_w slots each)
   int d;                 // warping: the final entries, posted by the prompt's first workgroup
+  int wa;                // warping, one-level form: every workgroup's largest entries (a line each: p_beam's, q_beam's)
+  int wb;                // ... and its candidates at or above the bounds (b_w slots each: two counts, then value | index)
   int acc;               // accumulator words of the one-hop sums: 2 banks x NACC lines
   int acc0;              // their values at launch, posted by the prompt's first workgroup: 2 x NACC slots
   int prompt_stride;
@@ -263,6 +265,7 @@ struct LayersArgs {
   int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
                          // bounded waits give up and the error path can be exercised without a hang
   int32_t* fault;
+  int warp_fast;         // warping: the one-level selection (bounds from the workgroups' largest entries) where it applies
   dsbd_next_beams nx;    // next-beam plan written along with the output beams (fused selection) ...
   int nx_on;             // ... when this is set
 };
@@ -670,8 +673,14 @@ __host__ __device__ inline SliceCut slice_cut(int nI, int V, int G) {
   return c;
 }
 
+// At most VL_MAX_VGPRS vector registers, so that a wave of the statistics pass (32 registers) fits on every SIMD beside
+// this kernel's two: 2 x 240 + 32 = 512.  (The attribute counts in halves of the unified register file of this
+// target: the compiler doubles the number it is given.  Without it the allocator takes whatever two waves per SIMD
+// leave it, up to 256, whether it needs them or not.)
+#define VL_MAX_VGPRS 240
 template <bool WARP, int NC>
-__global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
+__global__ __launch_bounds__(VL_BLOCK) __attribute__((amdgpu_num_vgpr(VL_MAX_VGPRS / 2)))
+void verify_layers_kernel(LayersArgs a) {
   __shared__ LayerShared<NC> sh;
   extern __shared__ __attribute__((aligned(16))) double dyn_lds[];
   const int prompt = a.prompt0 + blockIdx.x / a.G;
@@ -1218,6 +1227,10 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
     // column sit in R neighbouring lanes of one wave and are put on the column's maximum and added up by lane
     // exchanges that pair the lanes symmetrically (no table in the LDS, no barrier in between): every lane of a
     // column, in every workgroup of the prompt, gets the same bits.
+    bool warp_pieces = false;               // warping: the table of the workgroups' largest entries is filled
+    if constexpr (WARP) {
+      if (tid < 256) { sh.gpart[tid] = -1.0; sh.ptot[tid] = -1.0; }     // (workgroups without a piece keep this)
+    }
     {
       const int ncols = 2 * nI;
       int cshift = 0;
@@ -1273,6 +1286,22 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
       // (entries of workgroups without a piece are never written: the reader knows which those are)
       const bool single_piece = !WARP && cut.rows_per_wg == 0 && geo_pieces <= R;
       if (tid == 0) sh.ptot_ok = single_piece ? 1 : 0;
+      if constexpr (WARP) {
+        // Every workgroup's largest entry of either joint follows from what the gathering threads hold (a piece's
+        // largest exponential is 1 against the piece's own maximum): p_beam's largest entry in the piece of row i is
+        // (beam weight / row sum) exp(piece maximum - row maximum).  Every workgroup evaluates this alike, bit for
+        // bit, for every workgroup of the prompt (one piece per gathering thread; other cuts leave the table alone
+        // and the selection below takes its tree form).
+        // (worth it with many more workgroups than entries to keep: the K-th largest of a few largest entries is a
+        // poor bound.  Measured: 16 workgroups per prompt, K = 10: 247 us against the tree form's 202 us; 64
+        // workgroups, K = 32: 177 against 167 us; 64 and K = 10: 115 against 131 us; 256 and K = 10: 146 against 176 us.)
+        warp_pieces = cut.rows_per_wg == 0 && geo_pieces <= R && nI * geo_pieces >= 4 * a.top_k;
+        if (warp_pieces && c < ncols && r < geo_pieces && accM > -INFINITY) {
+          const int i = c >> 1;
+          const double largest = ((c & 1) ? sh.bw_q[i] : sh.bw_p[i]) / tot * exp_nonpos(accM - cm, sh.exp_tab);
+          ((c & 1) ? sh.ptot : sh.gpart)[i * cut.wg_per_row + r] = largest;
+        }
+      }
       if (single_piece && c < ncols && (c & 1) == 0 && r < geo_pieces) {
         const int i = c >> 1;
         sh.ptot[i * cut.wg_per_row + r] = (sh.bw_p[i] / tot) * (accS * exp_nonpos(accM - cm, sh.exp_tab));
@@ -1364,34 +1393,8 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         rank_cands(cvp, cip, min(sh.W_cnt[0], WARP_CAND), lv, li);
         rank_cands(cvq, ciq, min(sh.W_cnt[1], WARP_CAND), lv + K, li + K);
       };
-      // (1) a lower bound of the slice's K-th entry: the K-th largest of the maxima of 64 groups of eight threads
-      // (K of the slice's entries, from different groups, are at or above it)
-      {
-        double gp = tmax_p, gq = tmax_q;
-#pragma unroll
-        for (int off = 1; off <= 4; off <<= 1) { gp = fmax(gp, __shfl_xor(gp, off)); gq = fmax(gq, __shfl_xor(gq, off)); }
-        if ((lane & 7) == 0) { sh.tsum[wave * 8 + (lane >> 3)] = gp; sh.tsum[64 + wave * 8 + (lane >> 3)] = gq; }
-        if (tid < 2) sh.W_cnt[tid] = 0;
-      }
-      __syncthreads();
-      stamp(57);
-      {  // four threads count, for one of the 2 x 64 maxima, those ahead of it; the one with K - 1 ahead is the bound
-        const int m = tid >> 8, i = (tid >> 2) & 63, part = tid & 3;
-        const double v = sh.tsum[m * 64 + i];
-        int rank = 0;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int c = part + 4 * j;
-          const double o = sh.tsum[m * 64 + c];
-          rank += (o > v || (o == v && c < i)) ? 1 : 0;
-        }
-        rank += __shfl_xor(rank, 1);
-        rank += __shfl_xor(rank, 2);
-        if (part == 0 && rank == K - 1) sh.W_tau[m] = v;    // -1 when fewer than K groups hold anything: everything passes
-      }
-      __syncthreads();
-      stamp(58);
-      {  // (2) everything at or above the bound is a candidate
+      // everything at or above the bounds W_tau is a candidate (counts in W_cnt; the arrays hold the first WARP_CAND)
+      auto collect_at_or_above = [&]() {
         const double tp = sh.W_tau[0], tq = sh.W_tau[1];
         auto offer = [&](long long j, double vp, double vq) {
           if (vp >= tp) {
@@ -1414,34 +1417,196 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           }
           for (; j < r1; j += VL_BLOCK) offer(j, P[j], Q[j]);
         });
-      }
-      __syncthreads();
-      stamp(60);
-      if (sh.W_cnt[0] > WARP_CAND || sh.W_cnt[1] > WARP_CAND) {
-        // too many entries at or above the bound (many equal values, or a vocabulary of a few hundred tokens):
-        // every wave extracts the K first of its lanes' elements a rank at a time; those become the candidates
-        __syncthreads();                     // everybody has read the counts
-        double pv_prev = INFINITY, qv_prev = INFINITY;
-        int pi_prev = -1, qi_prev = -1;
-        for (int r = 0; r < K; ++r) {
-          double bp = -1.0, bq = -1.0;
-          int ip = INT_MAX, iq = INT_MAX;
-          for (long long j = tid; j < len; j += VL_BLOCK) {
-            const int fi = (int)(e_lo + j);
-            const double vp = ldp(j), vq = ldq(j);
-            if (cand_before(pv_prev, pi_prev, vp, fi) && cand_before(vp, fi, bp, ip)) { bp = vp; ip = fi; }
-            if (cand_before(qv_prev, qi_prev, vq, fi) && cand_before(vq, fi, bq, iq)) { bq = vq; iq = fi; }
+      };
+      // ===== One-level selection (at least K workgroups per prompt).  The K-th largest of the workgroups' largest
+      // entries is a lower bound of the joint's K-th entry (K entries of K different workgroups are at or above it),
+      // and with many more workgroups than K hardly anything else is: every workgroup posts its largest entries,
+      // collects everybody's, takes the bound, posts what its slice holds at or above it (a handful of entries in
+      // all), collects everybody's candidates and ranks them itself.  Two exchanges that everybody posts and at
+      // once collects from all, no tree, and every workgroup ends up with the lists, so the result needs no
+      // broadcast either.  If the candidates do not fit (a workgroup's share of the slots, WARP_CAND in all: many
+      // equal values, or the large entries crowded into a few slices), every workgroup sees that in the same
+      // counts and the tree form below takes over.  A region of slots per exchange: a workgroup posts the next
+      // layer's largest entries only after it has collected this layer's candidates from everybody, that is after
+      // everybody has read this layer's largest entries; likewise the other way round.
+      bool fast = a.warp_fast && a.G > 1 && warp_pieces;      // uniform over the prompt's workgroups
+      bool fast_done = false;
+      lds_f64* const all_p = (lds_f64*)sh.gpart;        // [G] every workgroup's largest entry of p_beam ...
+      lds_f64* const all_q = (lds_f64*)sh.ptot;         // ... and of q_beam (-1: the workgroup holds nothing)
+      lds_f64* const stage = (lds_f64*)sh.tsum;         // [64][8] first lines of the workgroups that hold candidates
+      lds_i32* const wl = (lds_i32*)sh.A_idx;           // [64] those workgroups
+      lds_f64* const off_p = (lds_f64*)sh.A_cum_p;      // [64] where their candidates go in the joint lists ...
+      lds_f64* const off_q = (lds_f64*)sh.A_cum_q;      // ... (as doubles: small integers, exact)
+      const double slack = 1.0 - 1e-12;                 // (a workgroup's own largest entry may differ from the table's in the last bit)
+      unsigned long long tag_w = 0;
+      int nW = 0;
+      while (true) {
+        // ---- the bounds W_tau
+        if (fast) {
+          // The K-th largest of the workgroups' largest entries, or anything below it, is a lower bound of the joint's
+          // K-th entry (K entries of K different workgroups are at or above it).  One wave per model finds it;
+          // fewer than K values leave -1: everything passes, the counts below show it, and the tree form takes over.
+          tag_w = exchange_tag(a.nonce + epoch + 1);
+          epoch += 1;
+          if (tid < 2) sh.W_cnt[tid] = 0;
+          if (wave < 2) {
+            lds_f64* const arr = wave ? all_q : all_p;
+            // (as 32-bit patterns of the values rounded down to floats, which order like the values; the answer is
+            // built from the leading bit down: the largest pattern, its low 12 bits zero, that K values reach)
+            unsigned int key[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const int w = lane * 4 + k;
+              const double v = w < a.G ? arr[w] : -1.0;
+              key[k] = v > 0.0 ? (unsigned int)__float_as_int(__double2float_rd(v)) : 0u;
+            }
+            unsigned int prefix = 0;
+#pragma unroll 1
+            for (int b = 30; b >= 12; --b) {
+              const unsigned int cand = prefix | (1u << b);
+              const int cnt = __popcll(__ballot(key[0] >= cand)) + __popcll(__ballot(key[1] >= cand)) +
+                              __popcll(__ballot(key[2] >= cand)) + __popcll(__ballot(key[3] >= cand));
+              if (cnt >= K) prefix = cand;
+            }
+            const float kth = prefix ? __int_as_float((int)prefix) : -1.0f;    // fewer than K values: everything passes
+            if (lane == 0) sh.W_tau[wave] = (double)kth;
           }
-          wave_first(bp, ip);
-          wave_first(bq, iq);
-          if (lane == 0) { cvp[wave * K + r] = bp; cip[wave * K + r] = ip; cvq[wave * K + r] = bq; ciq[wave * K + r] = iq; }
-          pv_prev = bp; pi_prev = ip; qv_prev = bq; qi_prev = iq;
+          __syncthreads();
+          stamp(57);
+          // the workgroups that can hold candidates (by the table, with a little slack), in workgroup order
+          {
+            const double tp = sh.W_tau[0] * slack, tq = sh.W_tau[1] * slack;
+            const bool flagged = tid < a.G && (all_p[min(tid, 255)] >= tp || all_q[min(tid, 255)] >= tq);
+            const unsigned long long fm = __ballot(flagged);
+            if (lane == 0) sh.scan_w[wave] = (double)__popcll(fm);
+            __syncthreads();
+            int before = 0, all = 0;
+#pragma unroll
+            for (int w = 0; w < VL_WAVES; ++w) { const int cw = (int)sh.scan_w[w]; before += w < wave ? cw : 0; all += cw; }
+            const int pos = before + __popcll(fm & ((1ull << lane) - 1ull));
+            if (flagged && pos < 64) wl[pos] = tid;
+            nW = all;
+          }
+        } else {
+          // Tree form (1): a lower bound of the slice's K-th entry: the K-th largest of the maxima of 64 groups of
+          // eight threads (K of the slice's entries, from different groups, are at or above it)
+          double gp = tmax_p, gq = tmax_q;
+#pragma unroll
+          for (int off = 1; off <= 4; off <<= 1) { gp = fmax(gp, __shfl_xor(gp, off)); gq = fmax(gq, __shfl_xor(gq, off)); }
+          if ((lane & 7) == 0) { sh.tsum[wave * 8 + (lane >> 3)] = gp; sh.tsum[64 + wave * 8 + (lane >> 3)] = gq; }
+          if (tid < 2) sh.W_cnt[tid] = 0;
+          __syncthreads();
+          stamp(57);
+          // four threads count, for one of the 2 x 64 maxima, those ahead of it; the one with K - 1 ahead is the bound
+          const int m = tid >> 8, i = (tid >> 2) & 63, part = tid & 3;
+          const double v = sh.tsum[m * 64 + i];
+          int rank = 0;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const int c = part + 4 * j;
+            const double o = sh.tsum[m * 64 + c];
+            rank += (o > v || (o == v && c < i)) ? 1 : 0;
+          }
+          rank += __shfl_xor(rank, 1);
+          rank += __shfl_xor(rank, 2);
+          if (part == 0 && rank == K - 1) sh.W_tau[m] = v;    // -1 when fewer than K groups hold anything: everything passes
         }
-        if (tid < 2) sh.W_cnt[tid] = VL_WAVES * K;
+        __syncthreads();
+        stamp(58);
+        collect_at_or_above();               // (2) everything at or above the bound is a candidate
+        __syncthreads();
+        stamp(60);
+        if (fast) {
+          // ---- the candidates of the workgroups that can hold any: counts and the first three in the first line
+          // of the workgroup's slots (one round trip for nearly everything), the rest behind it
+          const int cp = sh.W_cnt[0], cq = sh.W_cnt[1];
+          const int room = (a.sl.b_w - 2) / 2;             // entries a workgroup can post
+          const bool post = all_p[g] >= sh.W_tau[0] * slack || all_q[g] >= sh.W_tau[1] * slack;
+          Slot* const mine = slots + a.sl.wb + (long long)g * a.sl.b_w;
+          const int n_posted = cp + cq <= room ? cp + cq : 0;
+          if (post && tid < max(8, 2 + 2 * n_posted)) {
+            double payload;
+            if (tid < 2) payload = (double)(tid ? cq : cp);
+            else {
+              const int e = (tid - 2) >> 1;
+              if (e >= n_posted) payload = -1.0;
+              else payload = (tid & 1) ? (double)(e < cp ? cip[e] : ciq[e - cp]) : (e < cp ? cvp[e] : cvq[e - cp]);
+            }
+            slot_post(mine + tid, payload, tag_w);
+          }
+          const int n_poll = 8 * min(nW, 64);
+          for (int t = tid; t < n_poll; t += VL_BLOCK) {
+            double v = 0.0;
+            if (!slot_wait(slots + a.sl.wb + (long long)wl[t >> 3] * a.sl.b_w + (t & 7), tag_w, v, a.sync_limit)) give_up();
+            stage[t] = v;
+          }
+          __syncthreads();                                 // (also: everybody has posted from the candidate arrays)
+          if (sh.abort) return;
+          stamp(62);
+          if (wave < 2) {                                  // where every workgroup's candidates go, a wave per model
+            const bool in = lane < min(nW, 64);
+            const double mine_c = in ? stage[lane * 8 + wave] : 0.0;
+            const bool crowded = in && stage[lane * 8] + stage[lane * 8 + 1] > (double)room;
+            const double incl = wave_inclusive_scan(mine_c);
+            if (in) (wave ? off_q : off_p)[lane] = incl - mine_c;
+            const double total = __shfl(incl, 63);
+            const bool bad_w = __ballot(crowded) != 0ull || total > (double)WARP_CAND || nW > 64;
+            if (lane == 0) { sh.W_cnt[wave] = (int)total; sh.state[wave] = bad_w ? 1 : 0; }
+          }
+          __syncthreads();
+          const bool crowded_any = (sh.state[0] | sh.state[1]) != 0;
+          if (crowded_any) {                               // the same counts in every workgroup: all take the tree form
+            __syncthreads();                               // (the flags are read; the tree form writes them again)
+            fast = false;
+            continue;
+          }
+          for (int t = tid; t < nW * 64; t += VL_BLOCK) {      // (room < 64)
+            const int j = t >> 6, e = t & 63;
+            const int cpj = (int)stage[j * 8], cqj = (int)stage[j * 8 + 1];
+            if (e >= cpj + cqj) continue;
+            double v, ix;
+            if (e < 3) { v = stage[j * 8 + 2 + 2 * e]; ix = stage[j * 8 + 3 + 2 * e]; }
+            else {
+              Slot* const at = slots + a.sl.wb + (long long)wl[j] * a.sl.b_w + 2 + 2 * e;
+              v = 0.0; ix = 0.0;
+              if (!slot_wait2(at, at + 1, tag_w, v, ix, a.sync_limit)) give_up();
+            }
+            if (e < cpj) { const int at_l = (int)off_p[j] + e; cvp[at_l] = v; cip[at_l] = (int)ix; }
+            else { const int at_l = (int)off_q[j] + e - cpj; cvq[at_l] = v; ciq[at_l] = (int)ix; }
+          }
+          __syncthreads();
+          if (sh.abort) return;
+          stamp(63);
+        } else if (sh.W_cnt[0] > WARP_CAND || sh.W_cnt[1] > WARP_CAND) {
+          // too many entries at or above the bound (many equal values, or a vocabulary of a few hundred tokens):
+          // every wave extracts the K first of its lanes' elements a rank at a time; those become the candidates
+          __syncthreads();                     // everybody has read the counts
+          double pv_prev = INFINITY, qv_prev = INFINITY;
+          int pi_prev = -1, qi_prev = -1;
+          for (int r = 0; r < K; ++r) {
+            double bp = -1.0, bq = -1.0;
+            int ip = INT_MAX, iq = INT_MAX;
+            for (long long j = tid; j < len; j += VL_BLOCK) {
+              const int fi = (int)(e_lo + j);
+              const double vp = ldp(j), vq = ldq(j);
+              if (cand_before(pv_prev, pi_prev, vp, fi) && cand_before(vp, fi, bp, ip)) { bp = vp; ip = fi; }
+              if (cand_before(qv_prev, qi_prev, vq, fi) && cand_before(vq, fi, bq, iq)) { bq = vq; iq = fi; }
+            }
+            wave_first(bp, ip);
+            wave_first(bq, iq);
+            if (lane == 0) { cvp[wave * K + r] = bp; cip[wave * K + r] = ip; cvq[wave * K + r] = bq; ciq[wave * K + r] = iq; }
+            pv_prev = bp; pi_prev = ip; qv_prev = bq; qi_prev = iq;
+          }
+          if (tid < 2) sh.W_cnt[tid] = VL_WAVES * K;
+        }
+        rank_select();                         // barrier inside, after the counts are final
+        __syncthreads();
+        stamp(61);
+        fast_done = fast;
+        break;
       }
-      rank_select();                         // barrier inside, after the counts are final
-      __syncthreads();
-      stamp(61);
+      unsigned long long tag_d = 0;
+      if (!fast_done) {
       // (3) up the tree.  A list travels as 4K words (model, rank, value | index).
       auto post_list = [&](Slot* where, unsigned long long tag) {
         if (tid < 4 * K) {
@@ -1557,7 +1722,6 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
         merge_pass(cvp, cip, cvq, ciq, (n + 3) >> 2, lv, li, lv + K, li + K);
         __syncthreads();
       };
-      unsigned long long tag_d = 0;
       if (a.G > 1) {
         const int first = g - g % WARP_GROUP;
         const int n_mem = min(WARP_GROUP, a.G - first);
@@ -1585,8 +1749,9 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           merge_lists(n_groups);
         }
       }
+      }   // (tree form)
       stamp(65);
-      if (g == 0) {
+      if (g == 0 || fast_done) {
         if (wave == 0) {
           // (4) top-p on the kept entries (rank order: the shortest leading part whose share exceeds top_p) and
           // renormalisation; lanes 0..31 carry p_beam's list, lanes 32..63 q_beam's, one rank each.  The running
@@ -1634,7 +1799,7 @@ __global__ __launch_bounds__(VL_BLOCK) void verify_layers_kernel(LayersArgs a) {
           if (lane == 0) sh.nU = __popcll(vm);
         }
         __syncthreads();
-        if (a.G > 1 && tid < 1 + 6 * K) {          // (6) ... and down again: the count, then (index, p, q) of at most 2K entries
+        if (!fast_done && a.G > 1 && tid < 1 + 6 * K) {          // (6) ... and down again: the count, then (index, p, q) of at most 2K entries
           const int u = (tid - 1) / 3, f = (tid - 1) % 3;
           double payload = 0.0;
           if (tid == 0) payload = (double)sh.nU;
@@ -2514,12 +2679,14 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
     sl.r = off; sl.r_stride = G * sl.r_w; off += layers * sl.r_stride;
     sl.s = off; sl.s_stride = G * LINE_SLOTS; off += layers * sl.s_stride;
     sl.sc = off; sl.sc_stride = SUM_GROUPS * LINE_SLOTS; off += layers * sl.sc_stride;
-    sl.b = sl.c = sl.d = off; sl.b_w = 0;
+    sl.b = sl.c = sl.d = sl.wa = sl.wb = off; sl.b_w = 0;
     if (p->top_k > 0) {
       sl.b_w = up8(4 * p->top_k);
       sl.b = off; off += G * sl.b_w;
       sl.c = off; off += (G + WARP_GROUP - 1) / WARP_GROUP * sl.b_w;
       sl.d = off; off += up8(WARP_RESULT_SLOTS);
+      sl.wa = off; off += G * LINE_SLOTS;
+      sl.wb = off; off += G * sl.b_w;
     }
     sl.acc = off; off += 2 * NACC * LINE_SLOTS;
     sl.acc0 = off; off += up8(2 * NACC);
@@ -2722,6 +2889,7 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   la.G = pl.G; la.I_cap = pl.I_cap; la.sl = pl.sl; la.lds_elems = pl.lds_elems; la.fault = fault;
   la.lds_slice = pl.lds_elems;
   la.alias = alias ? 1 : 0;
+  la.warp_fast = knobs.warp_fast ? 1 : 0;
   la.nx_on = (next && !keep_one) ? 1 : 0;
   if (la.nx_on) la.nx = *next; else la.nx = dsbd_next_beams{};
   if (knobs.verify_lds_slice >= 0 && knobs.verify_lds_slice < la.lds_slice) la.lds_slice = knobs.verify_lds_slice;   // tuning / test knob

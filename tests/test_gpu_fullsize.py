@@ -122,12 +122,15 @@ def test_c5_verify_with_an_independent_draft_model(t):
     gu.check_verify_select(d, w, ref, t=t)
 
 
-@pytest.mark.parametrize("top_k,top_p,t", [(32, 0.9, -1.0), (32, 0.9, 0.6), (8, 1.0, -1.0)])
-def test_c5_verify_with_warping_whole_forest(c5, top_k, top_p, t):
+@pytest.mark.parametrize("top_k,top_p,t,fast", [(32, 0.9, -1.0, 1), (32, 0.9, 0.6, 1), (8, 1.0, -1.0, 1),
+                                                (10, 0.8, -1.0, 1), (10, 0.8, -1.0, 0)])
+def test_c5_verify_with_warping_whole_forest(c5, top_k, top_p, t, fast, knobs):
     """Warped joints at the full vocabulary: the benchmark's forest (draft tokens from the whole row: most lie
-    outside the kept entries) and one whose draft tokens come from the rows' largest logits."""
+    outside the kept entries) and one whose draft tokens come from the rows' largest logits.  top_k 10 / top_p 0.8 is
+    the paper's setting and the one bench.py times; fast = 0 runs it through the tree form of the selection."""
     import gpu_util as gu
     w, d = c5
+    knobs.set("DSBD_WARP_FAST", fast)
     res = d.verify(t=t, top_k=top_k, top_p=top_p)
     torch.cuda.synchronize()
     ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)

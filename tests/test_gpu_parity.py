@@ -369,12 +369,38 @@ def test_verify_with_warping_over_seeds(seed):
         gu.compare_verify(res, ref, w)
 
 
+@pytest.mark.parametrize("fast", [1, 0])
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("seed", [31, 32])
+def test_warping_selection_in_one_level_and_by_the_tree(seed, G, fast, knobs):
+    """The two forms of the top-k selection on the same inputs.  With many workgroups per prompt (forced here on a
+    mid-size vocabulary: 8 or 16 pieces per row) the bound comes from the table of the workgroups' largest entries
+    and the candidates travel in one exchange; DSBD_WARP_FAST=0 keeps the tree of merges.  top_k 16 on 64 workgroups
+    has just the 4 x top_k workgroups the one-level form asks for, top_k 24 has not and takes the tree either way."""
+    gu = _gu()
+    knobs.set("DSBD_VERIFY_G", G)
+    knobs.set("DSBD_WARP_FAST", fast)
+    w = make_workload("c5", L=1, Hq=1, Hkv=1, D=64, V=9000, seed=seed, noise_std=0.8, draft_top_k=3)
+    d = gu.DeviceWorkload(w)
+    for top_k, top_p, t in ((3, 1.0, -1.0), (8, 0.7, 0.6), (16, 0.9, -1.0), (24, 0.8, 0.3), (10, 0.8, -1.0)):
+        print("seed", seed, "G", G, "fast", fast, "top_k", top_k, "top_p", top_p, "t", t, flush=True)
+        res = d.verify(t=t, top_k=top_k, top_p=top_p)
+        torch.cuda.synchronize()
+        ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+        gu.compare_verify(res, ref, w)
+
+
+@pytest.mark.parametrize("G", [0, 64])
 @pytest.mark.parametrize("cfg,kw", [("c3", dict(V=5000)), ("c2", dict(V=700)), ("c4", dict(V=3000, n_prompts=3))])
-def test_warping_with_many_equal_entries(cfg, kw):
+def test_warping_with_many_equal_entries(cfg, kw, G, knobs):
     """Rows of equal logits: thousands of joint entries tie, the order of equal values (lower flat index first)
-    decides which are kept, and the selection has to leave its fast path (more candidates than it can hold)."""
+    decides which are kept, and the selection has to leave its fast path (more candidates than it can hold).  With 64
+    workgroups forced the one-level form is tried first: the candidates do not fit the workgroups' slots and all fall
+    back to the tree."""
     import dataclasses
     gu = _gu()
+    if G and cfg != "c4":
+        knobs.set("DSBD_VERIFY_G", G)
     w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, **kw)
     zp, zq = np.zeros_like(w.logits_p), np.zeros_like(w.logits_q)
     zp[1::3] = np.round(w.logits_p[1::3])            # some rows with a few distinct levels instead

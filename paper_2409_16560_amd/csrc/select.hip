@@ -115,4 +115,4 @@ extern "C" int32_t dsbd_select_beams(const dsbd_forest* f, const dsbd_verify_out
   return DSBD_OK;
 }
 
-extern "C" const char* dsbd_version(void) { return "dsbd 0.5 (gfx950)"; }
+extern "C" const char* dsbd_version(void) { return "dsbd 0.6 (gfx950)"; }

@@ -338,7 +338,7 @@ def main():
     if not args.no_warp:
         # the same verification with the warping operation on the joints (reported apart from the headline)
         k, p_ = args.warp_top_k, args.warp_top_p
-        wws = torch.empty(dsbd.dsbd_verify_forest_workspace_bytes(case.sets[0].forest, w.V, 0, 1, w.W_cap, args.t, k, p_),
+        wws = torch.empty(dsbd.dsbd_verify_forest_workspace_bytes(case.sets[0].forest, w.V, 0, 1, w.W_cap, 0.9, k, p_),
                           dtype=torch.uint8, device="cuda")
         call = lambda i: case.verify(i, workspace=wws, top_k=k, top_p=p_)
         reps = 20
@@ -350,9 +350,13 @@ def main():
         lk = dsbd.dsbd_timing_collect(reps)
         dsbd.dsbd_timing_enable(0, 0)
         case.check_faults()
+        # ... and with the dynamic width on top (t = 0.9): the setting of the paper's experiments (warped joints, Section 3.2's width)
+        dts = case.event_times(lambda i: case.verify(i, 0.9, workspace=wws, top_k=k, top_p=p_), reps)
+        case.check_faults()
         res.setdefault("next_rows", {})["warped_verify"] = {
             "top_k": k, "top_p": p_, "verify_ms": cts[len(cts) // 2], "verify_layers_kernel_ms": sum(lk) / max(1, len(lk)),
-            "plain_verify_ms": br["verify_ms"], "note": "dsbd_verify_forest with top_k / top_p set; not part of value"}
+            "plain_verify_ms": br["verify_ms"], "warped_dynamic_t0.9_verify_ms": dts[len(dts) // 2],
+            "note": "dsbd_verify_forest with top_k / top_p set; not part of value"}
     if not args.no_draft:
         # one beam-sampling step of the small model at the benchmark's shape: 16 beams in, 16 draws out (per prompt)
         W_S = 16

@@ -123,7 +123,7 @@ def test_c5_verify_with_an_independent_draft_model(t):
 
 
 @pytest.mark.parametrize("top_k,top_p,t,fast", [(32, 0.9, -1.0, 1), (32, 0.9, 0.6, 1), (8, 1.0, -1.0, 1),
-                                                (10, 0.8, -1.0, 1), (10, 0.8, -1.0, 0)])
+                                                (10, 0.8, -1.0, 1), (10, 0.8, -1.0, 0), (10, 0.8, 0.9, 1)])
 def test_c5_verify_with_warping_whole_forest(c5, top_k, top_p, t, fast, knobs):
     """Warped joints at the full vocabulary: the benchmark's forest (draft tokens from the whole row: most lie
     outside the kept entries) and one whose draft tokens come from the rows' largest logits.  top_k 10 / top_p 0.8 is

@@ -226,8 +226,8 @@ struct SlotLayout {
   int b, b_w;            // warping: every workgroup's candidate list, b_w slots each
   int c;                 // warping: the groups' merged lists (b_w slots each)
   int d;                 // warping: the final entries, posted by the prompt's first workgroup
-  int wa;                // warping, one-level form: every workgroup's largest entries (a line each: p_beam's, q_beam's)
-  int wb;                // ... and its candidates at or above the bounds (b_w slots each: two counts, then value | index)
+  int wb, wb_stride;     // warping, one-level form: the workgroups' candidates of layer l at wb + (l - 1) * wb_stride, b_w
+                         // slots per workgroup (two counts, then value | index)
   int acc;               // accumulator words of the one-hop sums: 2 banks x NACC lines
   int acc0;              // their values at launch, posted by the prompt's first workgroup: 2 x NACC slots
   int prompt_stride;
@@ -1418,17 +1418,17 @@ void verify_layers_kernel(LayersArgs a) {
           for (; j < r1; j += VL_BLOCK) offer(j, P[j], Q[j]);
         });
       };
-      // ===== One-level selection (at least K workgroups per prompt).  The K-th largest of the workgroups' largest
-      // entries is a lower bound of the joint's K-th entry (K entries of K different workgroups are at or above it),
-      // and with many more workgroups than K hardly anything else is: every workgroup posts its largest entries,
-      // collects everybody's, takes the bound, posts what its slice holds at or above it (a handful of entries in
-      // all), collects everybody's candidates and ranks them itself.  Two exchanges that everybody posts and at
-      // once collects from all, no tree, and every workgroup ends up with the lists, so the result needs no
-      // broadcast either.  If the candidates do not fit (a workgroup's share of the slots, WARP_CAND in all: many
-      // equal values, or the large entries crowded into a few slices), every workgroup sees that in the same
-      // counts and the tree form below takes over.  A region of slots per exchange: a workgroup posts the next
-      // layer's largest entries only after it has collected this layer's candidates from everybody, that is after
-      // everybody has read this layer's largest entries; likewise the other way round.
+      // ===== One-level selection (many more workgroups per prompt than entries to keep).  A lower bound of the joint's
+      // K-th entry comes from the table of every workgroup's largest entry, which every workgroup holds without an
+      // exchange (filled where the row sums are gathered); one pass collects what the slice holds at or above it (a
+      // handful of entries per prompt); the workgroups that can hold candidates post them, everybody collects and
+      // ranks them itself: one exchange, no tree, and every workgroup ends up with the lists, so the result needs no
+      // broadcast either.  If the candidates do not fit (a workgroup's share of the slots, 64 posting workgroups,
+      // WARP_CAND entries in all: many equal values, or the large entries crowded into a few slices), every workgroup
+      // sees that in the same counts and the tree form below takes over.  The candidates' slots are a region per
+      // layer, written once per launch: only the workgroups that post are waited for, so a workgroup without
+      // candidates (and, in a later layer, without a piece of a row) may still be reading a layer's lines when the
+      // others have moved on.
       bool fast = a.warp_fast && a.G > 1 && warp_pieces;      // uniform over the prompt's workgroups
       bool fast_done = false;
       lds_f64* const all_p = (lds_f64*)sh.gpart;        // [G] every workgroup's largest entry of p_beam ...
@@ -1522,7 +1522,8 @@ void verify_layers_kernel(LayersArgs a) {
           const int cp = sh.W_cnt[0], cq = sh.W_cnt[1];
           const int room = (a.sl.b_w - 2) / 2;             // entries a workgroup can post
           const bool post = all_p[g] >= sh.W_tau[0] * slack || all_q[g] >= sh.W_tau[1] * slack;
-          Slot* const mine = slots + a.sl.wb + (long long)g * a.sl.b_w;
+          Slot* const wb_l = slots + a.sl.wb + (long long)(l - 1) * a.sl.wb_stride;     // this layer's region
+          Slot* const mine = wb_l + (long long)g * a.sl.b_w;
           const int n_posted = cp + cq <= room ? cp + cq : 0;
           if (post && tid < max(8, 2 + 2 * n_posted)) {
             double payload;
@@ -1537,7 +1538,7 @@ void verify_layers_kernel(LayersArgs a) {
           const int n_poll = 8 * min(nW, 64);
           for (int t = tid; t < n_poll; t += VL_BLOCK) {
             double v = 0.0;
-            if (!slot_wait(slots + a.sl.wb + (long long)wl[t >> 3] * a.sl.b_w + (t & 7), tag_w, v, a.sync_limit)) give_up();
+            if (!slot_wait(wb_l + (long long)wl[t >> 3] * a.sl.b_w + (t & 7), tag_w, v, a.sync_limit)) give_up();
             stage[t] = v;
           }
           __syncthreads();                                 // (also: everybody has posted from the candidate arrays)
@@ -1567,7 +1568,7 @@ void verify_layers_kernel(LayersArgs a) {
             double v, ix;
             if (e < 3) { v = stage[j * 8 + 2 + 2 * e]; ix = stage[j * 8 + 3 + 2 * e]; }
             else {
-              Slot* const at = slots + a.sl.wb + (long long)wl[j] * a.sl.b_w + 2 + 2 * e;
+              Slot* const at = wb_l + (long long)wl[j] * a.sl.b_w + 2 + 2 * e;
               v = 0.0; ix = 0.0;
               if (!slot_wait2(at, at + 1, tag_w, v, ix, a.sync_limit)) give_up();
             }
@@ -2679,14 +2680,13 @@ VerifyPlan make_verify_plan(const dsbd_forest* f, int V, const dsbd_params* p, b
     sl.r = off; sl.r_stride = G * sl.r_w; off += layers * sl.r_stride;
     sl.s = off; sl.s_stride = G * LINE_SLOTS; off += layers * sl.s_stride;
     sl.sc = off; sl.sc_stride = SUM_GROUPS * LINE_SLOTS; off += layers * sl.sc_stride;
-    sl.b = sl.c = sl.d = sl.wa = sl.wb = off; sl.b_w = 0;
+    sl.b = sl.c = sl.d = sl.wb = off; sl.b_w = 0; sl.wb_stride = 0;
     if (p->top_k > 0) {
       sl.b_w = up8(4 * p->top_k);
       sl.b = off; off += G * sl.b_w;
       sl.c = off; off += (G + WARP_GROUP - 1) / WARP_GROUP * sl.b_w;
       sl.d = off; off += up8(WARP_RESULT_SLOTS);
-      sl.wa = off; off += G * LINE_SLOTS;
-      sl.wb = off; off += G * sl.b_w;
+      sl.wb = off; sl.wb_stride = G * sl.b_w; off += layers * sl.wb_stride;
     }
     sl.acc = off; off += 2 * NACC * LINE_SLOTS;
     sl.acc0 = off; off += up8(2 * NACC);

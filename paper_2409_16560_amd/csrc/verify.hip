@@ -1312,6 +1312,10 @@ void verify_layers_kernel(LayersArgs a) {
     // scaling, fused with this thread's part of F(1) = sum max(p_beam - q_beam, 0) (second entry of the chain)
     double f1 = 0.0;
     double tmax_p = -1.0, tmax_q = -1.0;     // warping: the largest scaled entries this thread has seen
+    // (the one-level selection of the warped kernel needs no scaled slices: it scales the few entries it compares
+    // on the fly and the slices are dead afterwards; only its fallback, the tree form, runs this pass after all)
+    const bool defer_scaling = WARP && a.warp_fast && a.G > 1 && warp_pieces;
+    auto scale_pass = [&]() {
     for (int i = i_lo; i <= i_hi; ++i) {
       const long long j_lo = max(e_lo, (long long)i * V) - e_lo;
       const long long j_hi = min(e_hi, (long long)(i + 1) * V) - e_lo;
@@ -1341,6 +1345,8 @@ void verify_layers_kernel(LayersArgs a) {
         }
       });
     }
+    };
+    if (!defer_scaling) scale_pass();
     if constexpr (WARP) {
       // ===== warping T: top-k / top-p on the two joints (Section 2.1; Section 3.1 "Details": p_beam = T o p/P).
       // Every workgroup finds the K first entries of its slice.  The lists travel up a tree: the first workgroup
@@ -1394,9 +1400,17 @@ void verify_layers_kernel(LayersArgs a) {
         rank_cands(cvq, ciq, min(sh.W_cnt[1], WARP_CAND), lv + K, li + K);
       };
       // everything at or above the bounds W_tau is a candidate (counts in W_cnt; the arrays hold the first WARP_CAND)
+      bool scaled = !defer_scaling;          // the slices hold joint entries (else exponentials against the piece's maximum)
       auto collect_at_or_above = [&]() {
         const double tp = sh.W_tau[0], tq = sh.W_tau[1];
-        auto offer = [&](long long j, double vp, double vq) {
+        // (unscaled slices: one piece of one row per workgroup; the same products as the scaling pass forms)
+        double mp = 1.0, mq = 1.0;
+        if (!scaled && i_lo <= i_hi) {
+          mp = sh.sp[i_lo] * exp_nonpos(sh.lm_p[0] - sh.max_p[i_lo], sh.exp_tab);
+          mq = sh.sq[i_lo] * exp_nonpos(sh.lm_q[0] - sh.max_q[i_lo], sh.exp_tab);
+        }
+        auto offer = [&](long long j, double vp_raw, double vq_raw) {
+          const double vp = vp_raw * mp, vq = vq_raw * mq;
           if (vp >= tp) {
             const int c = atomicAdd(&sh.W_cnt[0], 1);
             if (c < WARP_CAND) { cvp[c] = vp; cip[c] = (int)(e_lo + j); }
@@ -1558,6 +1572,7 @@ void verify_layers_kernel(LayersArgs a) {
           const bool crowded_any = (sh.state[0] | sh.state[1]) != 0;
           if (crowded_any) {                               // the same counts in every workgroup: all take the tree form
             __syncthreads();                               // (the flags are read; the tree form writes them again)
+            if (!scaled) { scale_pass(); scaled = true; __syncthreads(); }
             fast = false;
             continue;
           }
@@ -1764,11 +1779,16 @@ void verify_layers_kernel(LayersArgs a) {
           const double v = real ? lv[(is_q ? K : 0) + r] : 0.0;
           double cum = 0.0;
           int partner = -1;                  // lane of the other list's entry with the same index
-          for (int c = 0; c < K; ++c) {
-            const double vp_c = readlane_f64(v, c), vq_c = readlane_f64(v, 32 + c);
-            if (c <= r) cum += is_q ? vq_c : vp_c;
-            const int ip_c = __builtin_amdgcn_readlane(ix, c), iq_c = __builtin_amdgcn_readlane(ix, 32 + c);
-            if ((is_q ? ip_c : iq_c) == ix) partner = (is_q ? 0 : 32) + c;
+          {
+            // (the lists are read from the LDS, every lane of a half the same word: one read serves 32 lanes; lane
+            // reads of the other lanes' registers cost a scalar round trip each)
+            const int own = is_q ? K : 0, oth = is_q ? 0 : K;
+            for (int c = 0; c < K; ++c) {
+              const int i_own = li[own + c], i_oth = li[oth + c];
+              const double v_own = i_own != INT_MAX ? lv[own + c] : 0.0;
+              if (c <= r) cum += v_own;
+              if (i_oth == ix) partner = (is_q ? 0 : 32) + c;
+            }
           }
           const unsigned long long real_m = __ballot(real);
           const int n = __popcll(is_q ? (real_m >> 32) : (real_m & 0xffffffffull));     // real entries lead the list
@@ -1790,10 +1810,12 @@ void verify_layers_kernel(LayersArgs a) {
           const double other = (both && !is_q) ? w_partner : 0.0;
           const bool valid = kept && !(is_q && both);
           int rank = 0;
-          for (int c = 0; c < K; ++c) {      // the lists' lanes: c (p_beam) and 32 + c (q_beam)
-            const int ip_c = __builtin_amdgcn_readlane(ix, c), iq_c = __builtin_amdgcn_readlane(ix, 32 + c);
-            const int vp_c = __builtin_amdgcn_readlane((int)valid, c), vq_c = __builtin_amdgcn_readlane((int)valid, 32 + c);
-            rank += ((vp_c && ip_c < ix) ? 1 : 0) + ((vq_c && iq_c < ix) ? 1 : 0);
+          {
+            // the valid entries' indices side by side in the LDS (lane c: p_beam's list, 32 + c: q_beam's)
+            lds_i32* const vx = (lds_i32*)sh.A_idx;
+            vx[lane] = valid ? ix : INT_MAX;
+            wave_lds_fence();
+            for (int c = 0; c < K; ++c) rank += (vx[c] < ix ? 1 : 0) + (vx[32 + c] < ix ? 1 : 0);
           }
           if (valid) { sh.U_idx[rank] = ix; sh.U_p[rank] = is_q ? 0.0 : w; sh.U_q[rank] = is_q ? w : other; }
           const unsigned long long vm = __ballot(valid);

@@ -1230,6 +1230,7 @@ void verify_layers_kernel(LayersArgs a) {
     bool warp_pieces = false;               // warping: the table of the workgroups' largest entries is filled
     if constexpr (WARP) {
       if (tid < 256) { sh.gpart[tid] = -1.0; sh.ptot[tid] = -1.0; }     // (workgroups without a piece keep this)
+      lds_barrier();                          // (the gathering threads below write other entries than their own)
     }
     {
       const int ncols = 2 * nI;
@@ -1250,6 +1251,9 @@ void verify_layers_kernel(LayersArgs a) {
           double vs = 0.0, vm = 0.0;
           Slot* const sl0 = rs_bank + (long long)w * a.sl.r_w + 4 * i + (c & 1);
           mine = mine && slot_wait2(sl0, sl0 + 2, rs_tag, vs, vm, a.sync_limit);
+          if constexpr (WARP) {              // (kept for the table of the workgroups' largest entries, below)
+            if (cut.rows_per_wg == 0) ((c & 1) ? sh.ptot : sh.gpart)[min(w, 255)] = vm;
+          }
           const double Mn = fmax(accM, vm);
           accS = accS * exp_nonpos(accM - Mn, sh.exp_tab) + vs * exp_nonpos(vm - Mn, sh.exp_tab);
           accM = Mn;
@@ -1290,16 +1294,21 @@ void verify_layers_kernel(LayersArgs a) {
         // Every workgroup's largest entry of either joint follows from what the gathering threads hold (a piece's
         // largest exponential is 1 against the piece's own maximum): p_beam's largest entry in the piece of row i is
         // (beam weight / row sum) exp(piece maximum - row maximum).  Every workgroup evaluates this alike, bit for
-        // bit, for every workgroup of the prompt (one piece per gathering thread; other cuts leave the table alone
-        // and the selection below takes its tree form).
+        // bit, for every workgroup of the prompt (rows cut into pieces, a piece per workgroup; with whole rows per
+        // workgroup the table is left alone and the selection below takes its tree form).
         // (worth it with many more workgroups than entries to keep: the K-th largest of a few largest entries is a
         // poor bound.  Measured: 16 workgroups per prompt, K = 10: 247 us against the tree form's 202 us; 64
         // workgroups, K = 32: 177 against 167 us; 64 and K = 10: 115 against 131 us; 256 and K = 10: 146 against 176 us.)
-        warp_pieces = cut.rows_per_wg == 0 && geo_pieces <= R && nI * geo_pieces >= 4 * a.top_k;
-        if (warp_pieces && c < ncols && r < geo_pieces && accM > -INFINITY) {
+        warp_pieces = cut.rows_per_wg == 0 && nI * geo_pieces >= 4 * a.top_k;
+        if (warp_pieces && c < ncols) {
           const int i = c >> 1;
-          const double largest = ((c & 1) ? sh.bw_q[i] : sh.bw_p[i]) / tot * exp_nonpos(accM - cm, sh.exp_tab);
-          ((c & 1) ? sh.ptot : sh.gpart)[i * cut.wg_per_row + r] = largest;
+          const double scale = ((c & 1) ? sh.bw_q[i] : sh.bw_p[i]) / tot;
+          double* const tab = (c & 1) ? sh.ptot : sh.gpart;
+          const int w_lo = i * cut.wg_per_row, w_hi = w_lo + geo_pieces - 1;
+          for (int w = w_lo + r; w <= w_hi; w += R) {        // the pieces this thread gathered: their maxima are in the table
+            const double vm = tab[min(w, 255)];
+            tab[min(w, 255)] = vm > -INFINITY ? scale * exp_nonpos(vm - cm, sh.exp_tab) : -1.0;     // (an empty piece holds nothing)
+          }
         }
       }
       if (single_piece && c < ncols && (c & 1) == 0 && r < geo_pieces) {
@@ -2376,10 +2385,31 @@ void verify_layers_kernel(LayersArgs a) {
     // ===== width of the layer
     if (dynamic) {
       // alpha_j for j = 1..M (Eq. 3) from the chain; stop early if the residual mass vanishes
-      bool dead = false;
-      for (int j = 1; j <= M && !dead; ++j) {
-        if (!extend_chain(false)) return;
-        dead = !(sh.FF[j + 1] > 0.0);
+      if constexpr (WARP) {
+        // The warped joints are the short list every workgroup holds, an entry per lane: the first wave runs the
+        // whole chain by itself (c_{k+1} = c_k + F(c_k), F a sum over its lanes), no barrier per entry.  The same
+        // sums as extend_chain forms (there the other waves add zeros).
+        if (wave == 0) {
+          const bool in = lane < sh.nU;
+          const double up = in ? sh.U_p[lane] : 0.0, uq = in ? sh.U_q[lane] : 0.0;
+          int k = sh.kmax;               // 1: nothing is posted ahead of time for warped joints
+          double c = sh.cc[k], F = sh.FF[k];
+          for (int j = 1; j <= M; ++j) {
+            c += F;
+            F = wave_sum(fmax(up - c * uq, 0.0));
+            k += 1;
+            if (lane == 0) { sh.cc[k] = c; sh.FF[k] = F; }
+            if (!(F > 0.0)) break;
+          }
+          if (lane == 0) sh.kmax = k;
+        }
+        __syncthreads();
+      } else {
+        bool dead = false;
+        for (int j = 1; j <= M && !dead; ++j) {
+          if (!extend_chain(false)) return;
+          dead = !(sh.FF[j + 1] > 0.0);
+        }
       }
       const int kdone = sh.kmax;     // entries 1..kdone valid
       __syncthreads();

@@ -189,8 +189,11 @@ size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, 
  *     Verifications on DIFFERENT streams are kept apart by the library: the first call that arrives on another
  *     stream than the one before waits for the device to drain (once per device and process), and from then on
  *     every layer kernel is ordered behind the previous one by an event (6 us per call, which callers that stay on
- *     one stream never pay).  Not covered: a stream under graph capture (the call records nothing outside the
- *     capture; keep replays apart from other verifications yourself), dsbd_verify_forest_static() before the
+ *     one stream never pay).  A stream under graph capture: the call can be recorded (its second stream joins the
+ *     capture through the fork and join events; a one-thread kernel in front of the layer kernel counts the replays in
+ *     the workspace, so that every replay's exchange slots are told apart from the previous one's, which is why the
+ *     workspace must be the same memory at every replay), but it records nothing outside the capture: keep replays
+ *     apart from other verifications yourself.  Also not covered: dsbd_verify_forest_static() before the
  *     library's second stream exists, and other processes on the device.  Foreign kernels that occupy compute
  *     units only delay the layer kernel; every wait in it is bounded (3 s by default) and ends in
  *     DSBD_FAULT_SYNC_TIMEOUT with unusable outputs, never in a hang.

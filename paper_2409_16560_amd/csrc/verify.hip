@@ -262,6 +262,8 @@ struct LayersArgs {
   int alias;             // one model in both roles (same logits, same beam likelihoods): q_beam IS p_beam, kept once
   long long sync_limit;  // bound of every wait, in ticks of the 100 MHz wall clock
   unsigned long long nonce;   // base of this launch's exchange tags: no tag of an earlier launch on the same workspace can match
+  const unsigned long long* replay;   // launches recorded into a graph: a word of the workspace that a small kernel in front of
+                              // this one counts up at every replay (the arguments, nonce included, repeat); else null
   int mute_wg;           // test hook: this workgroup withholds its first post (-1: none), so that its partners'
                          // bounded waits give up and the error path can be exercised without a hang
   int32_t* fault;
@@ -691,6 +693,10 @@ void verify_layers_kernel(LayersArgs a) {
   unsigned int epoch = 0;      // exchanges so far (sets the tag); identical in every workgroup of the prompt
   unsigned int xchg = 0;       // of those, the ones on the two alternating banks
   Slot* const slots = prompt_slots(a, prompt);
+  // (a replayed launch: the replay count, which the kernel in front of this one has just raised, sets the tags apart
+  // from those of the graph's earlier replays)
+  const unsigned long long nonce =
+      a.nonce + (a.replay ? (__hip_atomic_load(a.replay, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) << 40) : 0ull);
   // (selected, not indexed: a run-time index into the kernel's argument block would move the whole block into scratch memory)
   const int slx0 = a.sl.x[0], slx1 = a.sl.x[1], slxc0 = a.sl.xc[0], slxc1 = a.sl.xc[1];
   auto bank_x = [&](unsigned int n) { return (n & 1) ? slx1 : slx0; };
@@ -709,7 +715,7 @@ void verify_layers_kernel(LayersArgs a) {
   // anybody adds to them (nobody does before the first layer's row sums, which wait for this workgroup's), and handed
   // to the others in tagged slots, collected during the first layer
   unsigned long long* const accs = reinterpret_cast<unsigned long long*>(slots + a.sl.acc);
-  const unsigned long long acc0_tag = exchange_tag(a.nonce + 0xFFFFFFull);
+  const unsigned long long acc0_tag = exchange_tag(nonce + 0xFFFFFFull);
   unsigned int achg = 0;       // accumulator exchanges so far (alternates their two banks)
   // (requested here, used at the end of the prologue: the round trip through the memory system runs beside it)
   unsigned long long acc0_w = 0;
@@ -1155,7 +1161,7 @@ void verify_layers_kernel(LayersArgs a) {
     // ===== all-reduce of the rows' maxima and sums.  Only the workgroups that hold a piece of row i post its four
     // values (sum and maximum of the piece, both models) and only those are polled.
     epoch += 1;
-    const unsigned long long rs_tag = exchange_tag(a.nonce + epoch);
+    const unsigned long long rs_tag = exchange_tag(nonce + epoch);
     Slot* const rs_bank = slots + a.sl.r + (long long)(l - 1) * a.sl.r_stride;
     if (tid < 4 * (i_hi - i_lo + 1) && !(l == 1 && (int)blockIdx.x == a.mute_wg)) {
       const int r = tid >> 2, which = tid & 3;
@@ -1469,7 +1475,7 @@ void verify_layers_kernel(LayersArgs a) {
           // The K-th largest of the workgroups' largest entries, or anything below it, is a lower bound of the joint's
           // K-th entry (K entries of K different workgroups are at or above it).  One wave per model finds it;
           // fewer than K values leave -1: everything passes, the counts below show it, and the tree form takes over.
-          tag_w = exchange_tag(a.nonce + epoch + 1);
+          tag_w = exchange_tag(nonce + epoch + 1);
           epoch += 1;
           if (tid < 2) sh.W_cnt[tid] = 0;
           if (wave < 2) {
@@ -1751,8 +1757,8 @@ void verify_layers_kernel(LayersArgs a) {
         const int first = g - g % WARP_GROUP;
         const int n_mem = min(WARP_GROUP, a.G - first);
         const int n_groups = (a.G + WARP_GROUP - 1) / WARP_GROUP;
-        const unsigned long long tag_b = exchange_tag(a.nonce + epoch + 1), tag_c = exchange_tag(a.nonce + epoch + 2);
-        tag_d = exchange_tag(a.nonce + epoch + 3);
+        const unsigned long long tag_b = exchange_tag(nonce + epoch + 1), tag_c = exchange_tag(nonce + epoch + 2);
+        tag_d = exchange_tag(nonce + epoch + 3);
         epoch += 3;
         post_list(slots + a.sl.b + (long long)g * a.sl.b_w, tag_b);
         if (g == first) {                    // the group's first workgroup merges the group's lists
@@ -1893,7 +1899,7 @@ void verify_layers_kernel(LayersArgs a) {
       const double tot = wg_total(f1);      // barrier inside: also publishes the scaled slices
       stamp(27);
       epoch += 1;
-      spec_tag = exchange_tag(a.nonce + epoch);
+      spec_tag = exchange_tag(nonce + epoch);
       spec_bank = slots + a.sl.s + (long long)(l - 1) * a.sl.s_stride;
       spec_gbank = slots + a.sl.sc + (long long)(l - 1) * a.sl.sc_stride;
       if (tid == 0) dense_post(spec_bank, a.G, g, tot, spec_tag);
@@ -2094,7 +2100,7 @@ void verify_layers_kernel(LayersArgs a) {
       Slot* bank = nullptr;
       if (!known_totals) {
         epoch += 1;
-        tag = exchange_tag(a.nonce + epoch);
+        tag = exchange_tag(nonce + epoch);
         bank = slots + bank_x(xchg++);
       }
       if (wave == 0) {
@@ -2766,6 +2772,7 @@ size_t carve_verify(WorkspaceCarver& ws, const dsbd_forest* f, int V, const Veri
   const size_t N = (size_t)f->n_nodes, P = (size_t)f->n_prompts;
   (void)V;
   ws.take<long long>(512);                 // timeline of the layer kernel (diagnostics), first in the workspace
+  ws.take<unsigned long long>(32);         // replay count of launches recorded into a graph (one word, a line of its own)
   *part = ws.take<float2>(2 * N * pl.nchunk);
   // slices that do not fit the LDS: a region per workgroup of a launch (the launches of a forest that runs in groups
   // of prompts follow each other and share the regions); exchange slots: a region per prompt
@@ -2812,6 +2819,10 @@ SideStream* side_stream_of_current_device(bool may_create) {
 }
 
 std::atomic<unsigned long long> g_launch_counter{0};
+
+// In front of a layer kernel that is recorded into a graph: every replay repeats the launch's arguments, so what tells
+// its exchange slots from those of the replay before is this count (whatever the word held to begin with).
+__global__ void bump_replay_count_kernel(unsigned long long* count) { *count += 1; }
 
 }  // namespace
 
@@ -2938,6 +2949,12 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   // Exchange slots carry a tag made of this number and the exchange's index: nothing an earlier launch left in the
   // workspace can pass for a value of this one, so the slots need no clearing.
   la.nonce = (g_launch_counter.fetch_add(1, std::memory_order_relaxed) + 1) << 24;
+  la.replay = nullptr;
+  if (capturing) {
+    unsigned long long* const count = reinterpret_cast<unsigned long long*>(wbase + 512 * sizeof(long long));
+    hipLaunchKernelGGL(bump_replay_count_kernel, dim3(1), dim3(1), 0, stream, count);
+    la.replay = count;
+  }
   la.G = pl.G; la.I_cap = pl.I_cap; la.sl = pl.sl; la.lds_elems = pl.lds_elems; la.fault = fault;
   la.lds_slice = pl.lds_elems;
   la.alias = alias ? 1 : 0;

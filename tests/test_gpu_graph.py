@@ -11,8 +11,10 @@ from dsbd_synth import make_workload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("top_k,top_p", [(0, 1.0), (8, 0.9)])
-def test_replays_of_a_captured_verification_on_new_inputs(top_k, top_p):
+@pytest.mark.parametrize("top_k,top_p,static", [(0, 1.0, False), (8, 0.9, False), (0, 1.0, True)])
+def test_replays_of_a_captured_verification_on_new_inputs(top_k, top_p, static):
+    """static: through the entry point that allocates nothing (its workspace is the library's own device array), the
+    one meant for callers under capture."""
     import gpu_util as gu
     import paper_2409_16560_amd as dsbd
     dsbd.dsbd_init()                      # (second stream and events exist before the capture)
@@ -26,7 +28,11 @@ def test_replays_of_a_captured_verification_on_new_inputs(top_k, top_p):
     work = torch.empty(nb, dtype=torch.uint8, device="cuda")
     s = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
-    call = lambda st: d.verify_select(t=0.7, result=res, next_beams=nx, workspace=work, stream=st, top_k=top_k, top_p=top_p)
+    if static:
+        call = lambda st: dsbd.dsbd_verify_forest_static(d.forest, d.logits_p, d.logits_q, d.blp, d.blq, d.u_accept, d.u_resid,
+                                                         d.u_fill, res, W_cap=w0.W_cap, t=0.7, stream=st)
+    else:
+        call = lambda st: d.verify_select(t=0.7, result=res, next_beams=nx, workspace=work, stream=st, top_k=top_k, top_p=top_p)
     call(None)                            # once eagerly (the library's first-call set-up is not part of the capture)
     torch.cuda.synchronize()
     with torch.cuda.stream(s):

@@ -1417,7 +1417,9 @@ void verify_layers_kernel(LayersArgs a) {
       // everything at or above the bounds W_tau is a candidate (counts in W_cnt; the arrays hold the first WARP_CAND)
       bool scaled = !defer_scaling;          // the slices hold joint entries (else exponentials against the piece's maximum)
       auto collect_at_or_above = [&]() {
-        const double tp = sh.W_tau[0], tq = sh.W_tau[1];
+        // (a little below the bounds: the values compared here and the ones the candidates are ranked by, below, may
+        // differ in the last bits)
+        const double tp = sh.W_tau[0] * (1.0 - 1e-12), tq = sh.W_tau[1] * (1.0 - 1e-12);
         // (unscaled slices: one piece of one row per workgroup; the same products as the scaling pass forms)
         double mp = 1.0, mq = 1.0;
         if (!scaled && i_lo <= i_hi) {
@@ -1544,6 +1546,28 @@ void verify_layers_kernel(LayersArgs a) {
         stamp(58);
         collect_at_or_above();               // (2) everything at or above the bound is a candidate
         __syncthreads();
+        // The candidates are ranked by value, equal values by index, and equal logits of a row must give equal
+        // values for that wherever in the row they sit (logits that came out of 16-bit arithmetic tie all the time).
+        // A slice entry is exp(z - piece maximum) x a factor of the piece: two roundings that differ from piece to
+        // piece.  So the few candidates get their value once more from the logit itself, in the one form that
+        // depends on the row only (the form the candidates of the accept tests use as well).  (Taken inside the
+        // pass above, by the thread that finds a candidate, it measured no faster, and slower with many candidates.)
+        auto canonical_values = [&]() {
+          const int n_p = min(sh.W_cnt[0], WARP_CAND), n_q = min(sh.W_cnt[1], WARP_CAND);
+          for (int t = tid; t < n_p + n_q; t += VL_BLOCK) {
+            const bool is_q = t >= n_p;
+            const int c = is_q ? t - n_p : t;
+            const int flat = is_q ? ciq[c] : cip[c];
+            if (flat < 0 || (long long)flat >= (long long)nI * V) continue;       // ("none": nothing to look up)
+            const int i = (int)div_floor(flat, V);
+            const int x = flat - i * V;
+            const float z = (is_q ? a.zq : a.zp)[(long long)sh.I_node[i] * V + x];
+            const double v = exp_nonpos((double)z - (is_q ? sh.max_q[i] : sh.max_p[i]), sh.exp_tab) * (is_q ? sh.sq[i] : sh.sp[i]);
+            if (is_q) cvq[c] = v; else cvp[c] = v;
+          }
+        };
+        canonical_values();
+        __syncthreads();
         stamp(60);
         if (fast) {
           // ---- the candidates of the workgroups that can hold any: counts and the first three in the first line
@@ -1629,6 +1653,8 @@ void verify_layers_kernel(LayersArgs a) {
             pv_prev = bp; pi_prev = ip; qv_prev = bq; qi_prev = iq;
           }
           if (tid < 2) sh.W_cnt[tid] = VL_WAVES * K;
+          __syncthreads();
+          canonical_values();
         }
         rank_select();                         // barrier inside, after the counts are final
         __syncthreads();

@@ -390,6 +390,34 @@ def test_warping_selection_in_one_level_and_by_the_tree(seed, G, fast, knobs):
         gu.compare_verify(res, ref, w)
 
 
+@pytest.mark.parametrize("quantum", ["half", "bf16"])
+@pytest.mark.parametrize("G", [2, 3, 16, 64])
+def test_warping_with_equal_logits_in_different_pieces_of_a_row(G, quantum, knobs):
+    """Logits on a coarse grid (multiples of 0.5, or rounded to bfloat16 as a 16-bit model's are): equal logits of one
+    row sit in different workgroups' pieces, whose slice entries are scaled piece by piece.  Equal logits must still give
+    equal joint entries, or the order of equal values (by index) that decides the top-k / top-p cut comes out different
+    from a row-by-row evaluation: the candidates are ranked by values recomputed from the logits in a form that depends
+    on the row alone.  (Found by a randomized sweep: wrong sampled tokens with two or more workgroups per prompt.)"""
+    import dataclasses
+    gu = _gu()
+    knobs.set("DSBD_VERIFY_G", G)
+    for seed, n_prompts in ((895529104, 2), (188831134, 2), (5, 1)):
+        w = make_workload("c4", n_prompts=n_prompts, W=(1, 6), tree_nodes=(2, 7), L=1, Hq=1, Hkv=1, D=64, V=2000, seed=seed,
+                          logit_std=1.0, noise_std=1.0, draft_top_k=4)
+        if quantum == "half":
+            q = lambda z: (np.round(z * 2) / 2).astype(np.float32)
+        else:
+            q = lambda z: torch.from_numpy(z).to(torch.bfloat16).to(torch.float32).numpy()
+        w = dataclasses.replace(w, logits_p=q(w.logits_p), logits_q=q(w.logits_q))
+        d = gu.DeviceWorkload(w)
+        for top_k, top_p, t in ((32, 0.6, 0.6), (32, 1.0, -1.0), (10, 0.8, -1.0), (31, 0.6, 0.3)):
+            print("seed", seed, "G", G, quantum, "top_k", top_k, "top_p", top_p, "t", t, flush=True)
+            res = d.verify(t=t, top_k=top_k, top_p=top_p)
+            torch.cuda.synchronize()
+            ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+            gu.compare_verify(res, ref, w)
+
+
 @pytest.mark.parametrize("G", [0, 64])
 @pytest.mark.parametrize("cfg,kw", [("c3", dict(V=5000)), ("c2", dict(V=700)), ("c4", dict(V=3000, n_prompts=3))])
 def test_warping_with_many_equal_entries(cfg, kw, G, knobs):

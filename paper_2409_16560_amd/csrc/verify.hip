@@ -64,46 +64,47 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ void online_add4(float& m, float& s, bool& bad, float x0, float x1, float x2, float x3) {
   const float L2E = 1.4426950408889634f;
   const float bm = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
-  bad |= !(fabsf(x0) <= FLT_MAX) | !(fabsf(x1) <= FLT_MAX) | !(fabsf(x2) <= FLT_MAX) | !(fabsf(x3) <= FLT_MAX);
+  bad |= !(x0 <= FLT_MAX) | !(x1 <= FLT_MAX) | !(x2 <= FLT_MAX) | !(x3 <= FLT_MAX);      // NaN or +Inf (-Inf: a masked token)
   if (bm > m) {
     s *= fast_exp2((m - bm) * L2E);
     m = bm;
   }
-  s += fast_exp2((x0 - m) * L2E) + fast_exp2((x1 - m) * L2E) + fast_exp2((x2 - m) * L2E) + fast_exp2((x3 - m) * L2E);
+  const float ref = m == -INFINITY ? 0.f : m;       // (nothing but masked tokens so far: they add 0, not exp(-Inf + Inf))
+  s += fast_exp2((x0 - ref) * L2E) + fast_exp2((x1 - ref) * L2E) + fast_exp2((x2 - ref) * L2E) + fast_exp2((x3 - ref) * L2E);
 }
 
 __device__ __forceinline__ void online_add16(float& m, float& s, bool& bad, float4 a, float4 b, float4 c, float4 d) {
   const float L2E = 1.4426950408889634f;
   const float v[16] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w, c.x, c.y, c.z, c.w, d.x, d.y, d.z, d.w};
   float bm = v[0];
-  float amax = fabsf(v[0]);
 #pragma unroll
-  for (int e = 1; e < 16; ++e) { bm = fmaxf(bm, v[e]); amax = fmaxf(amax, fabsf(v[e])); }
+  for (int e = 1; e < 16; ++e) bm = fmaxf(bm, v[e]);
   bool nan = false;
 #pragma unroll
   for (int e = 0; e < 16; ++e) nan |= (v[e] != v[e]);
-  bad |= nan | !(amax <= FLT_MAX);
+  bad |= nan | !(bm <= FLT_MAX);                     // NaN or +Inf (-Inf: a masked token, probability 0)
   if (bm > m) {
     s *= fast_exp2((m - bm) * L2E);
     m = bm;
   }
+  const float ref = m == -INFINITY ? 0.f : m;       // (nothing but masked tokens so far: they add 0, not exp(-Inf + Inf))
   float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
 #pragma unroll
   for (int e = 0; e < 16; e += 4) {
-    t0 += fast_exp2((v[e] - m) * L2E); t1 += fast_exp2((v[e + 1] - m) * L2E);
-    t2 += fast_exp2((v[e + 2] - m) * L2E); t3 += fast_exp2((v[e + 3] - m) * L2E);
+    t0 += fast_exp2((v[e] - ref) * L2E); t1 += fast_exp2((v[e + 1] - ref) * L2E);
+    t2 += fast_exp2((v[e + 2] - ref) * L2E); t3 += fast_exp2((v[e + 3] - ref) * L2E);
   }
   s += (t0 + t1) + (t2 + t3);
 }
 
 __device__ __forceinline__ void online_add1(float& m, float& s, bool& bad, float x) {
   const float L2E = 1.4426950408889634f;
-  bad |= !(fabsf(x) <= FLT_MAX);
+  bad |= !(x <= FLT_MAX);                            // NaN or +Inf
   if (x > m) {
     s *= fast_exp2((m - x) * L2E);
     m = x;
   }
-  s += fast_exp2((x - m) * L2E);
+  s += fast_exp2((x - (m == -INFINITY ? 0.f : m)) * L2E);
 }
 
 __device__ __forceinline__ void online_merge(float& m, float& s, float m2, float s2) {
@@ -1053,7 +1054,7 @@ void verify_layers_kernel(LayersArgs a) {
 #pragma unroll
       for (int k = 0; k < XU; ++k) {
         lmp = fmaxf(fmaxf(lmp, fpA[k]), fpB[k]); lmq = fmaxf(fmaxf(lmq, fqA[k]), fqB[k]);
-        nonfinite |= !(fabsf(fpA[k]) <= FLT_MAX) | !(fabsf(fqA[k]) <= FLT_MAX) | !(fabsf(fpB[k]) <= FLT_MAX) | !(fabsf(fqB[k]) <= FLT_MAX);
+        nonfinite |= !(fpA[k] <= FLT_MAX) | !(fqA[k] <= FLT_MAX) | !(fpB[k] <= FLT_MAX) | !(fqB[k] <= FLT_MAX);     // NaN or +Inf (-Inf: a masked token)
       }
       // (the rest of a long piece: maxima only, so four times as many logits in flight as in the rounds above)
       for (int x = xB + XU * VL_BLOCK; x < x_hi; x += 4 * XU * VL_BLOCK) {
@@ -1066,7 +1067,7 @@ void verify_layers_kernel(LayersArgs a) {
 #pragma unroll
         for (int k = 0; k < 4 * XU; ++k) {
           lmp = fmaxf(lmp, fp[k]); lmq = fmaxf(lmq, fq[k]);
-          nonfinite |= !(fabsf(fp[k]) <= FLT_MAX) | !(fabsf(fq[k]) <= FLT_MAX);
+          nonfinite |= !(fp[k] <= FLT_MAX) | !(fq[k] <= FLT_MAX);
         }
       }
       if (nonfinite) atomicOr(a.fault, DSBD_FAULT_NONFINITE);

@@ -612,6 +612,39 @@ def test_device_side_faults_are_reported_not_fatal():
     assert f & dsbd.DSBD_FAULT_NONFINITE and f & dsbd.DSBD_FAULT_TOKEN
 
 
+@pytest.mark.parametrize("G", [0, 64])
+@pytest.mark.parametrize("pattern", ["tail", "random", "both"])
+def test_masked_tokens_with_logit_minus_infinity(pattern, G, knobs):
+    """Logit processors forbid tokens by setting their logits to -Inf (padding entries of a vocabulary, banned
+    tokens).  Such entries have probability 0 and are no fault: the results are the oracle's, whole pieces of a row
+    may be masked (a contiguous tail over many workgroups), and the statistics pass treats them alike."""
+    gu = _gu()
+    if G:
+        knobs.set("DSBD_VERIFY_G", G)
+    for cfg, kw in (("c5", dict(V=9000)), ("c4", dict(V=3000, n_prompts=4))):
+        w = make_workload(cfg, L=1, Hq=1, Hkv=1, D=64, seed=5, draft_top_k=3, **kw)
+        rng = np.random.default_rng(1)
+        mask = np.zeros(w.V, dtype=bool)
+        if pattern in ("tail", "both"):
+            mask[int(0.6 * w.V):] = True
+        if pattern in ("random", "both"):
+            mask |= rng.random(w.V) < 0.3
+        mask[w.token[w.token >= 0]] = False              # drafted tokens stay allowed
+        mask[:64] = pattern == "both"                     # (and a masked stretch at the start of every row)
+        mask[w.token[w.token >= 0]] = False
+        w.logits_p[:, mask] = -np.inf
+        w.logits_q[:, mask] = -np.inf
+        d = gu.DeviceWorkload(w)
+        for top_k, top_p, t in ((0, 1.0, -1.0), (0, 1.0, 0.6), (10, 0.8, -1.0), (32, 0.9, 0.6)):
+            print(cfg, pattern, "G", G, "top_k", top_k, "t", t, "masked", int(mask.sum()), "of", w.V, flush=True)
+            res = d.verify(t=t, top_k=top_k, top_p=top_p)
+            torch.cuda.synchronize()
+            with np.errstate(all="ignore"):
+                ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+            gu.compare_verify(res, ref, w)                # (asserts a zero fault word as well)
+            gu.check_verify_select(d, w, ref, t=t, top_k=top_k, top_p=top_p)
+
+
 def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang(knobs):
     """Error path of the layer kernel's exchanges, forced from the host: one workgroup withholds its first post
     (test hook), every wait for it is bounded (2 ms here instead of 3 s), so all workgroups give up, the kernel ends

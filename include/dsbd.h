@@ -47,7 +47,7 @@ extern "C" {
 
 #define DSBD_FAULT_TOPOLOGY       1 /* parent outside its tree / not before the child / bad root    */
 #define DSBD_FAULT_TOKEN          2 /* token id outside [0, V)                                      */
-#define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit (-Inf is a masked token: probability 0)    */
+#define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit; -Inf (a masked token) in a whole row or at a drafted token */
 #define DSBD_FAULT_ZERO_RESIDUAL  8 /* a residual distribution had no mass                          */
 #define DSBD_FAULT_BOUNDS        16 /* a host-declared bound (max_*) is exceeded by the device data */
 #define DSBD_FAULT_SYNC_TIMEOUT  32 /* internal grid synchronisation gave up                        */
@@ -142,8 +142,10 @@ typedef struct dsbd_params {
 typedef struct dsbd_verify_in {
   int32_t V;                       /* vocabulary size                                                */
   const float*  logits_target;     /* [n_nodes,V] large model's logits at every node (row-major);    */
-                                   /*   -Inf = a masked token (probability 0), a row needs one finite */
-                                   /*   logit; NaN and +Inf raise DSBD_FAULT_NONFINITE                */
+                                   /*   -Inf = a masked token (probability 0); a row needs one finite */
+                                   /*   logit and a drafted token a finite logit in its parent's row  */
+                                   /*   (both models); NaN, +Inf, a row of -Inf only and a masked     */
+                                   /*   drafted token raise DSBD_FAULT_NONFINITE                      */
   const float*  logits_draft;      /* [n_nodes,V] small model's logits                               */
   const double* beam_logp_target;  /* [n_trees] stored log-likelihood of each input beam under p      */
   const double* beam_logp_draft;   /* [n_trees] ... under q (Section 2.1: beam sampling stores them)  */

@@ -190,6 +190,7 @@ struct FinishArgs {
   const float2* part;
   const int32_t *parent, *token;
   float *lse[2], *logp[2];     // outputs (any may be null)
+  int32_t* fault;
 };
 
 __device__ __forceinline__ float merged_lse(const float2* pp, int nchunk) {
@@ -207,10 +208,16 @@ __global__ __launch_bounds__(VS_BLOCK) void vocab_finish_kernel(FinishArgs a) {
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
     const float2* base = a.part + (a.alias ? 0 : (long long)m * a.n_nodes * a.nchunk);
-    if (a.lse[m]) a.lse[m][n] = merged_lse(base + (long long)n * a.nchunk, a.nchunk);
+    const float own = merged_lse(base + (long long)n * a.nchunk, a.nchunk);
+    if (own == -INFINITY) atomicOr(a.fault, DSBD_FAULT_NONFINITE);     // a row without a finite logit
+    if (a.lse[m]) a.lse[m][n] = own;
+    // A masked logit (-Inf) is a token of probability 0, but not at a drafted token: its beam would carry the
+    // likelihood 0, and a layer whose beams all do has no joint.  Reported like the other non-finite logits.
+    const float zt = has_parent ? a.z[m][(long long)par * a.V + tok] : 0.f;
+    if (zt == -INFINITY) atomicOr(a.fault, DSBD_FAULT_NONFINITE);
     if (a.logp[m]) {
       float lp = 0.f;
-      if (has_parent) lp = a.z[m][(long long)par * a.V + tok] - merged_lse(base + (long long)par * a.nchunk, a.nchunk);
+      if (has_parent) lp = zt - merged_lse(base + (long long)par * a.nchunk, a.nchunk);
       a.logp[m][n] = lp;
     }
   }
@@ -2921,7 +2928,7 @@ int32_t verify_impl(const dsbd_forest* f, const dsbd_verify_in* in, const dsbd_p
   FinishArgs fa;
   fa.z[0] = in->logits_target; fa.z[1] = in->logits_draft;
   fa.n_nodes = f->n_nodes; fa.V = in->V; fa.nchunk = pl.nchunk; fa.alias = alias ? 1 : 0; fa.part = part;
-  fa.parent = f->parent; fa.token = f->token;
+  fa.parent = f->parent; fa.token = f->token; fa.fault = fault;
   fa.lse[0] = out->lse_target; fa.lse[1] = out->lse_draft;
   fa.logp[0] = out->node_logp_target; fa.logp[1] = out->node_logp_draft;
   auto launch_stats = [&](hipStream_t st) {

@@ -610,6 +610,18 @@ def test_device_side_faults_are_reported_not_fatal():
     torch.cuda.synchronize()
     f = int(res.fault.item())
     assert f & dsbd.DSBD_FAULT_NONFINITE and f & dsbd.DSBD_FAULT_TOKEN
+    # -Inf is a masked token and no fault by itself, but a drafted token masked in its parent's row (either model)
+    # and a row without any finite logit are
+    for model, what in (("logits_p", "drafted"), ("logits_q", "drafted"), ("logits_p", "row"), ("logits_q", "row")):
+        w4 = make_workload("c2", L=40, V=500, Hq=4, Hkv=4)
+        n = int(np.flatnonzero(w4.parent >= 0)[2])
+        if what == "drafted":
+            getattr(w4, model)[w4.parent[n], w4.token[n]] = -np.inf
+        else:
+            getattr(w4, model)[n, :] = -np.inf
+        res = gu.DeviceWorkload(w4).verify()
+        torch.cuda.synchronize()
+        assert int(res.fault.item()) == dsbd.DSBD_FAULT_NONFINITE, (model, what)
 
 
 @pytest.mark.parametrize("G", [0, 64])

@@ -310,7 +310,8 @@ typedef struct dsbd_draft_in {
   int32_t max_prompt_beams;        /* host-side bound: most beams of one prompt (<= 64)                      */
   int32_t V;
   const int32_t* beam_off;         /* [n_prompts+1] device: beams of prompt p are rows beam_off[p] .. beam_off[p+1]-1 */
-  const float*   logits_draft;     /* [n_beams,V] small model's logits at those beams                        */
+  const float*   logits_draft;     /* [n_beams,V] small model's logits at those beams (-Inf = a masked token, */
+                                   /*   never drawn; a row needs one finite logit)                            */
   const double*  beam_logp_draft;  /* [n_beams] their stored log-likelihoods under the small model           */
   const float*   u;                /* [n_prompts,W_S] uniforms in [0,1), one per draw                        */
 } dsbd_draft_in;

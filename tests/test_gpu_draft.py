@@ -83,6 +83,25 @@ def test_draft_layer_full_vocabulary():
         assert np.max(np.abs(lp - rlp)) <= 1e-9
 
 
+@pytest.mark.parametrize("top_k,top_p", [(0, 1.0), (10, 0.8)])
+def test_draft_layer_with_masked_tokens(top_k, top_p):
+    """Logits of -Inf are tokens of probability 0 (never drawn), not a fault: a masked tail, masks per row, and a row
+    with a single allowed token."""
+    beam_off, z, cum, u = layer_inputs(11, [6, 3], 9000, 8)
+    rng = np.random.default_rng(2)
+    z[:, 5000:] = -np.inf
+    z[rng.random(z.shape) < 0.3] = -np.inf
+    z[4, :] = -np.inf; z[4, 123] = 0.5
+    z[np.arange(z.shape[0]), rng.integers(0, 5000, z.shape[0])] = 1.0
+    par, tok, lp, fault = run_draft_layer(beam_off, z, cum, u, 8, top_k, top_p)
+    with np.errstate(all="ignore"):
+        rpar, rtok, rlp = oracle_draft_layer(beam_off, z, cum, u, top_k, top_p)
+    assert fault == 0
+    assert np.array_equal(par, rpar) and np.array_equal(tok, rtok)
+    assert np.isfinite(z[par, tok]).all()
+    assert np.max(np.abs(lp - rlp)) <= 1e-9
+
+
 def test_draft_layer_reports_bad_inputs():
     beam_off, z, cum, u = layer_inputs(3, [3, 2], 500, 4)
     z_bad = z.copy(); z_bad[1, 17] = np.inf

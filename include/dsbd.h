@@ -188,7 +188,8 @@ size_t dsbd_verify_forest_workspace_bytes(const dsbd_forest* forest, int32_t V, 
  *     per-node outputs (lse_*, node_logp_*) on a second stream that the library creates once per device; the second
  *     stream starts after everything `stream` holds at the time of the call and `stream` continues only when both
  *     kernels are done, so the caller sees ordinary stream semantics.  If all four per-node outputs are NULL the
- *     pass is left out; non-finite logits are then reported only for the rows of beams that enter a layer.
+ *     pass is left out; NaN and +Inf logits are then reported only for the rows of beams that enter a layer, and
+ *     the two misuses of -Inf (a row of nothing else, a masked drafted token) not at all.
  *   - The layer kernel's workgroups wait for each other, so it needs its share of the device while it runs.
  *     Verifications on DIFFERENT streams are kept apart by the library: the first call that arrives on another
  *     stream than the one before waits for the device to drain (once per device and process), and from then on

@@ -270,3 +270,37 @@ def test_near_tie_counter_and_role_indexed_uniforms():
     r2 = run_oracle(w2)
     for k in ("node_status", "out_parent", "out_token", "out_node", "l_last"):
         assert np.array_equal(r0[k], r2[k])
+
+
+# ------------------------------------------------------------------ masked tokens
+@pytest.mark.parametrize("top_k,top_p,t", [(0, 1.0, -1.0), (0, 1.0, 0.6), (5, 0.8, -1.0), (8, 1.0, 0.5)])
+def test_masked_tokens_are_tokens_that_are_not_there(top_k, top_p, t):
+    """A logit of -Inf gives its token the probability 0 in every distribution of the method, so verifying with some
+    vocabulary entries masked in both models must be the same as verifying over the vocabulary without them (tokens
+    renumbered in order): same decisions, widths and draws, same likelihoods."""
+    for seed in range(6):
+        w = make_workload("c2", L=2, V=60, Hq=1, Hkv=1, D=64, seed=seed, noise_std=1.0)
+        rng = np.random.default_rng(seed)
+        keep = rng.random(w.V) < 0.6
+        keep[w.token[w.token >= 0]] = True                     # drafted tokens exist in both vocabularies
+        new_id = np.cumsum(keep) - 1
+        old_id = np.flatnonzero(keep)
+        zp, zq = w.logits_p.copy(), w.logits_q.copy()
+        zp[:, ~keep] = -np.inf
+        zq[:, ~keep] = -np.inf
+        tok_small = np.where(w.token >= 0, new_id[np.maximum(w.token, 0)], w.token).astype(np.int32)
+        args = (w.beam_logp_p, w.beam_logp_q, w.u_accept, w.u_resid, w.u_fill, 0, 1, w.W_cap, t)
+        with np.errstate(all="ignore"):
+            big = verify.verify_forest(w.tree_prompt, w.tree_off, w.parent, w.token, zp, zq, *args,
+                                       top_k=top_k, top_p=top_p)
+        small = verify.verify_forest(w.tree_prompt, w.tree_off, w.parent, tok_small,
+                                     np.ascontiguousarray(w.logits_p[:, keep]), np.ascontiguousarray(w.logits_q[:, keep]),
+                                     *args, top_k=top_k, top_p=top_p)
+        assert big["fault"] == small["fault"] == 0
+        for key in ("node_status", "l_last", "layer_width", "n_out", "out_parent", "out_node", "near_tie"):
+            assert np.array_equal(big[key], small[key]), (seed, key)
+        used = big["out_token"] >= 0
+        assert np.array_equal(used, small["out_token"] >= 0)
+        assert np.array_equal(big["out_token"][used], old_id[small["out_token"][used]]), seed
+        for key in ("lse_p", "lse_q", "node_logp_p", "node_logp_q", "out_logp_p", "out_logp_q"):
+            assert np.allclose(big[key], small[key], rtol=0, atol=1e-12), (seed, key)

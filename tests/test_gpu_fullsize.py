@@ -122,6 +122,30 @@ def test_c5_verify_with_an_independent_draft_model(t):
     gu.check_verify_select(d, w, ref, t=t)
 
 
+@pytest.mark.parametrize("top_k,top_p,t", [(0, 1.0, -1.0), (10, 0.8, 0.9)])
+def test_c5_verify_with_masked_vocabulary_entries(top_k, top_p, t):
+    """The benchmark's forest at the full vocabulary with the entries a padded output layer and a list of banned
+    tokens leave at -Inf: the last 256 entries and one in a hundred of the others, in both models."""
+    import gpu_util as gu
+    w = make_workload("c5", L=1, Hq=1, Hkv=1, D=64)
+    mask = np.random.default_rng(4).random(w.V) < 0.01
+    mask[-256:] = True
+    mask[w.token[w.token >= 0]] = False
+    w.logits_p[:, mask] = -np.inf
+    w.logits_q[:, mask] = -np.inf
+    d = gu.DeviceWorkload(w)
+    res = d.verify(t=t, top_k=top_k, top_p=top_p)
+    torch.cuda.synchronize()
+    with np.errstate(all="ignore"):
+        ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+    near = gu.compare_verify(res, ref, w)
+    tok = ref["out_token"][ref["out_token"] >= 0]
+    assert not mask[tok].any()
+    print("c5 masked top_k=%d t=%g: l_last %s widths %s masked %d near ties %d"
+          % (top_k, t, ref["l_last"].tolist(), ref["layer_width"].tolist(), int(mask.sum()), near), flush=True)
+    gu.check_verify_select(d, w, ref, t=t, top_k=top_k, top_p=top_p)
+
+
 @pytest.mark.parametrize("top_k,top_p,t,fast", [(32, 0.9, -1.0, 1), (32, 0.9, 0.6, 1), (8, 1.0, -1.0, 1),
                                                 (10, 0.8, -1.0, 1), (10, 0.8, -1.0, 0), (10, 0.8, 0.9, 1)])
 def test_c5_verify_with_warping_whole_forest(c5, top_k, top_p, t, fast, knobs):

@@ -148,7 +148,11 @@ typedef struct dsbd_verify_in {
                                    /*   drafted token raise DSBD_FAULT_NONFINITE                      */
   const float*  logits_draft;      /* [n_nodes,V] small model's logits                               */
   const double* beam_logp_target;  /* [n_trees] stored log-likelihood of each input beam under p      */
-  const double* beam_logp_draft;   /* [n_trees] ... under q (Section 2.1: beam sampling stores them)  */
+  const double* beam_logp_draft;   /* [n_trees] ... under q (Section 2.1: beam sampling stores them); */
+                                   /*   finite for at least one beam of every prompt, in both arrays  */
+                                   /*   (with DIFFERENT masks in the two models an output beam can    */
+                                   /*   come back with out_logp_draft = -Inf: a token drawn from the  */
+                                   /*   residual that the small model masks)                          */
   const float*  u_accept;          /* [n_nodes]            uniform in [0,1) for the node's accept test */
   const float*  u_resid;           /* [n_prompts,Lmax+2]   uniform for the residual sample of layer l  */
   const float*  u_fill;            /* [n_prompts,Lmax+2,W_cap] uniforms for the p_beam samples of layer l */

@@ -47,7 +47,7 @@ extern "C" {
 
 #define DSBD_FAULT_TOPOLOGY       1 /* parent outside its tree / not before the child / bad root    */
 #define DSBD_FAULT_TOKEN          2 /* token id outside [0, V)                                      */
-#define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit; -Inf (a masked token) in a whole row or at a drafted token */
+#define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit; -Inf (a masked token) in a whole row or at a drafted token; a prompt without a beam of finite stored likelihood */
 #define DSBD_FAULT_ZERO_RESIDUAL  8 /* a residual distribution had no mass                          */
 #define DSBD_FAULT_BOUNDS        16 /* a host-declared bound (max_*) is exceeded by the device data */
 #define DSBD_FAULT_SYNC_TIMEOUT  32 /* internal grid synchronisation gave up                        */
@@ -254,7 +254,9 @@ typedef struct dsbd_next_beams {
  * Select the beams of the next iteration from the verification outputs (Algorithm 1 returns the
  * beams of layer l_last; Section 3.3: the caches kept are those the output beams descend from).
  * keep_one != 0: keep only the output beam with the highest cumulative target log-likelihood
- * (lowest perplexity; ties to the lowest index), so a single cache survives (Section 3.4).
+ * (lowest perplexity; ties to the lowest index), so a single cache survives (Section 3.4).  The comparison is that
+ * of the fp64 values in out_logp_target: likelihoods of different beams that are equal in exact arithmetic may differ
+ * there in the last bit.
  * W_cap and Lmax must be the values used for dsbd_verify_forest.
  */
 int32_t dsbd_select_beams(const dsbd_forest* forest, const dsbd_verify_out* verified, int32_t W_cap,

@@ -1198,6 +1198,12 @@ void verify_layers_kernel(LayersArgs a) {
       const double eq = valid ? exp_nonpos(sh.cum_q[lane] - mq, sh.exp_tab) : 0.0;
       const double zp = wave_sum(ep), zq = wave_sum(eq);
       if (valid) { sh.bw_p[lane] = ep / zp; sh.bw_q[lane] = eq / zq; }
+      // no beam of the layer with a likelihood above 0 under one of the models (stored likelihoods of -Inf), or a
+      // likelihood that is no number: the joint is 0/0
+      const bool lost = !(mp > -INFINITY && mp < INFINITY && mq > -INFINITY && mq < INFINITY) ||
+                        __ballot(valid && (sh.cum_p[min(lane, 63)] != sh.cum_p[min(lane, 63)] ||
+                                           sh.cum_q[min(lane, 63)] != sh.cum_q[min(lane, 63)])) != 0ull;
+      if (lost && g == 0 && lane == 0) atomicOr(a.fault, DSBD_FAULT_NONFINITE);
     }
 
     // ===== and candidates = depth-l nodes whose parent is an input beam, in (rank, node) order

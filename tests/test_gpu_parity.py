@@ -622,6 +622,16 @@ def test_device_side_faults_are_reported_not_fatal():
         res = gu.DeviceWorkload(w4).verify()
         torch.cuda.synchronize()
         assert int(res.fault.item()) == dsbd.DSBD_FAULT_NONFINITE, (model, what)
+    # stored likelihoods: no beam of a prompt with a likelihood above 0 under one model, or one that is no number
+    for field, value in (("beam_logp_q", -np.inf), ("beam_logp_p", -np.inf), ("beam_logp_p", np.nan)):
+        w5 = make_workload("c2", L=40, V=500, Hq=4, Hkv=4)
+        if value != value:
+            getattr(w5, field)[1] = value
+        else:
+            getattr(w5, field)[:] = value
+        res = gu.DeviceWorkload(w5).verify()
+        torch.cuda.synchronize()
+        assert int(res.fault.item()) & dsbd.DSBD_FAULT_NONFINITE, (field, value)      # (other bits may follow from it)
 
 
 @pytest.mark.parametrize("G", [0, 64])

@@ -22,11 +22,14 @@ def _seq_key(seq):
 
 class SyntheticModels:
     """target: logits ~ std * N(0,1) per (sequence, token); draft: target + noise * N(0,1).
-    context_free=True: every sequence gets the logits of the empty one (the same p and q at every step)."""
+    context_free=True: every sequence gets the logits of the empty one (the same p and q at every step).
+    banned > 0: after every sequence about that share of the vocabulary is forbidden (the same tokens in both models,
+    another set per sequence; token 0 always stays): their logits are -Inf, as a logit processor leaves them."""
 
-    def __init__(self, V, seed=0, std=3.0, noise=0.5, context_free=False, Hq=4, Hkv=2, D=64):
+    def __init__(self, V, seed=0, std=3.0, noise=0.5, context_free=False, Hq=4, Hkv=2, D=64, banned=0.0):
         self.V, self.seed, self.std, self.noise, self.context_free = int(V), int(seed), float(std), float(noise), context_free
         self.Hq, self.Hkv, self.D = Hq, Hkv, D
+        self.banned = float(banned)
 
     def _normal(self, seq, stream, n):
         """n approximately normal values (Irwin-Hall of four uniforms, unit variance), float64."""
@@ -46,6 +49,12 @@ class SyntheticModels:
             a = self.std * self._normal(s, 1, self.V)
             zp[i] = a.astype(np.float32)
             zq[i] = (a + self.noise * self._normal(s, 2, self.V)).astype(np.float32)
+            if self.banned > 0.0:
+                # (four 24-bit uniforms summed, shifted and scaled as in _normal: their fractional parts are uniform)
+                gone = np.mod(self._normal(s, 6, self.V) * 1000.0, 1.0) < self.banned
+                gone[0] = False
+                zp[i, gone] = -np.inf
+                zq[i, gone] = -np.inf
         return zp, zq
 
     def qkv(self, seqs):

@@ -60,11 +60,12 @@ def test_loop_matches_the_oracle_loop(name, start, V, W_S, gamma, kw):
 @pytest.mark.parametrize("sweep", [0, 1])
 def test_loop_random_parameters(sweep):
     """Randomized sweep of the whole loop: prompts and input beams, draws per step above and below the number of
-    beams, draft depth 0..3, fixed and dynamic width, warping, one-cache mode, head groupings."""
+    beams, draft depth 0..3, fixed and dynamic width, warping, one-cache mode, head groupings, banned tokens."""
     import gpu_util as gu
     from paper_2409_16560_amd.loop import DecodeLoop
     from oracle.loop import OracleLoop
     rng = np.random.default_rng(3000 + sweep)
+    rng_banned = np.random.default_rng(5000 + sweep)
     g = lambda x: x.cpu().numpy()
     bits = lambda t_: t_.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
     for case in range(12):
@@ -83,7 +84,9 @@ def test_loop_random_parameters(sweep):
         what = "sweep %d case %d: V=%d start=%s W_S=%d gamma=%d %s heads %d/%d seeds %d %d" % (
             sweep, case, V, start, W_S, gamma, kw, Hq, Hkv, mseed, seed)
         print(what, flush=True)
-        m = SyntheticModels(V=V, seed=mseed, Hq=Hq, Hkv=Hkv, D=64)
+        banned = float(rng_banned.choice([0.0, 0.0, 0.3, 0.9]))     # share of the vocabulary at -Inf, per sequence
+        what += " banned %g" % banned
+        m = SyntheticModels(V=V, seed=mseed, Hq=Hq, Hkv=Hkv, D=64, banned=banned)
         lib = DecodeLoop(m, start, W_S, gamma, lambda n, stream: uniform01_f32(n, seed, stream), W_cap=8, kv_capacity=64, **kw)
         ora = OracleLoop(m, start, W_S, gamma, W_cap=8, seed=seed, **kw)
         for it in range(3):

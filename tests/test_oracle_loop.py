@@ -76,3 +76,24 @@ def test_steps_per_iteration_follow_the_efficiency_theorem(gamma, noise):
     for k in range(gamma):
         pk = alpha ** k * (1 - alpha)
         assert abs((steps == k + 1).mean() - pk) <= 4.5 * np.sqrt(pk * (1 - pk) / n) + 1e-3
+
+
+@pytest.mark.parametrize("kw", [dict(W_L=2, t=-1.0), dict(W_L=0, t=0.6, W_min=1), dict(W_L=3, t=-1.0, top_k=6, top_p=0.8)])
+def test_banned_tokens_never_enter_a_beam(kw):
+    """Models that forbid half of the vocabulary after every sequence (logits of -Inf): no beam ever continues with
+    a forbidden token, and the stored likelihoods stay those of the sequences."""
+    m = SyntheticModels(V=40, seed=3, Hq=2, Hkv=1, D=8, banned=0.5)
+    start = [[(5,), (9,)], [(2,)]]
+    with np.errstate(all="ignore"):
+        lp = OracleLoop(m, start, W_S=4, gamma=3, W_cap=8, seed=9, with_kv=False, **kw)
+        for it in range(5):
+            lp.step()
+    grown = 0
+    for p, pb in enumerate(lp.beams):
+        for s, b in enumerate(pb):
+            for i in range(1, len(b)):
+                assert np.isfinite(m.logits([b[:i]])[0][0, b[i]]), (p, s, i)
+            grown += len(b) - 1
+            with np.errstate(all="ignore"):
+                assert abs(lp.cum_p[p][s] - sequence_logp(m, b, 1, 0)) < 1e-9
+    assert grown > 10

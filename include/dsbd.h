@@ -47,7 +47,9 @@ extern "C" {
 
 #define DSBD_FAULT_TOPOLOGY       1 /* parent outside its tree / not before the child / bad root    */
 #define DSBD_FAULT_TOKEN          2 /* token id outside [0, V)                                      */
-#define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit; -Inf (a masked token) in a whole row or at a drafted token; a prompt without a beam of finite stored likelihood */
+#define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit; -Inf (a masked token) in a whole row or at */
+                                    /* a drafted token; a prompt without a beam of finite stored    */
+                                    /* likelihood                                                   */
 #define DSBD_FAULT_ZERO_RESIDUAL  8 /* a residual distribution had no mass                          */
 #define DSBD_FAULT_BOUNDS        16 /* a host-declared bound (max_*) is exceeded by the device data */
 #define DSBD_FAULT_SYNC_TIMEOUT  32 /* internal grid synchronisation gave up                        */

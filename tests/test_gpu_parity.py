@@ -610,6 +610,12 @@ def test_device_side_faults_are_reported_not_fatal():
     torch.cuda.synchronize()
     f = int(res.fault.item())
     assert f & dsbd.DSBD_FAULT_NONFINITE and f & dsbd.DSBD_FAULT_TOKEN
+    for model, col in (("logits_q", 3), ("logits_p", 499), ("logits_q", 256)):     # NaN, at places the pass reads in different ways
+        w3 = make_workload("c2", L=40, V=500, Hq=4, Hkv=4)
+        getattr(w3, model)[2, col] = np.nan
+        res = gu.DeviceWorkload(w3).verify()
+        torch.cuda.synchronize()
+        assert int(res.fault.item()) & dsbd.DSBD_FAULT_NONFINITE, (model, col)
     # -Inf is a masked token and no fault by itself, but a drafted token masked in its parent's row (either model)
     # and a row without any finite logit are
     for model, what in (("logits_p", "drafted"), ("logits_q", "drafted"), ("logits_p", "row"), ("logits_q", "row")):

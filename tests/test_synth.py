@@ -69,3 +69,17 @@ def test_scaled_down_variants_keep_structure():
     w = make_workload("c4", L=(16, 48), V=300)
     assert w.n_prompts == 16 and 16 <= w.n_trees <= 128
     assert np.all(np.diff(w.tree_prompt) >= 0)
+
+
+def test_synthetic_models_are_functions_of_the_sequence_and_ban_the_same_tokens_in_both():
+    from dsbd_synth import SyntheticModels
+    m = SyntheticModels(V=500, seed=7, banned=0.4)
+    zp, zq = m.logits([(1, 2, 3), (4,), (1, 2, 3)])
+    assert np.array_equal(zp[0], zp[2]) and np.array_equal(zq[0], zq[2])          # same sequence, same logits
+    gone = np.isneginf(zp)
+    assert np.array_equal(gone, np.isneginf(zq)) and not gone[:, 0].any()
+    assert 0.3 < gone.mean() < 0.5 and (gone[0] != gone[1]).any()                   # another set per sequence
+    assert np.isfinite(zp[~gone]).all() and np.isfinite(zq[~gone]).all()
+    plain = SyntheticModels(V=500, seed=7)
+    zp0, zq0 = plain.logits([(1, 2, 3)])
+    assert np.array_equal(zp0[0][~gone[0]], zp[0][~gone[0]])                      # banning changes nothing else

@@ -321,7 +321,8 @@ typedef struct dsbd_draft_in {
   const int32_t* beam_off;         /* [n_prompts+1] device: beams of prompt p are rows beam_off[p] .. beam_off[p+1]-1 */
   const float*   logits_draft;     /* [n_beams,V] small model's logits at those beams (-Inf = a masked token, */
                                    /*   never drawn; a row needs one finite logit)                            */
-  const double*  beam_logp_draft;  /* [n_beams] their stored log-likelihoods under the small model           */
+  const double*  beam_logp_draft;  /* [n_beams] their stored log-likelihoods under the small model (-Inf: a   */
+                                   /*   beam that is never continued; finite for one beam of every prompt)    */
   const float*   u;                /* [n_prompts,W_S] uniforms in [0,1), one per draw                        */
 } dsbd_draft_in;
 

@@ -48,8 +48,8 @@ extern "C" {
 #define DSBD_FAULT_TOPOLOGY       1 /* parent outside its tree / not before the child / bad root    */
 #define DSBD_FAULT_TOKEN          2 /* token id outside [0, V)                                      */
 #define DSBD_FAULT_NONFINITE      4 /* NaN or +Inf logit; -Inf (a masked token) in a whole row or at */
-                                    /* a drafted token; a prompt without a beam of finite stored    */
-                                    /* likelihood                                                   */
+                                    /* a drafted token; a layer without an input beam of finite     */
+                                    /* likelihood under one of the models                           */
 #define DSBD_FAULT_ZERO_RESIDUAL  8 /* a residual distribution had no mass                          */
 #define DSBD_FAULT_BOUNDS        16 /* a host-declared bound (max_*) is exceeded by the device data */
 #define DSBD_FAULT_SYNC_TIMEOUT  32 /* internal grid synchronisation gave up                        */
@@ -150,11 +150,13 @@ typedef struct dsbd_verify_in {
                                    /*   drafted token raise DSBD_FAULT_NONFINITE                      */
   const float*  logits_draft;      /* [n_nodes,V] small model's logits                               */
   const double* beam_logp_target;  /* [n_trees] stored log-likelihood of each input beam under p      */
-  const double* beam_logp_draft;   /* [n_trees] ... under q (Section 2.1: beam sampling stores them); */
-                                   /*   finite for at least one beam of every prompt, in both arrays  */
-                                   /*   (with DIFFERENT masks in the two models an output beam can    */
-                                   /*   come back with out_logp_draft = -Inf: a token drawn from the  */
-                                   /*   residual that the small model masks)                          */
+  const double* beam_logp_draft;   /* [n_trees] ... under q (Section 2.1: beam sampling stores them). */
+                                   /*   -Inf: a beam of probability 0 under that model (with DIFFERENT */
+                                   /*   masks in the two models an output beam can come back with     */
+                                   /*   out_logp_draft = -Inf: a token drawn from the residual that   */
+                                   /*   the small model masks).  A layer whose input beams ALL have   */
+                                   /*   -Inf under one model has no joint: DSBD_FAULT_NONFINITE, as   */
+                                   /*   for NaN and +Inf                                              */
   const float*  u_accept;          /* [n_nodes]            uniform in [0,1) for the node's accept test */
   const float*  u_resid;           /* [n_prompts,Lmax+2]   uniform for the residual sample of layer l  */
   const float*  u_fill;            /* [n_prompts,Lmax+2,W_cap] uniforms for the p_beam samples of layer l */

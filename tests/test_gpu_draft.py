@@ -102,6 +102,20 @@ def test_draft_layer_with_masked_tokens(top_k, top_p):
     assert np.max(np.abs(lp - rlp)) <= 1e-9
 
 
+def test_draft_layer_skips_beams_of_probability_zero():
+    """Beams with a stored likelihood of -Inf are never continued; the draws are the oracle's."""
+    for top_k, top_p in ((0, 1.0), (10, 0.8)):
+        beam_off, z, cum, u = layer_inputs(2, [5, 3], 4000, 8)
+        cum[1] = -np.inf
+        cum[6] = -np.inf
+        with np.errstate(all="ignore"):
+            rpar, rtok, rlp = oracle_draft_layer(beam_off, z, cum, u, top_k, top_p)
+        par, tok, lp, fault = run_draft_layer(beam_off, z, cum, u, 8, top_k, top_p)
+        assert fault == 0 and not np.isin(par, [1, 6]).any()
+        assert np.array_equal(par, rpar) and np.array_equal(tok, rtok)
+        assert np.max(np.abs(lp - rlp)) <= 1e-9
+
+
 def test_draft_layer_reports_bad_inputs():
     beam_off, z, cum, u = layer_inputs(3, [3, 2], 500, 4)
     z_bad = z.copy(); z_bad[1, 17] = np.inf

@@ -673,6 +673,25 @@ def test_masked_tokens_with_logit_minus_infinity(pattern, G, knobs):
             gu.check_verify_select(d, w, ref, t=t, top_k=top_k, top_p=top_p)
 
 
+@pytest.mark.parametrize("field", ["beam_logp_q", "beam_logp_p"])
+def test_an_input_beam_of_probability_zero_under_one_model(field):
+    """A stored likelihood of -Inf (what comes back for an output beam whose last token the other model masks): the
+    beam has the weight 0 in that model's joints; as long as every layer has another beam, the results are the
+    oracle's and no fault is raised."""
+    gu = _gu()
+    for seed in range(3):
+        w = make_workload("c3", L=1, Hq=1, Hkv=1, D=64, V=3000, seed=seed)
+        getattr(w, field)[1 + seed % 3] = -np.inf
+        d = gu.DeviceWorkload(w)
+        for top_k, top_p, t in ((0, 1.0, -1.0), (0, 1.0, 0.6), (10, 0.8, -1.0)):
+            with np.errstate(all="ignore"):
+                ref = gu.oracle_verify(w, t=t, top_k=top_k, top_p=top_p)
+            res = d.verify(t=t, top_k=top_k, top_p=top_p)
+            torch.cuda.synchronize()
+            gu.compare_verify(res, ref, w)
+            gu.check_verify_select(d, w, ref, t=t, top_k=top_k, top_p=top_p)
+
+
 def test_a_missing_partner_ends_in_a_fault_bit_not_in_a_hang(knobs):
     """Error path of the layer kernel's exchanges, forced from the host: one workgroup withholds its first post
     (test hook), every wait for it is bounded (2 ms here instead of 3 s), so all workgroups give up, the kernel ends
